@@ -1,0 +1,294 @@
+/*
+ * oco_oracle.c -- TEST INFRASTRUCTURE, not product code.
+ *
+ * Plain, slow, double-precision reference for the online learner of
+ * Sec. 3.3: K projected online-gradient-descent base learners (Sec. 3.1
+ * update, Assumption 2 domain), a Hedge meta learner over their cumulative
+ * losses, and the dynamic regret of Eq. (2) against a piecewise-constant
+ * comparator.  It follows the algorithm round by round in the paper's order
+ * and notation with plain loops: no blocking, no fusion, no reordering.
+ *
+ * It shares no code with the GPU library and may be called only from tests,
+ * the smoke check and the bench's reported CPU baseline.
+ *
+ * Readings of the paper taken here (each is listed in the design notes):
+ *  - each base learner uses the gradient at ITS OWN iterate w_t^i (Sec. 3.3);
+ *  - the Hedge exponent sums f_s(w_s^i) over s < t (the printed f_t inside
+ *    the sum over s is read as f_s), so p_1 is uniform and round t's weights
+ *    exclude round t's loss;
+ *  - the domain is the L2 ball of RADIUS D; the projection rescales only
+ *    when the norm exceeds D;
+ *  - w_1^i = 0.
+ *
+ * Losses are generalised-linear: f_t(w) = phi(<w, x_t>; y_t), so the
+ * gradient is phi'(z; y) x_t.  For the linear loss x_t is the gradient g_t.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { LOSS_LINEAR = 0, LOSS_SQUARED = 1, LOSS_LOGISTIC = 2 };
+
+/* phi(z; y) */
+double oco_oracle_loss(int loss, double z, double y)
+{
+    if (loss == LOSS_LINEAR) return z;
+    if (loss == LOSS_SQUARED) return (z - y) * (z - y);
+    /* logistic: log(1 + exp(-y z)), written so that exp never overflows */
+    double m = y * z;
+    return m > 0 ? log1p(exp(-m)) : -m + log1p(exp(m));
+}
+
+/* d phi / d z */
+double oco_oracle_slope(int loss, double z, double y)
+{
+    if (loss == LOSS_LINEAR) return 1.0;
+    if (loss == LOSS_SQUARED) return 2.0 * (z - y);
+    double m = y * z;
+    if (m > 0) { double e = exp(-m); return -y * e / (1.0 + e); }
+    return -y / (1.0 + exp(m));
+}
+
+/* Euclidean projection of v[0..d) onto { ||w||_2 <= D }, in place (Sec. 3.1). */
+void oco_oracle_project(double *v, int64_t d, double D)
+{
+    double s = 0.0;
+    for (int64_t j = 0; j < d; ++j) s += v[j] * v[j];
+    double nrm = sqrt(s);
+    if (nrm > D) {
+        double f = D / nrm;
+        for (int64_t j = 0; j < d; ++j) v[j] *= f;
+    }
+}
+
+/* Hedge weights p_i proportional to exp(-eps L_i) (Sec. 3.3), max-shifted. */
+void oco_oracle_hedge(const double *L, int64_t K, double eps, double *p)
+{
+    double m = -eps * L[0];
+    for (int64_t i = 1; i < K; ++i) if (-eps * L[i] > m) m = -eps * L[i];
+    double s = 0.0;
+    for (int64_t i = 0; i < K; ++i) { p[i] = exp(-eps * L[i] - m); s += p[i]; }
+    for (int64_t i = 0; i < K; ++i) p[i] /= s;
+}
+
+typedef struct {
+    /* all optional (NULL to skip); one entry per round */
+    double *p;      /* [T][K] weights used at round t                     */
+    double *z;      /* [T][K] <w_t^i, x_t>                                */
+    double *loss;   /* [T][K] f_t(w_t^i)                                  */
+    double *g2;     /* [T][K] ||grad f_t(w_t^i)||^2                       */
+    double *f;      /* [T]    f_t(w_t), w_t = sum_i p_t^i w_t^i           */
+    double *fu;     /* [T]    f_t(u_t)                                    */
+    double *zmix;   /* [T]    sum_i p_t^i z_t^i (must equal <w_t, x_t>)   */
+    double *wnorm;  /* [T][K] ||w_{t+1}^i|| after the projection          */
+} oco_oracle_trace;
+
+/*
+ * One run.  Inputs are the float32 buffers the GPU path consumes, widened to
+ * double.  Dense rounds: x[T][d].  Sparse rounds (nnz > 0): col/val[T][nnz],
+ * x == NULL; the step touches nnz coordinates, the norm is over all d.
+ *   norm_every == 0: the norm of the stepped vector is recomputed over all d
+ *                    coordinates every round (the definition);
+ *   norm_every  > 0: (sparse only) ||w||^2 is carried forward by adding
+ *                    w'_j^2 - w_j^2 over the touched coordinates and is
+ *                    recomputed over all d every norm_every rounds; the
+ *                    largest relative gap seen at those checks is returned in
+ *                    *max_drift.
+ * Comparator: u[S][d], segment s active for rounds seg_start[s] <= t <
+ * seg_start[s+1] (0-based rounds; the last segment runs to T).
+ * Outputs: W[K][d] = w_{T+1}^i, L[K] cumulative losses, p[K] = p_{T+1},
+ * wbar[d] = sum_i p_{T+1}^i w_{T+1}^i, *regret = Reg_T.
+ * Returns 0, or -1 on bad arguments / allocation failure.
+ */
+int oco_oracle_run(int64_t d, int64_t K, int64_t T, double D, const double *eta,
+                   double eps, int loss,
+                   const float *x, const int32_t *col, const float *val, int64_t nnz,
+                   const float *y, const float *u, const int64_t *seg_start, int64_t S,
+                   int64_t norm_every,
+                   double *W, double *L, double *p, double *wbar, double *regret,
+                   double *max_drift, const oco_oracle_trace *tr)
+{
+    if (d <= 0 || K <= 0 || T < 0 || S <= 0 || !eta || !u || !seg_start) return -1;
+    if (nnz > 0 ? (!col || !val) : !x) return -1;
+    if (loss != LOSS_LINEAR && !y) return -1;
+    if (nnz == 0) norm_every = 0;
+
+    double *z = malloc(sizeof(double) * K), *ell = malloc(sizeof(double) * K);
+    double *c = malloc(sizeof(double) * K), *n2 = calloc(K, sizeof(double));
+    double *wt = malloc(sizeof(double) * d);      /* the combined iterate w_t */
+    double *xt = malloc(sizeof(double) * d);      /* x_t widened (dense rows) */
+    if (!z || !ell || !c || !n2 || !wt || !xt) return -1;
+
+    memset(W, 0, sizeof(double) * K * d);
+    for (int64_t i = 0; i < K; ++i) L[i] = 0.0;
+    double reg = 0.0, drift = 0.0;
+    int64_t seg = 0;
+
+    for (int64_t t = 0; t < T; ++t) {
+        while (seg + 1 < S && t >= seg_start[seg + 1]) ++seg;
+        const float *ut = u + seg * d;
+        double yt = y ? (double)y[t] : 0.0;
+        const int32_t *ct = nnz ? col + t * nnz : NULL;
+        const float *vt = nnz ? val + t * nnz : NULL;
+
+        /* meta weights from the losses of rounds < t */
+        oco_oracle_hedge(L, K, eps, p);
+
+        /* predictions of the base learners, their losses and slopes */
+        double zu = 0.0, x2 = 0.0;
+        if (nnz) {
+            for (int64_t i = 0; i < K; ++i) {
+                double s = 0.0;
+                for (int64_t k = 0; k < nnz; ++k) s += W[i * d + ct[k]] * (double)vt[k];
+                z[i] = s;
+            }
+            for (int64_t k = 0; k < nnz; ++k) {
+                zu += (double)ut[ct[k]] * (double)vt[k];
+                x2 += (double)vt[k] * (double)vt[k];
+            }
+        } else {
+            for (int64_t j = 0; j < d; ++j) xt[j] = (double)x[t * d + j];
+            for (int64_t i = 0; i < K; ++i) {
+                double s = 0.0;
+                for (int64_t j = 0; j < d; ++j) s += W[i * d + j] * xt[j];
+                z[i] = s;
+            }
+            for (int64_t j = 0; j < d; ++j) { zu += (double)ut[j] * xt[j]; x2 += xt[j] * xt[j]; }
+        }
+        for (int64_t i = 0; i < K; ++i) {
+            ell[i] = oco_oracle_loss(loss, z[i], yt);
+            c[i] = oco_oracle_slope(loss, z[i], yt);
+        }
+
+        /* the combined iterate w_t = sum_i p_i w_t^i and its loss (Eq. (2)) */
+        double zw = 0.0, zmix = 0.0;
+        if (nnz) {
+            for (int64_t k = 0; k < nnz; ++k) {
+                double wj = 0.0;
+                for (int64_t i = 0; i < K; ++i) wj += p[i] * W[i * d + ct[k]];
+                zw += wj * (double)vt[k];
+            }
+        } else {
+            for (int64_t j = 0; j < d; ++j) {
+                double wj = 0.0;
+                for (int64_t i = 0; i < K; ++i) wj += p[i] * W[i * d + j];
+                wt[j] = wj;
+            }
+            for (int64_t j = 0; j < d; ++j) zw += wt[j] * xt[j];
+        }
+        for (int64_t i = 0; i < K; ++i) zmix += p[i] * z[i];
+        double ft = oco_oracle_loss(loss, zw, yt);
+        double fu = oco_oracle_loss(loss, zu, yt);
+        reg += ft - fu;
+
+        if (tr) {
+            for (int64_t i = 0; i < K; ++i) {
+                if (tr->p) tr->p[t * K + i] = p[i];
+                if (tr->z) tr->z[t * K + i] = z[i];
+                if (tr->loss) tr->loss[t * K + i] = ell[i];
+                if (tr->g2) tr->g2[t * K + i] = c[i] * c[i] * x2;
+            }
+            if (tr->f) tr->f[t] = ft;
+            if (tr->fu) tr->fu[t] = fu;
+            if (tr->zmix) tr->zmix[t] = zmix;
+        }
+
+        /* gradient step and projection of every base learner */
+        for (int64_t i = 0; i < K; ++i) {
+            double *w = W + i * d;
+            double a = eta[i] * c[i];
+            double s2;
+            if (nnz) {
+                double delta = 0.0;
+                for (int64_t k = 0; k < nnz; ++k) {
+                    double old = w[ct[k]];
+                    double nw = old - a * (double)vt[k];
+                    w[ct[k]] = nw;
+                    delta += nw * nw - old * old;
+                }
+                if (norm_every == 0) {
+                    s2 = 0.0;
+                    for (int64_t j = 0; j < d; ++j) s2 += w[j] * w[j];
+                } else {
+                    s2 = n2[i] + delta;
+                    if ((t + 1) % norm_every == 0) {
+                        double full = 0.0;
+                        for (int64_t j = 0; j < d; ++j) full += w[j] * w[j];
+                        double gap = fabs(full - s2) / (full > 1e-300 ? full : 1e-300);
+                        if (full > 0 && gap > drift) drift = gap;
+                        s2 = full;
+                    }
+                }
+            } else {
+                s2 = 0.0;
+                for (int64_t j = 0; j < d; ++j) {
+                    w[j] = w[j] - a * xt[j];
+                    s2 += w[j] * w[j];
+                }
+            }
+            double nrm = sqrt(s2);
+            if (nrm > D) {
+                double f = D / nrm;
+                for (int64_t j = 0; j < d; ++j) w[j] *= f;
+                s2 = D * D;
+                nrm = D;
+            }
+            n2[i] = s2;
+            if (tr && tr->wnorm) tr->wnorm[t * K + i] = nrm;
+            L[i] += ell[i];
+        }
+    }
+
+    oco_oracle_hedge(L, K, eps, p);
+    for (int64_t j = 0; j < d; ++j) {
+        double wj = 0.0;
+        for (int64_t i = 0; i < K; ++i) wj += p[i] * W[i * d + j];
+        wbar[j] = wj;
+    }
+    *regret = reg;
+    if (max_drift) *max_drift = drift;
+    free(z); free(ell); free(c); free(n2); free(wt); free(xt);
+    return 0;
+}
+
+/*
+ * R independent runs, one per thread at a time (OpenMP over runs, nothing
+ * else is parallel).  Strides follow the GPU library's input layout:
+ * x[T][d] when x_shared else x[R][T][d]; col/val[T][nnz] shared; y[R][T];
+ * u[R][S][d].  Outputs W[R][K][d], L[R][K], p[R][K], wbar[R][d], regret[R].
+ * Returns the number of runs that failed; *threads_used reports the team size.
+ */
+int oco_oracle_run_many(int64_t R, int64_t d, int64_t K, int64_t T, double D,
+                        const double *eta, double eps, int loss, int x_shared,
+                        const float *x, const int32_t *col, const float *val, int64_t nnz,
+                        const float *y, const float *u, const int64_t *seg_start, int64_t S,
+                        int64_t norm_every, int threads,
+                        double *W, double *L, double *p, double *wbar, double *regret,
+                        double *max_drift, int *threads_used)
+{
+    int bad = 0, used = 1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    used = omp_get_max_threads();
+    if ((int64_t)used > R) used = (int)(R > 0 ? R : 1);
+#else
+    (void)threads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : bad)
+    for (int64_t r = 0; r < R; ++r) {
+        const float *xr = x ? (x_shared ? x : x + r * T * d) : NULL;
+        double dr = 0.0;
+        int rc = oco_oracle_run(d, K, T, D, eta, eps, loss, xr, col, val, nnz,
+                                y ? y + r * T : NULL, u + r * S * d, seg_start, S, norm_every,
+                                W + r * K * d, L + r * K, p + r * K, wbar + r * d, regret + r,
+                                &dr, NULL);
+        if (max_drift) max_drift[r] = dr;
+        if (rc) bad += 1;
+    }
+    if (threads_used) *threads_used = used;
+    return bad;
+}
