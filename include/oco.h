@@ -1,0 +1,165 @@
+/*
+ * liboco -- batched simulation of the online-ensemble learner on one MI355X.
+ *
+ * The library advances R independent runs of the learner of Sec. 3.3: K
+ * projected online-gradient-descent base learners (Sec. 3.1 update on the
+ * domain of Assumption 2, an L2 ball of radius D), a Hedge meta learner over
+ * their cumulative losses, and the dynamic regret of Eq. (2) against a
+ * piecewise-constant comparator sequence.  Losses are generalised linear,
+ * f_t(w) = phi(<w, x_t>; y_t), so grad f_t(w) = phi'(<w, x_t>; y_t) x_t.
+ *
+ * Per run and round t (0-based here; the paper's round t+1), with
+ * L_t^i = sum_{s<t} f_s(w_s^i):
+ *     p_t^i      = exp(-eps L_t^i) / sum_j exp(-eps L_t^j)           (Hedge)
+ *     w_t        = sum_i p_t^i w_t^i                                 (combined iterate)
+ *     regret    += f_t(w_t) - f_t(u_t)                               (Eq. (2))
+ *     w_{t+1}^i  = Proj_{||w||<=D}[ w_t^i - eta_i grad f_t(w_t^i) ]  (each learner at its own iterate)
+ * starting from w_0^i = 0, L_0 = 0, regret = 0.
+ *
+ * Conventions
+ *  - Every function returns OCO_OK (0) or a negative oco_status; nothing
+ *    throws or aborts.  All argument checks happen on the host before any
+ *    kernel is launched.
+ *  - "host" / "device" is stated for every pointer.  The library allocates no
+ *    device memory: the caller provides one workspace (oco_workspace_bytes)
+ *    and owns every input and output buffer.  Device pointers must be at
+ *    least 16-byte aligned; the workspace 256-byte aligned.
+ *  - All GPU work is enqueued on the HIP stream given to oco_create.  Input
+ *    buffers are borrowed until that work has finished.
+ *  - Results are a pure function of (config, inputs): splitting [0, T) into
+ *    oco_run_rounds calls in any way gives bit-identical state and regret.
+ *  - Arithmetic: iterates, inner products and the projection in float32;
+ *    losses, cumulative losses, Hedge weights and regret in float64.
+ */
+#ifndef OCO_H
+#define OCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct oco_state oco_state; /* opaque host object */
+
+typedef enum {
+    OCO_OK = 0,
+    OCO_EINVAL = -1,  /* NULL pointer, non-positive size, non-finite parameter, misaligned buffer */
+    OCO_ESEQ = -2,    /* t0 is not the number of rounds already consumed */
+    OCO_ERANGE = -3,  /* t0 + n exceeds T, n exceeds n_max, or too many comparator segments */
+    OCO_ENOMEM = -4,  /* workspace smaller than oco_workspace_bytes */
+    OCO_EHIP = -5,    /* a HIP runtime call failed (no usable device, launch error) */
+    OCO_ENOCOMP = -6, /* oco_run_rounds before oco_set_comparator */
+    OCO_EUNSUPPORTED = -7 /* shape outside what the kernels cover (see oco_config) */
+} oco_status;
+
+typedef enum {
+    OCO_LINEAR = 0,   /* phi(z; y) = z            (x_t is the gradient g_t, y unused) */
+    OCO_SQUARED = 1,  /* phi(z; y) = (z - y)^2     gradient 2 (z - y) x_t             */
+    OCO_LOGISTIC = 2  /* phi(z; y) = log(1 + exp(-y z)), y in {-1, +1}                */
+} oco_loss;
+
+#define OCO_MAX_SEGMENTS 4096   /* comparator segments per run */
+#define OCO_MAX_K 64            /* base learners per run */
+#define OCO_MAX_DENSE_D 4096    /* dense rounds keep a learner's iterate in one wavefront's registers */
+#define OCO_MAX_NNZ 64          /* entries per sparse round */
+
+typedef struct {
+    int64_t d;            /* dimension of w; dense rounds need d <= OCO_MAX_DENSE_D   */
+    int64_t K;            /* base learners per run (the paper's N), 1..OCO_MAX_K      */
+    int64_t T;            /* horizon: total rounds                                    */
+    int64_t R;            /* independent runs                                         */
+    double D;             /* radius of the domain { ||w||_2 <= D } (Assumption 2)     */
+    double G;             /* gradient-norm bound of Assumption 2; informational --
+                             it enters only through the step grid                     */
+    const double *eta;    /* host, [K]: step sizes (see oco_step_grid); copied        */
+    double eps;           /* meta learning rate of Hedge, >= 0                        */
+    int32_t loss;         /* oco_loss                                                 */
+    int32_t x_shared;     /* 1: one round stream for all runs; 0: one per run
+                             (dense only; sparse streams are always shared)           */
+    int32_t sparse_nnz;   /* 0: dense rounds; >0: every round has exactly this many
+                             (column, value) entries, columns distinct within a round */
+    int32_t reserved;     /* must be 0                                                */
+    int64_t n_max;        /* largest n of any oco_run_rounds call; 0 means T          */
+} oco_config;
+
+typedef struct {
+    /* all device pointers, read-only, indexed by the round RELATIVE to t0 */
+    const float *x;       /* dense: [n][d] if x_shared, else run r at x + r*x_run_stride;
+                             for OCO_LINEAR this is the gradient stream g              */
+    const int32_t *col;   /* sparse: [n][nnz] column indices in [0, d)                 */
+    const float *val;     /* sparse: [n][nnz] values                                   */
+    const float *y;       /* run r at y + r*y_run_stride, [n] each; NULL for OCO_LINEAR */
+    int64_t x_run_stride; /* elements between runs of x; 0 means n*d                   */
+    int64_t y_run_stride; /* elements between runs of y; 0 means n                     */
+} oco_rounds;
+
+/* Step grid of the proof of Corollary 3: eta_i = 2^i D / (G sqrt(T)), i = 0..K-1
+ * (the paper indexes it i-1, i = 1..N).  out: host [K]. */
+int oco_step_grid(double D, double G, int64_t T, int64_t K, double *out);
+
+/* Number of base learners the proof of Corollary 3 prescribes: ceil(log2(1+T)/2) + 1. */
+int64_t oco_paper_num_learners(int64_t T);
+
+/* Bytes of device workspace oco_create needs for this config; 0 if the config is invalid
+ * or unsupported. */
+size_t oco_workspace_bytes(const oco_config *cfg);
+
+/* Validates cfg, lays the state out in the caller's device workspace and zeroes it
+ * (w_0 = 0, L_0 = 0, regret = 0) on `hip_stream` (a hipStream_t, NULL = default stream).
+ * dev_ws: device, >= oco_workspace_bytes(cfg) bytes, owned by the caller and borrowed until
+ * oco_destroy.  *out receives a host object to release with oco_destroy. */
+int oco_create(const oco_config *cfg, void *dev_ws, size_t ws_bytes, void *hip_stream,
+               oco_state **out);
+
+/* Comparator sequence of Eq. (2): u_dev device [R][S][d] float32 (borrowed until the last
+ * oco_run_rounds has finished), segment s of every run is active for rounds
+ * seg_start[s] <= t < seg_start[s+1] (last segment to T).  seg_start: host [S], copied,
+ * strictly increasing with seg_start[0] == 0; 1 <= S <= OCO_MAX_SEGMENTS. */
+int oco_set_comparator(oco_state *st, const float *u_dev, const int64_t *seg_start_host,
+                       int64_t S);
+
+/* Advances every run by rounds t0 .. t0+n-1.  t0 must equal the rounds consumed so far
+ * (OCO_ESEQ), t0 + n <= T and n <= n_max (OCO_ERANGE).  n == 0 is a no-op.  Asynchronous:
+ * returns after enqueueing on the stream. */
+int oco_run_rounds(oco_state *st, const oco_rounds *rounds, int64_t t0, int64_t n);
+
+/* Dynamic regret of every run over the rounds consumed so far.  out_host: host [R].
+ * Synchronises the stream. */
+int oco_regret(oco_state *st, double *out_host);
+
+/* Writes the current iterates w^i (W_dev: device [R][K][d]), the Hedge weights for the next
+ * round (p_dev: device [R][K]) and the combined iterate sum_i p^i w^i (wbar_dev: device
+ * [R][d]); any of the three may be NULL.  Asynchronous on the stream. */
+int oco_get_state(oco_state *st, float *W_dev, float *p_dev, float *wbar_dev);
+
+/* Cumulative base-learner losses L^i over the rounds consumed so far.  out_host: host [R][K].
+ * Synchronises the stream. */
+int oco_cum_losses(oco_state *st, double *out_host);
+
+/* Back to round 0 (w = 0, L = 0, regret = 0); keeps the comparator.  Asynchronous. */
+int oco_reset(oco_state *st);
+
+/* Kernel timing for benchmarks.  After oco_set_timing(st, 1) every oco_run_rounds call records
+ * HIP events on the state's stream around its two kernels; oco_last_timing waits for the most
+ * recent call's events and writes the durations in milliseconds to ms_host: host [2],
+ * [0] = the round kernel (steps S0-S2, S4 of a round: stream x, predict, slope, step, project),
+ * [1] = the meta kernel (Hedge weights, losses, regret).  OCO_EINVAL if timing is off or no call
+ * has been made since it was switched on. */
+int oco_set_timing(oco_state *st, int enable);
+int oco_last_timing(oco_state *st, float *ms_host);
+
+/* Rounds consumed so far, or a negative oco_status. */
+int64_t oco_rounds_done(const oco_state *st);
+
+/* Releases the host object (the device workspace stays the caller's).  NULL is allowed. */
+void oco_destroy(oco_state *st);
+
+/* Static, human-readable text for a status code. */
+const char *oco_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OCO_H */

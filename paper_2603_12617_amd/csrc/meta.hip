@@ -1,0 +1,240 @@
+// Meta learner and regret (Sec. 3.3 Hedge weights, Eq. (2) regret), state
+// export and state initialisation.
+//
+// The round kernels leave z_t^i = <w_t^i, x_t> (i < K) and z_t^u = <u_t, x_t>
+// in Z for the n rounds of a call.  Everything here is float64 on a handful of
+// scalars per round:
+//     l_t^i = phi(z_t^i; y_t)                       base losses
+//     L_t^i = L_{t-1}^i + l_{t-1}^i                 (running sum, strictly in round order)
+//     p_t^i = exp(-eps L_t^i) / sum_j exp(-eps L_t^j)
+//     <w_t, x_t> = sum_i p_t^i z_t^i                (w_t = sum_i p_t^i w_t^i is linear in w)
+//     regret += phi(<w_t, x_t>; y_t) - phi(z_t^u; y_t)
+// One workgroup per run walks the rounds in tiles: losses of a tile in
+// parallel over rounds, the running sums by K threads in round order, the
+// weights and the regret terms in parallel over rounds, and the regret sum by
+// one thread in round order -- so the result does not depend on how the
+// horizon is cut into calls.
+#include "oco_internal.h"
+
+namespace oco {
+namespace {
+
+template <int LOSS> __device__ __forceinline__ double phi(double z, double y)
+{
+    if (LOSS == 0) return z;
+    if (LOSS == 1) { const double e = z - y; return e * e; }
+    const double m = y * z;                       // log(1 + exp(-m)) without overflow
+    return m > 0.0 ? log1p(exp(-m)) : log1p(exp(m)) - m;
+}
+
+template <int LOSS>
+__global__ void __launch_bounds__(256) meta_kernel(const MetaArgs a)
+{
+    extern __shared__ double sm[];
+    const int TM = blockDim.x;
+    const int K = a.K;
+    double *lmat = sm;                 // [TM][K]: losses, then cumulative losses before the round
+    double *diff = sm + (size_t)TM * K; // [TM]
+    const int r = blockIdx.x;
+    const int j = threadIdx.x;
+    const float *Zr = a.Z + (int64_t)r * a.zl.zs_r;
+    const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
+
+    double Lacc = (j < K) ? a.L[(int64_t)r * K + j] : 0.0;   // thread i < K carries L^i
+    double reg = (j == 0) ? a.regret[r] : 0.0;
+
+    for (int t0 = 0; t0 < a.n; t0 += TM) {
+        const int cnt = min(TM, a.n - t0);
+        const int t = t0 + j;
+        double yt = 0.0;
+        if (j < cnt) {
+            yt = yrow ? (double)yrow[t] : 0.0;
+            for (int i = 0; i < K; ++i) {
+                const double z = (double)Zr[(int64_t)i * a.zl.zs_i + (int64_t)t * a.zl.zs_t];
+                lmat[j * K + i] = phi<LOSS>(z, yt);
+            }
+        }
+        __syncthreads();
+        if (j < K) {
+            for (int jj = 0; jj < cnt; ++jj) {
+                const double l = lmat[jj * K + j];
+                lmat[jj * K + j] = Lacc;
+                Lacc += l;
+            }
+        }
+        __syncthreads();
+        if (j < cnt) {
+            double Lmin = lmat[j * K];
+            for (int i = 1; i < K; ++i) Lmin = fmin(Lmin, lmat[j * K + i]);
+            double S = 0.0, zs = 0.0;
+            for (int i = 0; i < K; ++i) {
+                const double e = exp(-a.eps * (lmat[j * K + i] - Lmin));
+                const double z = (double)Zr[(int64_t)i * a.zl.zs_i + (int64_t)t * a.zl.zs_t];
+                S += e;
+                zs += e * z;
+            }
+            const double zhat = zs / S;
+            const double zu = (double)Zr[(int64_t)K * a.zl.zs_i + (int64_t)t * a.zl.zs_t];
+            diff[j] = phi<LOSS>(zhat, yt) - phi<LOSS>(zu, yt);
+        }
+        __syncthreads();
+        if (j == 0)
+            for (int jj = 0; jj < cnt; ++jj) reg += diff[jj];
+        // lmat/diff are rewritten only after the next tile's first barrier
+    }
+    if (j < K) a.L[(int64_t)r * K + j] = Lacc;
+    if (j == 0) a.regret[r] = reg;
+}
+
+// p = softmax(-eps L) of one run, into shared memory (first K threads)
+__device__ void hedge_weights(const double *L, int K, double eps, double *p_sh)
+{
+    if (threadIdx.x == 0) {
+        double Lmin = L[0];
+        for (int i = 1; i < K; ++i) Lmin = fmin(Lmin, L[i]);
+        double S = 0.0;
+        for (int i = 0; i < K; ++i) { p_sh[i] = exp(-eps * (L[i] - Lmin)); S += p_sh[i]; }
+        for (int i = 0; i < K; ++i) p_sh[i] /= S;
+    }
+    __syncthreads();
+}
+
+// dense layout: V[R][K][d], sigma float [R][K]
+__global__ void __launch_bounds__(256) export_dense_kernel(const ExportArgs a)
+{
+    __shared__ double p_sh[64];
+    __shared__ float s_sh[64];
+    const int r = blockIdx.y;
+    const int K = a.K;
+    hedge_weights(a.L + (int64_t)r * K, K, a.eps, p_sh);
+    if (threadIdx.x < K) s_sh[threadIdx.x] = static_cast<const float *>(a.sigma)[(int64_t)r * K + threadIdx.x];
+    __syncthreads();
+    if (a.p && blockIdx.x == 0 && threadIdx.x < K) a.p[(int64_t)r * K + threadIdx.x] = (float)p_sh[threadIdx.x];
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= a.d) return;
+    double acc = 0.0;
+    for (int i = 0; i < K; ++i) {
+        const float w = s_sh[i] * a.V[((int64_t)r * K + i) * a.d + j];
+        if (a.W) a.W[((int64_t)r * K + i) * a.d + j] = w;
+        acc += p_sh[i] * (double)w;
+    }
+    if (a.wbar) a.wbar[(int64_t)r * a.d + j] = (float)acc;
+}
+
+// sparse layout: V[d][RKp], sigma double [RKp].  64x64 transpose through LDS:
+// rows = coordinates, columns = learners.
+__global__ void __launch_bounds__(256) export_sparse_W_kernel(const ExportArgs a)
+{
+    __shared__ float tile[64][65];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t j0 = (int64_t)blockIdx.x * 64;
+    const int q0 = blockIdx.y * 64;
+    const int nq = a.R * a.K;
+    const double *sg = static_cast<const double *>(a.sigma);
+    const float s = (q0 + tx < nq) ? (float)sg[q0 + tx] : 0.f;
+    for (int row = ty; row < 64; row += 4) {
+        const int64_t j = j0 + row;
+        float v = 0.f;
+        if (j < a.d && q0 + tx < nq) v = (float)((double)a.V[j * a.RKp + q0 + tx] * (double)s);
+        tile[row][tx] = v;
+    }
+    __syncthreads();
+    for (int tq = ty; tq < 64; tq += 4) {
+        const int q = q0 + tq;
+        const int64_t j = j0 + tx;
+        if (q < nq && j < a.d) a.W[(int64_t)q * a.d + j] = tile[tx][tq];
+    }
+}
+
+__global__ void __launch_bounds__(256) export_sparse_p_wbar_kernel(const ExportArgs a)
+{
+    __shared__ double p_sh[64];
+    __shared__ double s_sh[64];
+    const int r = blockIdx.y;
+    const int K = a.K;
+    hedge_weights(a.L + (int64_t)r * K, K, a.eps, p_sh);
+    if (threadIdx.x < K) s_sh[threadIdx.x] = static_cast<const double *>(a.sigma)[r * K + threadIdx.x];
+    __syncthreads();
+    if (a.p && blockIdx.x == 0 && threadIdx.x < K) a.p[(int64_t)r * K + threadIdx.x] = (float)p_sh[threadIdx.x];
+    if (!a.wbar) return;
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= a.d) return;
+    double acc = 0.0;
+    for (int i = 0; i < K; ++i) {
+        const float w = (float)((double)a.V[j * a.RKp + r * K + i] * (double)(float)s_sh[i]);
+        acc += p_sh[i] * (double)w;
+    }
+    a.wbar[(int64_t)r * a.d + j] = (float)acc;
+}
+
+__global__ void __launch_bounds__(256) zero_kernel(uint4 *p, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n16; k += stride)
+        p[k] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+__global__ void __launch_bounds__(256) ones_kernel(void *p, int64_t n, int is_double)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n) return;
+    if (is_double) static_cast<double *>(p)[k] = 1.0; else static_cast<float *>(p)[k] = 1.0f;
+}
+
+}  // namespace
+
+hipError_t launch_meta(const MetaArgs &a, int loss, hipStream_t s)
+{
+    if (a.n <= 0) return hipSuccess;
+    const int TM = a.K <= 24 ? 256 : 64;
+    const size_t smem = sizeof(double) * ((size_t)TM * a.K + TM);
+    switch (loss) {
+        case 0: hipLaunchKernelGGL(meta_kernel<0>, dim3(a.R), dim3(TM), smem, s, a); break;
+        case 1: hipLaunchKernelGGL(meta_kernel<1>, dim3(a.R), dim3(TM), smem, s, a); break;
+        case 2: hipLaunchKernelGGL(meta_kernel<2>, dim3(a.R), dim3(TM), smem, s, a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_export(const ExportArgs &a, hipStream_t s)
+{
+    if (!a.W && !a.p && !a.wbar) return hipSuccess;
+    if (!a.sparse) {
+        dim3 grid((a.d + 255) / 256, a.R);
+        hipLaunchKernelGGL(export_dense_kernel, grid, dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
+    if (a.W) {
+        dim3 grid((unsigned)(((int64_t)a.d + 63) / 64), (a.R * a.K + 63) / 64);
+        hipLaunchKernelGGL(export_sparse_W_kernel, grid, dim3(256), 0, s, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (a.p || a.wbar) {
+        dim3 grid(a.wbar ? (unsigned)(((int64_t)a.d + 255) / 256) : 1u, a.R);
+        hipLaunchKernelGGL(export_sparse_p_wbar_kernel, grid, dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_init_state(void *zero_base, size_t zero_bytes, void *sigma, int64_t n_sigma,
+                             int sigma_is_double, hipStream_t s)
+{
+    const size_t n16 = zero_bytes / 16;
+    if (n16) {
+        const unsigned blocks = (unsigned)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+        hipLaunchKernelGGL(zero_kernel, dim3(blocks), dim3(256), 0, s, static_cast<uint4 *>(zero_base), n16);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (n_sigma) {
+        hipLaunchKernelGGL(ones_kernel, dim3((unsigned)((n_sigma + 255) / 256)), dim3(256), 0, s, sigma,
+                           n_sigma, sigma_is_double);
+        return hipGetLastError();
+    }
+    return hipSuccess;
+}
+
+}  // namespace oco

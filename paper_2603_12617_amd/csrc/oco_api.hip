@@ -1,0 +1,322 @@
+// Host side of the C ABI declared in include/oco.h: argument validation,
+// workspace layout, kernel sequencing.  No device memory is allocated here.
+#include "../../include/oco.h"
+#include "oco_internal.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace oco;
+
+namespace {
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Layout {
+    size_t off_V = 0, off_sigma = 0, off_n2 = 0, off_L = 0, off_regret = 0, off_eta = 0,
+           off_seg = 0, off_Z = 0, total = 0;
+    size_t state_bytes = 0;   // [off_V, off_V + state_bytes) is zeroed by reset (V, sigma, n2, L, regret)
+    int64_t n_sigma = 0;
+    int RKp = 0;
+    int64_t n_max = 0;
+};
+
+bool finite_pos(double v) { return std::isfinite(v) && v > 0.0; }
+
+// Returns OCO_OK and fills `lay`, or the status that describes what is wrong with cfg.
+int validate_and_layout(const oco_config *c, Layout *lay)
+{
+    if (!c || !c->eta) return OCO_EINVAL;
+    if (c->d <= 0 || c->K <= 0 || c->T <= 0 || c->R <= 0) return OCO_EINVAL;
+    if (c->reserved != 0 || c->n_max < 0) return OCO_EINVAL;
+    if (!finite_pos(c->D) || !finite_pos(c->G) || !std::isfinite(c->eps) || c->eps < 0.0) return OCO_EINVAL;
+    if (c->loss < OCO_LINEAR || c->loss > OCO_LOGISTIC) return OCO_EINVAL;
+    if (c->x_shared != 0 && c->x_shared != 1) return OCO_EINVAL;
+    if (c->sparse_nnz < 0) return OCO_EINVAL;
+    if (c->K > OCO_MAX_K) return OCO_EUNSUPPORTED;
+    for (int64_t i = 0; i < c->K; ++i)
+        if (!finite_pos(c->eta[i])) return OCO_EINVAL;
+    if (c->d > INT32_MAX || c->T > INT32_MAX || c->R > (1 << 24)) return OCO_EUNSUPPORTED;
+    const int64_t n_max = c->n_max == 0 ? c->T : (c->n_max < c->T ? c->n_max : c->T);
+    const int64_t RK = c->R * c->K;
+    if (RK > (1 << 26)) return OCO_EUNSUPPORTED;
+    if (c->sparse_nnz > 0) {
+        if (c->sparse_nnz > OCO_MAX_NNZ || c->sparse_nnz > c->d) return OCO_EUNSUPPORTED;
+        if (!c->x_shared) return OCO_EUNSUPPORTED;
+    } else if (!dense_supported(c->d)) {
+        return OCO_EUNSUPPORTED;
+    }
+    Layout l;
+    l.n_max = n_max;
+    size_t off = 0;
+    l.off_V = off;
+    if (c->sparse_nnz > 0) {
+        l.RKp = (int)align_up((size_t)RK, kWave);
+        off += align_up(sizeof(float) * (size_t)c->d * l.RKp, 256);
+        l.off_sigma = off; l.n_sigma = l.RKp;
+        off += align_up(sizeof(double) * l.RKp, 256);
+        l.off_n2 = off;
+        off += align_up(sizeof(double) * l.RKp, 256);
+    } else {
+        off += align_up(sizeof(float) * (size_t)RK * c->d, 256);
+        l.off_sigma = off; l.n_sigma = RK;
+        off += align_up(sizeof(float) * (size_t)RK, 256);
+        l.off_n2 = off;
+    }
+    l.off_L = off;       off += align_up(sizeof(double) * (size_t)RK, 256);
+    l.off_regret = off;  off += align_up(sizeof(double) * (size_t)c->R, 256);
+    l.state_bytes = off;
+    l.off_eta = off;     off += align_up(sizeof(float) * (size_t)c->K, 256);
+    l.off_seg = off;     off += align_up(sizeof(int64_t) * OCO_MAX_SEGMENTS, 256);
+    l.off_Z = off;       off += align_up(sizeof(float) * (size_t)c->R * (c->K + 1) * align_up(n_max, 64), 256);
+    l.total = off;
+    *lay = l;
+    return OCO_OK;
+}
+
+}  // namespace
+
+struct oco_state {
+    oco_config cfg;
+    std::vector<double> eta;
+    std::vector<float> eta_f;
+    std::vector<int64_t> seg_start;
+    Layout lay;
+    char *ws = nullptr;
+    hipStream_t stream = nullptr;
+    const float *u_dev = nullptr;
+    int64_t S = 0;
+    int64_t t_done = 0;
+    bool timing = false, timed = false;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+
+    ~oco_state() { for (auto e : ev) if (e) (void)hipEventDestroy(e); }
+    template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
+    ZLayout zlayout() const {
+        const int64_t nz = (int64_t)align_up((size_t)lay.n_max, 64);
+        if (cfg.sparse_nnz > 0) return ZLayout{cfg.K + 1, 1, cfg.R * (cfg.K + 1)};
+        return ZLayout{(cfg.K + 1) * nz, nz, 1};
+    }
+};
+
+extern "C" {
+
+int oco_step_grid(double D, double G, int64_t T, int64_t K, double *out)
+{
+    if (!out || K <= 0 || T <= 0 || !finite_pos(D) || !finite_pos(G)) return OCO_EINVAL;
+    const double base = D / (G * std::sqrt((double)T));
+    for (int64_t i = 0; i < K; ++i) out[i] = std::ldexp(base, (int)i);
+    return OCO_OK;
+}
+
+int64_t oco_paper_num_learners(int64_t T)
+{
+    if (T <= 0) return OCO_EINVAL;
+    return (int64_t)std::ceil(0.5 * std::log2(1.0 + (double)T)) + 1;
+}
+
+size_t oco_workspace_bytes(const oco_config *cfg)
+{
+    Layout l;
+    return validate_and_layout(cfg, &l) == OCO_OK ? l.total : 0;
+}
+
+int oco_reset(oco_state *st)
+{
+    if (!st) return OCO_EINVAL;
+    hipError_t e = launch_init_state(st->at<void>(st->lay.off_V), st->lay.state_bytes,
+                                     st->at<void>(st->lay.off_sigma), st->lay.n_sigma,
+                                     st->cfg.sparse_nnz > 0, st->stream);
+    if (e != hipSuccess) return OCO_EHIP;
+    st->t_done = 0;
+    return OCO_OK;
+}
+
+int oco_create(const oco_config *cfg, void *dev_ws, size_t ws_bytes, void *hip_stream, oco_state **out)
+{
+    if (!out) return OCO_EINVAL;
+    *out = nullptr;
+    Layout l;
+    int rc = validate_and_layout(cfg, &l);
+    if (rc != OCO_OK) return rc;
+    if (!dev_ws || (reinterpret_cast<uintptr_t>(dev_ws) & 255u)) return OCO_EINVAL;
+    if (ws_bytes < l.total) return OCO_ENOMEM;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return OCO_EHIP;
+
+    oco_state *st = new (std::nothrow) oco_state();
+    if (!st) return OCO_ENOMEM;
+    st->cfg = *cfg;
+    st->eta.assign(cfg->eta, cfg->eta + cfg->K);
+    st->eta_f.resize(cfg->K);
+    for (int64_t i = 0; i < cfg->K; ++i) st->eta_f[i] = (float)cfg->eta[i];
+    st->cfg.eta = st->eta.data();
+    st->lay = l;
+    st->ws = static_cast<char *>(dev_ws);
+    st->stream = static_cast<hipStream_t>(hip_stream);
+
+    if (hipMemcpyAsync(st->at<float>(l.off_eta), st->eta_f.data(), sizeof(float) * cfg->K,
+                       hipMemcpyHostToDevice, st->stream) != hipSuccess) {
+        delete st;
+        return OCO_EHIP;
+    }
+    rc = oco_reset(st);
+    if (rc != OCO_OK) { delete st; return rc; }
+    *out = st;
+    return OCO_OK;
+}
+
+int oco_set_comparator(oco_state *st, const float *u_dev, const int64_t *seg_start_host, int64_t S)
+{
+    if (!st || !u_dev || !seg_start_host || S <= 0) return OCO_EINVAL;
+    if (S > OCO_MAX_SEGMENTS) return OCO_ERANGE;
+    if (reinterpret_cast<uintptr_t>(u_dev) & 15u) return OCO_EINVAL;
+    if (seg_start_host[0] != 0) return OCO_EINVAL;
+    for (int64_t s = 1; s < S; ++s)
+        if (seg_start_host[s] <= seg_start_host[s - 1]) return OCO_EINVAL;
+    st->seg_start.assign(seg_start_host, seg_start_host + S);
+    if (hipMemcpyAsync(st->at<int64_t>(st->lay.off_seg), st->seg_start.data(), sizeof(int64_t) * S,
+                       hipMemcpyHostToDevice, st->stream) != hipSuccess)
+        return OCO_EHIP;
+    // the host vector may be reassigned by a later call: make sure the copy has left it
+    if (hipStreamSynchronize(st->stream) != hipSuccess) return OCO_EHIP;
+    st->u_dev = u_dev;
+    st->S = S;
+    return OCO_OK;
+}
+
+int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
+{
+    if (!st || !rd || n < 0 || t0 < 0) return OCO_EINVAL;
+    if (t0 != st->t_done) return OCO_ESEQ;
+    if (t0 + n > st->cfg.T || n > st->lay.n_max) return OCO_ERANGE;
+    if (!st->u_dev) return OCO_ENOCOMP;
+    if (n == 0) return OCO_OK;
+    const oco_config &c = st->cfg;
+    const bool sparse = c.sparse_nnz > 0;
+    if (sparse ? (!rd->col || !rd->val) : !rd->x) return OCO_EINVAL;
+    if (c.loss != OCO_LINEAR && !rd->y) return OCO_EINVAL;
+    if (rd->x_run_stride < 0 || rd->y_run_stride < 0) return OCO_EINVAL;
+    const int64_t xrs = rd->x_run_stride ? rd->x_run_stride : n * c.d;
+    const int64_t yrs = rd->y_run_stride ? rd->y_run_stride : n;
+    if (!sparse && !c.x_shared && xrs < n * c.d) return OCO_EINVAL;
+    if (rd->y && yrs < n) return OCO_EINVAL;
+    auto mis = [](const void *p, unsigned a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
+    if (mis(rd->x, 4) || mis(rd->y, 4) || mis(rd->col, 4) || mis(rd->val, 4)) return OCO_EINVAL;
+
+    const Layout &l = st->lay;
+    const ZLayout zl = st->zlayout();
+    hipError_t e;
+    if (st->timing && hipEventRecord(st->ev[0], st->stream) != hipSuccess) return OCO_EHIP;
+    if (sparse) {
+        SparseArgs a{};
+        a.col = rd->col; a.val = rd->val; a.y = rd->y; a.y_run_stride = yrs;
+        a.u = st->u_dev; a.seg_start = st->at<int64_t>(l.off_seg); a.S = (int)st->S;
+        a.V = st->at<float>(l.off_V); a.sigma = st->at<double>(l.off_sigma); a.n2 = st->at<double>(l.off_n2);
+        a.eta = st->at<float>(l.off_eta); a.Z = st->at<float>(l.off_Z); a.zl = zl;
+        a.d = (int)c.d; a.K = (int)c.K; a.R = (int)c.R; a.nnz = c.sparse_nnz; a.RKp = l.RKp;
+        a.t0 = t0; a.n = (int)n; a.D = c.D;
+        e = launch_sparse_rounds(a, c.loss, st->stream);
+    } else {
+        DenseArgs a{};
+        a.x = rd->x; a.x_run_stride = xrs; a.y = rd->y; a.y_run_stride = yrs;
+        a.u = st->u_dev; a.seg_start = st->at<int64_t>(l.off_seg); a.S = (int)st->S;
+        a.V = st->at<float>(l.off_V); a.sigma = st->at<float>(l.off_sigma);
+        a.eta = st->at<float>(l.off_eta); a.Z = st->at<float>(l.off_Z); a.zl = zl;
+        a.d = (int)c.d; a.K = (int)c.K; a.R = (int)c.R; a.t0 = t0; a.n = (int)n; a.D = (float)c.D;
+        a.x_shared = c.x_shared;
+        a.vec_ok = (c.d % 4 == 0) && !mis(rd->x, 16) && (c.x_shared || xrs % 4 == 0);
+        e = launch_dense_rounds(a, c.loss, st->stream);
+    }
+    if (e != hipSuccess) return OCO_EHIP;
+    if (st->timing && hipEventRecord(st->ev[1], st->stream) != hipSuccess) return OCO_EHIP;
+
+    MetaArgs m{};
+    m.Z = st->at<float>(l.off_Z); m.zl = zl; m.y = rd->y; m.y_run_stride = yrs;
+    m.L = st->at<double>(l.off_L); m.regret = st->at<double>(l.off_regret);
+    m.eps = c.eps; m.K = (int)c.K; m.R = (int)c.R; m.n = (int)n;
+    if (launch_meta(m, c.loss, st->stream) != hipSuccess) return OCO_EHIP;
+    if (st->timing) {
+        if (hipEventRecord(st->ev[2], st->stream) != hipSuccess) return OCO_EHIP;
+        st->timed = true;
+    }
+    st->t_done = t0 + n;
+    return OCO_OK;
+}
+
+int oco_regret(oco_state *st, double *out_host)
+{
+    if (!st || !out_host) return OCO_EINVAL;
+    if (hipMemcpyAsync(out_host, st->at<double>(st->lay.off_regret), sizeof(double) * st->cfg.R,
+                       hipMemcpyDeviceToHost, st->stream) != hipSuccess)
+        return OCO_EHIP;
+    return hipStreamSynchronize(st->stream) == hipSuccess ? OCO_OK : OCO_EHIP;
+}
+
+int oco_cum_losses(oco_state *st, double *out_host)
+{
+    if (!st || !out_host) return OCO_EINVAL;
+    if (hipMemcpyAsync(out_host, st->at<double>(st->lay.off_L), sizeof(double) * st->cfg.R * st->cfg.K,
+                       hipMemcpyDeviceToHost, st->stream) != hipSuccess)
+        return OCO_EHIP;
+    return hipStreamSynchronize(st->stream) == hipSuccess ? OCO_OK : OCO_EHIP;
+}
+
+int oco_get_state(oco_state *st, float *W_dev, float *p_dev, float *wbar_dev)
+{
+    if (!st) return OCO_EINVAL;
+    auto mis = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; };
+    if (mis(W_dev) || mis(p_dev) || mis(wbar_dev)) return OCO_EINVAL;
+    ExportArgs a{};
+    a.V = st->at<float>(st->lay.off_V);
+    a.sigma = st->at<void>(st->lay.off_sigma);
+    a.L = st->at<double>(st->lay.off_L);
+    a.eps = st->cfg.eps;
+    a.W = W_dev; a.p = p_dev; a.wbar = wbar_dev;
+    a.d = (int)st->cfg.d; a.K = (int)st->cfg.K; a.R = (int)st->cfg.R; a.RKp = st->lay.RKp;
+    a.sparse = st->cfg.sparse_nnz > 0;
+    return launch_export(a, st->stream) == hipSuccess ? OCO_OK : OCO_EHIP;
+}
+
+int oco_set_timing(oco_state *st, int enable)
+{
+    if (!st) return OCO_EINVAL;
+    if (enable)
+        for (auto &e : st->ev)
+            if (!e && hipEventCreate(&e) != hipSuccess) return OCO_EHIP;
+    st->timing = enable != 0;
+    st->timed = false;
+    return OCO_OK;
+}
+
+int oco_last_timing(oco_state *st, float *ms_host)
+{
+    if (!st || !ms_host || !st->timing || !st->timed) return OCO_EINVAL;
+    if (hipEventSynchronize(st->ev[2]) != hipSuccess) return OCO_EHIP;
+    if (hipEventElapsedTime(&ms_host[0], st->ev[0], st->ev[1]) != hipSuccess) return OCO_EHIP;
+    if (hipEventElapsedTime(&ms_host[1], st->ev[1], st->ev[2]) != hipSuccess) return OCO_EHIP;
+    return OCO_OK;
+}
+
+int64_t oco_rounds_done(const oco_state *st) { return st ? st->t_done : (int64_t)OCO_EINVAL; }
+
+void oco_destroy(oco_state *st) { delete st; }
+
+const char *oco_strerror(int status)
+{
+    switch (status) {
+        case OCO_OK: return "ok";
+        case OCO_EINVAL: return "invalid argument";
+        case OCO_ESEQ: return "t0 does not continue the rounds already consumed";
+        case OCO_ERANGE: return "round range or segment count out of range";
+        case OCO_ENOMEM: return "workspace too small";
+        case OCO_EHIP: return "HIP runtime error";
+        case OCO_ENOCOMP: return "comparator not set";
+        case OCO_EUNSUPPORTED: return "shape not supported by the kernels";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+// Internal declarations shared by the translation units of liboco (host API,
+// dense-round kernel, sparse-round kernel, meta/finalize kernels).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace oco {
+
+constexpr int kWave = 64;          // gfx950 wavefront width
+constexpr float kFoldLo = 0x1p-24f; // lazy scale is folded into the vector outside [lo, hi]
+constexpr float kFoldHi = 0x1p+24f;
+
+// Z holds, for the rounds of one oco_run_rounds call, the prediction
+// z_t^i = <w_t^i, x_t> of every base learner (i < K) and of the comparator
+// (i == K).  Element (r, i, t) lives at Z[r*zs_r + i*zs_i + t*zs_t].
+struct ZLayout {
+    int64_t zs_r, zs_i, zs_t;
+};
+
+// ---- dense rounds -----------------------------------------------------------
+struct DenseArgs {
+    const float *x;          // round stream (or gradient stream for the linear loss)
+    int64_t x_run_stride;    // elements between runs (unused when x_shared)
+    const float *y;          // labels, may be null (linear loss)
+    int64_t y_run_stride;
+    const float *u;          // comparator segments [R][S][d]
+    const int64_t *seg_start;// device copy, [S]
+    int S;
+    float *V;                // [R][K][d]  iterate = sigma * V
+    float *sigma;            // [R][K]
+    const float *eta;        // [K]
+    float *Z;
+    ZLayout zl;
+    int d, K, R;
+    int64_t t0;              // absolute index of the first round of this call
+    int n;                   // rounds in this call
+    float D;
+    int x_shared;
+    int vec_ok;              // rows of x are 16-byte aligned and d % 4 == 0
+};
+hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s);
+bool dense_supported(int64_t d);
+
+// ---- sparse rounds ----------------------------------------------------------
+struct SparseArgs {
+    const int32_t *col;      // [n][nnz]
+    const float *val;        // [n][nnz]
+    const float *y;
+    int64_t y_run_stride;
+    const float *u;          // [R][S][d]
+    const int64_t *seg_start;
+    int S;
+    float *V;                // [d][RKp]: coordinate-major, the R*K learners interleaved
+    double *sigma;           // [RKp]
+    double *n2;              // [RKp]  ||V column||^2
+    const float *eta;        // [K]
+    float *Z;
+    ZLayout zl;
+    int d, K, R, nnz, RKp;
+    int64_t t0;
+    int n;
+    double D;
+};
+hipError_t launch_sparse_rounds(const SparseArgs &a, int loss, hipStream_t s);
+
+// ---- meta learner + regret --------------------------------------------------
+struct MetaArgs {
+    const float *Z;
+    ZLayout zl;
+    const float *y;
+    int64_t y_run_stride;
+    double *L;               // [R][K] cumulative losses, updated in place
+    double *regret;          // [R]
+    double eps;
+    int K, R, n;
+};
+hipError_t launch_meta(const MetaArgs &a, int loss, hipStream_t s);
+
+// ---- state export -----------------------------------------------------------
+struct ExportArgs {
+    const float *V;
+    const void *sigma;       // float [R][K] (dense) or double [RKp] (sparse)
+    const double *L;
+    double eps;
+    float *W, *p, *wbar;     // any may be null
+    int d, K, R, RKp;
+    int sparse;
+};
+hipError_t launch_export(const ExportArgs &a, hipStream_t s);
+
+// fills `bytes` (a multiple of 16) of device memory with zero using a kernel,
+// and sets every sigma to 1
+hipError_t launch_init_state(void *zero_base, size_t zero_bytes, void *sigma, int64_t n_sigma,
+                             int sigma_is_double, hipStream_t s);
+
+}  // namespace oco

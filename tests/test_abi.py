@@ -1,0 +1,100 @@
+"""The C-ABI boundary without a GPU: the library loads, exports every function the header
+declares, and rejects bad arguments on the host before any device work."""
+import ctypes as C
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2603_12617_amd import binding as B
+from paper_2603_12617_amd import workloads as WL
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "oco.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(oco_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_function():
+    names = _declared()
+    assert len(names) >= 12
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(B.EXPORTS)
+
+
+def test_status_strings():
+    seen = {B.strerror(s) for s in range(0, -8, -1)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert B.strerror(-99) == "unknown status"
+
+
+def test_step_grid_and_learner_count():
+    np.testing.assert_allclose(B.oco_step_grid(1.0, 1.0, 10000, 15), WL.step_grid(1.0, 1.0, 10000, 15), rtol=1e-15)
+    np.testing.assert_allclose(B.oco_step_grid(2.0, 4.0, 100, 3), [0.05, 0.1, 0.2], rtol=1e-15)
+    assert [B.oco_paper_num_learners(T) for T in (1000, 10 ** 4, 10 ** 5)] == [6, 8, 10]
+    with pytest.raises(B.OcoError):
+        B.oco_step_grid(0.0, 1.0, 10, 2)
+    with pytest.raises(B.OcoError):
+        B.oco_step_grid(1.0, 1.0, 0, 2)
+
+
+def _cfg(**over):
+    base = dict(d=100, K=3, T=1000, R=4, D=1.0, G=1.0, eta=[0.01, 0.02, 0.04], eps=0.1, loss="squared")
+    base.update(over)
+    return B.make_config(**base)
+
+
+def test_workspace_bytes_is_zero_for_bad_configs():
+    ok, keep = _cfg()
+    assert B.oco_workspace_bytes(ok) > 4 * 4 * 3 * 100
+    for bad in (dict(d=0), dict(K=0), dict(T=0), dict(R=0), dict(D=0.0), dict(D=float("nan")),
+                dict(D=float("inf")), dict(G=-1.0), dict(eps=-0.1), dict(eps=float("nan")),
+                dict(loss=7), dict(eta=[0.1, -0.2, 0.3]), dict(eta=[0.1, float("inf"), 0.3]),
+                dict(n_max=-1), dict(d=4097), dict(K=65, eta=[0.1] * 65),
+                dict(nnz=65, d=1 << 20), dict(nnz=8, d=4), dict(nnz=8, d=1 << 20, x_shared=False)):
+        cfg, keep = _cfg(**bad)
+        assert B.oco_workspace_bytes(cfg) == 0, bad
+    cfg, keep = _cfg()
+    cfg.reserved = 1
+    assert B.oco_workspace_bytes(cfg) == 0
+    assert B.lib().oco_workspace_bytes(None) == 0
+
+
+def test_workspace_grows_with_the_call_size_and_covers_the_state():
+    small, k1 = _cfg(n_max=64)
+    big, k2 = _cfg(n_max=0)
+    assert B.oco_workspace_bytes(small) < B.oco_workspace_bytes(big)
+    c5, k3 = _cfg(d=1 << 20, K=8, R=16, T=100000, eta=[0.1] * 8, nnz=32, n_max=1000)
+    assert B.oco_workspace_bytes(c5) >= 4 * (1 << 20) * 128          # the 512 MB iterate block
+
+
+def test_create_rejects_bad_arguments_on_the_host():
+    L = B.lib()
+    cfg, keep = _cfg()
+    need = B.oco_workspace_bytes(cfg)
+    h = C.c_void_p()
+    assert L.oco_create(C.byref(cfg), 256, need, None, None) == B.OCO_EINVAL
+    assert L.oco_create(None, 256, need, None, C.byref(h)) == B.OCO_EINVAL
+    assert L.oco_create(C.byref(cfg), None, need, None, C.byref(h)) == B.OCO_EINVAL
+    assert L.oco_create(C.byref(cfg), 264, need, None, C.byref(h)) == B.OCO_EINVAL      # misaligned
+    assert L.oco_create(C.byref(cfg), 256, need - 1, None, C.byref(h)) == B.OCO_ENOMEM
+    bad, keep2 = _cfg(d=4097)
+    assert L.oco_create(C.byref(bad), 256, 1 << 40, None, C.byref(h)) == B.OCO_EUNSUPPORTED
+    assert h.value is None
+    # NULL handles are rejected, not dereferenced
+    assert L.oco_run_rounds(None, None, 0, 0) == B.OCO_EINVAL
+    assert L.oco_regret(None, None) == B.OCO_EINVAL
+    assert L.oco_get_state(None, None, None, None) == B.OCO_EINVAL
+    assert L.oco_set_comparator(None, None, None, 1) == B.OCO_EINVAL
+    assert L.oco_reset(None) == B.OCO_EINVAL
+    assert L.oco_set_timing(None, 1) == B.OCO_EINVAL
+    assert L.oco_last_timing(None, None) == B.OCO_EINVAL
+    assert L.oco_rounds_done(None) == B.OCO_EINVAL
+    L.oco_destroy(None)
