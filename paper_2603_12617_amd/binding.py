@@ -12,7 +12,8 @@ from typing import Optional, Sequence
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "liboco.so")
+# OCO_LIB overrides the library path (to try a differently tuned build of the same sources)
+LIB_PATH = os.environ.get("OCO_LIB") or os.path.join(HERE, "liboco.so")
 
 OCO_OK, OCO_EINVAL, OCO_ESEQ, OCO_ERANGE, OCO_ENOMEM, OCO_EHIP, OCO_ENOCOMP, OCO_EUNSUPPORTED = (
     0, -1, -2, -3, -4, -5, -6, -7)

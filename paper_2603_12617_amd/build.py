@@ -28,12 +28,14 @@ def sources_newer_than_lib() -> bool:
     return any(os.path.getmtime(f) > t for f in files)
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
+def build(verbose: bool = False, extra_flags=(), lib: str = LIB, tag: str = "") -> str:
+    """Compile and link.  `extra_flags`/`lib`/`tag` build a variant (e.g. other tile
+    shapes via -DOCO_CFG64=...) next to the default library."""
     os.makedirs(OBJ, exist_ok=True)
     cc = _hipcc()
 
     def one(src):
-        obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+        obj = os.path.join(OBJ, src.replace(".hip", tag + ".o"))
         cmd = [cc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0 or verbose:
@@ -44,12 +46,12 @@ def build(verbose: bool = False, extra_flags=()) -> str:
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(one, SOURCES))
-    cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
         raise RuntimeError("link failed")
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

@@ -7,8 +7,9 @@
 // reductions (DPP) and no learner ever waits for another -- each base learner
 // steps along the gradient at its own iterate.  One extra wavefront per run
 // carries the comparator u_t and only takes inner products.  The wavefronts of
-// a workgroup share the round stream: x is staged through LDS in tiles of RT
-// rounds, double buffered, one barrier per tile.
+// a workgroup share the round stream: x is copied from global memory straight
+// into an LDS ring of three tiles of RT rounds (global_load_lds, no staging
+// registers), two tiles ahead of the compute, one barrier per tile.
 //
 // One pass over the registers per round.  The iterate is kept as w = sigma*v
 // with a per-learner scalar sigma, so the projection onto the ball only
@@ -17,43 +18,52 @@
 //     nrm    =  ||v||^2                            (for the projection)
 //     q      =  <v, x_{t+1}>                       (next round's prediction)
 // then sigma <- D/||v|| if sigma ||v|| > D, and z_{t+1} = sigma q.  x_{t+1} is
-// read from LDS during the pass and stays in registers as the next round's x_t.
-// sigma is folded back into v, at the start of a round, once it has left
-// [2^-24, 2^24].
+// read from LDS during the pass, one chunk ahead of the arithmetic, and stays
+// in registers as the next round's x_t (two register sets that swap roles, the
+// round loop is unrolled by two).  sigma is folded back into v, at the start of
+// a round, once it has left [2^-24, 2^24].
 //
 // The kernel writes z_t^i for every round to Z; losses, Hedge weights and
 // regret are computed from Z by the meta kernel.
 #include "oco_internal.h"
 
+#include <cstdlib>
+
 namespace oco {
 namespace {
 
 template <int NPL> struct DenseCfg;
-// NPL: coordinates per lane.  WPB: wavefronts per workgroup.  RT: rounds per LDS tile.
-template <> struct DenseCfg<1>  { static constexpr int WPB = 4,  RT = 63; };
-template <> struct DenseCfg<2>  { static constexpr int WPB = 16, RT = 31; };
-template <> struct DenseCfg<4>  { static constexpr int WPB = 8,  RT = 31; };
-template <> struct DenseCfg<8>  { static constexpr int WPB = 8,  RT = 15; };
-template <> struct DenseCfg<16> { static constexpr int WPB = 8,  RT = 7; };
-template <> struct DenseCfg<32> { static constexpr int WPB = 8,  RT = 3; };
-template <> struct DenseCfg<64> { static constexpr int WPB = 8,  RT = 2; };
+// NPL: coordinates per lane.  MAXW: most wavefronts per workgroup (sets the register
+// budget).  RT: rounds per LDS tile (even; RT*NPL a multiple of 4).
+template <> struct DenseCfg<1>  { static constexpr int MAXW = 16, RT = 32; };
+template <> struct DenseCfg<2>  { static constexpr int MAXW = 16, RT = 16; };
+template <> struct DenseCfg<4>  { static constexpr int MAXW = 16, RT = 16; };
+template <> struct DenseCfg<8>  { static constexpr int MAXW = 16, RT = 8; };
+template <> struct DenseCfg<16> { static constexpr int MAXW = 16, RT = 2; };
+template <> struct DenseCfg<32> { static constexpr int MAXW = 8,  RT = 4; };
+template <> struct DenseCfg<64> { static constexpr int MAXW = 8,  RT = 2; };
+constexpr int kRing = 3;   // LDS tiles
 
 template <int VW> struct VecT;
 template <> struct VecT<1> { using type = float; };
 template <> struct VecT<2> { using type = float2; };
 template <> struct VecT<4> { using type = float4; };
 
-__device__ __forceinline__ float dpp_add(float v, const int ctrl_tag);
+template <int VW> __device__ __forceinline__ void unpack(const typename VecT<VW>::type &t, float (&o)[VW])
+{
+    if constexpr (VW == 4) { o[0] = t.x; o[1] = t.y; o[2] = t.z; o[3] = t.w; }
+    else if constexpr (VW == 2) { o[0] = t.x; o[1] = t.y; }
+    else { o[0] = t; }
+}
 
-// Sum over the 64 lanes, result broadcast to the whole wavefront.  Fixed
-// order: xor-butterfly inside each row of 16 lanes, then rows 0+1 and 2+3,
-// then the two halves.
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_term(float v)
 {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
 }
 
+// Sum over the 64 lanes, result uniform.  Fixed order: xor-butterfly inside each row of
+// 16 lanes, then rows 0+1 and 2+3, then the two halves.
 __device__ __forceinline__ float wave_sum(float v)
 {
     v += dpp_term<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
@@ -65,12 +75,14 @@ __device__ __forceinline__ float wave_sum(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
 template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
 {
     if (LOSS == 0) return 1.0f;
     if (LOSS == 1) return 2.0f * (z - y);
-    // logistic: -y / (1 + exp(y z)); exp overflow gives -y/inf = 0
-    return -y / (1.0f + expf(y * z));
+    // logistic: -y / (1 + exp(y z)); exp overflow gives -y * (1/inf) = -0
+    return -y * fast_rcp(1.0f + __expf(y * z));
 }
 
 template <int VW> __device__ __forceinline__ float combine(const float (&acc)[VW])
@@ -81,7 +93,7 @@ template <int VW> __device__ __forceinline__ float combine(const float (&acc)[VW
 }
 
 template <int NPL, int LOSS>
-__global__ void __launch_bounds__(DenseCfg<NPL>::WPB * kWave)
+__global__ void __launch_bounds__(DenseCfg<NPL>::MAXW * kWave)
 dense_rounds_kernel(const DenseArgs a)
 {
     using C = DenseCfg<NPL>;
@@ -89,198 +101,238 @@ dense_rounds_kernel(const DenseArgs a)
     constexpr int NV = NPL / VW;                // LDS reads per lane and round
     constexpr int DP = NPL * kWave;             // padded dimension
     constexpr int RT = C::RT;
-    constexpr int NT = C::WPB * kWave;
-    constexpr int TILE = (RT + 1) * DP;         // floats per LDS buffer (one look-ahead round)
-    constexpr int TILE4 = TILE / 4;
-    constexpr int PF = (TILE4 + NT - 1) / NT;   // float4 prefetch registers per thread
+    constexpr int TILE = RT * DP;               // floats per tile
+    constexpr int RING_ROUNDS = kRing * RT;
+    constexpr int NI = TILE / 4 / kWave;        // 1 KB copy instructions per tile
+    constexpr int CH = NV >= 2 ? 2 : 1;         // LDS reads per chunk
+    constexpr int NCH = NV / CH;
+    static_assert(TILE % (4 * kWave) == 0, "tile must be a whole number of 1 KB copies");
+    static_assert(RT % 2 == 0, "the round loop is unrolled by two");
     using V = typename VecT<VW>::type;
 
     extern __shared__ float4 smem4[];
-    float *xs = reinterpret_cast<float *>(smem4);
+    float *ring = reinterpret_cast<float *>(smem4);
 
     const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int wpb = nthreads >> 6;              // wavefronts in this workgroup
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = a.n;
     const int d = a.d;
     const int K = a.K;
 
-    // which (run, learner) this wavefront owns; learner K is the comparator
+    // ---- which task this wavefront owns: learner i < K, or the comparator (i == K) ----
     int r, i;
     bool active;
     if (a.x_shared) {
-        const int64_t q = (int64_t)blockIdx.x * C::WPB + wave;
+        const int64_t q = (int64_t)blockIdx.x * wpb + wave;
         active = q < (int64_t)a.R * (K + 1);
         r = active ? (int)(q / (K + 1)) : 0;
         i = active ? (int)(q % (K + 1)) : 0;
     } else {
         r = blockIdx.y;
-        i = blockIdx.x * C::WPB + wave;
+        i = blockIdx.x * wpb + wave;
         active = i <= K;
         if (!active) i = 0;
     }
+    const bool is_cmp = active && i == K;
     const float *xg = a.x_shared ? a.x : a.x + (int64_t)blockIdx.y * a.x_run_stride;
 
-    // ---- cooperative staging of x: tile k holds rounds k*RT .. k*RT+RT -----
-    float4 pf[PF];
-    auto issue = [&](int k) {
-#pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int e = p * NT + tid;
-            const int rr = e / (DP / 4), j4 = e % (DP / 4);
-            const int tt = k * RT + rr;
-            const bool ok = e < TILE4 && tt < n && j4 * 4 < d;
-            pf[p] = ok ? reinterpret_cast<const float4 *>(xg + (int64_t)tt * d)[j4]
-                       : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    };
-    auto commit = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int e = p * NT + tid;
-            if (e < TILE4) reinterpret_cast<float4 *>(xs + buf * TILE)[e] = pf[p];
-        }
-    };
-    auto stage_scalar = [&](int k, int buf) {   // any d, any alignment
-        for (int e = tid; e < TILE; e += NT) {
-            const int rr = e / DP, j = e % DP;
-            const int tt = k * RT + rr;
-            xs[buf * TILE + e] = (tt < n && j < d) ? xg[(int64_t)tt * d + j] : 0.f;
+    // ---- staging of x: tile k = rounds k*RT .. k*RT+RT-1 -> ring slot k % 3 ------
+    auto issue_tile = [&](int k) {
+        float *dst = ring + (k % kRing) * TILE;
+        if (a.vec_ok) {
+            for (int ii = wave; ii < NI; ii += wpb) {
+                const int e = ii * kWave + lane;               // float4 index in the tile
+                const int rr = e / (DP / 4), j4 = e % (DP / 4);
+                const int tt = k * RT + rr;
+                if (tt < n && j4 * 4 < d)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(xg + (int64_t)tt * d + j4 * 4),
+                        (__attribute__((address_space(3))) void *)(dst + ii * 4 * kWave), 16, 0, 0);
+            }
+        } else {                                               // any d, any alignment
+            for (int e = tid; e < TILE; e += nthreads) {
+                const int rr = e / DP, j = e % DP;
+                const int tt = k * RT + rr;
+                if (tt < n && j < d) dst[e] = xg[(int64_t)tt * d + j];
+            }
         }
     };
 
+    // padding coordinates (j >= d) of the ring are never written again: zero them once
+    for (int e = tid; e < kRing * TILE / 4; e += nthreads) smem4[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
     const int ntiles = (n + RT - 1) / RT;
-    if (a.vec_ok) { issue(0); commit(0); } else { stage_scalar(0, 0); }
+    issue_tile(0);
+    if (ntiles > 1) issue_tile(1);
     __syncthreads();
 
-    // ---- per-wavefront state -------------------------------------------------
-    float wv[NV][VW];      // v: iterate / sigma (or the comparator)
-    float xc[NV][VW];      // x_t of the current round
-    float sigma = 1.f, eta = 0.f, z = 0.f;
-    float zreg = 0.f, yreg = 0.f;
-    const bool is_cmp = (i == K);
-    int seg = 0;
-    int64_t next_seg = INT64_MAX;     // absolute round at which the comparator changes
-    float *zrow = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)i * a.zl.zs_i;
+    auto xrow = [&](int t) { return reinterpret_cast<const V *>(ring + (t % RING_ROUNDS) * DP); };
     const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
 
-    auto load_vec = [&](const float *src) {     // src: d floats in global memory
-#pragma unroll
-        for (int m = 0; m < NV; ++m)
-#pragma unroll
-            for (int e = 0; e < VW; ++e) {
-                const int j = (m * kWave + lane) * VW + e;
-                wv[m][e] = j < d ? src[j] : 0.f;
-            }
-    };
-    auto read_x = [&](const float *row, float (&dst)[NV][VW]) {
-#pragma unroll
-        for (int m = 0; m < NV; ++m) {
-            const V t = reinterpret_cast<const V *>(row)[m * kWave + lane];
-            if constexpr (VW == 4) { dst[m][0] = t.x; dst[m][1] = t.y; dst[m][2] = t.z; dst[m][3] = t.w; }
-            else if constexpr (VW == 2) { dst[m][0] = t.x; dst[m][1] = t.y; }
-            else { dst[m][0] = t; }
+    // Each role runs its own copy of the tile loop (same number of barriers in each), so
+    // that the register-resident vector of one role never meets another role's code.
+    if (!active) {
+        for (int k = 0; k < ntiles; ++k) {
+            if (k + 2 < ntiles) issue_tile(k + 2);
+            __syncthreads();
         }
-    };
-    auto dot_xc = [&]() {
-        float acc[VW];
-#pragma unroll
-        for (int e = 0; e < VW; ++e) acc[e] = 0.f;
-#pragma unroll
-        for (int m = 0; m < NV; ++m)
-#pragma unroll
-            for (int e = 0; e < VW; ++e) acc[e] = fmaf(wv[m][e], xc[m][e], acc[e]);
-        return wave_sum(combine<VW>(acc));
-    };
-
-    if (active) {
-        if (is_cmp) {
-            while (seg + 1 < a.S && a.seg_start[seg + 1] <= a.t0) ++seg;
-            next_seg = seg + 1 < a.S ? a.seg_start[seg + 1] : INT64_MAX;
-            load_vec(a.u + ((int64_t)r * a.S + seg) * d);
-        } else {
-            load_vec(a.V + ((int64_t)r * K + i) * d);
-            sigma = a.sigma[(int64_t)r * K + i];
-            eta = a.eta[i];
-        }
-        read_x(xs, xc);                 // x_0
-        z = sigma * dot_xc();           // z_0 = <w_0, x_0>
+        return;
     }
 
-    const float D = a.D;
-    const float D2 = D * D;
-
-    for (int k = 0; k < ntiles; ++k) {
-        const bool more = k + 1 < ntiles;
-        if (more && a.vec_ok) issue(k + 1);
-        const float *tile = xs + (k & 1) * TILE;
-        if (active) {
-            for (int rr = 0; rr < RT; ++rr) {
-                const int t = k * RT + rr;
-                if (t >= n) break;
-                if ((t & 63) == 0 && yrow) yreg = (t + lane < n) ? yrow[t + lane] : 0.f;
-                // record z_t
-                if (lane == (t & 63)) zreg = z;
-                const float *xnext = tile + (rr + 1) * DP;
-                if (is_cmp) {
-                    // comparator: no step; switch segment when the next round starts one
-                    if (a.t0 + t + 1 == next_seg) {
-                        ++seg;
-                        next_seg = seg + 1 < a.S ? a.seg_start[seg + 1] : INT64_MAX;
-                        load_vec(a.u + ((int64_t)r * a.S + seg) * d);
-                    }
-                    read_x(xnext, xc);
-                    z = dot_xc();
-                } else {
-                    // fold sigma into v first (never between computing z and using it, so
-                    // that z is the same whether or not a call boundary falls here)
-                    if (sigma < kFoldLo || sigma > kFoldHi) {
+    if (is_cmp) {
+        // ---- comparator wavefront: z_t = <u_t, x_t>, no step -----------------------------
+        float uv[NV][VW];
+        auto load_u = [&](int sg) {
+            const float *src = a.u + ((int64_t)r * a.S + sg) * d;
 #pragma unroll
-                        for (int m = 0; m < NV; ++m)
+            for (int m = 0; m < NV; ++m)
 #pragma unroll
-                            for (int e = 0; e < VW; ++e) wv[m][e] *= sigma;
-                        sigma = 1.f;
-                    }
-                    const float yt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(yreg), t & 63));
-                    const float c = slope<LOSS>(z, yt);
-                    const float b = (eta * c) / sigma;
-                    float an[VW], aq[VW];
-#pragma unroll
-                    for (int e = 0; e < VW; ++e) { an[e] = 0.f; aq[e] = 0.f; }
-#pragma unroll
-                    for (int m = 0; m < NV; ++m) {
-                        const V xn = reinterpret_cast<const V *>(xnext)[m * kWave + lane];
-                        float xnv[VW];
-                        if constexpr (VW == 4) { xnv[0] = xn.x; xnv[1] = xn.y; xnv[2] = xn.z; xnv[3] = xn.w; }
-                        else if constexpr (VW == 2) { xnv[0] = xn.x; xnv[1] = xn.y; }
-                        else { xnv[0] = xn; }
-#pragma unroll
-                        for (int e = 0; e < VW; ++e) {
-                            const float w1 = fmaf(-b, xc[m][e], wv[m][e]);
-                            wv[m][e] = w1;
-                            an[e] = fmaf(w1, w1, an[e]);
-                            aq[e] = fmaf(w1, xnv[e], aq[e]);
-                            xc[m][e] = xnv[e];
-                        }
-                    }
-                    const float nrm = wave_sum(combine<VW>(an));   // ||v||^2
-                    const float q = wave_sum(combine<VW>(aq));     // <v, x_{t+1}>
-                    if (sigma * sigma * nrm > D2) sigma = D / sqrtf(nrm);   // projection
-                    z = sigma * q;
+                for (int e = 0; e < VW; ++e) {
+                    const int j = (m * kWave + lane) * VW + e;
+                    uv[m][e] = j < d ? src[j] : 0.f;
                 }
+        };
+        auto dot_u = [&](const V *xr) {
+            float acc[VW];
+#pragma unroll
+            for (int e = 0; e < VW; ++e) acc[e] = 0.f;
+#pragma unroll
+            for (int m = 0; m < NV; ++m) {
+                float xv[VW];
+                unpack<VW>(xr[m * kWave + lane], xv);
+#pragma unroll
+                for (int e = 0; e < VW; ++e) acc[e] = fmaf(uv[m][e], xv[e], acc[e]);
+                if (NV > 4 && (m & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+            }
+            return wave_sum(combine<VW>(acc));
+        };
+        int seg = 0;
+        while (seg + 1 < a.S && a.seg_start[seg + 1] <= a.t0) ++seg;
+        int64_t next_seg = seg + 1 < a.S ? a.seg_start[seg + 1] : INT64_MAX;   // absolute round
+        load_u(seg);
+        float z = dot_u(xrow(0)), zreg = 0.f;
+        float *zrow = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)K * a.zl.zs_i;
+        for (int k = 0; k < ntiles; ++k) {
+            if (k + 2 < ntiles) issue_tile(k + 2);
+            const int rmax = min(RT, n - k * RT);
+#pragma unroll 1
+            for (int rr = 0; rr < rmax; ++rr) {
+                const int t = k * RT + rr;
+                if (lane == (t & 63)) zreg = z;
+                if (a.t0 + t + 1 == next_seg) {     // the next round starts a new segment
+                    ++seg;
+                    next_seg = seg + 1 < a.S ? a.seg_start[seg + 1] : INT64_MAX;
+                    load_u(seg);
+                }
+                z = dot_u(xrow(t + 1));
                 if ((t & 63) == 63 || t == n - 1) {
                     const int tb = t & ~63;
                     if (tb + lane <= t) zrow[(int64_t)(tb + lane) * a.zl.zs_t] = zreg;
                 }
             }
+            __syncthreads();
         }
-        if (more) {
-            if (a.vec_ok) commit((k + 1) & 1); else stage_scalar(k + 1, (k + 1) & 1);
-        }
-        __syncthreads();
+        return;
     }
 
-    if (active && !is_cmp) {
+    // ---- learner wavefront ---------------------------------------------------------------
+    float wv[NV][VW];           // v = iterate / sigma
+    float xa[NV][VW], xb[NV][VW];   // x_t / x_{t+1}, swapping roles every round
+    float sigma = a.sigma[(int64_t)r * K + i];
+    const float eta = a.eta[i];
+    float z, zreg = 0.f, yreg = 0.f;
+    {
+        const float *src = a.V + ((int64_t)r * K + i) * d;
+        float acc[VW];
+#pragma unroll
+        for (int e = 0; e < VW; ++e) acc[e] = 0.f;
+#pragma unroll
+        for (int m = 0; m < NV; ++m) {
+            unpack<VW>(xrow(0)[m * kWave + lane], xa[m]);
+#pragma unroll
+            for (int e = 0; e < VW; ++e) {
+                const int j = (m * kWave + lane) * VW + e;
+                wv[m][e] = j < d ? src[j] : 0.f;
+                acc[e] = fmaf(wv[m][e], xa[m][e], acc[e]);
+                xb[m][e] = 0.f;
+            }
+        }
+        z = sigma * wave_sum(combine<VW>(acc));       // z_0 = <w_0, x_0>
+    }
+
+    const float D = a.D;
+    const float D2 = D * D;
+    float *zrow = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)i * a.zl.zs_i;
+
+    // one round: consumes xc = x_t, fills xn = x_{t+1}
+    auto round = [&](int t, float (&xc)[NV][VW], float (&xn)[NV][VW]) {
+        if ((t & 63) == 0 && yrow) yreg = (t + lane < n) ? yrow[t + lane] : 0.f;
+        const float yt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(yreg), t & 63));
+        if (lane == (t & 63)) zreg = z;
+        // fold sigma into v first (never between computing z and using it, so that z is
+        // the same whether or not a call boundary falls here)
+        if (sigma < kFoldLo || sigma > kFoldHi) {
+#pragma unroll
+            for (int m = 0; m < NV; ++m)
+#pragma unroll
+                for (int e = 0; e < VW; ++e) wv[m][e] *= sigma;
+            sigma = 1.f;
+        }
+        const float b = (eta * slope<LOSS>(z, yt)) * fast_rcp(sigma);
+        const V *xr = xrow(t + 1);
+        float an[VW], aq[VW];
+#pragma unroll
+        for (int e = 0; e < VW; ++e) { an[e] = 0.f; aq[e] = 0.f; }
+#pragma unroll
+        for (int j = 0; j < CH; ++j) unpack<VW>(xr[j * kWave + lane], xn[j]);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if (c + 1 < NCH) {
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    const int m = (c + 1) * CH + j;
+                    unpack<VW>(xr[m * kWave + lane], xn[m]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                const int m = c * CH + j;
+#pragma unroll
+                for (int e = 0; e < VW; ++e) {
+                    const float w1 = fmaf(-b, xc[m][e], wv[m][e]);
+                    wv[m][e] = w1;
+                    an[e] = fmaf(w1, w1, an[e]);
+                    aq[e] = fmaf(w1, xn[m][e], aq[e]);
+                }
+            }
+            if (NCH > 2) __builtin_amdgcn_sched_barrier(0);
+        }
+        const float nrm = wave_sum(combine<VW>(an));    // ||v||^2
+        const float q = wave_sum(combine<VW>(aq));      // <v, x_{t+1}>
+        if (sigma * sigma * nrm > D2) sigma = D * __builtin_amdgcn_rsqf(nrm);   // projection
+        z = sigma * q;
+        if ((t & 63) == 63 || t == n - 1) {              // flush the z of rounds (t & ~63) .. t
+            const int tb = t & ~63;
+            if (tb + lane <= t) zrow[(int64_t)(tb + lane) * a.zl.zs_t] = zreg;
+        }
+    };
+
+    for (int k = 0; k < ntiles; ++k) {
+        if (k + 2 < ntiles) issue_tile(k + 2);
+        const int rmax = min(RT, n - k * RT);
+#pragma unroll 1
+        for (int rr = 0; rr < rmax; rr += 2) {
+            const int t = k * RT + rr;
+            round(t, xa, xb);
+            if (rr + 1 < rmax) round(t + 1, xb, xa);
+        }
+        __syncthreads();   // tile k+1 (and k+2) have landed; tile k may be overwritten
+    }
+
+    {
         float *dst = a.V + ((int64_t)r * K + i) * d;
 #pragma unroll
         for (int m = 0; m < NV; ++m)
@@ -297,15 +349,7 @@ template <int NPL>
 hipError_t launch_npl(const DenseArgs &a, int loss, hipStream_t s)
 {
     using C = DenseCfg<NPL>;
-    const size_t smem = sizeof(float) * 2 * (C::RT + 1) * NPL * kWave;
-    dim3 grid;
-    if (a.x_shared) {
-        const int64_t tasks = (int64_t)a.R * (a.K + 1);
-        grid = dim3((unsigned)((tasks + C::WPB - 1) / C::WPB), 1, 1);
-    } else {
-        grid = dim3((unsigned)((a.K + 1 + C::WPB - 1) / C::WPB), (unsigned)a.R, 1);
-    }
-    const dim3 block(C::WPB * kWave);
+    const size_t smem = sizeof(float) * kRing * C::RT * NPL * kWave;
     void (*kern)(const DenseArgs) = nullptr;
     switch (loss) {
         case 0: kern = dense_rounds_kernel<NPL, 0>; break;
@@ -318,7 +362,44 @@ hipError_t launch_npl(const DenseArgs &a, int loss, hipStream_t s)
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, grid, block, smem, s, a);
+    int dev = 0, ncu = 256;
+    if (hipGetDevice(&dev) == hipSuccess)
+        (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (ncu <= 0) ncu = 256;
+
+    // Wavefronts per workgroup: the value that leaves the least work on the busiest compute
+    // unit.  With c workgroups resident per unit the grid is taken in ceil(nWG / (ncu*c))
+    // batches; a batch puts l = resident*wpb/4 wavefronts on each SIMD and its duration
+    // grows with l as g(l), fitted to sweeps on MI355X: up to about four wavefronts per SIMD
+    // mostly fill each other's stalls (the round is a dependent chain), beyond that they
+    // share the issue slots.
+    auto g = [](double l) { return l <= 1.0 ? 1.0 : (l <= 4.0 ? 1.0 + 0.1 * (l - 1.0) : 1.3 + 0.35 * (l - 4.0)); };
+    const int per_run = a.K + 1;
+    int best = 0;
+    double best_cost = 0.0;
+    for (int w = C::MAXW; w >= 1; --w) {
+        int c = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, reinterpret_cast<const void *>(kern),
+                                                         w * kWave, smem) != hipSuccess || c <= 0)
+            continue;
+        const int64_t nwg = a.x_shared ? ((int64_t)a.R * per_run + w - 1) / w
+                                       : (int64_t)a.R * ((per_run + w - 1) / w);
+        const int64_t batches = (nwg + (int64_t)ncu * c - 1) / ((int64_t)ncu * c);
+        const int64_t resident = nwg < (int64_t)ncu * c ? (nwg + ncu - 1) / ncu : c;   // per unit
+        const double cost = (double)batches * g((double)(resident * w) / 4.0);
+        if (best == 0 || cost < best_cost * (1.0 - 1e-9)) { best = w; best_cost = cost; }
+    }
+    if (const char *ov = getenv("OCO_DENSE_WPB")) {      // tuning override: wavefronts per workgroup
+        const int w = atoi(ov);
+        if (w >= 1 && w <= C::MAXW) best = w;
+    }
+    if (best == 0) return hipErrorInvalidConfiguration;
+    dim3 grid;
+    if (a.x_shared)
+        grid = dim3((unsigned)(((int64_t)a.R * per_run + best - 1) / best), 1, 1);
+    else
+        grid = dim3((unsigned)((per_run + best - 1) / best), (unsigned)a.R, 1);
+    hipLaunchKernelGGL(kern, grid, dim3(best * kWave), smem, s, a);
     return hipGetLastError();
 }
 
