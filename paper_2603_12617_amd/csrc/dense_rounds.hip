@@ -14,10 +14,15 @@
 // One pass over the registers per round.  The iterate is kept as w = sigma*v
 // with a per-learner scalar sigma, so the projection onto the ball only
 // changes sigma.  In round t the pass computes
-//     v      <- v - (eta c_t / sigma) x_t          (gradient step, c_t = phi'(z_t; y_t))
-//     nrm    =  ||v||^2                            (for the projection)
+//     v      <- v - b x_t,  b = eta c_t / sigma    (gradient step, c_t = phi'(z_t; y_t))
 //     q      =  <v, x_{t+1}>                       (next round's prediction)
-// then sigma <- D/||v|| if sigma ||v|| > D, and z_{t+1} = sigma q.  x_{t+1} is
+// and the norm needed by the projection follows from scalars already at hand,
+//     ||v - b x_t||^2 = ||v||^2 - 2 b <v, x_t> + b^2 ||x_t||^2
+// (<v, x_t> is the previous round's q, ||x_t||^2 comes from a small pre-pass
+// over the round stream), carried in float64 and re-measured exactly, as
+// sum_j v_j^2 inside the pass, at every 64th round of the horizon so that
+// rounding cannot accumulate.  Then sigma <- D/||v|| if sigma ||v|| > D, and
+// z_{t+1} = sigma q.  x_{t+1} is
 // read from LDS during the pass, one chunk ahead of the arithmetic, and stays
 // in registers as the next round's x_t (two register sets that swap roles, the
 // round loop is unrolled by two).  sigma is folded back into v, at the start of
@@ -63,15 +68,22 @@ __device__ __forceinline__ float dpp_term(float v)
 }
 
 // Sum over the 64 lanes, result uniform.  Fixed order: xor-butterfly inside each row of
-// 16 lanes, then rows 0+1 and 2+3, then the two halves.
+// 16 lanes, then rows 0+1 and 2+3, then the two halves.  The two cross-row steps are
+// written as v_add_f32 with a DPP row broadcast and a row mask: rows outside the mask keep
+// their value, so one instruction does what mov+mov_dpp+add would.  (A DPP operand needs
+// two wait states after the VALU write that produced it, hence the s_nop.)
 __device__ __forceinline__ float wave_sum(float v)
 {
     v += dpp_term<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
     v += dpp_term<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
     v += dpp_term<0x141, 0xF>(v);   // row_half_mirror
     v += dpp_term<0x140, 0xF>(v);   // row_mirror
-    v += dpp_term<0x142, 0xA>(v);   // row_bcast15 into rows 1 and 3
-    v += dpp_term<0x143, 0xC>(v);   // row_bcast31 into rows 2 and 3
+    asm("s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"   // rows 1, 3 += row 0, 2
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"   // rows 2, 3 += rows 0+1
+        "s_nop 0"
+        : "+v"(v));
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
@@ -242,8 +254,9 @@ dense_rounds_kernel(const DenseArgs a)
     float wv[NV][VW];           // v = iterate / sigma
     float xa[NV][VW], xb[NV][VW];   // x_t / x_{t+1}, swapping roles every round
     float sigma = a.sigma[(int64_t)r * K + i];
+    double n2 = a.n2[(int64_t)r * K + i];       // ||v||^2
     const float eta = a.eta[i];
-    float z, zreg = 0.f, yreg = 0.f;
+    float qv, z, zreg = 0.f, yreg = 0.f, x2reg = 0.f;   // qv = <v, x_t>, z = sigma qv
     {
         const float *src = a.V + ((int64_t)r * K + i) * d;
         float acc[VW];
@@ -260,32 +273,20 @@ dense_rounds_kernel(const DenseArgs a)
                 xb[m][e] = 0.f;
             }
         }
-        z = sigma * wave_sum(combine<VW>(acc));       // z_0 = <w_0, x_0>
+        qv = wave_sum(combine<VW>(acc));
+        z = sigma * qv;                               // z_0 = <w_0, x_0>
     }
+    const float *x2row = a.x2 + (a.x_shared ? 0 : (int64_t)r * a.x2_run_stride);
+    const int phase = (int)(a.t0 & 63);               // exact norms at absolute rounds = 63 mod 64
 
     const float D = a.D;
     const float D2 = D * D;
     float *zrow = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)i * a.zl.zs_i;
 
-    // one round: consumes xc = x_t, fills xn = x_{t+1}
-    auto round = [&](int t, float (&xc)[NV][VW], float (&xn)[NV][VW]) {
-        if ((t & 63) == 0 && yrow) yreg = (t + lane < n) ? yrow[t + lane] : 0.f;
-        const float yt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(yreg), t & 63));
-        if (lane == (t & 63)) zreg = z;
-        // fold sigma into v first (never between computing z and using it, so that z is
-        // the same whether or not a call boundary falls here)
-        if (sigma < kFoldLo || sigma > kFoldHi) {
+    // the pass over the registers: step and next-round dot
+    auto pass = [&](float b, const V *xr, float (&xc)[NV][VW], float (&xn)[NV][VW], float (&aq)[VW]) {
 #pragma unroll
-            for (int m = 0; m < NV; ++m)
-#pragma unroll
-                for (int e = 0; e < VW; ++e) wv[m][e] *= sigma;
-            sigma = 1.f;
-        }
-        const float b = (eta * slope<LOSS>(z, yt)) * fast_rcp(sigma);
-        const V *xr = xrow(t + 1);
-        float an[VW], aq[VW];
-#pragma unroll
-        for (int e = 0; e < VW; ++e) { an[e] = 0.f; aq[e] = 0.f; }
+        for (int e = 0; e < VW; ++e) aq[e] = 0.f;
 #pragma unroll
         for (int j = 0; j < CH; ++j) unpack<VW>(xr[j * kWave + lane], xn[j]);
 #pragma unroll
@@ -304,16 +305,54 @@ dense_rounds_kernel(const DenseArgs a)
                 for (int e = 0; e < VW; ++e) {
                     const float w1 = fmaf(-b, xc[m][e], wv[m][e]);
                     wv[m][e] = w1;
-                    an[e] = fmaf(w1, w1, an[e]);
                     aq[e] = fmaf(w1, xn[m][e], aq[e]);
                 }
             }
             if (NCH > 2) __builtin_amdgcn_sched_barrier(0);
         }
-        const float nrm = wave_sum(combine<VW>(an));    // ||v||^2
-        const float q = wave_sum(combine<VW>(aq));      // <v, x_{t+1}>
+    };
+
+    // one round: consumes xc = x_t, fills xn = x_{t+1}
+    auto round = [&](int t, float (&xc)[NV][VW], float (&xn)[NV][VW]) {
+        if ((t & 63) == 0) {
+            if (yrow) yreg = (t + lane < n) ? yrow[t + lane] : 0.f;
+            x2reg = (t + lane < n) ? x2row[t + lane] : 0.f;
+        }
+        const float yt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(yreg), t & 63));
+        const float x2t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x2reg), t & 63));
+        if (lane == (t & 63)) zreg = z;
+        // fold sigma into v first (never between computing z and using it, so that z is
+        // the same whether or not a call boundary falls here)
+        if (sigma < kFoldLo || sigma > kFoldHi) {
+#pragma unroll
+            for (int m = 0; m < NV; ++m)
+#pragma unroll
+                for (int e = 0; e < VW; ++e) wv[m][e] *= sigma;
+            n2 *= (double)sigma * (double)sigma;
+            qv = z;
+            sigma = 1.f;
+        }
+        const float b = (eta * slope<LOSS>(z, yt)) * fast_rcp(sigma);
+        float aq[VW];
+        pass(b, xrow(t + 1), xc, xn, aq);
+        if (((phase + t) & 63) == 63) {                  // re-measure ||v||^2 exactly
+            float an[VW];
+#pragma unroll
+            for (int e = 0; e < VW; ++e) an[e] = 0.f;
+#pragma unroll
+            for (int m = 0; m < NV; ++m)
+#pragma unroll
+                for (int e = 0; e < VW; ++e) an[e] = fmaf(wv[m][e], wv[m][e], an[e]);
+            n2 = (double)wave_sum(combine<VW>(an));
+        } else {
+            const double bd = (double)b;
+            n2 = fma(bd * bd, (double)x2t, fma(-2.0 * bd, (double)qv, n2));
+            n2 = n2 > 0.0 ? n2 : 0.0;
+        }
+        qv = wave_sum(combine<VW>(aq));                  // <v, x_{t+1}>
+        const float nrm = (float)n2;                     // ||v||^2
         if (sigma * sigma * nrm > D2) sigma = D * __builtin_amdgcn_rsqf(nrm);   // projection
-        z = sigma * q;
+        z = sigma * qv;
         if ((t & 63) == 63 || t == n - 1) {              // flush the z of rounds (t & ~63) .. t
             const int tb = t & ~63;
             if (tb + lane <= t) zrow[(int64_t)(tb + lane) * a.zl.zs_t] = zreg;
@@ -341,8 +380,23 @@ dense_rounds_kernel(const DenseArgs a)
                 const int j = (m * kWave + lane) * VW + e;
                 if (j < d) dst[j] = wv[m][e];
             }
-        if (lane == 0) a.sigma[(int64_t)r * K + i] = sigma;
+        if (lane == 0) { a.sigma[(int64_t)r * K + i] = sigma; a.n2[(int64_t)r * K + i] = n2; }
     }
+}
+
+// ||x_t||^2 of every round row: one wavefront per row, fixed summation order.
+__global__ void __launch_bounds__(256) xnorm2_kernel(const float *x, int64_t run_stride, int nruns,
+                                                     int n, int d, float *out, int64_t out_stride)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= (int64_t)nruns * n) return;
+    const int rr = (int)(row / n), t = (int)(row % n);
+    const float *src = x + (int64_t)rr * run_stride + (int64_t)t * d;
+    float acc = 0.f;
+    for (int j = lane; j < d; j += 64) acc = fmaf(src[j], src[j], acc);
+    const float tot = wave_sum(acc);
+    if (lane == 0) out[(int64_t)rr * out_stride + t] = tot;
 }
 
 template <int NPL>
@@ -410,6 +464,14 @@ bool dense_supported(int64_t d) { return d >= 1 && d <= 64 * kWave; }
 hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s)
 {
     if (a.n <= 0) return hipSuccess;
+    {
+        const int nruns = a.x_shared ? 1 : a.R;
+        const int64_t rows = (int64_t)nruns * a.n;
+        hipLaunchKernelGGL(xnorm2_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a.x,
+                           a.x_shared ? 0 : a.x_run_stride, nruns, a.n, a.d, a.x2, a.x2_run_stride);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     const int npl = (a.d + kWave - 1) / kWave;
     if (npl <= 1) return launch_npl<1>(a, loss, s);
     if (npl <= 2) return launch_npl<2>(a, loss, s);

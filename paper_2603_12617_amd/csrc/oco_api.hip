@@ -16,7 +16,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
     size_t off_V = 0, off_sigma = 0, off_n2 = 0, off_L = 0, off_regret = 0, off_eta = 0,
-           off_seg = 0, off_Z = 0, total = 0;
+           off_seg = 0, off_Z = 0, off_X2 = 0, total = 0;
     size_t state_bytes = 0;   // [off_V, off_V + state_bytes) is zeroed by reset (V, sigma, n2, L, regret)
     int64_t n_sigma = 0;
     int RKp = 0;
@@ -64,6 +64,7 @@ int validate_and_layout(const oco_config *c, Layout *lay)
         l.off_sigma = off; l.n_sigma = RK;
         off += align_up(sizeof(float) * (size_t)RK, 256);
         l.off_n2 = off;
+        off += align_up(sizeof(double) * (size_t)RK, 256);
     }
     l.off_L = off;       off += align_up(sizeof(double) * (size_t)RK, 256);
     l.off_regret = off;  off += align_up(sizeof(double) * (size_t)c->R, 256);
@@ -71,6 +72,10 @@ int validate_and_layout(const oco_config *c, Layout *lay)
     l.off_eta = off;     off += align_up(sizeof(float) * (size_t)c->K, 256);
     l.off_seg = off;     off += align_up(sizeof(int64_t) * OCO_MAX_SEGMENTS, 256);
     l.off_Z = off;       off += align_up(sizeof(float) * (size_t)c->R * (c->K + 1) * align_up(n_max, 64), 256);
+    if (c->sparse_nnz == 0) {
+        l.off_X2 = off;
+        off += align_up(sizeof(float) * (size_t)(c->x_shared ? 1 : c->R) * align_up(n_max, 64), 256);
+    }
     l.total = off;
     *lay = l;
     return OCO_OK;
@@ -224,6 +229,8 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
         a.x = rd->x; a.x_run_stride = xrs; a.y = rd->y; a.y_run_stride = yrs;
         a.u = st->u_dev; a.seg_start = st->at<int64_t>(l.off_seg); a.S = (int)st->S;
         a.V = st->at<float>(l.off_V); a.sigma = st->at<float>(l.off_sigma);
+        a.n2 = st->at<double>(l.off_n2); a.x2 = st->at<float>(l.off_X2);
+        a.x2_run_stride = (int64_t)align_up((size_t)l.n_max, 64);
         a.eta = st->at<float>(l.off_eta); a.Z = st->at<float>(l.off_Z); a.zl = zl;
         a.d = (int)c.d; a.K = (int)c.K; a.R = (int)c.R; a.t0 = t0; a.n = (int)n; a.D = (float)c.D;
         a.x_shared = c.x_shared;

@@ -29,6 +29,9 @@ struct DenseArgs {
     int S;
     float *V;                // [R][K][d]  iterate = sigma * V
     float *sigma;            // [R][K]
+    double *n2;              // [R][K]  ||V row||^2
+    float *x2;               // scratch: ||x_t||^2 per round of this call, [n] or [R][x2_run_stride]
+    int64_t x2_run_stride;
     const float *eta;        // [K]
     float *Z;
     ZLayout zl;
