@@ -222,7 +222,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
         a.V = st->at<float>(l.off_V); a.sigma = st->at<double>(l.off_sigma); a.n2 = st->at<double>(l.off_n2);
         a.eta = st->at<float>(l.off_eta); a.Z = st->at<float>(l.off_Z); a.zl = zl;
         a.d = (int)c.d; a.K = (int)c.K; a.R = (int)c.R; a.nnz = c.sparse_nnz; a.RKp = l.RKp;
-        a.t0 = t0; a.n = (int)n; a.D = c.D;
+        a.t0 = t0; a.n = (int)n; a.D = c.D; a.prefetch = 1;
         e = launch_sparse_rounds(a, c.loss, st->stream);
     } else {
         DenseArgs a{};

@@ -64,6 +64,7 @@ struct SparseArgs {
     int64_t t0;
     int n;
     double D;
+    int prefetch;            // 1: second wavefront warms L2 ahead of the rounds
 };
 hipError_t launch_sparse_rounds(const SparseArgs &a, int loss, hipStream_t s);
 
