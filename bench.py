@@ -118,6 +118,8 @@ def main():
     ap.add_argument("--config", default="c4", choices=sorted(DESCR))
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run a plain 1 GiB device copy three times (calibrates HBM byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this path runs on ONE GPU (runs are independent and would shard with no "
@@ -132,6 +134,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+
+    if a.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4}))
+        return 0
 
     keep = {}
     main_res = run_workload(a.config, a.steps, a.warmup, WL, B, torch, keep)
