@@ -16,7 +16,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
     size_t off_V = 0, off_sigma = 0, off_n2 = 0, off_L = 0, off_regret = 0, off_eta = 0,
-           off_seg = 0, off_Z = 0, off_X2 = 0, total = 0;
+           off_seg = 0, off_Z = 0, off_X2 = 0, off_gram = 0, total = 0;
     size_t state_bytes = 0;   // [off_V, off_V + state_bytes) is zeroed by reset (V, sigma, n2, L, regret)
     int64_t n_sigma = 0;
     int RKp = 0;
@@ -75,6 +75,9 @@ int validate_and_layout(const oco_config *c, Layout *lay)
     if (c->sparse_nnz == 0) {
         l.off_X2 = off;
         off += align_up(sizeof(float) * (size_t)(c->x_shared ? 1 : c->R) * align_up(n_max, 64), 256);
+    } else {
+        l.off_gram = off;
+        off += align_up(sparse_scratch_bytes(n_max), 256);
     }
     l.total = off;
     *lay = l;
@@ -223,6 +226,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
         a.eta = st->at<float>(l.off_eta); a.Z = st->at<float>(l.off_Z); a.zl = zl;
         a.d = (int)c.d; a.K = (int)c.K; a.R = (int)c.R; a.nnz = c.sparse_nnz; a.RKp = l.RKp;
         a.t0 = t0; a.n = (int)n; a.D = c.D; a.prefetch = 1;
+        a.scratch = st->at<char>(l.off_gram);
         e = launch_sparse_rounds(a, c.loss, st->stream);
     } else {
         DenseArgs a{};

@@ -64,9 +64,11 @@ struct SparseArgs {
     int64_t t0;
     int n;
     double D;
-    int prefetch;            // 1: second wavefront warms L2 ahead of the rounds
+    int prefetch;            // 1: idle wavefronts warm L2 with the next window's rows
+    void *scratch;           // sparse_scratch_bytes(n_max) bytes: per-window Gram data of the call
 };
 hipError_t launch_sparse_rounds(const SparseArgs &a, int loss, hipStream_t s);
+size_t sparse_scratch_bytes(int64_t n_max);
 
 // ---- meta learner + regret --------------------------------------------------
 struct MetaArgs {

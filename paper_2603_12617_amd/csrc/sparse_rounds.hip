@@ -17,13 +17,23 @@
 // the per-learner scalar work (slope, step, norm, projection) runs
 // lane-parallel with no reduction.
 //
-// The path is a dependent chain of T rounds per learner, so what matters is
-// the latency of one round.  A workgroup is two wavefronts: the first runs the
-// rounds; the second only reads, a bounded number of rounds ahead, one word of
-// every 128-byte line the first will need, so that the gathers hit in L2
-// instead of waiting for HBM.  Column indices and values of a round are one
-// vector load (lane j holds entry j) issued two rounds early and broadcast
-// with v_readlane.
+// Taking memory out of the chain.  The path is a dependent chain of T rounds
+// per learner; a round that gathers from and scatters to HBM costs two memory
+// round trips (on gfx9 loads and stores of one wavefront share a counter and
+// return out of order, so every gather has to drain the previous scatters).
+// In v-space the step is linear, v_t = v_s - sum_{s<=r<t} b_r x_r, hence inside
+// a window of 64 rounds
+//     <v_t, x_t> = <v_window_start, x_t> - sum_{r<t in window} b_r <x_r, x_t>.
+// Per window the kernel therefore runs three phases:
+//   A  all wavefronts: q0_t = <v_start, x_t> for the 64 rounds (bulk gathers);
+//   B  one wavefront: the 64 dependent rounds on scalars and LDS only
+//      (prediction, slope, step size b_t, norm, projection); the Gram terms
+//      <x_r, x_t> come from a pre-pass over the round stream and are almost
+//      all zero (two sparse rows rarely share a column); meanwhile the other
+//      wavefronts pull the next window's rows into L2;
+//   C  all wavefronts: V[col] += -b_t x_t[col] as no-return float atomics, the
+//      entries split over wavefronts by column so that the adds to one address
+//      are issued by one wavefront in round order (bitwise reproducible).
 //
 // The comparator's predictions <u_t, x_t> do not depend on the learners and
 // are taken by a separate, fully parallel kernel (one thread per run-round).
@@ -33,15 +43,18 @@
 // into v now and then: V[:, q] *= sigma_q, ||v||^2 *= sigma_q^2, sigma_q = 1.
 // The rounds are launched in segments that end at every 2048th round of the
 // horizon; after each segment a grid-wide kernel folds the 64-learner column
-// groups whose smallest sigma has dropped below 2^-20 (a streaming pass at HBM
-// speed, and a no-op otherwise).  Should a sigma fall below 2^-60 inside a
-// segment (steps many orders of magnitude larger than the ball), the working
-// wavefront folds its own columns in place, slowly but safely.  All fold
-// decisions depend on the state and the absolute round index only, so results
-// do not depend on how the horizon is cut into calls.
+// groups whose smallest sigma has dropped below 2^-64 (a streaming pass at HBM
+// speed, and a no-op otherwise).  Should a sigma fall below 2^-100 inside a
+// segment (steps many orders of magnitude larger than the ball), the chain
+// wavefront folds its own columns in place, slowly but safely.  Windows are
+// aligned to multiples of 64 rounds of the horizon and all fold decisions
+// depend on the state and the absolute round index only.
 #include "oco_internal.h"
+#include <stddef.h>
+#include <stdlib.h>
+#include "../../include/oco.h"
 
-#include <cstdlib>
+#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
 
 namespace oco {
 namespace {
@@ -53,145 +66,351 @@ template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
     return -y * __builtin_amdgcn_rcpf(1.0f + __expf(y * z));
 }
 
-constexpr double kSparseFoldLo = 0x1p-60;    // in-kernel emergency fold
-constexpr double kSparseFoldSoft = 0x1p-20;  // fold between segments
+// V is updated by float atomics, which execute in L2: every read of V in the window kernel
+// goes to L2 as well (a device-scope relaxed load never hits in the per-CU cache).
+__device__ __forceinline__ float ldv(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Workgroup barrier that first waits for every global access of this wavefront (loads,
+// stores, no-return atomics) to be acknowledged.
+__device__ __forceinline__ void wg_sync()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
+
+#ifndef OCO_FOLD_LO
+#define OCO_FOLD_LO 0x1p-100
+#define OCO_FOLD_SOFT 0x1p-64
+#endif
+constexpr double kSparseFoldLo = OCO_FOLD_LO;    // in-kernel emergency fold
+constexpr double kSparseFoldSoft = OCO_FOLD_SOFT;  // fold between segments
 constexpr int kSegment = 2048;               // rounds per launch segment (absolute alignment)
-constexpr int kPrefetchAhead = 48;   // rounds the reading wavefront may run ahead
-constexpr int kPrefetchBatch = 16;   // rounds whose lines it requests before waiting
+constexpr int kWin = 64;                     // rounds per window (absolute alignment)
+constexpr int kSpWaves = 16;                 // wavefronts per workgroup
 
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_term(float v)
+// Pre-pass over the round stream, one workgroup per window of the launch:
+// G[s][t] = <x_s, x_t> for s < t, mask[s] = bit t set iff rounds s and t share a column,
+// X2[t] = ||x_t||^2.  Window w of the launch covers rounds [wstart(w), wstart(w+1)).
+struct WinPlan {
+    int64_t t0;      // absolute round of the launch's first round
+    int n;           // rounds in the launch
+    __host__ __device__ int first_len() const { const int f = (int)(kWin - t0 % kWin); return f < n ? f : n; }
+    __host__ __device__ int count() const { const int f = first_len(); return 1 + (n - f + kWin - 1) / kWin; }
+    __host__ __device__ int start(int w) const { return w == 0 ? 0 : first_len() + (w - 1) * kWin; }
+    __host__ __device__ int len(int w) const { const int s = start(w); const int l = w == 0 ? first_len() : kWin; return l < n - s ? l : n - s; }
+};
+
+// What the pre-pass leaves per window for the rounds kernel.
+struct WinRec {
+    float x2[kWin];                     // ||x_t||^2
+    unsigned long long mask[kWin];      // bit t of mask[s]: rounds s < t share a column
+    int off[kSpWaves + 1];              // phase C: wavefront c owns perm[off[c] .. off[c+1])
+    int ng;                             // number of set mask bits
+    int pad[32 - kSpWaves - 2];
+    unsigned short perm[kWin * OCO_MAX_NNZ];   // entries of the window sorted by column (stable)
+    float g[kWin * (kWin - 1) / 2];     // <x_s, x_t> of the set mask bits, in (s, t) order
+};
+static_assert(sizeof(WinRec) % 256 == 0, "window records stay 256-byte aligned");
+constexpr int kRecHeadInts = (int)(offsetof(WinRec, perm) / 4);
+
+__global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, const float *val, int nnz,
+                                                          WinPlan plan, WinRec *recs)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+    __shared__ int cs[kWin * OCO_MAX_NNZ];
+    __shared__ float vs[kWin * OCO_MAX_NNZ];
+    __shared__ unsigned long long key[kWin * OCO_MAX_NNZ];      // (column, position)
+    __shared__ unsigned short sorted[kWin * OCO_MAX_NNZ];
+    __shared__ unsigned int mk[kWin][2];
+    __shared__ int rowoff[kWin + 1];
+    __shared__ unsigned short pair_s[kWin * (kWin - 1) / 2], pair_t[kWin * (kWin - 1) / 2];
+    const int w = blockIdx.x;
+    const int ws = plan.start(w), wl = plan.len(w);
+    const int total = wl * nnz;
+    const unsigned mdiv = ((1u << 18) + nnz - 1) / nnz;       // e / nnz == (e * mdiv) >> 18 for e < 4096
+    WinRec &rec = recs[w];
+    for (int e = threadIdx.x; e < total; e += blockDim.x) {
+        const int c = col[(int64_t)ws * nnz + e];
+        cs[e] = c;
+        vs[e] = val[(int64_t)ws * nnz + e];
+        key[e] = ((unsigned long long)(unsigned)c << 12) | (unsigned)e;
+    }
+    for (int e = threadIdx.x; e < kWin * 2; e += blockDim.x) mk[e >> 1][e & 1] = 0u;
+    __syncthreads();
+    // rank of every entry under the order (column, position): a stable sort by column
+    for (int e = threadIdx.x; e < total; e += blockDim.x) {
+        const unsigned long long ke = key[e];
+        int rank = 0;
+        for (int f = 0; f < total; ++f) rank += key[f] < ke ? 1 : 0;
+        sorted[rank] = (unsigned short)e;
+    }
+    if (threadIdx.x < kWin) {
+        float acc = 0.f;
+        if (threadIdx.x < wl)
+            for (int a = 0; a < nnz; ++a) acc = fmaf(vs[threadIdx.x * nnz + a], vs[threadIdx.x * nnz + a], acc);
+        rec.x2[threadIdx.x] = acc;
+    }
+    __syncthreads();
+    // rounds that share a column sit next to each other in the sorted order
+    for (int k = threadIdx.x; k < total; k += blockDim.x) {
+        const int e = sorted[k];
+        rec.perm[k] = (unsigned short)e;
+        const int c = cs[e];
+        const int s = (int)(((unsigned)e * mdiv) >> 18);
+        for (int k2 = k + 1; k2 < total && cs[sorted[k2]] == c; ++k2) {
+            const int t = (int)(((unsigned)sorted[k2] * mdiv) >> 18);
+            if (t > s) atomicOr(&mk[s][t >> 5], 1u << (t & 31));
+        }
+    }
+    if (threadIdx.x <= kSpWaves) {
+        // equal shares of the sorted entries, cut only where the column changes
+        int k = (int)((int64_t)threadIdx.x * total / kSpWaves);
+        while (k > 0 && k < total && cs[sorted[k]] == cs[sorted[k - 1]]) ++k;
+        rec.off[threadIdx.x] = k;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int acc = 0;
+        for (int s2 = 0; s2 < kWin; ++s2) {
+            rowoff[s2] = acc;
+            acc += __popc(mk[s2][0]) + __popc(mk[s2][1]);
+        }
+        rowoff[kWin] = acc;
+        rec.ng = acc;
+    }
+    __syncthreads();
+    if (threadIdx.x < kWin) {
+        const int s2 = threadIdx.x;
+        unsigned long long m = (unsigned long long)mk[s2][0] | ((unsigned long long)mk[s2][1] << 32);
+        rec.mask[s2] = m;
+        int o = rowoff[s2];
+        while (m) {
+            const int t = __builtin_ctzll(m);
+            m &= m - 1;
+            pair_s[o] = (unsigned short)s2;
+            pair_t[o] = (unsigned short)t;
+            ++o;
+        }
+    }
+    __syncthreads();
+    // <x_s, x_t> of the pairs that share a column, each by one thread in a fixed order
+    const int ng = rowoff[kWin];
+    for (int o = threadIdx.x; o < ng; o += blockDim.x) {
+        const int s2 = pair_s[o], t = pair_t[o];
+        float g = 0.f;
+        for (int a = 0; a < nnz; ++a) {
+            const int ca = cs[s2 * nnz + a];
+            for (int b = 0; b < nnz; ++b)
+                if (cs[t * nnz + b] == ca) g = fmaf(vs[s2 * nnz + a], vs[t * nnz + b], g);
+        }
+        rec.g[o] = g;
+    }
 }
 
-__device__ __forceinline__ float wave_sum(float v)     // fixed order, result uniform
+__device__ __forceinline__ int bcast_i(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
+__device__ __forceinline__ float bcast_f(float v, int l)
 {
-    v += dpp_term<0xB1, 0xF>(v);
-    v += dpp_term<0x4E, 0xF>(v);
-    v += dpp_term<0x141, 0xF>(v);
-    v += dpp_term<0x140, 0xF>(v);
-    v += dpp_term<0x142, 0xA>(v);
-    v += dpp_term<0x143, 0xC>(v);
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
 }
 
-// NZ: compile-time bound on the entries per round (nnz <= NZ <= 64)
-template <int NZ, int LOSS>
-__global__ void __launch_bounds__(2 * kWave) sparse_rounds_kernel(const SparseArgs a)
+// LDS of the rounds kernel that is staged per window (two copies: the next window is
+// staged while the dependent rounds of the current one run)
+struct WinStage {
+    int cw[kWin * OCO_MAX_NNZ];
+    float vw[kWin * OCO_MAX_NNZ];
+    int head[kRecHeadInts];                      // x2 | mask | off | ng
+    unsigned int perm2[kWin * OCO_MAX_NNZ / 2];
+    float gl[kWin * (kWin - 1) / 2];
+};
+
+__device__ __forceinline__ void stage_window(WinStage &st, const SparseArgs &a, const WinRec &rec, int ws, int total,
+                                             int tid, int nthr)
 {
-    __shared__ int progress;                 // rounds finished by the first wavefront
+    const int ng = rec.ng;
+    const int nnz = a.nnz;
+    for (int e = tid; e < total; e += nthr) {
+        st.cw[e] = a.col[(int64_t)ws * nnz + e];
+        st.vw[e] = a.val[(int64_t)ws * nnz + e];
+    }
+    const int *hsrc = reinterpret_cast<const int *>(&rec);
+    for (int e = tid; e < kRecHeadInts; e += nthr) st.head[e] = hsrc[e];
+    const unsigned int *psrc = reinterpret_cast<const unsigned int *>(rec.perm);
+    for (int e = tid; e < (total + 1) / 2; e += nthr) st.perm2[e] = psrc[e];
+    for (int e = tid; e < ng; e += nthr) st.gl[e] = rec.g[e];
+}
+
+template <int LOSS>
+__global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const SparseArgs a, WinPlan plan, int wbeg, int wend)
+{
+    __shared__ float q0[kWin][kWave];        // <v_start, x_t>, then corrected in place
+    __shared__ float bw[kWin][kWave];        // step sizes b_t of the window
+    __shared__ float yv[kWin][kWave];        // labels
+    __shared__ __align__(16) WinStage stage[2];
+
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nnz = a.nnz;
-    const int n = a.n;
-    const int q0 = blockIdx.x * kWave;       // first learner (column) of this workgroup
-    if (threadIdx.x == 0) progress = 0;
-    __syncthreads();
-
-    if (wave == 1) {
-        if (!a.prefetch) return;
-        // ---- reading wavefront: pull the lines of coming rounds into L2 ---------------
-        const int j = lane & 31, half = lane >> 5;      // entry j (and j+32), first/second line
-        const float *base = a.V + q0 + half * 32;
-        float sink = 0.f;
-        for (int tb = 0; tb < n; tb += kPrefetchBatch) {
-            int spins = 0;
-            while (tb > *(volatile int *)&progress + kPrefetchAhead && ++spins < (1 << 18))
-                __builtin_amdgcn_s_sleep(4);
-            float got[kPrefetchBatch][2];
-#pragma unroll
-            for (int u = 0; u < kPrefetchBatch; ++u) {
-                const int t = tb + u;
-                got[u][0] = got[u][1] = 0.f;
-                if (t < n) {
-                    if (j < nnz) got[u][0] = base[(int64_t)a.col[(int64_t)t * nnz + j] * a.RKp];
-                    if (NZ > 32 && j + 32 < nnz)
-                        got[u][1] = base[(int64_t)a.col[(int64_t)t * nnz + j + 32] * a.RKp];
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < kPrefetchBatch; ++u) sink += got[u][0] + got[u][1];
-        }
-        if (sink == 1.2345e30f) a.Z[0] = sink;          // never true; keeps the loads alive
-        return;
-    }
-
-    // ---- working wavefront: lane = learner q = r*K + i -------------------------------------
+    const unsigned mdiv = ((1u << 18) + nnz - 1) / nnz;       // e / nnz == (e * mdiv) >> 18 for e < 4096
+    const int q = blockIdx.x * kWave + lane;        // learner (column) of this lane
+    const unsigned uq = (unsigned)q;                // zero-extended: scalar row base + 32-bit lane offset
     const int nq = a.R * a.K;
-    const int q = q0 + lane;
     const bool valid = q < nq;
     const int qq = valid ? q : 0;
     const int r = qq / a.K, i = qq % a.K;
     const float eta = valid ? a.eta[i] : 0.f;
-    double sigma = a.sigma[q];
-    double n2 = a.n2[q];
-    const double D2 = a.D * a.D;
-    float *Vq = a.V + q;                             // column of this lane (padded columns exist)
+    float *Vq = a.V + q;
     const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
     float *zrow = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)i * a.zl.zs_i;
+    const double D2 = a.D * a.D;
+    const WinRec *recs = static_cast<const WinRec *>(a.scratch);
+    double sigma = 1.0, n2 = 0.0;
+    if (wave == 0) { sigma = a.sigma[q]; n2 = a.n2[q]; }
+    // Wait for these loads here.  Left to the compiler, the wait lands at their first use inside
+    // the round loop, where it also waits for the previous round's store, every round.
+    float eta_r = eta;
+    asm volatile("" : "+v"(eta_r), "+v"(sigma), "+v"(n2));
 
-    // entries of a round, lane j = entry j; lanes >= nnz repeat entry 0 with value 0
-    const int jl = lane < nnz ? lane : 0;
-    auto load_round = [&](int t, int &c, float &x, float &y) {
-        if (t < n) {
-            c = a.col[(int64_t)t * nnz + jl];
-            x = lane < nnz ? a.val[(int64_t)t * nnz + lane] : 0.f;
-            y = yrow ? yrow[t] : 0.f;
-        } else { c = 0; x = 0.f; y = 0.f; }
-    };
-    int c0, c1, c2;
-    float x0, x1, x2, y0, y1, y2;
-    load_round(0, c0, x0, y0);
-    load_round(1, c1, x1, y1);
-
-    for (int t = 0; t < n; ++t) {
-        // gather the touched coordinates of all 64 learners: NZ coalesced row reads
-        float v[NZ], xv[NZ];
-        int64_t off[NZ];
+    stage_window(stage[0], a, recs[wbeg], plan.start(wbeg), plan.len(wbeg) * nnz, threadIdx.x, blockDim.x);
+    wg_sync();
+    for (int w = wbeg; w < wend; ++w) {
+        WinStage &st = stage[(w - wbeg) & 1];
+        const int *cw = st.cw;
+        const float *vw = st.vw;
+        const float *x2s = reinterpret_cast<const float *>(st.head);
+        const unsigned long long *ms = reinterpret_cast<const unsigned long long *>(st.head + kWin);
+        const int *offs = st.head + kWin + 2 * kWin;
+        const unsigned short *perm = reinterpret_cast<const unsigned short *>(st.perm2);
+        const float *gl = st.gl;
+        const int ws = plan.start(w), wl = plan.len(w);
+        // ---- A: q0_t = <v_start, x_t>, rounds dealt to the wavefronts, two at a time --------
+        // (a lane fetches one entry of the round; the column and value reach the others by readlane)
+        for (int t = wave; t < wl && !(a.prefetch & 2); t += 2 * kSpWaves) {
+            const int tb = t + kSpWaves;
+            const bool hb = tb < wl;
+            const int tbc = hb ? tb : t;
+            const int la = lane < nnz ? lane : nnz - 1;
+            const int ca = cw[t * nnz + la], cb = cw[tbc * nnz + la];
+            const float xa = vw[t * nnz + la], xb = vw[tbc * nnz + la];
+            float accA[4] = {0.f, 0.f, 0.f, 0.f}, accB[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int j0 = 0; j0 < nnz; j0 += 32) {
+                float va[32], vb[32];
 #pragma unroll
-        for (int j = 0; j < NZ; ++j) {
-            off[j] = (int64_t)__builtin_amdgcn_readlane(c0, j) * a.RKp;
-            xv[j] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x0), j));
-            v[j] = Vq[off[j]];
-        }
-        load_round(t + 2, c2, x2, y2);                 // stream, two rounds early
-        const float X2 = wave_sum(x0 * x0);            // ||x_t||^2 (lanes >= nnz hold 0)
-
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+                for (int u = 0; u < 32; ++u) {
+                    const int j = j0 + u < nnz ? j0 + u : nnz - 1;
+                    va[u] = ldv(a.V + (int64_t)bcast_i(ca, j) * a.RKp + uq);
+                    vb[u] = ldv(a.V + (int64_t)bcast_i(cb, j) * a.RKp + uq);
+                }
 #pragma unroll
-        for (int j = 0; j < NZ; ++j) acc[j & 3] = fmaf(v[j], xv[j], acc[j & 3]);
-        const float qv = (acc[0] + acc[1]) + (acc[2] + acc[3]);      // <v, x_t>
-        const float sf = (float)sigma;
-        const float z = sf * qv;
-        if (valid) zrow[(int64_t)t * a.zl.zs_t] = z;
-        const float b = (eta * slope<LOSS>(z, y0)) * __builtin_amdgcn_rcpf(sf);
-#pragma unroll
-        for (int j = 0; j < NZ; ++j)
-            if (j < nnz) Vq[off[j]] = fmaf(-b, xv[j], v[j]);
-
-        const double bd = (double)b;
-        n2 = fma(bd * bd, (double)X2, fma(-2.0 * bd, (double)qv, n2));
-        n2 = n2 > 0.0 ? n2 : 0.0;
-        if (sigma * sigma * n2 > D2) sigma = a.D * rsqrt(n2);                        // projection
-        if (__any(sigma < kSparseFoldLo)) {
-            // fold sigma into the columns of this wavefront and re-measure ||v||^2
-            const float s = (float)sigma;
-            double m2 = 0.0;
-            for (int64_t j = 0; j < a.d; ++j) {
-                const float w = Vq[j * a.RKp] * s;
-                Vq[j * a.RKp] = w;
-                m2 += (double)w * (double)w;
+                for (int u = 0; u < 32; ++u) {
+                    const bool in = j0 + u < nnz;
+                    const int j = in ? j0 + u : nnz - 1;
+                    const float sa = in ? bcast_f(xa, j) : 0.f, sb = in ? bcast_f(xb, j) : 0.f;
+                    accA[u & 3] = fmaf(va[u], sa, accA[u & 3]);
+                    accB[u & 3] = fmaf(vb[u], sb, accB[u & 3]);
+                }
             }
-            n2 = m2;
-            sigma = 1.0;
+            q0[t][lane] = (accA[0] + accA[1]) + (accA[2] + accA[3]);
+            yv[t][lane] = yrow ? yrow[ws + t] : 0.f;
+            if (hb) {
+                q0[tb][lane] = (accB[0] + accB[1]) + (accB[2] + accB[3]);
+                yv[tb][lane] = yrow ? yrow[ws + tb] : 0.f;
+            }
         }
-        if (lane == 0) *(volatile int *)&progress = t + 1;
-        c0 = c1; x0 = x1; y0 = y1;
-        c1 = c2; x1 = x2; y1 = y2;
+        wg_sync();
+        // ---- B: the dependent rounds, scalars and LDS only (wavefront 0) ---------------------
+        if (wave == 0) {
+            int gp = 0;                                          // next Gram value of the window
+            float qn = q0[0][lane], yn = yv[0][lane], x2n = x2s[0];
+            unsigned long long mn = ms[0];
+            for (int t = 0; t < wl && !(a.prefetch & 8); ++t) {
+                const float qv = qn, yy = yn, x2 = x2n;          // <v_t, x_t>, y_t, ||x_t||^2
+                const unsigned long long mt = mn;                // later rounds sharing a column
+                const int tn = t + 1 < wl ? t + 1 : t;
+                qn = q0[tn][lane]; yn = yv[tn][lane]; x2n = x2s[tn]; mn = ms[tn];   // next round, early
+                const float sf = (float)sigma;
+                const float z = sf * qv;
+                if (valid) zrow[(int64_t)(ws + t) * a.zl.zs_t] = z;
+                const float b = (eta_r * slope<LOSS>(z, yy)) * __builtin_amdgcn_rcpf(sf);
+                bw[t][lane] = b;
+                // (readfirstlane returns int: go through unsigned, or the low word sign-extends)
+                unsigned long long m =
+                    (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)mt) |
+                    ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(mt >> 32)) << 32);
+                if (m) {
+                    const bool next_hit = (m >> tn) & 1;
+                    while (m) {
+                        const int t2 = __builtin_ctzll(m);
+                        m &= m - 1;
+                        q0[t2][lane] = fmaf(-b, gl[gp++], q0[t2][lane]);
+                    }
+                    if (next_hit) qn = q0[tn][lane];
+                }
+                const double bd = (double)b;
+                n2 = fma(bd * bd, (double)x2, fma(-2.0 * bd, (double)qv, n2));
+                n2 = n2 > 0.0 ? n2 : 0.0;
+                if (sigma * sigma * n2 > D2) sigma = a.D * rsqrt(n2);      // projection
+                if (__any(sigma < kSparseFoldLo)) {
+                    // emergency fold.  v = v_start - sum_{r<=t} b_r x_r is not in memory yet:
+                    // apply the window's steps so far, fold, and restart the window after t.
+                    for (int rr = 0; rr <= t; ++rr)
+                        for (int j = 0; j < nnz; ++j) {
+                            float *p = Vq + (int64_t)cw[rr * nnz + j] * a.RKp;
+                            *p = ldv(p) + (-bw[rr][lane] * vw[rr * nnz + j]);
+                        }
+                    const float s = (float)sigma;
+                    double m2 = 0.0;
+                    for (int64_t j = 0; j < a.d; ++j) {
+                        const float wv = ldv(Vq + j * a.RKp) * s;
+                        Vq[j * a.RKp] = wv;
+                        m2 += (double)wv * (double)wv;
+                    }
+                    n2 = m2;
+                    sigma = 1.0;
+                    for (int rr = 0; rr <= t; ++rr) bw[rr][lane] = 0.f;      // already applied
+                    for (int t2 = t + 1; t2 < wl; ++t2) {                     // fresh <v, x_t2>
+                        float acc = 0.f;
+                        for (int j = 0; j < nnz; ++j)
+                            acc = fmaf(ldv(Vq + (int64_t)cw[t2 * nnz + j] * a.RKp), vw[t2 * nnz + j], acc);
+                        q0[t2][lane] = acc;
+                    }
+                    qn = q0[tn][lane];
+                }
+            }
+        } else if (w + 1 < wend) {
+            // ---- meanwhile the other wavefronts stage the next window -------------------------
+            stage_window(stage[(w + 1 - wbeg) & 1], a, recs[w + 1], plan.start(w + 1), plan.len(w + 1) * nnz,
+                         (int)threadIdx.x - kWave, (kSpWaves - 1) * kWave);
+        }
+        wg_sync();
+        // ---- C: V[col] += -b_t x_t[col]; all entries of a column belong to one wavefront ------
+        if (!(a.prefetch & 4)) {
+            const int beg = __builtin_amdgcn_readfirstlane(offs[wave]);
+            const int end = __builtin_amdgcn_readfirstlane(offs[wave + 1]);
+            for (int k0 = beg; k0 < end; k0 += kWave) {
+                const int cnt = end - k0 < kWave ? end - k0 : kWave;
+                const int ee = perm[k0 + (lane < cnt ? lane : cnt - 1)];
+                const int cc = cw[ee];
+                const float xx = vw[ee];
+                const int tt = (int)(((unsigned)ee * mdiv) >> 18);
+                for (int u0 = 0; u0 < cnt; u0 += 8) {
+                    float bb[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int uu = u0 + u < cnt ? u0 + u : cnt - 1;
+                        bb[u] = bw[bcast_i(tt, uu)][lane];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (u0 + u < cnt)
+                            unsafeAtomicAdd(a.V + (int64_t)bcast_i(cc, u0 + u) * a.RKp + uq, -bb[u] * bcast_f(xx, u0 + u));
+                }
+            }
+        }
+        wg_sync();
     }
-    a.sigma[q] = sigma;
-    a.n2[q] = n2;
+    if (wave == 0) { a.sigma[q] = sigma; a.n2[q] = n2; }
 }
 
 // z_u[r][t] = <u_t, x_t>: independent of the learners, one thread per (round, run)
@@ -237,55 +456,51 @@ __global__ void __launch_bounds__(64) sparse_fold_finish_kernel(double *sigma, d
     sigma[q] = 1.0;
 }
 
-template <int NZ>
-hipError_t launch_nz(const SparseArgs &a, int loss, hipStream_t s)
-{
-    const int nblk = (a.R * a.K + kWave - 1) / kWave;
-    switch (loss) {
-        case 0: hipLaunchKernelGGL((sparse_rounds_kernel<NZ, 0>), dim3(nblk), dim3(2 * kWave), 0, s, a); break;
-        case 1: hipLaunchKernelGGL((sparse_rounds_kernel<NZ, 1>), dim3(nblk), dim3(2 * kWave), 0, s, a); break;
-        case 2: hipLaunchKernelGGL((sparse_rounds_kernel<NZ, 2>), dim3(nblk), dim3(2 * kWave), 0, s, a); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
-}
-
 }  // namespace
+
+size_t sparse_scratch_bytes(int64_t n_max)
+{
+    return (size_t)(n_max / kWin + 2) * sizeof(WinRec);
+}
 
 hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s)
 {
     SparseArgs a = a0;
-    if (const char *e = getenv("OCO_SPARSE_PREFETCH")) a.prefetch = atoi(e);
+    a.prefetch = 0;
+    if (const char *dbg = getenv("OCO_SPARSE_DBG")) a.prefetch = atoi(dbg);
     if (a.n <= 0) return hipSuccess;
+    if (a.nnz > OCO_MAX_NNZ) return hipErrorInvalidValue;
     const int64_t nthr = (int64_t)a.n * a.R;
     hipLaunchKernelGGL(sparse_comparator_kernel, dim3((unsigned)((nthr + 255) / 256)), dim3(256), 0, s, a);
+
+    // scratch: one record per window of the call
+    const WinPlan plan{a.t0, a.n};
+    const int nwin = plan.count();
+    hipLaunchKernelGGL(sparse_gram_kernel, dim3(nwin), dim3(256), 0, s, a.col, a.val, a.nnz, plan,
+                       static_cast<WinRec *>(a.scratch));
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+
+    // segments end at the multiples of kSegment of the horizon, which are window boundaries
     const int groups = a.RKp / kWave;
-    for (int done = 0; done < a0.n;) {
-        const int64_t tabs = a0.t0 + done;
-        int len = (int)(kSegment - tabs % kSegment);          // up to the next multiple of kSegment
-        if (len > a0.n - done) len = a0.n - done;
-        SparseArgs g = a;
-        g.col = a.col + (int64_t)done * a.nnz;
-        g.val = a.val + (int64_t)done * a.nnz;
-        g.y = a.y ? a.y + done : nullptr;
-        g.Z = a.Z + (int64_t)done * a.zl.zs_t;
-        g.t0 = tabs;
-        g.n = len;
-        if (a.nnz <= 8) e = launch_nz<8>(g, loss, s);
-        else if (a.nnz <= 16) e = launch_nz<16>(g, loss, s);
-        else if (a.nnz <= 32) e = launch_nz<32>(g, loss, s);
-        else if (a.nnz <= 64) e = launch_nz<64>(g, loss, s);
-        else e = hipErrorInvalidValue;
-        if (e != hipSuccess) return e;
-        done += len;
-        if ((a0.t0 + done) % kSegment == 0) {                 // a segment of the horizon ended
+    for (int wbeg = 0; wbeg < nwin;) {
+        const int64_t seg_end = ((a.t0 + plan.start(wbeg)) / kSegment + 1) * kSegment;   // absolute
+        int wend = wbeg + 1;
+        while (wend < nwin && a.t0 + plan.start(wend) < seg_end) ++wend;
+        switch (loss) {
+            case 0: hipLaunchKernelGGL(sparse_window_kernel<0>, dim3(groups), dim3(kSpWaves * kWave), 0, s, a, plan, wbeg, wend); break;
+            case 1: hipLaunchKernelGGL(sparse_window_kernel<1>, dim3(groups), dim3(kSpWaves * kWave), 0, s, a, plan, wbeg, wend); break;
+            case 2: hipLaunchKernelGGL(sparse_window_kernel<2>, dim3(groups), dim3(kSpWaves * kWave), 0, s, a, plan, wbeg, wend); break;
+            default: return hipErrorInvalidValue;
+        }
+        const int64_t reached = a.t0 + plan.start(wend - 1) + plan.len(wend - 1);
+        if (reached % kSegment == 0) {                        // a segment of the horizon ended
             hipLaunchKernelGGL(sparse_fold_kernel, dim3(1024, groups), dim3(256), 0, s, a.V, a.sigma, a.d, a.RKp);
             hipLaunchKernelGGL(sparse_fold_finish_kernel, dim3(groups), dim3(kWave), 0, s, a.sigma, a.n2);
-            e = hipGetLastError();
-            if (e != hipSuccess) return e;
         }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        wbeg = wend;
     }
     return hipSuccess;
 }
