@@ -104,16 +104,19 @@ struct WinPlan {
 };
 
 // What the pre-pass leaves per window for the rounds kernel.
+struct RoundRec {
+    unsigned long long mask;            // bit t of round s: rounds s < t share a column
+    double x2;                          // ||x_s||^2 (summed in float32)
+};
 struct WinRec {
-    float x2[kWin];                     // ||x_t||^2
-    unsigned long long mask[kWin];      // bit t of mask[s]: rounds s < t share a column
+    RoundRec rr[kWin];
     int off[kSpWaves + 1];              // phase C: wavefront c owns perm[off[c] .. off[c+1])
     int ng;                             // number of set mask bits
     int pad[32 - kSpWaves - 2];
     unsigned short perm[kWin * OCO_MAX_NNZ];   // entries of the window sorted by column (stable)
     float g[kWin * (kWin - 1) / 2];     // <x_s, x_t> of the set mask bits, in (s, t) order
 };
-static_assert(sizeof(WinRec) % 256 == 0, "window records stay 256-byte aligned");
+static_assert(sizeof(WinRec) % 128 == 0, "window records stay 256-byte aligned");
 constexpr int kRecHeadInts = (int)(offsetof(WinRec, perm) / 4);
 
 __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, const float *val, int nnz,
@@ -150,7 +153,7 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
         float acc = 0.f;
         if (threadIdx.x < wl)
             for (int a = 0; a < nnz; ++a) acc = fmaf(vs[threadIdx.x * nnz + a], vs[threadIdx.x * nnz + a], acc);
-        rec.x2[threadIdx.x] = acc;
+        rec.rr[threadIdx.x].x2 = (double)acc;
     }
     __syncthreads();
     // rounds that share a column sit next to each other in the sorted order
@@ -184,7 +187,7 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
     if (threadIdx.x < kWin) {
         const int s2 = threadIdx.x;
         unsigned long long m = (unsigned long long)mk[s2][0] | ((unsigned long long)mk[s2][1] << 32);
-        rec.mask[s2] = m;
+        rec.rr[s2].mask = m;
         int o = rowoff[s2];
         while (m) {
             const int t = __builtin_ctzll(m);
@@ -220,7 +223,7 @@ __device__ __forceinline__ float bcast_f(float v, int l)
 struct WinStage {
     int cw[kWin * OCO_MAX_NNZ];
     float vw[kWin * OCO_MAX_NNZ];
-    int head[kRecHeadInts];                      // x2 | mask | off | ng
+    int head[kRecHeadInts];                      // rr | off | ng (rr[kWin] may be read, never used)
     unsigned int perm2[kWin * OCO_MAX_NNZ / 2];
     float gl[kWin * (kWin - 1) / 2];
 };
@@ -241,20 +244,37 @@ __device__ __forceinline__ void stage_window(WinStage &st, const SparseArgs &a, 
     for (int e = tid; e < ng; e += nthr) st.gl[e] = rec.g[e];
 }
 
-template <int LOSS>
+// 1/sqrt(x) for a finite x > 0: the hardware estimate and one third-order correction
+__device__ __forceinline__ double rsqrt_pos(double x)
+{
+    const double y = __builtin_amdgcn_rsq(x);
+    const double e = fma(-x * y, y, 1.0);
+    return fma(y * e, fma(e, 0.375, 0.5), y);
+}
+
+// A workgroup owns LPW learners (LPW = 64, 32, 16 or 8; fewer learners per workgroup spread a
+// small problem over more compute units).  A wavefront is EPI = 64 / LPW slots of LPW lanes:
+// lane = slot * LPW + learner, and one memory instruction touches EPI rows of V.
+template <int LPW> struct Chain {
+    float q0[kWin + 1][LPW];       // <v_start, x_t>, then corrected in place (row kWin: read ahead only)
+    float yv[kWin + 1][LPW];       // labels
+    float bw[kWin][LPW];           // step sizes b_t of the window
+};
+
+template <int LOSS, int LPW>
 __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const SparseArgs a, WinPlan plan, int wbeg, int wend)
 {
-    __shared__ float q0[kWin][kWave];        // <v_start, x_t>, then corrected in place
-    __shared__ float bw[kWin][kWave];        // step sizes b_t of the window
-    __shared__ float yv[kWin][kWave];        // labels
+    constexpr int EPI = kWave / LPW;
+    __shared__ Chain<LPW> ch;
     __shared__ __align__(16) WinStage stage[2];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l = lane % LPW, e = lane / LPW;       // learner and slot of this lane
     const int nnz = a.nnz;
     const unsigned mdiv = ((1u << 18) + nnz - 1) / nnz;       // e / nnz == (e * mdiv) >> 18 for e < 4096
-    const int q = blockIdx.x * kWave + lane;        // learner (column) of this lane
-    const unsigned uq = (unsigned)q;                // zero-extended: scalar row base + 32-bit lane offset
+    const int q = blockIdx.x * LPW + l;             // learner (column of V) of this lane
+    const unsigned uq = (unsigned)q;
     const int nq = a.R * a.K;
     const bool valid = q < nq;
     const int qq = valid ? q : 0;
@@ -262,15 +282,18 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     const float eta = valid ? a.eta[i] : 0.f;
     float *Vq = a.V + q;
     const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
-    float *zrow = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)i * a.zl.zs_i;
+    const unsigned zoff = (unsigned)(r * a.zl.zs_r + i * a.zl.zs_i);
     const double D2 = a.D * a.D;
     const WinRec *recs = static_cast<const WinRec *>(a.scratch);
+    const bool chain = wave == 0 && lane < LPW;     // the lanes that run the dependent rounds
     double sigma = 1.0, n2 = 0.0;
-    if (wave == 0) { sigma = a.sigma[q]; n2 = a.n2[q]; }
+    if (chain) { sigma = a.sigma[q]; n2 = a.n2[q]; }
     // Wait for these loads here.  Left to the compiler, the wait lands at their first use inside
     // the round loop, where it also waits for the previous round's store, every round.
     float eta_r = eta;
     asm volatile("" : "+v"(eta_r), "+v"(sigma), "+v"(n2));
+    double sd2 = sigma * sigma;
+    float sf = (float)sigma, isf = __builtin_amdgcn_rcpf(sf);
 
     stage_window(stage[0], a, recs[wbeg], plan.start(wbeg), plan.len(wbeg) * nnz, threadIdx.x, blockDim.x);
     wg_sync();
@@ -278,139 +301,180 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         WinStage &st = stage[(w - wbeg) & 1];
         const int *cw = st.cw;
         const float *vw = st.vw;
-        const float *x2s = reinterpret_cast<const float *>(st.head);
-        const unsigned long long *ms = reinterpret_cast<const unsigned long long *>(st.head + kWin);
-        const int *offs = st.head + kWin + 2 * kWin;
+        const RoundRec *rr = reinterpret_cast<const RoundRec *>(st.head);
+        const int *offs = st.head + 4 * kWin;
         const unsigned short *perm = reinterpret_cast<const unsigned short *>(st.perm2);
         const float *gl = st.gl;
         const int ws = plan.start(w), wl = plan.len(w);
-        // ---- A: q0_t = <v_start, x_t>, rounds dealt to the wavefronts, two at a time --------
-        // (a lane fetches one entry of the round; the column and value reach the others by readlane)
-        for (int t = wave; t < wl && !(a.prefetch & 2); t += 2 * kSpWaves) {
-            const int tb = t + kSpWaves;
-            const bool hb = tb < wl;
-            const int tbc = hb ? tb : t;
-            const int la = lane < nnz ? lane : nnz - 1;
-            const int ca = cw[t * nnz + la], cb = cw[tbc * nnz + la];
-            const float xa = vw[t * nnz + la], xb = vw[tbc * nnz + la];
-            float accA[4] = {0.f, 0.f, 0.f, 0.f}, accB[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int j0 = 0; j0 < nnz; j0 += 32) {
-                float va[32], vb[32];
+        // ---- A: q0_t = <v_start, x_t>; a wavefront takes rounds wave, wave + 16, ..., RA at a
+        // time; slot e of the wavefront takes the entries j = e, e + EPI, ... of a round ----------
+        {
+            constexpr int RA = LPW == 64 ? 2 : 4;
+            constexpr int BK = LPW == 64 ? 16 : (LPW == 8 ? 4 : 8);   // RA * BK gathers in flight
+            const int NL = (nnz + EPI - 1) / EPI;
+            for (int tg = wave; tg < wl; tg += RA * kSpWaves) {
+                float acc[RA][4], yl[RA];
 #pragma unroll
-                for (int u = 0; u < 32; ++u) {
-                    const int j = j0 + u < nnz ? j0 + u : nnz - 1;
-                    va[u] = ldv(a.V + (int64_t)bcast_i(ca, j) * a.RKp + uq);
-                    vb[u] = ldv(a.V + (int64_t)bcast_i(cb, j) * a.RKp + uq);
+                for (int ra = 0; ra < RA; ++ra) {
+                    acc[ra][0] = acc[ra][1] = acc[ra][2] = acc[ra][3] = 0.f;
+                    const int t = tg + ra * kSpWaves < wl ? tg + ra * kSpWaves : tg;
+                    yl[ra] = yrow ? yrow[ws + t] : 0.f;             // in flight with the gathers
+                }
+                for (int k0 = 0; k0 < NL; k0 += BK) {
+                    float vv[RA][BK];
+#pragma unroll
+                    for (int ra = 0; ra < RA; ++ra) {
+                        const int t = tg + ra * kSpWaves < wl ? tg + ra * kSpWaves : tg;
+#pragma unroll
+                        for (int u = 0; u < BK; ++u) {
+                            const int j = (k0 + u) * EPI + e;
+                            const bool in = k0 + u < NL && j < nnz;
+                            vv[ra][u] = ldv(a.V + (int64_t)cw[t * nnz + (in ? j : 0)] * a.RKp + uq);
+                        }
+                    }
+#pragma unroll
+                    for (int ra = 0; ra < RA; ++ra) {
+                        const int t = tg + ra * kSpWaves < wl ? tg + ra * kSpWaves : tg;
+#pragma unroll
+                        for (int u = 0; u < BK; ++u) {
+                            const int j = (k0 + u) * EPI + e;
+                            const bool in = k0 + u < NL && j < nnz;
+                            const float xv = in ? vw[t * nnz + (in ? j : 0)] : 0.f;
+                            acc[ra][u & 3] = fmaf(vv[ra][u], xv, acc[ra][u & 3]);
+                        }
+                    }
                 }
 #pragma unroll
-                for (int u = 0; u < 32; ++u) {
-                    const bool in = j0 + u < nnz;
-                    const int j = in ? j0 + u : nnz - 1;
-                    const float sa = in ? bcast_f(xa, j) : 0.f, sb = in ? bcast_f(xb, j) : 0.f;
-                    accA[u & 3] = fmaf(va[u], sa, accA[u & 3]);
-                    accB[u & 3] = fmaf(vb[u], sb, accB[u & 3]);
+                for (int ra = 0; ra < RA; ++ra) {
+                    const int t = tg + ra * kSpWaves;
+                    float sum = (acc[ra][0] + acc[ra][1]) + (acc[ra][2] + acc[ra][3]);
+#pragma unroll
+                    for (int sh = 32; sh >= LPW; sh >>= 1) sum += __shfl_xor(sum, sh);
+                    if (t < wl && lane < LPW) {
+                        ch.q0[t][l] = sum;
+                        ch.yv[t][l] = yl[ra];
+                    }
                 }
-            }
-            q0[t][lane] = (accA[0] + accA[1]) + (accA[2] + accA[3]);
-            yv[t][lane] = yrow ? yrow[ws + t] : 0.f;
-            if (hb) {
-                q0[tb][lane] = (accB[0] + accB[1]) + (accB[2] + accB[3]);
-                yv[tb][lane] = yrow ? yrow[ws + tb] : 0.f;
             }
         }
         wg_sync();
-        // ---- B: the dependent rounds, scalars and LDS only (wavefront 0) ---------------------
-        if (wave == 0) {
+        // ---- B: the dependent rounds, scalars and LDS only (LPW lanes of wavefront 0) ----------
+        if (chain) {
             int gp = 0;                                          // next Gram value of the window
-            float qn = q0[0][lane], yn = yv[0][lane], x2n = x2s[0];
-            unsigned long long mn = ms[0];
-            for (int t = 0; t < wl && !(a.prefetch & 8); ++t) {
-                const float qv = qn, yy = yn, x2 = x2n;          // <v_t, x_t>, y_t, ||x_t||^2
-                const unsigned long long mt = mn;                // later rounds sharing a column
-                const int tn = t + 1 < wl ? t + 1 : t;
-                qn = q0[tn][lane]; yn = yv[tn][lane]; x2n = x2s[tn]; mn = ms[tn];   // next round, early
-                const float sf = (float)sigma;
+            float qn = ch.q0[0][l], yn = ch.yv[0][l];
+            RoundRec rn = rr[0];
+            float *zs = a.Z + (int64_t)ws * a.zl.zs_t;
+            for (int t = 0; t < wl; ++t) {
+                const float qv = qn, yy = yn;                    // <v_t, x_t>, y_t
+                const RoundRec rc = rn;                          // collisions with later rounds, ||x_t||^2
+                qn = ch.q0[t + 1][l]; yn = ch.yv[t + 1][l]; rn = rr[t + 1];        // next round, early
                 const float z = sf * qv;
-                if (valid) zrow[(int64_t)(ws + t) * a.zl.zs_t] = z;
-                const float b = (eta_r * slope<LOSS>(z, yy)) * __builtin_amdgcn_rcpf(sf);
-                bw[t][lane] = b;
+                if (valid) zs[zoff] = z;
+                zs += a.zl.zs_t;
+                const float b = (eta_r * slope<LOSS>(z, yy)) * isf;
+                ch.bw[t][l] = b;
                 // (readfirstlane returns int: go through unsigned, or the low word sign-extends)
                 unsigned long long m =
-                    (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)mt) |
-                    ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(mt >> 32)) << 32);
+                    (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)rc.mask) |
+                    ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(rc.mask >> 32)) << 32);
                 if (m) {
-                    const bool next_hit = (m >> tn) & 1;
+                    const bool next_hit = (m >> (t + 1)) & 1;
                     while (m) {
                         const int t2 = __builtin_ctzll(m);
                         m &= m - 1;
-                        q0[t2][lane] = fmaf(-b, gl[gp++], q0[t2][lane]);
+                        ch.q0[t2][l] = fmaf(-b, gl[gp++], ch.q0[t2][l]);
                     }
-                    if (next_hit) qn = q0[tn][lane];
+                    if (next_hit) qn = ch.q0[t + 1][l];
                 }
+                // ||v - b x||^2 = ||v||^2 + b (b ||x||^2 - 2 <v, x>)
                 const double bd = (double)b;
-                n2 = fma(bd * bd, (double)x2, fma(-2.0 * bd, (double)qv, n2));
+                n2 = fma(bd, fma(bd, rc.x2, (double)(-2.f * qv)), n2);
                 n2 = n2 > 0.0 ? n2 : 0.0;
-                if (sigma * sigma * n2 > D2) sigma = a.D * rsqrt(n2);      // projection
+                if (n2 * sd2 > D2) {                             // projection: sigma = D / ||v||
+                    sigma = a.D * rsqrt_pos(n2);
+                    sd2 = sigma * sigma;
+                    sf = (float)sigma;
+                    isf = __builtin_amdgcn_rcpf(sf);
+                }
                 if (__any(sigma < kSparseFoldLo)) {
                     // emergency fold.  v = v_start - sum_{r<=t} b_r x_r is not in memory yet:
                     // apply the window's steps so far, fold, and restart the window after t.
-                    for (int rr = 0; rr <= t; ++rr)
+                    for (int rd = 0; rd <= t; ++rd)
                         for (int j = 0; j < nnz; ++j) {
-                            float *p = Vq + (int64_t)cw[rr * nnz + j] * a.RKp;
-                            *p = ldv(p) + (-bw[rr][lane] * vw[rr * nnz + j]);
+                            float *p = Vq + (int64_t)cw[rd * nnz + j] * a.RKp;
+                            *p = ldv(p) + (-ch.bw[rd][l] * vw[rd * nnz + j]);
                         }
-                    const float s = (float)sigma;
                     double m2 = 0.0;
                     for (int64_t j = 0; j < a.d; ++j) {
-                        const float wv = ldv(Vq + j * a.RKp) * s;
+                        const float wv = ldv(Vq + j * a.RKp) * sf;
                         Vq[j * a.RKp] = wv;
                         m2 += (double)wv * (double)wv;
                     }
                     n2 = m2;
-                    sigma = 1.0;
-                    for (int rr = 0; rr <= t; ++rr) bw[rr][lane] = 0.f;      // already applied
-                    for (int t2 = t + 1; t2 < wl; ++t2) {                     // fresh <v, x_t2>
+                    sigma = 1.0; sd2 = 1.0; sf = 1.f; isf = 1.f;
+                    for (int rd = 0; rd <= t; ++rd) ch.bw[rd][l] = 0.f;      // already applied
+                    for (int t2 = t + 1; t2 < wl; ++t2) {                    // fresh <v, x_t2>
                         float acc = 0.f;
                         for (int j = 0; j < nnz; ++j)
                             acc = fmaf(ldv(Vq + (int64_t)cw[t2 * nnz + j] * a.RKp), vw[t2 * nnz + j], acc);
-                        q0[t2][lane] = acc;
+                        ch.q0[t2][l] = acc;
                     }
-                    qn = q0[tn][lane];
+                    qn = ch.q0[t + 1][l];
                 }
             }
-        } else if (w + 1 < wend) {
+        } else if (wave != 0 && w + 1 < wend) {
             // ---- meanwhile the other wavefronts stage the next window -------------------------
             stage_window(stage[(w + 1 - wbeg) & 1], a, recs[w + 1], plan.start(w + 1), plan.len(w + 1) * nnz,
                          (int)threadIdx.x - kWave, (kSpWaves - 1) * kWave);
+            if (a.prefetch) {
+                // ... and pull its rows of V towards L2 (one lane per row segment of this workgroup)
+                const int ns = plan.start(w + 1), ntot = plan.len(w + 1) * nnz;
+                float sink = 0.f;
+                for (int en = (int)threadIdx.x - kWave; en < ntot; en += (kSpWaves - 1) * kWave)
+                    sink += ldv(a.V + (int64_t)a.col[(int64_t)ns * nnz + en] * a.RKp + blockIdx.x * LPW);
+                if (sink == 1.2345e30f) a.Z[0] = sink;          // never true; keeps the loads alive
+            }
         }
         wg_sync();
-        // ---- C: V[col] += -b_t x_t[col]; all entries of a column belong to one wavefront ------
-        if (!(a.prefetch & 4)) {
+        // ---- C: V[col] += -b_t x_t[col].  All entries of a column belong to one wavefront, which
+        // walks its share of the column-sorted list EPI entries per instruction; entries of one
+        // column that meet in an instruction are summed across slots first (fixed order) ---------
+        {
             const int beg = __builtin_amdgcn_readfirstlane(offs[wave]);
             const int end = __builtin_amdgcn_readfirstlane(offs[wave + 1]);
-            for (int k0 = beg; k0 < end; k0 += kWave) {
-                const int cnt = end - k0 < kWave ? end - k0 : kWave;
-                const int ee = perm[k0 + (lane < cnt ? lane : cnt - 1)];
-                const int cc = cw[ee];
-                const float xx = vw[ee];
-                const int tt = (int)(((unsigned)ee * mdiv) >> 18);
-                for (int u0 = 0; u0 < cnt; u0 += 8) {
-                    float bb[8];
+            constexpr int NI = 4;                                // instructions per batch
+            for (int k0 = beg; k0 < end; k0 += NI * EPI) {
+                int cc[NI];
+                float xv[NI];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int uu = u0 + u < cnt ? u0 + u : cnt - 1;
-                        bb[u] = bw[bcast_i(tt, uu)][lane];
+                for (int n = 0; n < NI; ++n) {
+                    const int k = k0 + n * EPI + e;
+                    const bool act = k < end;
+                    const int ee = perm[act ? k : end - 1];
+                    const int t = (int)(((unsigned)ee * mdiv) >> 18);
+                    cc[n] = act ? cw[ee] : -1;
+                    xv[n] = act ? -ch.bw[t][l] * vw[ee] : 0.f;
+                }
+#pragma unroll
+                for (int n = 0; n < NI; ++n) {
+                    bool last = true;
+                    if (EPI > 1) {
+#pragma unroll
+                        for (int sh = 1; sh < EPI; sh <<= 1) {
+                            const float ox = __shfl_up(xv[n], sh * LPW);
+                            const int oc = __shfl_up(cc[n], sh * LPW);
+                            if (e >= sh && oc == cc[n]) xv[n] += ox;
+                        }
+                        const int nc = __shfl_down(cc[n], LPW);
+                        last = e == EPI - 1 || nc != cc[n];
                     }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        if (u0 + u < cnt)
-                            unsafeAtomicAdd(a.V + (int64_t)bcast_i(cc, u0 + u) * a.RKp + uq, -bb[u] * bcast_f(xx, u0 + u));
+                    if (cc[n] >= 0 && last) unsafeAtomicAdd(a.V + (int64_t)cc[n] * a.RKp + uq, xv[n]);
                 }
             }
         }
         wg_sync();
     }
-    if (wave == 0) { a.sigma[q] = sigma; a.n2[q] = n2; }
+    if (chain) { a.sigma[q] = sigma; a.n2[q] = n2; }
 }
 
 // z_u[r][t] = <u_t, x_t>: independent of the learners, one thread per (round, run)
@@ -458,6 +522,47 @@ __global__ void __launch_bounds__(64) sparse_fold_finish_kernel(double *sigma, d
 
 }  // namespace
 
+namespace {
+
+// The largest share that still gives every compute unit a workgroup, at least 8.
+int sparse_learners_per_workgroup(int nq)
+{
+    int lpw = 64;
+    if (const char *f = getenv("OCO_SPARSE_LPW")) {
+        const int v = atoi(f);
+        if (v == 8 || v == 16 || v == 32 || v == 64) return v;
+    }
+    while (lpw > 8 && (nq + lpw - 1) / lpw < 256) lpw >>= 1;
+    return lpw;
+}
+
+template <int LOSS>
+hipError_t launch_window_loss(const SparseArgs &a, int lpw, const WinPlan &plan, int wbeg, int wend, hipStream_t s)
+{
+    const int nq = a.R * a.K;
+    const dim3 grid((unsigned)((nq + lpw - 1) / lpw)), block(kSpWaves * kWave);
+    switch (lpw) {
+        case 64: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 64>), grid, block, 0, s, a, plan, wbeg, wend); break;
+        case 32: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 32>), grid, block, 0, s, a, plan, wbeg, wend); break;
+        case 16: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 16>), grid, block, 0, s, a, plan, wbeg, wend); break;
+        case 8: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 8>), grid, block, 0, s, a, plan, wbeg, wend); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_window(const SparseArgs &a, int loss, int lpw, const WinPlan &plan, int wbeg, int wend, hipStream_t s)
+{
+    switch (loss) {
+        case 0: return launch_window_loss<0>(a, lpw, plan, wbeg, wend, s);
+        case 1: return launch_window_loss<1>(a, lpw, plan, wbeg, wend, s);
+        case 2: return launch_window_loss<2>(a, lpw, plan, wbeg, wend, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
 size_t sparse_scratch_bytes(int64_t n_max)
 {
     return (size_t)(n_max / kWin + 2) * sizeof(WinRec);
@@ -466,8 +571,6 @@ size_t sparse_scratch_bytes(int64_t n_max)
 hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s)
 {
     SparseArgs a = a0;
-    a.prefetch = 0;
-    if (const char *dbg = getenv("OCO_SPARSE_DBG")) a.prefetch = atoi(dbg);
     if (a.n <= 0) return hipSuccess;
     if (a.nnz > OCO_MAX_NNZ) return hipErrorInvalidValue;
     const int64_t nthr = (int64_t)a.n * a.R;
@@ -483,16 +586,13 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s)
 
     // segments end at the multiples of kSegment of the horizon, which are window boundaries
     const int groups = a.RKp / kWave;
+    const int lpw = sparse_learners_per_workgroup(a.R * a.K);
     for (int wbeg = 0; wbeg < nwin;) {
         const int64_t seg_end = ((a.t0 + plan.start(wbeg)) / kSegment + 1) * kSegment;   // absolute
         int wend = wbeg + 1;
         while (wend < nwin && a.t0 + plan.start(wend) < seg_end) ++wend;
-        switch (loss) {
-            case 0: hipLaunchKernelGGL(sparse_window_kernel<0>, dim3(groups), dim3(kSpWaves * kWave), 0, s, a, plan, wbeg, wend); break;
-            case 1: hipLaunchKernelGGL(sparse_window_kernel<1>, dim3(groups), dim3(kSpWaves * kWave), 0, s, a, plan, wbeg, wend); break;
-            case 2: hipLaunchKernelGGL(sparse_window_kernel<2>, dim3(groups), dim3(kSpWaves * kWave), 0, s, a, plan, wbeg, wend); break;
-            default: return hipErrorInvalidValue;
-        }
+        e = launch_window(a, loss, lpw, plan, wbeg, wend, s);
+        if (e != hipSuccess) return e;
         const int64_t reached = a.t0 + plan.start(wend - 1) + plan.len(wend - 1);
         if (reached % kSegment == 0) {                        // a segment of the horizon ended
             hipLaunchKernelGGL(sparse_fold_kernel, dim3(1024, groups), dim3(256), 0, s, a.V, a.sigma, a.d, a.RKp);

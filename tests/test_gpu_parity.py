@@ -96,6 +96,37 @@ def test_sparse_rounds_match_the_oracle(over):
     _check(wl, data, _gpu(wl, data), norm_every=0, label="c5 %s" % over)
 
 
+@pytest.mark.parametrize("lpw", [8, 16, 32, 64])
+def test_sparse_rounds_for_every_workgroup_share(lpw, monkeypatch):
+    """The sparse kernel gives a workgroup 8, 16, 32 or 64 learners (chosen from R*K; small
+    cases always get 8).  OCO_SPARSE_LPW forces a share, read at every launch."""
+    monkeypatch.setenv("OCO_SPARSE_LPW", str(lpw))
+    for over in (dict(T=700, R=20, d=512, K=5, nnz=8, wstar_nnz=16),
+                 dict(T=300, R=9, d=4096, K=8, wstar_nnz=64),
+                 dict(T=200, R=2, d=300, K=2, nnz=64, wstar_nnz=30, eta=(2.0, 400.0))):
+        wl = WL.make("c5", **over)
+        data = WL.generate(wl)
+        print("case c5 lpw", lpw, over, flush=True)
+        _check(wl, data, _gpu(wl, data), norm_every=0, label="c5 lpw=%d %s" % (lpw, over))
+
+
+@pytest.mark.parametrize("lpw", [8, 64])
+def test_sparse_rounds_with_a_column_in_every_round(lpw, monkeypatch):
+    """A feature present in every round (a bias column) makes every pair of rounds of a window
+    collide and puts 64 equal columns next to each other in the scatter order."""
+    monkeypatch.setenv("OCO_SPARSE_LPW", str(lpw))
+    wl = WL.make("c5", T=400, R=3, d=2048, K=4, wstar_nnz=32)
+    data = WL.generate(wl)
+    col = data["col"]
+    for t in range(wl.T):
+        if (col[t] == wl.d - 1).any():
+            continue
+        col[t, t % wl.nnz] = wl.d - 1
+    assert all(len(np.unique(col[t])) == wl.nnz for t in range(wl.T))
+    print("case c5 bias column lpw", lpw, flush=True)
+    _check(wl, data, _gpu(wl, data), norm_every=0, label="c5 bias column lpw=%d" % lpw)
+
+
 @pytest.mark.parametrize("name,over,chunks", [
     ("c2", dict(T=500, R=3, d=100, K=15), (1, 7, 64, 333)),
     ("c3", dict(T=400, R=2, d=1000, K=17, seg_len=90), (13, 128)),
