@@ -18,7 +18,15 @@
  *    exclude round t's loss;
  *  - the domain is the L2 ball of RADIUS D; the projection rescales only
  *    when the norm exceeds D;
- *  - w_1^i = 0.
+ *  - w_1^i = 0;
+ *  - optimistic update (Eq. (3)): hint h_t = gradient of the previous round at
+ *    the previously played iterate, h_1 = 0, w^_1 = 0; for K > 1 every learner
+ *    runs it independently and Hedge weighs the played iterates;
+ *  - Lemma 1 / Theorem 1: a negative regret is taken as 0.
+ * Also here: the accepted-length / acceleration-rate bounds of Lemma 1 and
+ * Theorem 1 (closed forms) and the optimistic two-step update of Eq. (3).
+ * Every function is pinned by tests that do not call it to produce their
+ * expectation (tests/test_oracle_pins.py, tests/test_oracle_pins_next.py).
  *
  * Losses are generalised-linear: f_t(w) = phi(<w, x_t>; y_t), so the
  * gradient is phi'(z; y) x_t.  For the linear loss x_t is the gradient g_t.
@@ -287,6 +295,158 @@ int oco_oracle_run_many(int64_t R, int64_t d, int64_t K, int64_t T, double D,
                                 W + r * K * d, L + r * K, p + r * K, wbar + r * d, regret + r,
                                 &dr, NULL);
         if (max_drift) max_drift[r] = dr;
+        if (rc) bad += 1;
+    }
+    if (threads_used) *threads_used = used;
+    return bad;
+}
+
+/*
+ * Accepted-length and acceleration-rate bounds (Lemma 1, Theorem 1) for one run
+ * with dynamic regret reg over T steps, candidate length k and draft/target
+ * inference-time ratio alpha:
+ *   out[0] = (k+1) T / (1 + (k+1) sqrt(reg / (2T)))   lower bound on E|x^|
+ *   out[1] = (k+1) T                                   upper bound on E|x^|
+ *   out[2] = out[0] / (T (alpha k + 1))                lower bound on gamma
+ *   out[3] = (k+1) / (alpha k + 1)                     upper bound on gamma
+ * Reading: the lemma's regret is a sum of KL divergences, hence >= 0; a
+ * negative regret (possible against an arbitrary comparator) is taken as 0.
+ */
+void oco_oracle_accel_bounds(double reg, int64_t T, int64_t k, double alpha, double *out)
+{
+    double r = reg > 0.0 ? reg : 0.0;
+    double k1 = (double)(k + 1);
+    double denom = 1.0 + k1 * sqrt(r / (2.0 * (double)T));
+    out[0] = k1 * (double)T / denom;
+    out[1] = k1 * (double)T;
+    out[2] = out[0] / ((double)T * (alpha * (double)k + 1.0));
+    out[3] = k1 / (alpha * (double)k + 1.0);
+}
+
+/*
+ * Optimistic online gradient descent, Eq. (3), with the last-round gradient as
+ * the hint (Sec. 3.2), for K independent learners with steps eta[i] on a dense
+ * round stream, combined by the same Hedge meta learner as oco_oracle_run.
+ * Per learner:  h_1 = 0, w^_1 = 0;
+ *   w_t      = Proj[w^_t - eta h_t]                 (the iterate that is played)
+ *   g_t      = phi'(<w_t, x_t>; y_t) x_t            (gradient at the played iterate)
+ *   w^_{t+1} = Proj[w^_t - eta g_t],   h_{t+1} = g_t.
+ * With K = 1 this is the paper's optimistic update; for K > 1 every learner runs
+ * it on its own and Hedge weighs the played iterates by their losses (the paper
+ * names optimism inside the ensemble as future work and gives no algorithm).
+ * Outputs: W[K][d] = w_{T+1} (played next), What[K][d] = w^_{T+1} (may be NULL),
+ * L, p = p_{T+1}, wbar = sum_i p^i w_{T+1}^i, *regret; *delta (may be NULL) is
+ * [K] sums of ||h_t - g_t||^2; tr->z / tr->loss / tr->p / tr->f / tr->fu /
+ * tr->zmix as in oco_oracle_run (z of the played iterates).
+ */
+int oco_oracle_run_optimistic(int64_t d, int64_t K, int64_t T, double D, const double *eta,
+                              double eps, int loss, const float *x, const float *y,
+                              const float *u, const int64_t *seg_start, int64_t S,
+                              double *W, double *What, double *L, double *p, double *wbar,
+                              double *regret, double *delta, const oco_oracle_trace *tr)
+{
+    if (d <= 0 || K <= 0 || T < 0 || S <= 0 || !eta || !u || !seg_start || !x) return -1;
+    if (loss != LOSS_LINEAR && !y) return -1;
+    double *hat = calloc(K * d, sizeof(double));   /* w^_t */
+    double *h = calloc(K * d, sizeof(double));     /* h_t */
+    double *z = malloc(sizeof(double) * K), *ell = malloc(sizeof(double) * K);
+    double *xt = malloc(sizeof(double) * d), *g = malloc(sizeof(double) * d);
+    if (!hat || !h || !z || !ell || !xt || !g) return -1;
+    for (int64_t i = 0; i < K; ++i) { L[i] = 0.0; if (delta) delta[i] = 0.0; }
+    double reg = 0.0;
+    int64_t seg = 0;
+
+    for (int64_t t = 0; t <= T; ++t) {
+        /* the iterate to play in round t (for t == T: the state handed back) */
+        for (int64_t i = 0; i < K; ++i) {
+            double *w = W + i * d;
+            for (int64_t j = 0; j < d; ++j) w[j] = hat[i * d + j] - eta[i] * h[i * d + j];
+            oco_oracle_project(w, d, D);
+        }
+        if (t == T) break;
+        while (seg + 1 < S && t >= seg_start[seg + 1]) ++seg;
+        const float *ut = u + seg * d;
+        double yt = y ? (double)y[t] : 0.0;
+        for (int64_t j = 0; j < d; ++j) xt[j] = (double)x[t * d + j];
+        oco_oracle_hedge(L, K, eps, p);
+
+        double zu = 0.0, zw = 0.0, zmix = 0.0;
+        for (int64_t j = 0; j < d; ++j) zu += (double)ut[j] * xt[j];
+        for (int64_t i = 0; i < K; ++i) {
+            double sdot = 0.0;
+            for (int64_t j = 0; j < d; ++j) sdot += W[i * d + j] * xt[j];
+            z[i] = sdot;
+            ell[i] = oco_oracle_loss(loss, z[i], yt);
+            zmix += p[i] * z[i];
+        }
+        for (int64_t j = 0; j < d; ++j) {
+            double wj = 0.0;
+            for (int64_t i = 0; i < K; ++i) wj += p[i] * W[i * d + j];
+            zw += wj * xt[j];
+        }
+        double ft = oco_oracle_loss(loss, zw, yt), fu = oco_oracle_loss(loss, zu, yt);
+        reg += ft - fu;
+        if (tr) {
+            for (int64_t i = 0; i < K; ++i) {
+                if (tr->p) tr->p[t * K + i] = p[i];
+                if (tr->z) tr->z[t * K + i] = z[i];
+                if (tr->loss) tr->loss[t * K + i] = ell[i];
+            }
+            if (tr->f) tr->f[t] = ft;
+            if (tr->fu) tr->fu[t] = fu;
+            if (tr->zmix) tr->zmix[t] = zmix;
+        }
+        for (int64_t i = 0; i < K; ++i) {
+            double c = oco_oracle_slope(loss, z[i], yt);
+            double dsum = 0.0;
+            for (int64_t j = 0; j < d; ++j) {
+                g[j] = c * xt[j];
+                double df = h[i * d + j] - g[j];
+                dsum += df * df;
+            }
+            if (delta) delta[i] += dsum;
+            for (int64_t j = 0; j < d; ++j) {
+                hat[i * d + j] -= eta[i] * g[j];
+                h[i * d + j] = g[j];
+            }
+            oco_oracle_project(hat + i * d, d, D);
+            L[i] += ell[i];
+        }
+    }
+    oco_oracle_hedge(L, K, eps, p);
+    for (int64_t j = 0; j < d; ++j) {
+        double wj = 0.0;
+        for (int64_t i = 0; i < K; ++i) wj += p[i] * W[i * d + j];
+        wbar[j] = wj;
+    }
+    if (What) memcpy(What, hat, sizeof(double) * K * d);
+    *regret = reg;
+    free(hat); free(h); free(z); free(ell); free(xt); free(g);
+    return 0;
+}
+
+/* R independent optimistic runs, one per thread at a time; layout as oco_oracle_run_many. */
+int oco_oracle_run_many_optimistic(int64_t R, int64_t d, int64_t K, int64_t T, double D,
+                                   const double *eta, double eps, int loss, int x_shared,
+                                   const float *x, const float *y, const float *u,
+                                   const int64_t *seg_start, int64_t S, int threads,
+                                   double *W, double *L, double *p, double *wbar, double *regret,
+                                   int *threads_used)
+{
+    int bad = 0, used = 1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+    used = omp_get_max_threads();
+    if ((int64_t)used > R) used = (int)(R > 0 ? R : 1);
+#else
+    (void)threads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : bad)
+    for (int64_t r = 0; r < R; ++r) {
+        int rc = oco_oracle_run_optimistic(d, K, T, D, eta, eps, loss, x_shared ? x : x + r * T * d,
+                                           y ? y + r * T : NULL, u + r * S * d, seg_start, S,
+                                           W + r * K * d, NULL, L + r * K, p + r * K, wbar + r * d,
+                                           regret + r, NULL, NULL);
         if (rc) bad += 1;
     }
     if (threads_used) *threads_used = used;

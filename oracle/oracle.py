@@ -50,6 +50,18 @@ def lib() -> C.CDLL:
             + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
             + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int]
             + [C.c_void_p] * 5 + [C.c_void_p, C.c_void_p])
+        _lib.oco_oracle_accel_bounds.restype = None
+        _lib.oco_oracle_accel_bounds.argtypes = [d, C.c_int64, C.c_int64, d, C.c_void_p]
+        _lib.oco_oracle_run_optimistic.restype = C.c_int
+        _lib.oco_oracle_run_optimistic.argtypes = (
+            [C.c_int64, C.c_int64, C.c_int64, d, C.c_void_p, d, C.c_int]
+            + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
+            + [C.c_void_p] * 7 + [C.c_void_p])
+        _lib.oco_oracle_run_many_optimistic.restype = C.c_int
+        _lib.oco_oracle_run_many_optimistic.argtypes = (
+            [C.c_int64] * 4 + [d, C.c_void_p, d, C.c_int, C.c_int]
+            + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int]
+            + [C.c_void_p] * 5 + [C.c_void_p])
     return _lib
 
 
@@ -125,6 +137,45 @@ def run(d: int, K: int, T: int, D: float, eta, eps: float, loss: str, *,
     return res
 
 
+def accel_bounds(reg: float, T: int, k: int, alpha: float) -> np.ndarray:
+    """[len_lo, len_hi, gamma_lo, gamma_hi] of Lemma 1 / Theorem 1."""
+    out = np.empty(4)
+    lib().oco_oracle_accel_bounds(float(reg), int(T), int(k), float(alpha), _ptr(out))
+    return out
+
+
+def run_optimistic(d: int, K: int, T: int, D: float, eta, eps: float, loss: str, *,
+                   x, y=None, u=None, seg_start=None, trace: bool = False) -> Dict[str, np.ndarray]:
+    """One run of K optimistic learners (Eq. (3), last-gradient hint) on a dense stream."""
+    eta = np.ascontiguousarray(eta, dtype=np.float64)
+    assert eta.size == K
+    x, y, u = _f32(x), _f32(y), _f32(u)
+    u = u.reshape(-1, d)
+    S = u.shape[0]
+    seg_start = (np.zeros(1, np.int64) if seg_start is None
+                 else np.ascontiguousarray(seg_start, dtype=np.int64))
+    assert seg_start.size == S and x.shape == (T, d)
+    W = np.empty((K, d)); What = np.empty((K, d)); L = np.empty(K); p = np.empty(K); wbar = np.empty(d)
+    reg = np.zeros(1); delta = np.zeros(K)
+    tr = None
+    res: Dict[str, np.ndarray] = {}
+    if trace:
+        tr = _Trace()
+        for name, shape in (("p", (T, K)), ("z", (T, K)), ("loss", (T, K)),
+                            ("f", (T,)), ("fu", (T,)), ("zmix", (T,))):
+            arr = np.zeros(shape)
+            res["tr_" + name] = arr
+            setattr(tr, name, arr.ctypes.data)
+    rc = lib().oco_oracle_run_optimistic(d, K, T, float(D), _ptr(eta), float(eps), LOSS_ID[loss],
+                                         _ptr(x), _ptr(y), _ptr(u), _ptr(seg_start), S,
+                                         _ptr(W), _ptr(What), _ptr(L), _ptr(p), _ptr(wbar), _ptr(reg),
+                                         _ptr(delta), C.byref(tr) if tr is not None else None)
+    if rc != 0:
+        raise ValueError("oco_oracle_run_optimistic rejected its arguments")
+    res.update(W=W, What=What, L=L, p=p, wbar=wbar, regret=float(reg[0]), delta=delta)
+    return res
+
+
 def run_workload(wl, data, *, threads: int = 0, norm_every: Optional[int] = None):
     """All R runs of a workload (fields as in paper_2603_12617_amd.workloads:
     any object with d, K, T, R, D, eta, eps, loss, x_shared, nnz), one run per
@@ -142,6 +193,16 @@ def run_workload(wl, data, *, threads: int = 0, norm_every: Optional[int] = None
         norm_every = 1000 if nnz else 0
     W = np.empty((R, K, d)); L = np.empty((R, K)); p = np.empty((R, K)); wbar = np.empty((R, d))
     reg = np.zeros(R); drift = np.zeros(R); used = C.c_int(0)
+    if getattr(wl, "optimistic", False):
+        assert nnz == 0, "the optimistic update is defined here for dense streams"
+        bad = lib().oco_oracle_run_many_optimistic(R, d, K, T, float(wl.D), _ptr(eta), float(wl.eps),
+                                                   LOSS_ID[wl.loss], int(bool(wl.x_shared)),
+                                                   _ptr(x), _ptr(y), _ptr(u), _ptr(seg_start), S,
+                                                   int(threads), _ptr(W), _ptr(L), _ptr(p), _ptr(wbar),
+                                                   _ptr(reg), C.byref(used))
+        if bad:
+            raise ValueError("oco_oracle_run_many_optimistic: %d runs failed" % bad)
+        return dict(W=W, L=L, p=p, wbar=wbar, regret=reg, max_drift=drift, threads=used.value)
     bad = lib().oco_oracle_run_many(R, d, K, T, float(wl.D), _ptr(eta), float(wl.eps),
                                     LOSS_ID[wl.loss], int(bool(wl.x_shared)),
                                     _ptr(x), _ptr(col), _ptr(val), nnz, _ptr(y), _ptr(u),

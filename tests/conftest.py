@@ -28,7 +28,7 @@ def read_golden(name):
             rows = [[float(v) for v in row.split()] for row in val.split(";")]
             arr = np.array(rows, dtype=np.float64)
             out[key] = arr[0, 0] if arr.size == 1 and key in (
-                "d", "K", "T", "D", "eps", "regret", "bound") else (arr[0] if len(rows) == 1 else arr)
+                "d", "K", "T", "D", "eps", "regret", "bound", "delta", "eta") else (arr[0] if len(rows) == 1 else arr)
     return out
 
 
