@@ -47,8 +47,8 @@ def roofline_model(wl):
     return "alu", f, PEAK_FP32_TFLOPS, "TFLOP/s", 1e12
 
 
-def run_workload(name, steps, warmup, WL, B, torch, keep=None):
-    wl = WL.make(name)
+def run_workload(name, steps, warmup, WL, B, torch, keep=None, optimistic=False):
+    wl = WL.make(name, optimistic=optimistic)
     data = WL.generate(wl)
     sim = B.Simulation(wl, data)
     W = torch.empty((wl.R, wl.K, wl.d), dtype=torch.float32, device="cuda")
@@ -78,7 +78,7 @@ def run_workload(name, steps, warmup, WL, B, torch, keep=None):
                meta_kernel_ms=float(sum(k[1] for k in kern_ms) / steps),
                regret_mean=float(reg.mean()))
     if keep is not None:
-        keep.update(data=data, regret=reg)
+        keep.update(data=data, regret=reg, accel=sim.accel_bounds(4, 0.05))
     sim.close()
     del sim, W, p, wbar
     torch.cuda.empty_cache()
@@ -165,6 +165,9 @@ def main():
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                      "frac": achieved / peak, "traffic": traffic, "kernel": "round kernel (S0-S2,S4)"},
     }
+    ab = keep["accel"]
+    line["accel_bounds_k4_alpha0.05"] = {"gamma_lower_mean": float(ab[:, 2].mean()), "gamma_upper": float(ab[0, 3]),
+                                         "note": "Theorem 1 from the regret of each run, mean over runs"}
     if wl.nnz:
         line["algorithmic_value"] = {"value": wl.R * wl.K * wl.T * wl.nnz / (main_res["ms_per_step"] * 1e-3),
                                      "unit": "touched learner-coordinates/s (R*K*T*nnz/s)"}
@@ -186,6 +189,11 @@ def main():
             r = run_workload(name, 2, 1, WL, B, torch)
             others[name] = {"value": r["value"], "ms_per_step": r["ms_per_step"],
                             "round_kernel_ms": r["round_kernel_ms"], "meta_kernel_ms": r["meta_kernel_ms"]}
+        for name in ("c3", "c4"):          # the optimistic two-step update (Eq. (3)) on the same streams
+            r = run_workload(name, 2, 1, WL, B, torch, optimistic=True)
+            others[name + "_optimistic"] = {"value": r["value"], "ms_per_step": r["ms_per_step"],
+                                            "round_kernel_ms": r["round_kernel_ms"],
+                                            "meta_kernel_ms": r["meta_kernel_ms"]}
         line["other_workloads"] = others
 
     print(json.dumps(line))

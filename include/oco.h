@@ -83,7 +83,16 @@ typedef struct {
                              (dense only; sparse streams are always shared)           */
     int32_t sparse_nnz;   /* 0: dense rounds; >0: every round has exactly this many
                              (column, value) entries, columns distinct within a round */
-    int32_t reserved;     /* must be 0                                                */
+    int32_t optimistic;   /* 0: plain update w_{t+1} = Proj[w_t - eta grad f_t(w_t)] (Sec. 3.1);
+                             1: optimistic two-step update of Eq. (3) with the last round's
+                             gradient as hint (Sec. 3.2), every base learner on its own:
+                               w_t = Proj[w^_t - eta h_t],  w^_{t+1} = Proj[w^_t - eta grad f_t(w_t)],
+                               h_{t+1} = grad f_t(w_t),  h_1 = 0,  w^_1 = 0.
+                             Predictions, losses and regret are those of the played iterates
+                             w_t; oco_get_state returns the iterates that would be played
+                             next.  K = 1 is the paper's method; for K > 1 Hedge weighs the
+                             played iterates (not analysed in the paper).  Dense rounds only
+                             (OCO_EUNSUPPORTED with sparse_nnz > 0)                       */
     int64_t n_max;        /* largest n of any oco_run_rounds call; 0 means T          */
 } oco_config;
 
@@ -136,6 +145,18 @@ int oco_regret(oco_state *st, double *out_host);
  * round (p_dev: device [R][K]) and the combined iterate sum_i p^i w^i (wbar_dev: device
  * [R][d]); any of the three may be NULL.  Asynchronous on the stream. */
 int oco_get_state(oco_state *st, float *W_dev, float *p_dev, float *wbar_dev);
+
+/* Accepted-length and acceleration-rate bounds of Lemma 1 and Theorem 1 for every run, from
+ * its dynamic regret Reg over the t rounds consumed so far, the candidate length k >= 1 and
+ * the draft/target inference-time ratio alpha >= 0:
+ *   out[r][0] = (k+1) t / (1 + (k+1) sqrt(Reg / (2 t)))     lower bound on the expected length
+ *   out[r][1] = (k+1) t                                      upper bound
+ *   out[r][2] = out[r][0] / (t (alpha k + 1))                lower bound on the rate gamma
+ *   out[r][3] = (k+1) / (alpha k + 1)                        upper bound
+ * A negative regret (possible against an arbitrary comparator; the lemma's regret is a sum of
+ * KL terms) is taken as 0.  out_dev: device [R][4] float64, caller-owned.  OCO_ESEQ before the
+ * first round.  Asynchronous on the stream. */
+int oco_accel_bounds(oco_state *st, int64_t k, double alpha, double *out_dev);
 
 /* Cumulative base-learner losses L^i over the rounds consumed so far.  out_host: host [R][K].
  * Synchronises the stream. */

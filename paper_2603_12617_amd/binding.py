@@ -20,14 +20,14 @@ OCO_OK, OCO_EINVAL, OCO_ESEQ, OCO_ERANGE, OCO_ENOMEM, OCO_EHIP, OCO_ENOCOMP, OCO
 LOSS_ID = {"linear": 0, "squared": 1, "logistic": 2}
 EXPORTS = ("oco_step_grid", "oco_paper_num_learners", "oco_workspace_bytes", "oco_create",
            "oco_set_comparator", "oco_run_rounds", "oco_regret", "oco_get_state",
-           "oco_cum_losses", "oco_reset", "oco_set_timing", "oco_last_timing", "oco_rounds_done", "oco_destroy", "oco_strerror")
+           "oco_cum_losses", "oco_accel_bounds", "oco_reset", "oco_set_timing", "oco_last_timing", "oco_rounds_done", "oco_destroy", "oco_strerror")
 
 
 class OcoConfig(C.Structure):
     _fields_ = [("d", C.c_int64), ("K", C.c_int64), ("T", C.c_int64), ("R", C.c_int64),
                 ("D", C.c_double), ("G", C.c_double), ("eta", C.POINTER(C.c_double)),
                 ("eps", C.c_double), ("loss", C.c_int32), ("x_shared", C.c_int32),
-                ("sparse_nnz", C.c_int32), ("reserved", C.c_int32), ("n_max", C.c_int64)]
+                ("sparse_nnz", C.c_int32), ("optimistic", C.c_int32), ("n_max", C.c_int64)]
 
 
 class OcoRounds(C.Structure):
@@ -73,6 +73,8 @@ def lib() -> C.CDLL:
         L.oco_regret.argtypes = [vp, vp]
         L.oco_cum_losses.restype = C.c_int
         L.oco_cum_losses.argtypes = [vp, vp]
+        L.oco_accel_bounds.restype = C.c_int
+        L.oco_accel_bounds.argtypes = [vp, i64, C.c_double, vp]
         L.oco_get_state.restype = C.c_int
         L.oco_get_state.argtypes = [vp, vp, vp, vp]
         L.oco_reset.restype = C.c_int
@@ -101,13 +103,13 @@ def _check(status: int, where: str) -> None:
 
 
 def make_config(*, d, K, T, R, D, G, eta: Sequence[float], eps, loss, x_shared=True, nnz=0,
-                n_max=0):
+                n_max=0, optimistic=False):
     """Returns (OcoConfig, keepalive) -- keepalive owns the eta array."""
     eta_arr = (C.c_double * len(eta))(*[float(e) for e in eta])
     cfg = OcoConfig(int(d), int(K), int(T), int(R), float(D), float(G),
                     C.cast(eta_arr, C.POINTER(C.c_double)), float(eps),
                     LOSS_ID[loss] if isinstance(loss, str) else int(loss), int(bool(x_shared)),
-                    int(nnz), 0, int(n_max))
+                    int(nnz), int(bool(optimistic)), int(n_max))
     return cfg, eta_arr
 
 
@@ -171,6 +173,11 @@ def oco_cum_losses(h: int, R: int, K: int) -> np.ndarray:
     return out
 
 
+def oco_accel_bounds(h: int, k: int, alpha: float, out) -> None:
+    """out: device float64 tensor [R][4] (length bounds, rate bounds of Lemma 1 / Theorem 1)."""
+    _check(lib().oco_accel_bounds(h, int(k), float(alpha), _dptr(out)), "oco_accel_bounds")
+
+
 def oco_get_state(h: int, W=None, p=None, wbar=None) -> None:
     _check(lib().oco_get_state(h, _dptr(W), _dptr(p), _dptr(wbar)), "oco_get_state")
 
@@ -217,7 +224,7 @@ class Simulation:
         self.seg_start = np.ascontiguousarray(data["seg_start"], dtype=np.int64)
         self.cfg, self._keep = make_config(d=wl.d, K=wl.K, T=wl.T, R=wl.R, D=wl.D, G=wl.G, eta=wl.eta,
                                            eps=wl.eps, loss=wl.loss, x_shared=wl.x_shared, nnz=wl.nnz,
-                                           n_max=n_max)
+                                           n_max=n_max, optimistic=getattr(wl, "optimistic", False))
         nbytes = oco_workspace_bytes(self.cfg)
         if nbytes == 0:
             raise OcoError(OCO_EINVAL, "oco_workspace_bytes")
@@ -253,6 +260,12 @@ class Simulation:
 
     def cum_losses(self) -> np.ndarray:
         return oco_cum_losses(self.h, self.wl.R, self.wl.K)
+
+    def accel_bounds(self, k: int, alpha: float) -> np.ndarray:
+        out = self.torch.empty((self.wl.R, 4), dtype=self.torch.float64, device=self.dev)
+        oco_accel_bounds(self.h, k, alpha, out)
+        self.sync()
+        return out.cpu().numpy()
 
     def state(self, want_W: bool = True):
         torch, wl = self.torch, self.wl

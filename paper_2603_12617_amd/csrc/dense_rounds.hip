@@ -104,7 +104,7 @@ template <int VW> __device__ __forceinline__ float combine(const float (&acc)[VW
     return acc[0];
 }
 
-template <int NPL, int LOSS>
+template <int NPL, int LOSS, bool OPT>
 __global__ void __launch_bounds__(DenseCfg<NPL>::MAXW * kWave)
 dense_rounds_kernel(const DenseArgs a)
 {
@@ -257,6 +257,13 @@ dense_rounds_kernel(const DenseArgs a)
     double n2 = a.n2[(int64_t)r * K + i];       // ||v||^2
     const float eta = a.eta[i];
     float qv, z, zreg = 0.f, yreg = 0.f, x2reg = 0.f;   // qv = <v, x_t>, z = sigma qv
+    // optimistic update: the hint is ha * x_{t-1}; hp = <w^_t, x_{t-1}>; g01 = <x_{t-1}, x_t>
+    float ha = 0.f, hp = 0.f, x2prev = 0.f, g01reg = 0.f;
+    if (OPT) {
+        ha = a.ha[(int64_t)r * K + i];
+        hp = a.hp[(int64_t)r * K + i];
+        x2prev = a.x2last[a.x_shared ? 0 : r];
+    }
     {
         const float *src = a.V + ((int64_t)r * K + i) * d;
         float acc[VW];
@@ -277,6 +284,7 @@ dense_rounds_kernel(const DenseArgs a)
         z = sigma * qv;                               // z_0 = <w_0, x_0>
     }
     const float *x2row = a.x2 + (a.x_shared ? 0 : (int64_t)r * a.x2_run_stride);
+    const float *g01row = OPT ? a.g01 + (a.x_shared ? 0 : (int64_t)r * a.x2_run_stride) : nullptr;
     const int phase = (int)(a.t0 & 63);               // exact norms at absolute rounds = 63 mod 64
 
     const float D = a.D;
@@ -317,10 +325,23 @@ dense_rounds_kernel(const DenseArgs a)
         if ((t & 63) == 0) {
             if (yrow) yreg = (t + lane < n) ? yrow[t + lane] : 0.f;
             x2reg = (t + lane < n) ? x2row[t + lane] : 0.f;
+            if (OPT) g01reg = (t + lane < n) ? g01row[t + lane] : 0.f;
         }
         const float yt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(yreg), t & 63));
         const float x2t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x2reg), t & 63));
-        if (lane == (t & 63)) zreg = z;
+        // the prediction that is played and scored: plain, z = <w_t, x_t>; optimistic,
+        // w_t = s (w^_t - ha x_{t-1}) with s from ||w^_t - ha x_{t-1}||^2, all from scalars
+        float zp = z;
+        if (OPT) {
+            const float g01t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g01reg), t & 63));
+            const double had = (double)ha;
+            const double m = fma(had * had, (double)x2prev,
+                                 fma(-2.0 * had, (double)hp, (double)sigma * (double)sigma * n2));
+            const float mf = (float)m;
+            const float sp = mf > D2 ? D * __builtin_amdgcn_rsqf(mf) : 1.f;
+            zp = sp * fmaf(-ha, g01t, z);
+        }
+        if (lane == (t & 63)) zreg = zp;
         // fold sigma into v first (never between computing z and using it, so that z is
         // the same whether or not a call boundary falls here)
         if (sigma < kFoldLo || sigma > kFoldHi) {
@@ -332,7 +353,9 @@ dense_rounds_kernel(const DenseArgs a)
             qv = z;
             sigma = 1.f;
         }
-        const float b = (eta * slope<LOSS>(z, yt)) * fast_rcp(sigma);
+        const float step = eta * slope<LOSS>(zp, yt);       // w-space step along x_t
+        const float b = step * fast_rcp(sigma);
+        const float qold = qv;
         float aq[VW];
         pass(b, xrow(t + 1), xc, xn, aq);
         if (((phase + t) & 63) == 63) {                  // re-measure ||v||^2 exactly
@@ -353,6 +376,11 @@ dense_rounds_kernel(const DenseArgs a)
         const float nrm = (float)n2;                     // ||v||^2
         if (sigma * sigma * nrm > D2) sigma = D * __builtin_amdgcn_rsqf(nrm);   // projection
         z = sigma * qv;
+        if (OPT) {                                       // next round's hint and <w^_{t+1}, x_t>
+            hp = sigma * fmaf(-b, x2t, qold);
+            ha = step;
+            x2prev = x2t;
+        }
         if ((t & 63) == 63 || t == n - 1) {              // flush the z of rounds (t & ~63) .. t
             const int tb = t & ~63;
             if (tb + lane <= t) zrow[(int64_t)(tb + lane) * a.zl.zs_t] = zreg;
@@ -381,12 +409,15 @@ dense_rounds_kernel(const DenseArgs a)
                 if (j < d) dst[j] = wv[m][e];
             }
         if (lane == 0) { a.sigma[(int64_t)r * K + i] = sigma; a.n2[(int64_t)r * K + i] = n2; }
+        if (OPT && lane == 0) { a.ha[(int64_t)r * K + i] = ha; a.hp[(int64_t)r * K + i] = hp; }
     }
 }
 
-// ||x_t||^2 of every round row: one wavefront per row, fixed summation order.
+// ||x_t||^2 of every round row and, if g01 is given, <x_{t-1}, x_t> (x_{-1} = the last row of the
+// previous call, kept in xlast): one wavefront per row, fixed summation order.
 __global__ void __launch_bounds__(256) xnorm2_kernel(const float *x, int64_t run_stride, int nruns,
-                                                     int n, int d, float *out, int64_t out_stride)
+                                                     int n, int d, float *out, int64_t out_stride,
+                                                     float *g01, const float *xlast)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -397,6 +428,24 @@ __global__ void __launch_bounds__(256) xnorm2_kernel(const float *x, int64_t run
     for (int j = lane; j < d; j += 64) acc = fmaf(src[j], src[j], acc);
     const float tot = wave_sum(acc);
     if (lane == 0) out[(int64_t)rr * out_stride + t] = tot;
+    if (g01) {
+        const float *prev = t > 0 ? src - d : xlast + (int64_t)rr * d;
+        float ac2 = 0.f;
+        for (int j = lane; j < d; j += 64) ac2 = fmaf(prev[j], src[j], ac2);
+        const float t2 = wave_sum(ac2);
+        if (lane == 0) g01[(int64_t)rr * out_stride + t] = t2;
+    }
+}
+
+// keeps the last round row of a call (and its squared norm) for the next call's hint terms
+__global__ void __launch_bounds__(256) keep_last_row_kernel(const float *x, int64_t run_stride, int n, int d,
+                                                            const float *x2, int64_t x2_stride, float *xlast,
+                                                            float *x2last)
+{
+    const int rr = blockIdx.y;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < d) xlast[(int64_t)rr * d + j] = x[(int64_t)rr * run_stride + (int64_t)(n - 1) * d + j];
+    if (j == 0) x2last[rr] = x2[(int64_t)rr * x2_stride + n - 1];
 }
 
 template <int NPL>
@@ -405,10 +454,13 @@ hipError_t launch_npl(const DenseArgs &a, int loss, hipStream_t s)
     using C = DenseCfg<NPL>;
     const size_t smem = sizeof(float) * kRing * C::RT * NPL * kWave;
     void (*kern)(const DenseArgs) = nullptr;
-    switch (loss) {
-        case 0: kern = dense_rounds_kernel<NPL, 0>; break;
-        case 1: kern = dense_rounds_kernel<NPL, 1>; break;
-        case 2: kern = dense_rounds_kernel<NPL, 2>; break;
+    switch (loss * 2 + (a.optimistic ? 1 : 0)) {
+        case 0: kern = dense_rounds_kernel<NPL, 0, false>; break;
+        case 1: kern = dense_rounds_kernel<NPL, 0, true>; break;
+        case 2: kern = dense_rounds_kernel<NPL, 1, false>; break;
+        case 3: kern = dense_rounds_kernel<NPL, 1, true>; break;
+        case 4: kern = dense_rounds_kernel<NPL, 2, false>; break;
+        case 5: kern = dense_rounds_kernel<NPL, 2, true>; break;
         default: return hipErrorInvalidValue;
     }
     if (smem > 64 * 1024) {
@@ -464,23 +516,29 @@ bool dense_supported(int64_t d) { return d >= 1 && d <= 64 * kWave; }
 hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s)
 {
     if (a.n <= 0) return hipSuccess;
+    const int nruns = a.x_shared ? 1 : a.R;
+    const int64_t xstride = a.x_shared ? 0 : a.x_run_stride;
     {
-        const int nruns = a.x_shared ? 1 : a.R;
         const int64_t rows = (int64_t)nruns * a.n;
-        hipLaunchKernelGGL(xnorm2_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a.x,
-                           a.x_shared ? 0 : a.x_run_stride, nruns, a.n, a.d, a.x2, a.x2_run_stride);
+        hipLaunchKernelGGL(xnorm2_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a.x, xstride, nruns,
+                           a.n, a.d, a.x2, a.x2_run_stride, a.optimistic ? a.g01 : nullptr,
+                           a.optimistic ? a.xlast : nullptr);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     const int npl = (a.d + kWave - 1) / kWave;
-    if (npl <= 1) return launch_npl<1>(a, loss, s);
-    if (npl <= 2) return launch_npl<2>(a, loss, s);
-    if (npl <= 4) return launch_npl<4>(a, loss, s);
-    if (npl <= 8) return launch_npl<8>(a, loss, s);
-    if (npl <= 16) return launch_npl<16>(a, loss, s);
-    if (npl <= 32) return launch_npl<32>(a, loss, s);
-    if (npl <= 64) return launch_npl<64>(a, loss, s);
-    return hipErrorInvalidValue;
+    hipError_t e = hipErrorInvalidValue;
+    if (npl <= 1) e = launch_npl<1>(a, loss, s);
+    else if (npl <= 2) e = launch_npl<2>(a, loss, s);
+    else if (npl <= 4) e = launch_npl<4>(a, loss, s);
+    else if (npl <= 8) e = launch_npl<8>(a, loss, s);
+    else if (npl <= 16) e = launch_npl<16>(a, loss, s);
+    else if (npl <= 32) e = launch_npl<32>(a, loss, s);
+    else if (npl <= 64) e = launch_npl<64>(a, loss, s);
+    if (e != hipSuccess || !a.optimistic) return e;
+    hipLaunchKernelGGL(keep_last_row_kernel, dim3((unsigned)((a.d + 255) / 256), (unsigned)nruns), dim3(256), 0, s,
+                       a.x, xstride, a.n, a.d, a.x2, a.x2_run_stride, a.xlast, a.x2last);
+    return hipGetLastError();
 }
 
 }  // namespace oco

@@ -99,22 +99,38 @@ __device__ void hedge_weights(const double *L, int K, double eps, double *p_sh)
     __syncthreads();
 }
 
-// dense layout: V[R][K][d], sigma float [R][K]
+// dense layout: V[R][K][d], sigma float [R][K].  Optimistic mode: V holds the intermediate
+// model and the iterate handed out is the one played next, Proj[sigma V - ha x_last] (Eq. (3)).
 __global__ void __launch_bounds__(256) export_dense_kernel(const ExportArgs a)
 {
     __shared__ double p_sh[64];
-    __shared__ float s_sh[64];
+    __shared__ float s_sh[64], h_sh[64], f_sh[64];
     const int r = blockIdx.y;
     const int K = a.K;
     hedge_weights(a.L + (int64_t)r * K, K, a.eps, p_sh);
-    if (threadIdx.x < K) s_sh[threadIdx.x] = static_cast<const float *>(a.sigma)[(int64_t)r * K + threadIdx.x];
+    if (threadIdx.x < K) {
+        const int64_t q = (int64_t)r * K + threadIdx.x;
+        const float sg = static_cast<const float *>(a.sigma)[q];
+        float ha = 0.f, f = 1.f;
+        if (a.optimistic) {
+            ha = a.ha[q];
+            const double x2l = (double)a.x2last[a.x_shared ? 0 : r];
+            const double m = fma((double)ha * (double)ha, x2l,
+                                 fma(-2.0 * (double)ha, (double)a.hp[q], (double)sg * (double)sg * a.n2[q]));
+            const float mf = (float)m;
+            if (mf > a.D * a.D) f = a.D * __builtin_amdgcn_rsqf(mf);
+        }
+        s_sh[threadIdx.x] = sg; h_sh[threadIdx.x] = ha; f_sh[threadIdx.x] = f;
+    }
     __syncthreads();
     if (a.p && blockIdx.x == 0 && threadIdx.x < K) a.p[(int64_t)r * K + threadIdx.x] = (float)p_sh[threadIdx.x];
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= a.d) return;
+    const float xl = a.optimistic ? a.xlast[(a.x_shared ? 0 : (int64_t)r * a.d) + j] : 0.f;
     double acc = 0.0;
     for (int i = 0; i < K; ++i) {
-        const float w = s_sh[i] * a.V[((int64_t)r * K + i) * a.d + j];
+        float w = s_sh[i] * a.V[((int64_t)r * K + i) * a.d + j];
+        if (a.optimistic) w = f_sh[i] * fmaf(-h_sh[i], xl, w);
         if (a.W) a.W[((int64_t)r * K + i) * a.d + j] = w;
         acc += p_sh[i] * (double)w;
     }
@@ -181,6 +197,21 @@ __global__ void __launch_bounds__(256) ones_kernel(void *p, int64_t n, int is_do
     if (is_double) static_cast<double *>(p)[k] = 1.0; else static_cast<float *>(p)[k] = 1.0f;
 }
 
+// Lemma 1 / Theorem 1, one thread per run
+__global__ void __launch_bounds__(256) accel_bounds_kernel(const double *regret, int R, double t, double k,
+                                                           double alpha, double *out)
+{
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= R) return;
+    const double reg = regret[r] > 0.0 ? regret[r] : 0.0;
+    const double k1 = k + 1.0;
+    const double lo = k1 * t / (1.0 + k1 * sqrt(reg / (2.0 * t)));
+    out[4 * r + 0] = lo;
+    out[4 * r + 1] = k1 * t;
+    out[4 * r + 2] = lo / (t * (alpha * k + 1.0));
+    out[4 * r + 3] = k1 / (alpha * k + 1.0);
+}
+
 }  // namespace
 
 hipError_t launch_meta(const MetaArgs &a, int loss, hipStream_t s)
@@ -217,6 +248,14 @@ hipError_t launch_export(const ExportArgs &a, hipStream_t s)
         return hipGetLastError();
     }
     return hipSuccess;
+}
+
+hipError_t launch_accel_bounds(const double *regret, int R, int64_t t, int64_t k, double alpha, double *out,
+                               hipStream_t s)
+{
+    hipLaunchKernelGGL(accel_bounds_kernel, dim3((R + 255) / 256), dim3(256), 0, s, regret, R, (double)t,
+                       (double)k, alpha, out);
+    return hipGetLastError();
 }
 
 hipError_t launch_init_state(void *zero_base, size_t zero_bytes, void *sigma, int64_t n_sigma,

@@ -17,6 +17,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
     size_t off_V = 0, off_sigma = 0, off_n2 = 0, off_L = 0, off_regret = 0, off_eta = 0,
            off_seg = 0, off_Z = 0, off_X2 = 0, off_gram = 0, total = 0;
+    size_t off_ha = 0, off_hp = 0, off_xlast = 0, off_x2last = 0, off_G01 = 0;   // optimistic mode only
     size_t state_bytes = 0;   // [off_V, off_V + state_bytes) is zeroed by reset (V, sigma, n2, L, regret)
     int64_t n_sigma = 0;
     int RKp = 0;
@@ -30,7 +31,7 @@ int validate_and_layout(const oco_config *c, Layout *lay)
 {
     if (!c || !c->eta) return OCO_EINVAL;
     if (c->d <= 0 || c->K <= 0 || c->T <= 0 || c->R <= 0) return OCO_EINVAL;
-    if (c->reserved != 0 || c->n_max < 0) return OCO_EINVAL;
+    if ((c->optimistic != 0 && c->optimistic != 1) || c->n_max < 0) return OCO_EINVAL;
     if (!finite_pos(c->D) || !finite_pos(c->G) || !std::isfinite(c->eps) || c->eps < 0.0) return OCO_EINVAL;
     if (c->loss < OCO_LINEAR || c->loss > OCO_LOGISTIC) return OCO_EINVAL;
     if (c->x_shared != 0 && c->x_shared != 1) return OCO_EINVAL;
@@ -44,7 +45,7 @@ int validate_and_layout(const oco_config *c, Layout *lay)
     if (RK > (1 << 26)) return OCO_EUNSUPPORTED;
     if (c->sparse_nnz > 0) {
         if (c->sparse_nnz > OCO_MAX_NNZ || c->sparse_nnz > c->d) return OCO_EUNSUPPORTED;
-        if (!c->x_shared) return OCO_EUNSUPPORTED;
+        if (!c->x_shared || c->optimistic) return OCO_EUNSUPPORTED;
     } else if (!dense_supported(c->d)) {
         return OCO_EUNSUPPORTED;
     }
@@ -68,6 +69,13 @@ int validate_and_layout(const oco_config *c, Layout *lay)
     }
     l.off_L = off;       off += align_up(sizeof(double) * (size_t)RK, 256);
     l.off_regret = off;  off += align_up(sizeof(double) * (size_t)c->R, 256);
+    if (c->optimistic) {
+        const size_t nx = c->x_shared ? 1 : (size_t)c->R;
+        l.off_ha = off;      off += align_up(sizeof(float) * (size_t)RK, 256);
+        l.off_hp = off;      off += align_up(sizeof(float) * (size_t)RK, 256);
+        l.off_xlast = off;   off += align_up(sizeof(float) * nx * (size_t)c->d, 256);
+        l.off_x2last = off;  off += align_up(sizeof(float) * nx, 256);
+    }
     l.state_bytes = off;
     l.off_eta = off;     off += align_up(sizeof(float) * (size_t)c->K, 256);
     l.off_seg = off;     off += align_up(sizeof(int64_t) * OCO_MAX_SEGMENTS, 256);
@@ -75,6 +83,10 @@ int validate_and_layout(const oco_config *c, Layout *lay)
     if (c->sparse_nnz == 0) {
         l.off_X2 = off;
         off += align_up(sizeof(float) * (size_t)(c->x_shared ? 1 : c->R) * align_up(n_max, 64), 256);
+        if (c->optimistic) {
+            l.off_G01 = off;
+            off += align_up(sizeof(float) * (size_t)(c->x_shared ? 1 : c->R) * align_up(n_max, 64), 256);
+        }
     } else {
         l.off_gram = off;
         off += align_up(sparse_scratch_bytes(n_max), 256);
@@ -239,6 +251,12 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
         a.d = (int)c.d; a.K = (int)c.K; a.R = (int)c.R; a.t0 = t0; a.n = (int)n; a.D = (float)c.D;
         a.x_shared = c.x_shared;
         a.vec_ok = (c.d % 4 == 0) && !mis(rd->x, 16) && (c.x_shared || xrs % 4 == 0);
+        a.optimistic = c.optimistic;
+        if (c.optimistic) {
+            a.ha = st->at<float>(l.off_ha); a.hp = st->at<float>(l.off_hp);
+            a.g01 = st->at<float>(l.off_G01);
+            a.xlast = st->at<float>(l.off_xlast); a.x2last = st->at<float>(l.off_x2last);
+        }
         e = launch_dense_rounds(a, c.loss, st->stream);
     }
     if (e != hipSuccess) return OCO_EHIP;
@@ -266,6 +284,15 @@ int oco_regret(oco_state *st, double *out_host)
     return hipStreamSynchronize(st->stream) == hipSuccess ? OCO_OK : OCO_EHIP;
 }
 
+int oco_accel_bounds(oco_state *st, int64_t k, double alpha, double *out_dev)
+{
+    if (!st || !out_dev || k < 1 || !std::isfinite(alpha) || alpha < 0.0) return OCO_EINVAL;
+    if (reinterpret_cast<uintptr_t>(out_dev) & 7u) return OCO_EINVAL;
+    if (st->t_done <= 0) return OCO_ESEQ;
+    return launch_accel_bounds(st->at<double>(st->lay.off_regret), (int)st->cfg.R, st->t_done, k, alpha,
+                               out_dev, st->stream) == hipSuccess ? OCO_OK : OCO_EHIP;
+}
+
 int oco_cum_losses(oco_state *st, double *out_host)
 {
     if (!st || !out_host) return OCO_EINVAL;
@@ -288,6 +315,13 @@ int oco_get_state(oco_state *st, float *W_dev, float *p_dev, float *wbar_dev)
     a.W = W_dev; a.p = p_dev; a.wbar = wbar_dev;
     a.d = (int)st->cfg.d; a.K = (int)st->cfg.K; a.R = (int)st->cfg.R; a.RKp = st->lay.RKp;
     a.sparse = st->cfg.sparse_nnz > 0;
+    a.optimistic = st->cfg.optimistic;
+    if (a.optimistic) {
+        a.ha = st->at<float>(st->lay.off_ha); a.hp = st->at<float>(st->lay.off_hp);
+        a.xlast = st->at<float>(st->lay.off_xlast); a.x2last = st->at<float>(st->lay.off_x2last);
+        a.n2 = st->at<double>(st->lay.off_n2);
+        a.x_shared = st->cfg.x_shared; a.D = (float)st->cfg.D;
+    }
     return launch_export(a, st->stream) == hipSuccess ? OCO_OK : OCO_EHIP;
 }
 

@@ -41,6 +41,13 @@ struct DenseArgs {
     float D;
     int x_shared;
     int vec_ok;              // rows of x are 16-byte aligned and d % 4 == 0
+    // optimistic two-step update (Eq. (3)); V then holds the intermediate model w^
+    int optimistic;
+    float *ha;               // [R][K]  eta_i c_{t-1}^i: the hint is ha * x_{t-1}
+    float *hp;               // [R][K]  <w^_t, x_{t-1}>
+    float *g01;              // scratch like x2: <x_{t-1}, x_t> per round of this call
+    float *xlast;            // [1 or R][d]  last round row of the previous call (0 before round 0)
+    float *x2last;           // [1 or R]     its squared norm
 };
 hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s);
 bool dense_supported(int64_t d);
@@ -92,8 +99,16 @@ struct ExportArgs {
     float *W, *p, *wbar;     // any may be null
     int d, K, R, RKp;
     int sparse;
+    // optimistic (dense only): the exported iterate is Proj[sigma V - ha xlast]
+    int optimistic;
+    const float *ha, *hp, *xlast, *x2last;
+    const double *n2;
+    int x_shared;
+    float D;
 };
 hipError_t launch_export(const ExportArgs &a, hipStream_t s);
+hipError_t launch_accel_bounds(const double *regret, int R, int64_t t, int64_t k, double alpha, double *out,
+                               hipStream_t s);
 
 // fills `bytes` (a multiple of 16) of device memory with zero using a kernel,
 // and sets every sigma to 1

@@ -62,8 +62,16 @@ def test_workspace_bytes_is_zero_for_bad_configs():
         cfg, keep = _cfg(**bad)
         assert B.oco_workspace_bytes(cfg) == 0, bad
     cfg, keep = _cfg()
-    cfg.reserved = 1
+    cfg.optimistic = 2
     assert B.oco_workspace_bytes(cfg) == 0
+    cfg, keep = _cfg(d=1 << 20, nnz=8)
+    assert B.oco_workspace_bytes(cfg) > 0
+    cfg.optimistic = 1                              # the optimistic update is dense only
+    assert B.oco_workspace_bytes(cfg) == 0
+    plain, k1 = _cfg()
+    opt, k2 = _cfg()
+    opt.optimistic = 1
+    assert B.oco_workspace_bytes(opt) > B.oco_workspace_bytes(plain)
     assert B.lib().oco_workspace_bytes(None) == 0
 
 

@@ -96,6 +96,66 @@ def test_sparse_rounds_match_the_oracle(over):
     _check(wl, data, _gpu(wl, data), norm_every=0, label="c5 %s" % over)
 
 
+# the optimistic two-step update (Eq. (3), last-gradient hint): K = 1 is the paper's method
+OPTIMISTIC = [
+    ("c1", dict(T=300, d=10, R=2)),
+    ("c1", dict(T=257, d=64, R=3, x_shared=False)),
+    ("c2", dict(T=500, R=3, d=100, K=1, eta=(0.05,))),
+    ("c2", dict(T=400, R=3, d=100, K=15)),
+    ("c2", dict(T=200, R=2, d=131, K=5)),
+    ("c3", dict(T=600, R=3, d=1000, K=17, seg_len=100)),
+    ("c3", dict(T=300, R=2, d=2048, K=3, seg_len=64, eta=(0.01, 0.3, 5.0))),
+    ("c4", dict(T=301, R=3, d=4096, K=16)),
+    ("c4", dict(T=150, R=2, d=3000, K=2, eta=(0.5, 20.0))),
+]
+
+
+@pytest.mark.parametrize("name,over", OPTIMISTIC)
+def test_optimistic_rounds_match_the_oracle(name, over):
+    wl = WL.make(name, optimistic=True, **over)
+    data = WL.generate(wl)
+    print("case optimistic", name, over, flush=True)
+    _check(wl, data, _gpu(wl, data), label="optimistic %s %s" % (name, over))
+
+
+@pytest.mark.parametrize("name,over,chunks", [
+    ("c2", dict(T=300, R=3, d=100, K=15), (1, 7, 64)),
+    ("c3", dict(T=300, R=2, d=1000, K=5, seg_len=90), (13, 128)),
+    ("c4", dict(T=130, R=2, d=4096, K=4), (3, 100)),
+])
+def test_optimistic_results_do_not_depend_on_how_the_horizon_is_cut(name, over, chunks):
+    """The hint of a call's first round needs the previous call's last round row: it is kept in
+    the workspace, and the state after T rounds is bit-identical under any split."""
+    wl = WL.make(name, optimistic=True, **over)
+    data = WL.generate(wl)
+    whole = _gpu(wl, data)
+    for c in chunks:
+        print("case optimistic", name, over, "chunk", c, flush=True)
+        part = _gpu(wl, data, chunk=c, n_max=c)
+        for k in ("regret", "L", "W", "p", "wbar"):
+            assert np.array_equal(whole[k], part[k]), (k, c)
+
+
+def test_accel_bounds_match_the_oracle():
+    """Lemma 1 / Theorem 1 from the regret on the device, against the reference's closed forms."""
+    wl = WL.make("c3", T=500, R=7, d=130, K=5, seg_len=100)
+    data = WL.generate(wl)
+    sim = B.Simulation(wl, data)
+    with pytest.raises(B.OcoError):
+        sim.accel_bounds(4, 0.1)                      # no rounds yet
+    sim.run(0, 300)
+    reg = sim.regret()
+    for k, alpha in ((1, 0.0), (4, 0.05), (9, 0.5)):
+        got = sim.accel_bounds(k, alpha)
+        want = np.array([_oracle().accel_bounds(reg[r], 300, k, alpha) for r in range(wl.R)])
+        np.testing.assert_allclose(got, want, rtol=1e-14, atol=0)
+    with pytest.raises(B.OcoError):
+        sim.accel_bounds(0, 0.1)
+    with pytest.raises(B.OcoError):
+        sim.accel_bounds(3, -1.0)
+    sim.close()
+
+
 @pytest.mark.parametrize("lpw", [8, 16, 32, 64])
 def test_sparse_rounds_for_every_workgroup_share(lpw, monkeypatch):
     """The sparse kernel gives a workgroup 8, 16, 32 or 64 learners (chosen from R*K; small
@@ -253,20 +313,22 @@ def test_user_stream_is_honoured():
 
 # ---------------------------------------------------------------- full sizes ----
 FULL = [
-    ("c1", None, None),
-    ("c2", None, None),
-    ("c3", [0, 37, 101, 128, 199, 255], None),
-    ("c4", [0, 1, 333, 512, 800, 1023], None),
-    ("c5", [0, 15], 1000),
+    ("c1", None, None, False),
+    ("c2", None, None, False),
+    ("c3", [0, 37, 101, 128, 199, 255], None, False),
+    ("c4", [0, 1, 333, 512, 800, 1023], None, False),
+    ("c5", [0, 15], 1000, False),
+    ("c2", None, None, True),
+    ("c3", [0, 64, 255], None, True),
 ]
 
 
-@pytest.mark.parametrize("name,runs,norm_every", FULL)
-def test_benchmark_configurations_match_the_oracle(name, runs, norm_every):
+@pytest.mark.parametrize("name,runs,norm_every,optimistic", FULL)
+def test_benchmark_configurations_match_the_oracle(name, runs, norm_every, optimistic):
     """The five benchmark configurations at full size, in the launch configuration the bench
     times (one oco_run_rounds call for the whole horizon); the oracle recomputes every output
-    of the listed runs."""
-    wl = WL.make(name)
+    of the listed runs.  c2 and c3 also with the optimistic update."""
+    wl = WL.make(name, optimistic=optimistic)
     print("generating", name, flush=True)
     data = WL.generate(wl)
     print("gpu", name, flush=True)
