@@ -237,3 +237,43 @@ def run_slice(wl: Workload, data: Dict[str, Optional[np.ndarray]], runs) -> tupl
     if data["x"] is not None and not wl.x_shared:
         sub["x"] = np.ascontiguousarray(data["x"][runs])
     return replace(wl, R=int(runs.size)), sub
+
+
+# ---------------------------------------------------------------------------
+# Synthetic draft / target distributions for the verification step of Algorithm 1
+# (stand-ins for the token distributions of a draft and a target LLM; no method
+# arithmetic here: logits, softmax, and the draws the method consumes as inputs).
+SPECDEC = {
+    "v1": dict(B=96, k=4, V=1000),        # small: the CPU reference finishes in seconds
+    "v2": dict(B=1024, k=4, V=32000),     # Llama-2 / Vicuna vocabulary
+    "v3": dict(B=256, k=4, V=151936),     # Qwen3 vocabulary
+}
+
+
+def specdec_inputs(B: int, k: int, V: int, seed: int = 0, sharp: float = 2.5, noise: float = 0.6,
+                   exact_frac: float = 0.0):
+    """Returns dict(p [B][k+1][V] f32, q [B][k][V] f32, tok [B][k] i32, r [B][k] f32, u [B] u32).
+    Target logits are sharp * N(0,1) (a few dominant tokens, a long tail); the draft's are the
+    target's plus noise * N(0,1); a fraction exact_frac of the draft rows equals the target row
+    (always accepted).  tok[b][j] is drawn from q[b][j]."""
+    rng = np.random.Generator(np.random.Philox(key=[(seed & 0xFFFFFFFF) << 32 | 0x5D, B * 1000003 + k * 1009 + V]))
+    p = np.empty((B, k + 1, V), np.float32)
+    q = np.empty((B, k, V), np.float32)
+    tok = np.empty((B, k), np.int32)
+    step = max(1, (1 << 24) // ((k + 1) * V))
+    for b0 in range(0, B, step):
+        b1 = min(B, b0 + step)
+        lp = sharp * rng.standard_normal((b1 - b0, k + 1, V))
+        lq = lp[:, :k] + noise * rng.standard_normal((b1 - b0, k, V))
+        same = rng.random((b1 - b0, k)) < exact_frac
+        lq[same] = lp[:, :k][same]
+        pp = np.exp(lp - lp.max(axis=2, keepdims=True)); pp /= pp.sum(axis=2, keepdims=True)
+        qq = np.exp(lq - lq.max(axis=2, keepdims=True)); qq /= qq.sum(axis=2, keepdims=True)
+        p[b0:b1] = pp
+        q[b0:b1] = qq
+        cdf = np.cumsum(qq, axis=2)
+        draw = rng.random((b1 - b0, k, 1)) * cdf[:, :, -1:]
+        tok[b0:b1] = np.minimum((cdf < draw).sum(axis=2), V - 1)
+    r = rng.random((B, k), dtype=np.float32)
+    u = rng.integers(0, 1 << 32, size=B, dtype=np.uint64).astype(np.uint32)
+    return dict(p=p, q=q, tok=tok, r=r, u=u)
