@@ -20,7 +20,8 @@ OCO_OK, OCO_EINVAL, OCO_ESEQ, OCO_ERANGE, OCO_ENOMEM, OCO_EHIP, OCO_ENOCOMP, OCO
 LOSS_ID = {"linear": 0, "squared": 1, "logistic": 2}
 EXPORTS = ("oco_step_grid", "oco_paper_num_learners", "oco_workspace_bytes", "oco_create",
            "oco_set_comparator", "oco_run_rounds", "oco_regret", "oco_get_state",
-           "oco_cum_losses", "oco_accel_bounds", "oco_reset", "oco_set_timing", "oco_last_timing", "oco_rounds_done", "oco_destroy", "oco_strerror")
+           "oco_cum_losses", "oco_accel_bounds", "oco_reset", "oco_set_timing", "oco_last_timing", "oco_rounds_done", "oco_destroy", "oco_strerror",
+           "sd_verify", "sd_acceptance", "sd_strerror")
 
 
 class OcoConfig(C.Structure):
@@ -83,6 +84,12 @@ def lib() -> C.CDLL:
         L.oco_set_timing.argtypes = [vp, C.c_int]
         L.oco_last_timing.restype = C.c_int
         L.oco_last_timing.argtypes = [vp, vp]
+        L.sd_verify.restype = C.c_int
+        L.sd_verify.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
+        L.sd_acceptance.restype = C.c_int
+        L.sd_acceptance.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+        L.sd_strerror.restype = C.c_char_p
+        L.sd_strerror.argtypes = [C.c_int]
         L.oco_rounds_done.restype = i64
         L.oco_rounds_done.argtypes = [vp]
         L.oco_destroy.restype = None
@@ -296,3 +303,34 @@ class Simulation:
             self.close()
         except Exception:
             pass
+
+
+# ---------------------------------------------------------------------------
+# Verification step of speculative decoding (include/specdec.h)
+class SdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, lib().sd_strerror(status).decode(), status))
+
+
+def _stream_ptr(stream):
+    return None if stream is None else stream.cuda_stream
+
+
+def sd_verify(p, q, tok, r, u, n_out, next_out, stream=None) -> None:
+    """p [B][k+1][V] f32, q [B][k][V] f32, tok [B][k] i32, r [B][k] f32, u [B] u32 (as int32/uint32
+    torch tensor), n_out / next_out [B] i32 -- all CUDA tensors.  Asynchronous."""
+    B, k, V = q.shape
+    assert tuple(p.shape) == (B, k + 1, V) and tuple(tok.shape) == (B, k) and tuple(r.shape) == (B, k)
+    rc = lib().sd_verify(_dptr(p), _dptr(q), _dptr(tok), _dptr(r), _dptr(u), B, k, V,
+                         _dptr(n_out), _dptr(next_out), _stream_ptr(stream))
+    if rc != 0:
+        raise SdError(rc, "sd_verify")
+
+
+def sd_acceptance(p, q, acc_out, stream=None) -> None:
+    """acc_out [B][k] f64 = sum_x min(p, q) per draft position.  Asynchronous."""
+    B, k, V = q.shape
+    rc = lib().sd_acceptance(_dptr(p), _dptr(q), B, k, V, _dptr(acc_out), _stream_ptr(stream))
+    if rc != 0:
+        raise SdError(rc, "sd_acceptance")

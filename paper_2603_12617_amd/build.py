@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liboco.so")
-SOURCES = ["oco_api.hip", "dense_rounds.hip", "sparse_rounds.hip", "meta.hip"]
+SOURCES = ["oco_api.hip", "dense_rounds.hip", "sparse_rounds.hip", "meta.hip", "specdec.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -24,7 +24,8 @@ def sources_newer_than_lib() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    files = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", "oco.h")]
+    files = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [
+        os.path.join(HERE, "..", "include", h) for h in ("oco.h", "specdec.h")]
     return any(os.path.getmtime(f) > t for f in files)
 
 
@@ -44,7 +45,7 @@ def build(verbose: bool = False, extra_flags=(), lib: str = LIB, tag: str = "") 
             raise RuntimeError("hipcc failed on " + src)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=5) as ex:
         objs = list(ex.map(one, SOURCES))
     cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)

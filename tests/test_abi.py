@@ -15,9 +15,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    src = open(os.path.join(ROOT, "include", "oco.h")).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(oco_[a-z_]+)\s*\(", src)))
+    names = set()
+    for header, prefix in (("oco.h", "oco"), ("specdec.h", "sd")):
+        src = open(os.path.join(ROOT, "include", header)).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names |= set(re.findall(r"\b(%s_[a-z_]+)\s*\(" % prefix, src))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_function():
@@ -106,3 +109,17 @@ def test_create_rejects_bad_arguments_on_the_host():
     assert L.oco_last_timing(None, None) == B.OCO_EINVAL
     assert L.oco_rounds_done(None) == B.OCO_EINVAL
     L.oco_destroy(None)
+
+
+def test_specdec_host_validation():
+    L = B.lib()
+    one = C.c_void_p(256)          # any non-null, aligned address: rejected before it is touched
+    assert L.sd_verify(None, one, one, one, one, 1, 1, 8, one, one, None) == -1
+    assert L.sd_verify(one, one, one, one, one, 0, 1, 8, one, one, None) == -1
+    assert L.sd_verify(one, one, one, one, one, 1, 65, 8, one, one, None) == -2
+    assert L.sd_verify(one, one, one, one, one, 1, 4, 262145, one, one, None) == -2
+    assert L.sd_verify(C.c_void_p(258), one, one, one, one, 1, 4, 8, one, one, None) == -1
+    assert L.sd_acceptance(one, None, 1, 1, 8, one, None) == -1
+    assert L.sd_acceptance(one, one, 1, 1, 8, C.c_void_p(260), None) == -1
+    assert L.sd_acceptance(one, one, 1, 0, 8, one, None) == -1
+    assert L.sd_strerror(0) == b"ok" and L.sd_strerror(-7) == b"unknown status"

@@ -1,0 +1,106 @@
+"""Parity of the verification kernels (through the C ABI) with the CPU reference: accepted
+lengths and resampled tokens bit-exact (the draw is defined in integer arithmetic), acceptance
+rates to float64 rounding."""
+import numpy as np
+import pytest
+
+from paper_2603_12617_amd import binding as B
+from paper_2603_12617_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle():
+    from oracle import specdec_oracle as SO
+    return SO
+
+
+def _gpu(d, want_acc=True):
+    import torch
+    dev = torch.device("cuda:0")
+    p, q = torch.from_numpy(d["p"]).to(dev), torch.from_numpy(d["q"]).to(dev)
+    tok, r = torch.from_numpy(d["tok"]).to(dev), torch.from_numpy(d["r"]).to(dev)
+    u = torch.from_numpy(d["u"].view(np.int32)).to(dev)
+    Bn, k, V = d["q"].shape
+    n = torch.full((Bn,), -7, dtype=torch.int32, device=dev)
+    nx = torch.full((Bn,), -7, dtype=torch.int32, device=dev)
+    B.sd_verify(p, q, tok, r, u, n, nx)
+    acc = None
+    if want_acc:
+        acc = torch.empty((Bn, k), dtype=torch.float64, device=dev)
+        B.sd_acceptance(p, q, acc)
+        acc = acc.cpu().numpy()
+    torch.cuda.synchronize()
+    return n.cpu().numpy(), nx.cpu().numpy(), acc
+
+
+CASES = [
+    dict(B=96, k=4, V=1000),
+    dict(B=33, k=1, V=7),
+    dict(B=40, k=7, V=1024),                 # exactly one segment
+    dict(B=40, k=3, V=1025),                 # one token into the second segment
+    dict(B=25, k=5, V=5000, noise=0.05),     # good draft: long accepted runs
+    dict(B=25, k=5, V=4099, noise=3.0),      # bad draft: early rejections, odd V (scalar loads)
+    dict(B=16, k=64, V=300, exact_frac=0.9),  # the largest k
+    dict(B=6, k=2, V=262144),                # the largest V
+    dict(B=50, k=4, V=32000, exact_frac=0.5),
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_verify_and_acceptance_match_the_oracle(case):
+    d = WL.specdec_inputs(seed=11, **case)
+    print("case", case, flush=True)
+    n, nx, acc = _gpu(d)
+    rn, rnx = _oracle().verify(d["p"], d["q"], d["tok"], d["r"], d["u"])
+    assert np.array_equal(n, rn), np.nonzero(n != rn)
+    assert np.array_equal(nx, rnx), np.nonzero(nx != rnx)
+    np.testing.assert_allclose(acc, _oracle().acceptance(d["p"], d["q"]), rtol=1e-13, atol=1e-15)
+    k = case["k"]
+    print("  accepted-length histogram", np.bincount(rn, minlength=k + 1))
+
+
+def test_degenerate_rows():
+    V, k = 2000, 3
+    d = WL.specdec_inputs(B=8, k=k, V=V, seed=3)
+    # step 0: draft == target everywhere -> all accepted, draw from p_k
+    d["q"][0] = d["p"][0, :k]
+    # step 1: residual vanishes at 2^-40 although the test rejects (p < q by one float32 ulp at the token only)
+    d["q"][1] = d["p"][1, :k]
+    t = int(d["tok"][1, 0]); d["r"][1, 0] = np.float32(0.99999994)
+    d["q"][1, 0, t] = np.nextafter(d["p"][1, 0, t], np.float32(2.0))
+    # step 2: one-hot target, draft token elsewhere with p = 0 -> rejected at once, next = the hot token
+    d["p"][2] = 0.0; d["p"][2, :, 77] = 1.0
+    d["tok"][2, 0] = 5
+    # step 3: tokens out of range are clamped
+    d["tok"][3] = [-3, V + 10, 7]
+    # step 4: all-zero target rows (not a distribution): n = 0 unless q(tok) = 0, next = 0
+    d["p"][4] = 0.0
+    # step 5: u extremes
+    d["u"][5] = 0xFFFFFFFF
+    d["u"][6] = 0
+    n, nx, _ = _gpu(d, want_acc=False)
+    rn, rnx = _oracle().verify(d["p"], d["q"], d["tok"], d["r"], d["u"])
+    assert np.array_equal(n, rn) and np.array_equal(nx, rnx), (n, rn, nx, rnx)
+    assert n[0] == k and n[2] == 0 and nx[2] == 77 and nx[4] == 0
+
+
+def test_full_size_vocabularies_sampled_against_the_oracle():
+    """The two benchmark shapes, in the launch configuration the bench times; the oracle
+    recomputes a sample of the steps one by one."""
+    for name in ("v2", "v3"):
+        shape = WL.SPECDEC[name]
+        print("generating", name, shape, flush=True)
+        d = WL.specdec_inputs(seed=1, **shape)
+        n, nx, acc = _gpu(d)
+        idx = np.linspace(0, shape["B"] - 1, 24).astype(int)
+        sub = {k: v[idx] for k, v in d.items()}
+        rn, rnx = _oracle().verify(sub["p"], sub["q"], sub["tok"], sub["r"], sub["u"])
+        assert np.array_equal(n[idx], rn) and np.array_equal(nx[idx], rnx)
+        np.testing.assert_allclose(acc[idx], _oracle().acceptance(sub["p"], sub["q"]), rtol=1e-13)
+        # properties that hold at any size
+        assert ((0 <= n) & (n <= shape["k"])).all() and ((0 <= nx) & (nx < shape["V"])).all()
+        assert ((acc > 0) & (acc <= 1 + 1e-6)).all()
+        # accepted-length distribution against Eq. (1): P(n >= 1) = mean acceptance of position 0
+        se = np.sqrt(0.25 / shape["B"])
+        assert abs((n >= 1).mean() - acc[:, 0].mean()) < 5 * se
