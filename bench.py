@@ -85,6 +85,66 @@ def run_workload(name, steps, warmup, WL, B, torch, keep=None, optimistic=False)
     return out
 
 
+def run_specdec(name, reps, WL, B, torch, with_cpu=False):
+    """The verification step of Algorithm 1 (next row of the scope table) on one synthetic batch:
+    sd_verify and sd_acceptance timed per launch with events on the launch stream.  Between
+    launches a 1 GiB buffer is read through, so that no row of the previous launch is still in
+    the 256 MB Infinity Cache (a write pass alone would leave dirty lines whose write-back then
+    competes with the timed kernel's reads)."""
+    import numpy as np
+    shape = WL.SPECDEC[name]
+    d = WL.specdec_inputs(seed=1, **shape)
+    dev = torch.device("cuda:0")
+    p, q = torch.from_numpy(d["p"]).to(dev), torch.from_numpy(d["q"]).to(dev)
+    tok, r = torch.from_numpy(d["tok"]).to(dev), torch.from_numpy(d["r"]).to(dev)
+    u = torch.from_numpy(d["u"].view(np.int32)).to(dev)
+    Bn, k, V = d["q"].shape
+    n = torch.empty((Bn,), dtype=torch.int32, device=dev)
+    nx = torch.empty_like(n)
+    acc = torch.empty((Bn, k), dtype=torch.float64, device=dev)
+    flush = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+    tv, ta = [], []
+    for rep in range(reps + 1):
+        flush.sum()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        B.sd_verify(p, q, tok, r, u, n, nx)
+        e[1].record()
+        flush.sum()
+        e2 = torch.cuda.Event(enable_timing=True)
+        e2.record()
+        B.sd_acceptance(p, q, acc)
+        e[2].record()
+        torch.cuda.synchronize()
+        if rep:                                   # first launch is the warm-up
+            tv.append(e[0].elapsed_time(e[1]))
+            ta.append(e2.elapsed_time(e[2]))
+    nn = n.cpu().numpy()
+    rows = float(((nn < k) * 2 + (nn >= k)).sum())
+    bytes_v = rows * V * 4 + Bn * k * 20.0        # rows needed + gathered scalars (tok, r, p, q) + outputs
+    bytes_a = float(Bn) * k * 2 * V * 4
+    mv, ma = sum(tv) / len(tv), sum(ta) / len(ta)
+    out = {"shape": shape, "mean_accepted": float(nn.mean()),
+           "verify": {"ms": mv, "steps_per_s": Bn / (mv * 1e-3),
+                      "roofline": {"bound": "hbm", "achieved": bytes_v / (mv * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                                   "unit": "GB/s", "frac": bytes_v / (mv * 1e-3) / 1e9 / PEAK_HBM_GBS}},
+           "acceptance": {"ms": ma,
+                          "roofline": {"bound": "hbm", "achieved": bytes_a / (ma * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                                       "unit": "GB/s", "frac": bytes_a / (ma * 1e-3) / 1e9 / PEAK_HBM_GBS}}}
+    if with_cpu:
+        from oracle import specdec_oracle as SO
+        m = min(Bn, 256)
+        t0 = time.perf_counter()
+        rn, rnx = SO.verify(d["p"][:m], d["q"][:m], d["tok"][:m], d["r"][:m], d["u"][:m])
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": m / dt, "unit": "steps/s", "cores": 1, "kind": "oracle",
+                               "sample": "%d of %d steps, %.2f s wall" % (m, Bn, dt)}
+        out["parity_exact"] = bool((rn == nn[:m]).all() and (rnx == nx.cpu().numpy()[:m]).all())
+    del p, q, flush
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(wl, data, WL):
     """The fp64 reference as it stands, one run per thread, on a bounded sample."""
     from oracle import oracle as O
@@ -115,7 +175,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="c4", choices=sorted(DESCR))
+    ap.add_argument("--config", default="c4", choices=sorted(DESCR) + ["v2", "v3"])
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     ap.add_argument("--copy-probe", action="store_true",
@@ -142,6 +202,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4}))
+        return 0
+
+    if a.config in ("v2", "v3"):       # the verification kernels alone (used for their rocprofv3 summaries)
+        print(json.dumps({"workload": "specdec " + a.config, **run_specdec(a.config, a.steps, WL, B, torch)}))
         return 0
 
     keep = {}
@@ -194,6 +258,8 @@ def main():
             others[name + "_optimistic"] = {"value": r["value"], "ms_per_step": r["ms_per_step"],
                                             "round_kernel_ms": r["round_kernel_ms"],
                                             "meta_kernel_ms": r["meta_kernel_ms"]}
+        for name in ("v2", "v3"):          # verification step of Algorithm 1 on synthetic distributions
+            others["specdec_" + name] = run_specdec(name, 5, WL, B, torch, with_cpu=not a.no_cpu)
         line["other_workloads"] = others
 
     print(json.dumps(line))

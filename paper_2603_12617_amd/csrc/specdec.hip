@@ -3,8 +3,10 @@
 //
 // Both kernels stream rows of V probabilities from HBM and are bound by that traffic.
 // sd_verify reads, per step, 2k gathered scalars and then only the rows it needs: p and q at
-// the first rejected position (or p at position k).  One workgroup per step; the row is read
-// once, summed per 1024-token segment as 64-bit integers (units of 2^-40: integer sums do not
+// the first rejected position (or p at position k).  One workgroup per step (several resident
+// per compute unit, so that one step's gather and search latencies hide behind the others'
+// streaming); the row is read once with 16-byte loads, summed per 1024-token
+// segment as 64-bit integers (units of 2^-40: integer sums do not
 // depend on the order, so the draw is reproducible bit for bit), the segment holding the
 // target mass is found from the segment sums, and only that segment is read again to find
 // the token.
@@ -14,15 +16,9 @@
 
 namespace {
 
-constexpr int kThreads = 1024;
-constexpr int kWaves = kThreads / 64;
-constexpr int kMaxSeg = SD_MAX_V / kThreads;
+// The verify kernel comes in two workgroup sizes: 256 threads (eight steps resident per compute
+// unit) for batches that fill the chip, 1024 threads when there are few steps.
 typedef unsigned long long u64;
-
-__device__ __forceinline__ u64 to_fixed(float m)
-{
-    return __float2ull_rz(m * 0x1p40f);           // exact scaling, truncation
-}
 
 __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int mask)
 {
@@ -45,12 +41,46 @@ __device__ __forceinline__ u64 shfl_up_u64(u64 v, int delta)
     return ((u64)hi << 32) | lo;
 }
 
+// the four residual masses of tokens x .. x+3 (x a multiple of 4), in units of 2^-40, as
+// integer-valued floats: scaling by 2^40 is exact and v_trunc drops the fraction
+__device__ __forceinline__ void load_mass(const float *pr, const float *qr, int x, int V, int vec_ok, float (&f)[4])
+{
+    float pv[4] = {0.f, 0.f, 0.f, 0.f}, qv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (vec_ok) {
+        if (x < V) {
+            const float4 a = *reinterpret_cast<const float4 *>(pr + x);
+            pv[0] = a.x; pv[1] = a.y; pv[2] = a.z; pv[3] = a.w;
+            if (qr) {
+                const float4 c = *reinterpret_cast<const float4 *>(qr + x);
+                qv[0] = c.x; qv[1] = c.y; qv[2] = c.z; qv[3] = c.w;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (x + e < V) { pv[e] = pr[x + e]; if (qr) qv[e] = qr[x + e]; }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) f[e] = truncf((qr ? fmaxf(0.f, pv[e] - qv[e]) : pv[e]) * 0x1p40f);
+}
+
+__device__ __forceinline__ double shfl_xor_f64(double v, int mask)
+{
+    const u64 b = (u64)__double_as_longlong(v);
+    return __longlong_as_double((long long)shfl_xor_u64(b, mask));
+}
+
+template <int kThreads>
 __global__ void __launch_bounds__(kThreads) sd_verify_kernel(const float *p, const float *q, const int32_t *tok,
                                                              const float *r, const uint32_t *u, int k, int V,
-                                                             int32_t *n_out, int32_t *next_out)
+                                                             int vec_ok, int32_t *n_out, int32_t *next_out)
 {
+    constexpr int kWaves = kThreads / 64;
+    constexpr int kSeg = 4 * kThreads;            // tokens per segment: four per thread
+    constexpr int kMaxSeg = SD_MAX_V / kSeg;
     __shared__ int n_sh, seg_sh, next_sh;
-    __shared__ u64 seg[kMaxSeg];
+    constexpr int kUnroll = 4;
+    __shared__ u64 seg[kMaxSeg + kUnroll];
     __shared__ u64 wtot[kWaves];
     __shared__ u64 z_sh, base_sh, target_sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -73,20 +103,31 @@ __global__ void __launch_bounds__(kThreads) sd_verify_kernel(const float *p, con
     const int n = n_sh;
     const float *pr = p + (b * (k + 1) + n) * V;
     const float *qr = n < k ? q + (b * k + n) * V : nullptr;
-    const int nseg = (V + kThreads - 1) / kThreads;
+    const int nseg = (V + kSeg - 1) / kSeg;
 
     for (int attempt = 0; attempt < 2; ++attempt) {
         for (int s = tid; s < nseg; s += kThreads) seg[s] = 0;
         __syncthreads();
-        // ---- one pass over the row: integer mass of every 1024-token segment ---------------
-        for (int s = 0; s < nseg; ++s) {
-            const int x = s * kThreads + tid;
-            float m = 0.f;
-            if (x < V) m = qr ? fmaxf(0.f, pr[x] - qr[x]) : pr[x];
-            u64 f = to_fixed(m);
+        // ---- one pass over the row: integer mass of every segment of kSeg tokens ------------
+        // (a wavefront's share of a segment is < 2^49 units, so float64 sums of the integer
+        // masses are exact and their order is immaterial)
+        for (int s0 = 0; s0 < nseg; s0 += kUnroll) {       // kUnroll segments (2 kUnroll loads) in flight
+            float f[kUnroll][4];
 #pragma unroll
-            for (int sh = 32; sh >= 1; sh >>= 1) f += shfl_xor_u64(f, sh);
-            if (lane == 0 && f) atomicAdd(&seg[s], f);
+            for (int w = 0; w < kUnroll; ++w)                   // past the row: zeros
+                load_mass(pr, qr, (s0 + w) * kSeg + tid * 4, V, vec_ok, f[w]);
+            double t[kUnroll];
+#pragma unroll
+            for (int w = 0; w < kUnroll; ++w)
+                t[w] = ((double)f[w][0] + (double)f[w][1]) + ((double)f[w][2] + (double)f[w][3]);
+#pragma unroll
+            for (int sh = 32; sh >= 1; sh >>= 1)
+#pragma unroll
+                for (int w = 0; w < kUnroll; ++w) t[w] += shfl_xor_f64(t[w], sh);
+            if (lane == 0)
+#pragma unroll
+                for (int w = 0; w < kUnroll; ++w)
+                    if (t[w] != 0.0) atomicAdd(&seg[s0 + w], (u64)t[w]);   // s0 + w < nseg + kUnroll: seg has the room
         }
         __syncthreads();
         // ---- total mass, target, and the segment that holds it (wavefront 0) ---------------
@@ -108,7 +149,7 @@ __global__ void __launch_bounds__(kThreads) sd_verify_kernel(const float *p, con
             const u64 Z = bcast_u64(incl, 63);
             const u64 target = __umul64hi(Z, (u64)u[b] << 32);       // floor(Z u / 2^32) < Z
             const u64 excl = incl - run;
-            // first segment whose inclusive prefix exceeds the target
+            // the first segment whose inclusive prefix exceeds the target
             int found = -1;
             u64 base = 0;
 #pragma unroll
@@ -130,12 +171,14 @@ __global__ void __launch_bounds__(kThreads) sd_verify_kernel(const float *p, con
     }
     // ---- second look at one segment: the token at which the prefix passes the target --------
     {
-        const int s = seg_sh;
-        const int x = s * kThreads + tid;
-        float m = 0.f;
-        if (x < V) m = qr ? fmaxf(0.f, pr[x] - qr[x]) : pr[x];
-        const u64 f = to_fixed(m);
-        u64 incl = f;
+        const int x = seg_sh * kSeg + tid * 4;
+        float ff[4];
+        load_mass(pr, qr, x, V, vec_ok, ff);
+        u64 f[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f[e] = (u64)ff[e];
+        const u64 mine = (f[0] + f[1]) + (f[2] + f[3]);
+        u64 incl = mine;
 #pragma unroll
         for (int sh = 1; sh < 64; sh <<= 1) {
             const u64 o = shfl_up_u64(incl, sh);
@@ -143,9 +186,15 @@ __global__ void __launch_bounds__(kThreads) sd_verify_kernel(const float *p, con
         }
         if (lane == 63) wtot[wave] = incl;
         __syncthreads();
-        u64 off = base_sh;
-        for (int w = 0; w < wave; ++w) off += wtot[w];
-        if (off + incl > target_sh && off + incl - f <= target_sh) next_sh = x;     // exactly one thread
+        u64 before = base_sh + incl - mine;
+        for (int w = 0; w < wave; ++w) before += wtot[w];
+        const u64 target = target_sh;
+        if (before <= target && before + mine > target) {          // exactly one thread
+            int e = 0;
+            u64 c = before + f[0];
+            while (c <= target) { ++e; c += f[e]; }
+            next_sh = x + e;
+        }
         __syncthreads();
         if (tid == 0) { n_out[b] = n; next_out[b] = next_sh; }
     }
@@ -165,7 +214,18 @@ __global__ void __launch_bounds__(256) sd_acceptance_kernel(const float *p, cons
         const float4 *p4 = reinterpret_cast<const float4 *>(pr);
         const float4 *q4 = reinterpret_cast<const float4 *>(qr);
         const int n4 = V / 4;
-        for (int e = threadIdx.x; e < n4; e += 256) {
+        int e = threadIdx.x;
+        for (; e + 768 < n4; e += 1024) {          // four independent 16-byte loads per stream in flight
+            float4 a[4], c[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { a[w] = p4[e + 256 * w]; c[w] = q4[e + 256 * w]; }
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                a0 += (double)fminf(a[w].x, c[w].x) + (double)fminf(a[w].y, c[w].y);
+                a1 += (double)fminf(a[w].z, c[w].z) + (double)fminf(a[w].w, c[w].w);
+            }
+        }
+        for (; e < n4; e += 256) {
             const float4 a = p4[e], c = q4[e];
             a0 += (double)fminf(a.x, c.x) + (double)fminf(a.y, c.y);
             a1 += (double)fminf(a.z, c.z) + (double)fminf(a.w, c.w);
@@ -208,8 +268,14 @@ int sd_verify(const float *p_dev, const float *q_dev, const int32_t *tok_dev, co
         return SD_EINVAL;
     const int rc = check_sizes(B, k, V);
     if (rc != SD_OK) return rc;
-    hipLaunchKernelGGL(sd_verify_kernel, dim3((unsigned)B), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
-                       p_dev, q_dev, tok_dev, r_dev, u_dev, (int)k, (int)V, n_dev, next_dev);
+    const int vec_ok = (V % 4 == 0) && !misaligned(p_dev, 16) && !misaligned(q_dev, 16);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (B >= 1024)
+        hipLaunchKernelGGL(sd_verify_kernel<256>, dim3((unsigned)B), dim3(256), 0, s, p_dev, q_dev, tok_dev, r_dev,
+                           u_dev, (int)k, (int)V, vec_ok, n_dev, next_dev);
+    else
+        hipLaunchKernelGGL(sd_verify_kernel<1024>, dim3((unsigned)B), dim3(1024), 0, s, p_dev, q_dev, tok_dev, r_dev,
+                           u_dev, (int)k, (int)V, vec_ok, n_dev, next_dev);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_EHIP;
 }
 

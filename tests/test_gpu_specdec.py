@@ -44,6 +44,8 @@ CASES = [
     dict(B=16, k=64, V=300, exact_frac=0.9),  # the largest k
     dict(B=6, k=2, V=262144),                # the largest V
     dict(B=50, k=4, V=32000, exact_frac=0.5),
+    dict(B=1100, k=3, V=2500),               # >= 1024 steps: the 256-thread kernel
+    dict(B=1030, k=2, V=1023, noise=2.0),
 ]
 
 
