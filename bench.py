@@ -131,6 +131,11 @@ def run_specdec(name, reps, WL, B, torch, with_cpu=False):
            "acceptance": {"ms": ma,
                           "roofline": {"bound": "hbm", "achieved": bytes_a / (ma * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                                        "unit": "GB/s", "frac": bytes_a / (ma * 1e-3) / 1e9 / PEAK_HBM_GBS}}}
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        tr = json.load(open(tpath))
+        out["verify"]["roofline"]["traffic"] = tr.get(name + "_verify")
+        out["acceptance"]["roofline"]["traffic"] = tr.get(name + "_acceptance")
     if with_cpu:
         from oracle import specdec_oracle as SO
         m = min(Bn, 256)
