@@ -45,7 +45,10 @@ template <> struct DenseCfg<2>  { static constexpr int MAXW = 16, RT = 16; };
 template <> struct DenseCfg<4>  { static constexpr int MAXW = 16, RT = 16; };
 template <> struct DenseCfg<8>  { static constexpr int MAXW = 16, RT = 8; };
 template <> struct DenseCfg<16> { static constexpr int MAXW = 16, RT = 2; };
-template <> struct DenseCfg<32> { static constexpr int MAXW = 8,  RT = 4; };
+#ifndef OCO_MAXW32
+#define OCO_MAXW32 12
+#endif
+template <> struct DenseCfg<32> { static constexpr int MAXW = OCO_MAXW32, RT = 2; };
 template <> struct DenseCfg<64> { static constexpr int MAXW = 8,  RT = 2; };
 constexpr int kRing = 3;   // LDS tiles
 
@@ -413,334 +416,6 @@ dense_rounds_kernel(const DenseArgs a)
     }
 }
 
-// Two interleaved wave_sum()s: the same adds in the same order for each value, with the
-// wait states a DPP operand needs filled by the other value's instruction.
-__device__ __forceinline__ void wave_sum2(float &u, float &v)
-{
-    u += dpp_term<0xB1, 0xF>(u);  v += dpp_term<0xB1, 0xF>(v);
-    u += dpp_term<0x4E, 0xF>(u);  v += dpp_term<0x4E, 0xF>(v);
-    u += dpp_term<0x141, 0xF>(u); v += dpp_term<0x141, 0xF>(v);
-    u += dpp_term<0x140, 0xF>(u); v += dpp_term<0x140, 0xF>(v);
-    asm("s_nop 1\n\t"
-        "v_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
-        "v_add_f32_dpp %1, %1, %1 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
-        "s_nop 0\n\t"
-        "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-        "v_add_f32_dpp %1, %1, %1 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
-        "s_nop 0"
-        : "+v"(u), "+v"(v));
-    u = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(u), 63));
-    v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
-}
-
-// Variant for large d: one wavefront owns TWO base learners of a run.  The two learners read
-// the same round rows, so each LDS read of x feeds two learners, and a wavefront carries two
-// independent dependent chains (prediction -> slope -> step -> norm -> projection), which
-// fill each other's latencies.  x is not kept in registers between rounds here: a round reads
-// x_t (for the step) and x_{t+1} (for the next prediction) from LDS, in chunks, one chunk
-// ahead of the arithmetic.  Per learner the arithmetic and its order are those of
-// dense_rounds_kernel, so the two kernels give bit-identical results.  Tasks per run: the
-// ceil(K/2) learner pairs, then the comparator.
-template <int NPL, int LOSS>
-__global__ void __launch_bounds__(DenseCfg<NPL>::MAXW * kWave)
-dense_pair_kernel(const DenseArgs a)
-{
-    using C = DenseCfg<NPL>;
-    constexpr int VW = NPL >= 4 ? 4 : NPL;
-    constexpr int NV = NPL / VW;
-    constexpr int DP = NPL * kWave;
-    constexpr int RT = C::RT;
-    constexpr int TILE = RT * DP;
-    constexpr int RING_ROUNDS = kRing * RT;
-    constexpr int NI = TILE / 4 / kWave;
-    constexpr int CH = 1;                       // LDS reads of x_t (and of x_{t+1}) per chunk
-    constexpr int NCH = NV / CH;
-    using V = typename VecT<VW>::type;
-
-    extern __shared__ float4 smem4[];
-    float *ring = reinterpret_cast<float *>(smem4);
-
-    const int tid = threadIdx.x;
-    const int nthreads = blockDim.x;
-    const int wpb = nthreads >> 6;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n = a.n;
-    const int d = a.d;
-    const int K = a.K;
-    const int P = (K + 1) / 2;                  // learner pairs per run; task P is the comparator
-
-    int r, sidx;
-    bool active;
-    if (a.x_shared) {
-        const int64_t q = (int64_t)blockIdx.x * wpb + wave;
-        active = q < (int64_t)a.R * (P + 1);
-        r = active ? (int)(q / (P + 1)) : 0;
-        sidx = active ? (int)(q % (P + 1)) : 0;
-    } else {
-        r = blockIdx.y;
-        sidx = blockIdx.x * wpb + wave;
-        active = sidx <= P;
-        if (!active) sidx = 0;
-    }
-    const bool is_cmp = active && sidx == P;
-    const float *xg = a.x_shared ? a.x : a.x + (int64_t)blockIdx.y * a.x_run_stride;
-
-    auto issue_tile = [&](int k) {
-        float *dst = ring + (k % kRing) * TILE;
-        if (a.vec_ok) {
-            for (int ii = wave; ii < NI; ii += wpb) {
-                const int e = ii * kWave + lane;
-                const int rr = e / (DP / 4), j4 = e % (DP / 4);
-                const int tt = k * RT + rr;
-                if (tt < n && j4 * 4 < d)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void *)(xg + (int64_t)tt * d + j4 * 4),
-                        (__attribute__((address_space(3))) void *)(dst + ii * 4 * kWave), 16, 0, 0);
-            }
-        } else {
-            for (int e = tid; e < TILE; e += nthreads) {
-                const int rr = e / DP, j = e % DP;
-                const int tt = k * RT + rr;
-                if (tt < n && j < d) dst[e] = xg[(int64_t)tt * d + j];
-            }
-        }
-    };
-
-    for (int e = tid; e < kRing * TILE / 4; e += nthreads) smem4[e] = make_float4(0.f, 0.f, 0.f, 0.f);
-    __syncthreads();
-    const int ntiles = (n + RT - 1) / RT;
-    issue_tile(0);
-    if (ntiles > 1) issue_tile(1);
-    __syncthreads();
-
-    auto xrow = [&](int t) { return reinterpret_cast<const V *>(ring + (t % RING_ROUNDS) * DP); };
-    const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
-
-    if (!active) {
-        for (int k = 0; k < ntiles; ++k) {
-            if (k + 2 < ntiles) issue_tile(k + 2);
-            __syncthreads();
-        }
-        return;
-    }
-
-    if (is_cmp) {
-        // ---- comparator wavefront: z_t = <u_t, x_t>, no step (as in dense_rounds_kernel) -------
-        float uv[NV][VW];
-        auto load_u = [&](int sg) {
-            const float *src = a.u + ((int64_t)r * a.S + sg) * d;
-#pragma unroll
-            for (int m = 0; m < NV; ++m)
-#pragma unroll
-                for (int e = 0; e < VW; ++e) {
-                    const int j = (m * kWave + lane) * VW + e;
-                    uv[m][e] = j < d ? src[j] : 0.f;
-                }
-        };
-        auto dot_u = [&](const V *xr) {
-            float acc[VW];
-#pragma unroll
-            for (int e = 0; e < VW; ++e) acc[e] = 0.f;
-#pragma unroll
-            for (int m = 0; m < NV; ++m) {
-                float xv[VW];
-                unpack<VW>(xr[m * kWave + lane], xv);
-#pragma unroll
-                for (int e = 0; e < VW; ++e) acc[e] = fmaf(uv[m][e], xv[e], acc[e]);
-                if (NV > 4 && (m & 3) == 3) __builtin_amdgcn_sched_barrier(0);
-            }
-            return wave_sum(combine<VW>(acc));
-        };
-        int seg = 0;
-        while (seg + 1 < a.S && a.seg_start[seg + 1] <= a.t0) ++seg;
-        int64_t next_seg = seg + 1 < a.S ? a.seg_start[seg + 1] : INT64_MAX;
-        load_u(seg);
-        float z = dot_u(xrow(0)), zreg = 0.f;
-        float *zrow = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)K * a.zl.zs_i;
-        for (int k = 0; k < ntiles; ++k) {
-            if (k + 2 < ntiles) issue_tile(k + 2);
-            const int rmax = min(RT, n - k * RT);
-#pragma unroll 1
-            for (int rr = 0; rr < rmax; ++rr) {
-                const int t = k * RT + rr;
-                if (lane == (t & 63)) zreg = z;
-                if (a.t0 + t + 1 == next_seg) {
-                    ++seg;
-                    next_seg = seg + 1 < a.S ? a.seg_start[seg + 1] : INT64_MAX;
-                    load_u(seg);
-                }
-                z = dot_u(xrow(t + 1));
-                if ((t & 63) == 63 || t == n - 1) {
-                    const int tb = t & ~63;
-                    if (tb + lane <= t) zrow[(int64_t)(tb + lane) * a.zl.zs_t] = zreg;
-                }
-            }
-            __syncthreads();
-        }
-        return;
-    }
-
-    // ---- a pair of learners ------------------------------------------------------------------
-    const int i0 = 2 * sidx;
-    const bool two = i0 + 1 < K;                // K odd: the last wavefront has one learner
-    const int i1 = two ? i0 + 1 : i0;           // (the second slot then mirrors the first, unstored)
-    float w0[NV][VW], w1[NV][VW];
-    float sg0 = a.sigma[(int64_t)r * K + i0], sg1 = a.sigma[(int64_t)r * K + i1];
-    double n20 = a.n2[(int64_t)r * K + i0], n21 = a.n2[(int64_t)r * K + i1];
-    const float eta0 = a.eta[i0], eta1 = a.eta[i1];
-    float qv0, qv1, z0, z1, zreg0 = 0.f, zreg1 = 0.f, yreg = 0.f, x2reg = 0.f;
-    {
-        const float *s0 = a.V + ((int64_t)r * K + i0) * d, *s1 = a.V + ((int64_t)r * K + i1) * d;
-        float ac0[VW], ac1[VW];
-#pragma unroll
-        for (int e = 0; e < VW; ++e) ac0[e] = ac1[e] = 0.f;
-#pragma unroll
-        for (int m = 0; m < NV; ++m) {
-            float xv[VW];
-            unpack<VW>(xrow(0)[m * kWave + lane], xv);
-#pragma unroll
-            for (int e = 0; e < VW; ++e) {
-                const int j = (m * kWave + lane) * VW + e;
-                w0[m][e] = j < d ? s0[j] : 0.f;
-                w1[m][e] = j < d ? s1[j] : 0.f;
-                ac0[e] = fmaf(w0[m][e], xv[e], ac0[e]);
-                ac1[e] = fmaf(w1[m][e], xv[e], ac1[e]);
-            }
-        }
-        qv0 = combine<VW>(ac0); qv1 = combine<VW>(ac1);
-        wave_sum2(qv0, qv1);
-        z0 = sg0 * qv0; z1 = sg1 * qv1;
-    }
-    const float *x2row = a.x2 + (a.x_shared ? 0 : (int64_t)r * a.x2_run_stride);
-    const int phase = (int)(a.t0 & 63);
-    const float D = a.D;
-    const float D2 = D * D;
-    float *zrow0 = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)i0 * a.zl.zs_i;
-    float *zrow1 = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)i1 * a.zl.zs_i;
-
-    auto round = [&](int t) {
-        if ((t & 63) == 0) {
-            if (yrow) yreg = (t + lane < n) ? yrow[t + lane] : 0.f;
-            x2reg = (t + lane < n) ? x2row[t + lane] : 0.f;
-        }
-        const float yt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(yreg), t & 63));
-        const float x2t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x2reg), t & 63));
-        if (lane == (t & 63)) { zreg0 = z0; zreg1 = z1; }
-        if (sg0 < kFoldLo || sg0 > kFoldHi) {
-#pragma unroll
-            for (int m = 0; m < NV; ++m)
-#pragma unroll
-                for (int e = 0; e < VW; ++e) w0[m][e] *= sg0;
-            n20 *= (double)sg0 * (double)sg0;
-            qv0 = z0;
-            sg0 = 1.f;
-        }
-        if (sg1 < kFoldLo || sg1 > kFoldHi) {
-#pragma unroll
-            for (int m = 0; m < NV; ++m)
-#pragma unroll
-                for (int e = 0; e < VW; ++e) w1[m][e] *= sg1;
-            n21 *= (double)sg1 * (double)sg1;
-            qv1 = z1;
-            sg1 = 1.f;
-        }
-        const float b0 = (eta0 * slope<LOSS>(z0, yt)) * fast_rcp(sg0);
-        const float b1 = (eta1 * slope<LOSS>(z1, yt)) * fast_rcp(sg1);
-        // the pass: step both learners along x_t, dot the stepped vectors with x_{t+1}
-        float aq0[VW], aq1[VW];
-#pragma unroll
-        for (int e = 0; e < VW; ++e) aq0[e] = aq1[e] = 0.f;
-        {
-            const V *xc = xrow(t), *xn = xrow(t + 1);
-#pragma unroll
-            for (int m = 0; m < NV; ++m) {
-                float xcv[VW], xnv[VW];
-                unpack<VW>(xc[m * kWave + lane], xcv);
-                unpack<VW>(xn[m * kWave + lane], xnv);
-#pragma unroll
-                for (int e = 0; e < VW; ++e) {
-                    const float u0 = fmaf(-b0, xcv[e], w0[m][e]);
-                    const float u1 = fmaf(-b1, xcv[e], w1[m][e]);
-                    w0[m][e] = u0;
-                    w1[m][e] = u1;
-                    aq0[e] = fmaf(u0, xnv[e], aq0[e]);
-                    aq1[e] = fmaf(u1, xnv[e], aq1[e]);
-                }
-            }
-            // issue order for the scheduler: two chunks of LDS reads ahead, then per chunk the
-            // FMAs of one chunk and the reads of the chunk after next
-            __builtin_amdgcn_sched_group_barrier(0x100, 2 * CH, 0);
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                __builtin_amdgcn_sched_group_barrier(0x100, 2 * CH, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 4 * CH * VW, 0);
-            }
-        }
-        const float qo0 = qv0, qo1 = qv1;
-        qv0 = combine<VW>(aq0); qv1 = combine<VW>(aq1);
-        if (((phase + t) & 63) == 63) {                  // re-measure ||v||^2 exactly
-            float an0[VW], an1[VW];
-#pragma unroll
-            for (int e = 0; e < VW; ++e) an0[e] = an1[e] = 0.f;
-#pragma unroll
-            for (int m = 0; m < NV; ++m)
-#pragma unroll
-                for (int e = 0; e < VW; ++e) {
-                    an0[e] = fmaf(w0[m][e], w0[m][e], an0[e]);
-                    an1[e] = fmaf(w1[m][e], w1[m][e], an1[e]);
-                }
-            float s0 = combine<VW>(an0), s1 = combine<VW>(an1);
-            wave_sum2(s0, s1);
-            n20 = (double)s0; n21 = (double)s1;
-        } else {
-            const double bd0 = (double)b0, bd1 = (double)b1;
-            n20 = fma(bd0 * bd0, (double)x2t, fma(-2.0 * bd0, (double)qo0, n20));
-            n21 = fma(bd1 * bd1, (double)x2t, fma(-2.0 * bd1, (double)qo1, n21));
-            n20 = n20 > 0.0 ? n20 : 0.0;
-            n21 = n21 > 0.0 ? n21 : 0.0;
-        }
-        wave_sum2(qv0, qv1);                             // <v, x_{t+1}> of both learners
-        const float nr0 = (float)n20, nr1 = (float)n21;
-        if (sg0 * sg0 * nr0 > D2) sg0 = D * __builtin_amdgcn_rsqf(nr0);
-        if (sg1 * sg1 * nr1 > D2) sg1 = D * __builtin_amdgcn_rsqf(nr1);
-        z0 = sg0 * qv0; z1 = sg1 * qv1;
-        if ((t & 63) == 63 || t == n - 1) {
-            const int tb = t & ~63;
-            if (tb + lane <= t) {
-                zrow0[(int64_t)(tb + lane) * a.zl.zs_t] = zreg0;
-                if (two) zrow1[(int64_t)(tb + lane) * a.zl.zs_t] = zreg1;
-            }
-        }
-    };
-
-    for (int k = 0; k < ntiles; ++k) {
-        if (k + 2 < ntiles) issue_tile(k + 2);
-        const int rmax = min(RT, n - k * RT);
-#pragma unroll 1
-        for (int rr = 0; rr < rmax; ++rr) round(k * RT + rr);
-        __syncthreads();
-    }
-
-    {
-        float *d0 = a.V + ((int64_t)r * K + i0) * d, *d1 = a.V + ((int64_t)r * K + i1) * d;
-#pragma unroll
-        for (int m = 0; m < NV; ++m)
-#pragma unroll
-            for (int e = 0; e < VW; ++e) {
-                const int j = (m * kWave + lane) * VW + e;
-                if (j < d) {
-                    d0[j] = w0[m][e];
-                    if (two) d1[j] = w1[m][e];
-                }
-            }
-        if (lane == 0) {
-            a.sigma[(int64_t)r * K + i0] = sg0; a.n2[(int64_t)r * K + i0] = n20;
-            if (two) { a.sigma[(int64_t)r * K + i1] = sg1; a.n2[(int64_t)r * K + i1] = n21; }
-        }
-    }
-}
-
 // ||x_t||^2 of every round row and, if g01 is given, <x_{t-1}, x_t> (x_{-1} = the last row of the
 // previous call, kept in xlast): one wavefront per row, fixed summation order.
 __global__ void __launch_bounds__(256) xnorm2_kernel(const float *x, int64_t run_stride, int nruns,
@@ -776,35 +451,12 @@ __global__ void __launch_bounds__(256) keep_last_row_kernel(const float *x, int6
     if (j == 0) x2last[rr] = x2[(int64_t)rr * x2_stride + n - 1];
 }
 
-// One wavefront per learner, or one per pair of learners (plain update only).  Measured on
-// MI355X the pairs win for 1024 < d <= 2048 (about 12 %); for d <= 1024 the single-learner
-// kernel has the better occupancy, and for d > 2048 the pair's 128 state registers leave too
-// few for the rest.  OCO_DENSE_PAIR=0/1 forces the choice (d > 512 only) for tuning and tests.
-bool use_pairs(const DenseArgs &a, int npl)
-{
-    if (a.optimistic || a.K < 2) return false;
-    if (const char *ov = getenv("OCO_DENSE_PAIR")) return atoi(ov) != 0 && npl >= 16;
-    return npl == 32;
-}
-
 template <int NPL>
 hipError_t launch_npl(const DenseArgs &a, int loss, hipStream_t s)
 {
     using C = DenseCfg<NPL>;
     const size_t smem = sizeof(float) * kRing * C::RT * NPL * kWave;
     void (*kern)(const DenseArgs) = nullptr;
-    bool pair = false;
-    if constexpr (NPL >= 16) pair = use_pairs(a, NPL);
-    if (pair) {
-        if constexpr (NPL >= 16) {
-            switch (loss) {
-                case 0: kern = dense_pair_kernel<NPL, 0>; break;
-                case 1: kern = dense_pair_kernel<NPL, 1>; break;
-                case 2: kern = dense_pair_kernel<NPL, 2>; break;
-                default: return hipErrorInvalidValue;
-            }
-        }
-    } else
     switch (loss * 2 + (a.optimistic ? 1 : 0)) {
         case 0: kern = dense_rounds_kernel<NPL, 0, false>; break;
         case 1: kern = dense_rounds_kernel<NPL, 0, true>; break;
@@ -831,10 +483,15 @@ hipError_t launch_npl(const DenseArgs &a, int loss, hipStream_t s)
     // mostly fill each other's stalls (the round is a dependent chain), beyond that they
     // share the issue slots.
     auto g = [](double l) { return l <= 1.0 ? 1.0 : (l <= 4.0 ? 1.0 + 0.1 * (l - 1.0) : 1.3 + 0.35 * (l - 4.0)); };
-    const int per_run = pair ? (a.K + 1) / 2 + 1 : a.K + 1;      // wavefronts per run
+    const int per_run = a.K + 1;
     int best = 0;
     double best_cost = 0.0;
     for (int w = C::MAXW; w >= 1; --w) {
+        // Candidates: multiples of four (a workgroup's wavefronts are dealt to the four SIMDs in
+        // turn, and with a barrier per tile the fullest SIMD sets the pace: other sizes measured
+        // 20-60 % slower), sizes that divide a run's tasks evenly, and tiny workgroups for tiny runs.
+        const bool candidate = w % 4 == 0 || (w >= 3 && per_run % w == 0) || (per_run < 4 && w == per_run);
+        if (!candidate) continue;
         int c = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, reinterpret_cast<const void *>(kern),
                                                          w * kWave, smem) != hipSuccess || c <= 0)

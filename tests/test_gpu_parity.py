@@ -96,30 +96,6 @@ def test_sparse_rounds_match_the_oracle(over):
     _check(wl, data, _gpu(wl, data), norm_every=0, label="c5 %s" % over)
 
 
-@pytest.mark.parametrize("name,over", [
-    ("c4", dict(T=200, R=3, d=2048, K=16)),
-    ("c3", dict(T=260, R=2, d=1500, K=5, seg_len=64)),     # odd K: the last wavefront holds one learner
-    ("c2", dict(T=150, R=2, d=1100, K=2)),                 # per-run streams
-    ("c4", dict(T=130, R=2, d=4096, K=4)),
-])
-def test_paired_and_single_learner_kernels_agree_bitwise(name, over, monkeypatch):
-    """For 1024 < d <= 2048 a wavefront carries two learners (one LDS read of x feeds both); per
-    learner the arithmetic and its order are those of the one-learner kernel.  OCO_DENSE_PAIR
-    forces either kernel."""
-    wl = WL.make(name, **over)
-    data = WL.generate(wl)
-    monkeypatch.setenv("OCO_DENSE_PAIR", "0")
-    single = _gpu(wl, data)
-    monkeypatch.setenv("OCO_DENSE_PAIR", "1")
-    paired = _gpu(wl, data)
-    for k in ("regret", "L", "W", "p", "wbar"):
-        assert np.array_equal(single[k], paired[k]), k
-    part = _gpu(wl, data, chunk=37, n_max=37)
-    for k in ("regret", "L", "W", "p", "wbar"):
-        assert np.array_equal(paired[k], part[k]), k
-    _check(wl, data, paired, label="paired %s %s" % (name, over))
-
-
 # the optimistic two-step update (Eq. (3), last-gradient hint): K = 1 is the paper's method
 OPTIMISTIC = [
     ("c1", dict(T=300, d=10, R=2)),
