@@ -258,7 +258,7 @@ def main():
             r = run_workload(name, 2, 1, WL, B, torch)
             others[name] = {"value": r["value"], "ms_per_step": r["ms_per_step"],
                             "round_kernel_ms": r["round_kernel_ms"], "meta_kernel_ms": r["meta_kernel_ms"]}
-        for name in ("c3", "c4"):          # the optimistic two-step update (Eq. (3)) on the same streams
+        for name in ("c3", "c4", "c5"):    # the optimistic two-step update (Eq. (3)) on the same streams
             r = run_workload(name, 2, 1, WL, B, torch, optimistic=True)
             others[name + "_optimistic"] = {"value": r["value"], "ms_per_step": r["ms_per_step"],
                                             "round_kernel_ms": r["round_kernel_ms"],

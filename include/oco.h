@@ -91,8 +91,7 @@ typedef struct {
                              Predictions, losses and regret are those of the played iterates
                              w_t; oco_get_state returns the iterates that would be played
                              next.  K = 1 is the paper's method; for K > 1 Hedge weighs the
-                             played iterates (not analysed in the paper).  Dense rounds only
-                             (OCO_EUNSUPPORTED with sparse_nnz > 0)                       */
+                             played iterates (not analysed in the paper)                  */
     int64_t n_max;        /* largest n of any oco_run_rounds call; 0 means T          */
 } oco_config;
 

@@ -139,6 +139,19 @@ __global__ void __launch_bounds__(256) export_dense_kernel(const ExportArgs a)
 
 // sparse layout: V[d][RKp], sigma double [RKp].  64x64 transpose through LDS:
 // rows = coordinates, columns = learners.
+// optimistic mode: scale f and hint coefficient ha of the iterate played next, Proj[sigma v - ha x_last]
+__device__ __forceinline__ void played_scale(const ExportArgs &a, int q, double sg, float &f, float &ha)
+{
+    f = 1.f;
+    ha = 0.f;
+    if (!a.optimistic) return;
+    ha = a.ha[q];
+    const double m = fma((double)ha * (double)ha, (double)a.x2last[q],
+                         fma(-2.0 * (double)ha, (double)a.hp[q], sg * sg * a.n2[q]));
+    const float mf = (float)m;
+    if (mf > a.D * a.D) f = a.D * __builtin_amdgcn_rsqf(mf);
+}
+
 __global__ void __launch_bounds__(256) export_sparse_W_kernel(const ExportArgs a)
 {
     __shared__ float tile[64][65];
@@ -148,10 +161,15 @@ __global__ void __launch_bounds__(256) export_sparse_W_kernel(const ExportArgs a
     const int nq = a.R * a.K;
     const double *sg = static_cast<const double *>(a.sigma);
     const float s = (q0 + tx < nq) ? (float)sg[q0 + tx] : 0.f;
+    float f = 1.f, ha = 0.f;
+    if (q0 + tx < nq) played_scale(a, q0 + tx, sg[q0 + tx], f, ha);
     for (int row = ty; row < 64; row += 4) {
         const int64_t j = j0 + row;
         float v = 0.f;
-        if (j < a.d && q0 + tx < nq) v = (float)((double)a.V[j * a.RKp + q0 + tx] * (double)s);
+        if (j < a.d && q0 + tx < nq) {
+            v = (float)((double)a.V[j * a.RKp + q0 + tx] * (double)s);
+            if (a.optimistic) v = f * fmaf(-ha, a.xlast[j], v);
+        }
         tile[row][tx] = v;
     }
     __syncthreads();
@@ -166,10 +184,15 @@ __global__ void __launch_bounds__(256) export_sparse_p_wbar_kernel(const ExportA
 {
     __shared__ double p_sh[64];
     __shared__ double s_sh[64];
+    __shared__ float f_sh[64], h_sh[64];
     const int r = blockIdx.y;
     const int K = a.K;
     hedge_weights(a.L + (int64_t)r * K, K, a.eps, p_sh);
-    if (threadIdx.x < K) s_sh[threadIdx.x] = static_cast<const double *>(a.sigma)[r * K + threadIdx.x];
+    if (threadIdx.x < K) {
+        const double sg = static_cast<const double *>(a.sigma)[r * K + threadIdx.x];
+        s_sh[threadIdx.x] = sg;
+        played_scale(a, r * K + threadIdx.x, sg, f_sh[threadIdx.x], h_sh[threadIdx.x]);
+    }
     __syncthreads();
     if (a.p && blockIdx.x == 0 && threadIdx.x < K) a.p[(int64_t)r * K + threadIdx.x] = (float)p_sh[threadIdx.x];
     if (!a.wbar) return;
@@ -177,7 +200,8 @@ __global__ void __launch_bounds__(256) export_sparse_p_wbar_kernel(const ExportA
     if (j >= a.d) return;
     double acc = 0.0;
     for (int i = 0; i < K; ++i) {
-        const float w = (float)((double)a.V[j * a.RKp + r * K + i] * (double)(float)s_sh[i]);
+        float w = (float)((double)a.V[j * a.RKp + r * K + i] * (double)(float)s_sh[i]);
+        if (a.optimistic) w = f_sh[i] * fmaf(-h_sh[i], a.xlast[j], w);
         acc += p_sh[i] * (double)w;
     }
     a.wbar[(int64_t)r * a.d + j] = (float)acc;

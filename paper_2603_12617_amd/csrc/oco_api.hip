@@ -18,6 +18,7 @@ struct Layout {
     size_t off_V = 0, off_sigma = 0, off_n2 = 0, off_L = 0, off_regret = 0, off_eta = 0,
            off_seg = 0, off_Z = 0, off_X2 = 0, off_gram = 0, total = 0;
     size_t off_ha = 0, off_hp = 0, off_xlast = 0, off_x2last = 0, off_G01 = 0;   // optimistic mode only
+    size_t off_lastcol = 0, off_lastval = 0;                                       // optimistic + sparse
     size_t state_bytes = 0;   // [off_V, off_V + state_bytes) is zeroed by reset (V, sigma, n2, L, regret)
     int64_t n_sigma = 0;
     int RKp = 0;
@@ -45,7 +46,7 @@ int validate_and_layout(const oco_config *c, Layout *lay)
     if (RK > (1 << 26)) return OCO_EUNSUPPORTED;
     if (c->sparse_nnz > 0) {
         if (c->sparse_nnz > OCO_MAX_NNZ || c->sparse_nnz > c->d) return OCO_EUNSUPPORTED;
-        if (!c->x_shared || c->optimistic) return OCO_EUNSUPPORTED;
+        if (!c->x_shared) return OCO_EUNSUPPORTED;
     } else if (!dense_supported(c->d)) {
         return OCO_EUNSUPPORTED;
     }
@@ -69,7 +70,14 @@ int validate_and_layout(const oco_config *c, Layout *lay)
     }
     l.off_L = off;       off += align_up(sizeof(double) * (size_t)RK, 256);
     l.off_regret = off;  off += align_up(sizeof(double) * (size_t)c->R, 256);
-    if (c->optimistic) {
+    if (c->optimistic && c->sparse_nnz > 0) {
+        l.off_ha = off;      off += align_up(sizeof(float) * (size_t)l.RKp, 256);
+        l.off_hp = off;      off += align_up(sizeof(float) * (size_t)l.RKp, 256);
+        l.off_x2last = off;  off += align_up(sizeof(float) * (size_t)l.RKp, 256);
+        l.off_lastcol = off; off += align_up(sizeof(int32_t) * OCO_MAX_NNZ, 256);
+        l.off_lastval = off; off += align_up(sizeof(float) * OCO_MAX_NNZ, 256);
+        l.off_xlast = off;   off += align_up(sizeof(float) * (size_t)c->d, 256);
+    } else if (c->optimistic) {
         const size_t nx = c->x_shared ? 1 : (size_t)c->R;
         l.off_ha = off;      off += align_up(sizeof(float) * (size_t)RK, 256);
         l.off_hp = off;      off += align_up(sizeof(float) * (size_t)RK, 256);
@@ -239,6 +247,12 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
         a.d = (int)c.d; a.K = (int)c.K; a.R = (int)c.R; a.nnz = c.sparse_nnz; a.RKp = l.RKp;
         a.t0 = t0; a.n = (int)n; a.D = c.D; a.prefetch = 1;
         a.scratch = st->at<char>(l.off_gram);
+        a.optimistic = c.optimistic;
+        if (c.optimistic) {
+            a.ha = st->at<float>(l.off_ha); a.hp = st->at<float>(l.off_hp); a.hx = st->at<float>(l.off_x2last);
+            a.last_col = st->at<int32_t>(l.off_lastcol); a.last_val = st->at<float>(l.off_lastval);
+            a.xlast_dense = st->at<float>(l.off_xlast);
+        }
         e = launch_sparse_rounds(a, c.loss, st->stream);
     } else {
         DenseArgs a{};

@@ -73,6 +73,14 @@ struct SparseArgs {
     double D;
     int prefetch;            // 1: idle wavefronts warm L2 with the next window's rows
     void *scratch;           // sparse_scratch_bytes(n_max) bytes: per-window Gram data of the call
+    // optimistic two-step update (Eq. (3)); V then holds the intermediate model w^
+    int optimistic;
+    float *ha;               // [RKp]  eta_i c_{t-1}^i: the hint is ha * x_{t-1}
+    float *hp;               // [RKp]  <w^_t, x_{t-1}>
+    float *hx;               // [RKp]  ||x_{t-1}||^2 (the same for all learners; kept per lane)
+    int32_t *last_col;       // [OCO_MAX_NNZ]  last round row of the previous call (zeros before round 0)
+    float *last_val;         // [OCO_MAX_NNZ]
+    float *xlast_dense;      // [d]  the same row scattered into a dense vector (for the export)
 };
 hipError_t launch_sparse_rounds(const SparseArgs &a, int loss, hipStream_t s);
 size_t sparse_scratch_bytes(int64_t n_max);
@@ -99,7 +107,8 @@ struct ExportArgs {
     float *W, *p, *wbar;     // any may be null
     int d, K, R, RKp;
     int sparse;
-    // optimistic (dense only): the exported iterate is Proj[sigma V - ha xlast]
+    // optimistic: the exported iterate is Proj[sigma V - ha xlast].  Dense: xlast [1 or R][d],
+    // x2last [1 or R].  Sparse: xlast [d] (dense copy of the last sparse row), x2last [RKp].
     int optimistic;
     const float *ha, *hp, *xlast, *x2last;
     const double *n2;

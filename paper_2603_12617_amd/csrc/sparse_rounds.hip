@@ -113,6 +113,7 @@ struct WinRec {
     int off[kSpWaves + 1];              // phase C: wavefront c owns perm[off[c] .. off[c+1])
     int ng;                             // number of set mask bits
     int pad[32 - kSpWaves - 2];
+    float g01[kWin];                    // <x_{t-1}, x_t> (optimistic update only; x_{-1}: previous call's last row)
     unsigned short perm[kWin * OCO_MAX_NNZ];   // entries of the window sorted by column (stable)
     float g[kWin * (kWin - 1) / 2];     // <x_s, x_t> of the set mask bits, in (s, t) order
 };
@@ -120,7 +121,8 @@ static_assert(sizeof(WinRec) % 128 == 0, "window records stay 256-byte aligned")
 constexpr int kRecHeadInts = (int)(offsetof(WinRec, perm) / 4);
 
 __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, const float *val, int nnz,
-                                                          WinPlan plan, WinRec *recs)
+                                                          WinPlan plan, WinRec *recs, int optimistic,
+                                                          const int32_t *last_col, const float *last_val)
 {
     __shared__ int cs[kWin * OCO_MAX_NNZ];
     __shared__ float vs[kWin * OCO_MAX_NNZ];
@@ -166,6 +168,23 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
             const int t = (int)(((unsigned)sorted[k2] * mdiv) >> 18);
             if (t > s) atomicOr(&mk[s][t >> 5], 1u << (t & 31));
         }
+    }
+    if (optimistic && threadIdx.x >= 64 && threadIdx.x < 64 + kWin) {
+        // <x_{t-1}, x_t> for the hint of round t: the row before the window's first is the call's
+        // previous row, or the row kept from the previous call
+        const int t = threadIdx.x - 64;
+        float g = 0.f;
+        if (t < wl) {
+            const int32_t *pc = t > 0 ? nullptr : (ws > 0 ? col + (int64_t)(ws - 1) * nnz : last_col);
+            const float *pv = t > 0 ? nullptr : (ws > 0 ? val + (int64_t)(ws - 1) * nnz : last_val);
+            for (int a2 = 0; a2 < nnz; ++a2) {
+                const int ca = t > 0 ? cs[(t - 1) * nnz + a2] : pc[a2];
+                const float va = t > 0 ? vs[(t - 1) * nnz + a2] : pv[a2];
+                for (int b2 = 0; b2 < nnz; ++b2)
+                    if (cs[t * nnz + b2] == ca) g = fmaf(va, vs[t * nnz + b2], g);
+            }
+        }
+        rec.g01[t] = g;
     }
     if (threadIdx.x <= kSpWaves) {
         // equal shares of the sorted entries, cut only where the column changes
@@ -261,7 +280,7 @@ template <int LPW> struct Chain {
     float bw[kWin][LPW];           // step sizes b_t of the window
 };
 
-template <int LOSS, int LPW>
+template <int LOSS, int LPW, bool OPT>
 __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const SparseArgs a, WinPlan plan, int wbeg, int wend)
 {
     constexpr int EPI = kWave / LPW;
@@ -294,6 +313,11 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     asm volatile("" : "+v"(eta_r), "+v"(sigma), "+v"(n2));
     double sd2 = sigma * sigma;
     float sf = (float)sigma, isf = __builtin_amdgcn_rcpf(sf);
+    // optimistic update (Eq. (3)): hint ha * x_{t-1}, hp = <w^_t, x_{t-1}>, x2p = ||x_{t-1}||^2
+    float ha = 0.f, hp = 0.f, x2p = 0.f;
+    if (OPT && chain) { ha = a.ha[q]; hp = a.hp[q]; x2p = a.hx[q]; }
+    if (OPT) asm volatile("" : "+v"(ha), "+v"(hp), "+v"(x2p));
+    const float Df = (float)a.D, D2f = Df * Df;
 
     stage_window(stage[0], a, recs[wbeg], plan.start(wbeg), plan.len(wbeg) * nnz, threadIdx.x, blockDim.x);
     wg_sync();
@@ -303,6 +327,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         const float *vw = st.vw;
         const RoundRec *rr = reinterpret_cast<const RoundRec *>(st.head);
         const int *offs = st.head + 4 * kWin;
+        const float *g01 = reinterpret_cast<const float *>(st.head + 4 * kWin + 32);
         const unsigned short *perm = reinterpret_cast<const unsigned short *>(st.perm2);
         const float *gl = st.gl;
         const int ws = plan.start(w), wl = plan.len(w);
@@ -368,10 +393,19 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                 const float qv = qn, yy = yn;                    // <v_t, x_t>, y_t
                 const RoundRec rc = rn;                          // collisions with later rounds, ||x_t||^2
                 qn = ch.q0[t + 1][l]; yn = ch.yv[t + 1][l]; rn = rr[t + 1];        // next round, early
-                const float z = sf * qv;
+                float z = sf * qv;
+                if (OPT) {
+                    // played iterate w_t = s (w^_t - ha x_{t-1}), s from ||w^_t - ha x_{t-1}||^2: scalars only
+                    const double had = (double)ha;
+                    const double m = fma(had * had, (double)x2p, fma(-2.0 * had, (double)hp, sd2 * n2));
+                    const float mf = (float)m;
+                    const float sp = mf > D2f ? Df * __builtin_amdgcn_rsqf(mf) : 1.f;
+                    z = sp * fmaf(-ha, g01[t], z);
+                }
                 if (valid) zs[zoff] = z;
                 zs += a.zl.zs_t;
-                const float b = (eta_r * slope<LOSS>(z, yy)) * isf;
+                const float step = eta_r * slope<LOSS>(z, yy);
+                const float b = step * isf;
                 ch.bw[t][l] = b;
                 // (readfirstlane returns int: go through unsigned, or the low word sign-extends)
                 unsigned long long m =
@@ -395,6 +429,11 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                     sd2 = sigma * sigma;
                     sf = (float)sigma;
                     isf = __builtin_amdgcn_rcpf(sf);
+                }
+                if (OPT) {                                      // next round's hint and <w^_{t+1}, x_t>
+                    hp = sf * fmaf(-b, (float)rc.x2, qv);
+                    ha = step;
+                    x2p = (float)rc.x2;
                 }
                 if (__any(sigma < kSparseFoldLo)) {
                     // emergency fold.  v = v_start - sum_{r<=t} b_r x_r is not in memory yet:
@@ -475,6 +514,25 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         wg_sync();
     }
     if (chain) { a.sigma[q] = sigma; a.n2[q] = n2; }
+    if (OPT && chain) { a.ha[q] = ha; a.hp[q] = hp; a.hx[q] = x2p; }
+}
+
+// Keeps the last round row of a call for the next call's first hint and for the export:
+// first the old row is cleared from the dense copy, then the new one is written.
+__global__ void __launch_bounds__(64) sparse_clear_last_kernel(const int32_t *last_col, float *xlast_dense, int nnz)
+{
+    if ((int)threadIdx.x < nnz) xlast_dense[last_col[threadIdx.x]] = 0.f;
+}
+__global__ void __launch_bounds__(64) sparse_keep_last_kernel(const int32_t *col, const float *val, int n, int nnz,
+                                                              int32_t *last_col, float *last_val, float *xlast_dense)
+{
+    const int j = threadIdx.x;
+    if (j >= nnz) return;
+    const int c = col[(int64_t)(n - 1) * nnz + j];
+    const float v = val[(int64_t)(n - 1) * nnz + j];
+    last_col[j] = c;
+    last_val[j] = v;
+    xlast_dense[c] = v;
 }
 
 // z_u[r][t] = <u_t, x_t>: independent of the learners, one thread per (round, run)
@@ -536,16 +594,16 @@ int sparse_learners_per_workgroup(int nq)
     return lpw;
 }
 
-template <int LOSS>
+template <int LOSS, bool OPT>
 hipError_t launch_window_loss(const SparseArgs &a, int lpw, const WinPlan &plan, int wbeg, int wend, hipStream_t s)
 {
     const int nq = a.R * a.K;
     const dim3 grid((unsigned)((nq + lpw - 1) / lpw)), block(kSpWaves * kWave);
     switch (lpw) {
-        case 64: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 64>), grid, block, 0, s, a, plan, wbeg, wend); break;
-        case 32: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 32>), grid, block, 0, s, a, plan, wbeg, wend); break;
-        case 16: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 16>), grid, block, 0, s, a, plan, wbeg, wend); break;
-        case 8: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 8>), grid, block, 0, s, a, plan, wbeg, wend); break;
+        case 64: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 64, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
+        case 32: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 32, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
+        case 16: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 16, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
+        case 8: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 8, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -554,9 +612,12 @@ hipError_t launch_window_loss(const SparseArgs &a, int lpw, const WinPlan &plan,
 hipError_t launch_window(const SparseArgs &a, int loss, int lpw, const WinPlan &plan, int wbeg, int wend, hipStream_t s)
 {
     switch (loss) {
-        case 0: return launch_window_loss<0>(a, lpw, plan, wbeg, wend, s);
-        case 1: return launch_window_loss<1>(a, lpw, plan, wbeg, wend, s);
-        case 2: return launch_window_loss<2>(a, lpw, plan, wbeg, wend, s);
+        case 0: return a.optimistic ? launch_window_loss<0, true>(a, lpw, plan, wbeg, wend, s)
+                                    : launch_window_loss<0, false>(a, lpw, plan, wbeg, wend, s);
+        case 1: return a.optimistic ? launch_window_loss<1, true>(a, lpw, plan, wbeg, wend, s)
+                                    : launch_window_loss<1, false>(a, lpw, plan, wbeg, wend, s);
+        case 2: return a.optimistic ? launch_window_loss<2, true>(a, lpw, plan, wbeg, wend, s)
+                                    : launch_window_loss<2, false>(a, lpw, plan, wbeg, wend, s);
         default: return hipErrorInvalidValue;
     }
 }
@@ -580,7 +641,7 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s)
     const WinPlan plan{a.t0, a.n};
     const int nwin = plan.count();
     hipLaunchKernelGGL(sparse_gram_kernel, dim3(nwin), dim3(256), 0, s, a.col, a.val, a.nnz, plan,
-                       static_cast<WinRec *>(a.scratch));
+                       static_cast<WinRec *>(a.scratch), a.optimistic, a.last_col, a.last_val);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -601,6 +662,13 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s)
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         wbeg = wend;
+    }
+    if (a.optimistic) {
+        hipLaunchKernelGGL(sparse_clear_last_kernel, dim3(1), dim3(64), 0, s, a.last_col, a.xlast_dense, a.nnz);
+        hipLaunchKernelGGL(sparse_keep_last_kernel, dim3(1), dim3(64), 0, s, a.col, a.val, a.n, a.nnz, a.last_col,
+                           a.last_val, a.xlast_dense);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }

@@ -136,6 +136,47 @@ def test_optimistic_results_do_not_depend_on_how_the_horizon_is_cut(name, over, 
             assert np.array_equal(whole[k], part[k]), (k, c)
 
 
+def _check_sparse_optimistic(wl, data, got, label):
+    """The reference's optimistic update takes dense rows: scatter the sparse stream (small d)."""
+    O = _oracle()
+    x = np.zeros((wl.T, wl.d), np.float32)
+    x[np.arange(wl.T)[:, None], data["col"]] = data["val"]
+    for r in range(wl.R):
+        ref = O.run_optimistic(wl.d, wl.K, wl.T, wl.D, wl.eta, wl.eps, wl.loss, x=x, y=data["y"][r],
+                               u=data["u"][r], seg_start=data["seg_start"])
+        dreg = abs(got["regret"][r] - ref["regret"]) / max(abs(ref["regret"]), 1.0)
+        dW = np.abs(got["W"][r] - ref["W"]).max()
+        dp = np.abs(got["p"][r] - ref["p"]).max()
+        dwb = np.abs(got["wbar"][r] - ref["wbar"]).max()
+        dL = (np.abs(got["L"][r] - ref["L"]) / np.maximum(np.abs(ref["L"]), 1.0)).max()
+        print("%s run %d regret rel %.2e  W %.2e  p %.2e  wbar %.2e  L rel %.2e" % (label, r, dreg, dW, dp, dwb, dL))
+        assert dreg <= REG_RTOL and dL <= REG_RTOL and dW <= ABS_TOL and dwb <= ABS_TOL and dp <= ABS_TOL
+
+
+@pytest.mark.parametrize("over", [
+    dict(T=700, R=3, d=2048, K=8, wstar_nnz=64),
+    dict(T=300, R=20, d=512, K=5, nnz=8, wstar_nnz=16),
+    dict(T=400, R=2, d=300, K=2, nnz=64, wstar_nnz=30, eta=(2.0, 400.0)),      # folds of the lazy scale
+    dict(T=130, R=1, d=64, K=1, nnz=1, wstar_nnz=4),
+])
+def test_sparse_optimistic_rounds_match_the_oracle(over, monkeypatch):
+    wl = WL.make("c5", optimistic=True, **over)
+    data = WL.generate(wl)
+    print("case c5 optimistic", over, flush=True)
+    whole = _gpu(wl, data)
+    _check_sparse_optimistic(wl, data, whole, "c5 optimistic %s" % over)
+    # call boundaries: the last row of a call is kept for the next call's first hint
+    part = _gpu(wl, data, chunk=128, n_max=128)
+    for k in ("regret", "L", "W", "p", "wbar"):
+        assert np.array_equal(whole[k], part[k]), k
+    odd = _gpu(wl, data, chunk=37, n_max=37)
+    for k in ("regret", "L", "W", "p", "wbar"):
+        scale = max(1.0, float(np.abs(whole[k]).max()))
+        np.testing.assert_allclose(odd[k], whole[k], rtol=0, atol=2e-6 * scale, err_msg=k)
+    monkeypatch.setenv("OCO_SPARSE_LPW", "64")
+    _check_sparse_optimistic(wl, data, _gpu(wl, data), "c5 optimistic lpw=64 %s" % over)
+
+
 def test_accel_bounds_match_the_oracle():
     """Lemma 1 / Theorem 1 from the regret on the device, against the reference's closed forms."""
     wl = WL.make("c3", T=500, R=7, d=130, K=5, seg_len=100)
