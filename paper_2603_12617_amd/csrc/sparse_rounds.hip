@@ -11,11 +11,13 @@
 //
 // Layout.  The round stream is shared by all runs, so every learner of every
 // run touches the SAME coordinates in a round.  V is stored coordinate-major
-// with the R*K learners interleaved, V[j][q], q = r*K + i: the 64 lanes of a
-// wavefront are 64 learners, one coordinate of all of them is one contiguous
-// 256-byte row segment, every gather and scatter is fully coalesced and all
+// with the R*K learners interleaved, V[j][q], q = r*K + i: a lane is a learner,
+// one coordinate of the learners of a workgroup is one contiguous row segment
+// (256 bytes for 64 learners), every gather and scatter is coalesced and all
 // the per-learner scalar work (slope, step, norm, projection) runs
-// lane-parallel with no reduction.
+// lane-parallel with no reduction.  A workgroup owns 64, 32, 16 or 8 learners:
+// few learners per workgroup spread a small problem over more compute units,
+// and a memory instruction then covers several rows at once.
 //
 // Taking memory out of the chain.  The path is a dependent chain of T rounds
 // per learner; a round that gathers from and scatters to HBM costs two memory
@@ -30,7 +32,8 @@
 //      (prediction, slope, step size b_t, norm, projection); the Gram terms
 //      <x_r, x_t> come from a pre-pass over the round stream and are almost
 //      all zero (two sparse rows rarely share a column); meanwhile the other
-//      wavefronts pull the next window's rows into L2;
+//      wavefronts stage the next window's stream and pre-pass record into a
+//      second LDS buffer and pull its rows of V into L2;
 //   C  all wavefronts: V[col] += -b_t x_t[col] as no-return float atomics, the
 //      entries split over wavefronts by column so that the adds to one address
 //      are issued by one wavefront in round order (bitwise reproducible).
@@ -49,6 +52,11 @@
 // wavefront folds its own columns in place, slowly but safely.  Windows are
 // aligned to multiples of 64 rounds of the horizon and all fold decisions
 // depend on the state and the absolute round index only.
+//
+// The optimistic two-step update (Eq. (3)) only adds scalars to phase B: the
+// played iterate's prediction follows from <w^_t, x_t>, <w^_t, x_{t-1}>,
+// <x_{t-1}, x_t> and ||x_{t-1}||^2, so V holds the intermediate model and the
+// memory phases are unchanged.
 #include "oco_internal.h"
 #include <stddef.h>
 #include <stdlib.h>
