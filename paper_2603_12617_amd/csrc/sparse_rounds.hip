@@ -15,7 +15,7 @@
 // one coordinate of the learners of a workgroup is one contiguous row segment
 // (256 bytes for 64 learners), every gather and scatter is coalesced and all
 // the per-learner scalar work (slope, step, norm, projection) runs
-// lane-parallel with no reduction.  A workgroup owns 64, 32, 16 or 8 learners:
+// lane-parallel with no reduction.  A workgroup owns 64, 32, 16, 8 or 4 learners:
 // few learners per workgroup spread a small problem over more compute units,
 // and a memory instruction then covers several rows at once.
 //
@@ -279,7 +279,7 @@ __device__ __forceinline__ double rsqrt_pos(double x)
     return fma(y * e, fma(e, 0.375, 0.5), y);
 }
 
-// A workgroup owns LPW learners (LPW = 64, 32, 16 or 8; fewer learners per workgroup spread a
+// A workgroup owns LPW learners (LPW = 64, 32, 16, 8 or 4; fewer learners per workgroup spread a
 // small problem over more compute units).  A wavefront is EPI = 64 / LPW slots of LPW lanes:
 // lane = slot * LPW + learner, and one memory instruction touches EPI rows of V.
 template <int LPW> struct Chain {
@@ -343,7 +343,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         // time; slot e of the wavefront takes the entries j = e, e + EPI, ... of a round ----------
         {
             constexpr int RA = LPW == 64 ? 2 : 4;
-            constexpr int BK = LPW == 64 ? 16 : (LPW == 8 ? 4 : 8);   // RA * BK gathers in flight
+            constexpr int BK = LPW == 64 ? 16 : (LPW >= 16 ? 8 : (LPW == 8 ? 4 : 2));   // RA * BK gathers in flight
             const int NL = (nnz + EPI - 1) / EPI;
             for (int tg = wave; tg < wl; tg += RA * kSpWaves) {
                 float acc[RA][4], yl[RA];
@@ -590,15 +590,15 @@ __global__ void __launch_bounds__(64) sparse_fold_finish_kernel(double *sigma, d
 
 namespace {
 
-// The largest share that still gives every compute unit a workgroup, at least 8.
+// The largest share that still gives every compute unit a workgroup, at least 4.
 int sparse_learners_per_workgroup(int nq)
 {
     int lpw = 64;
     if (const char *f = getenv("OCO_SPARSE_LPW")) {
         const int v = atoi(f);
-        if (v == 8 || v == 16 || v == 32 || v == 64) return v;
+        if (v == 4 || v == 8 || v == 16 || v == 32 || v == 64) return v;
     }
-    while (lpw > 8 && (nq + lpw - 1) / lpw < 256) lpw >>= 1;
+    while (lpw > 4 && (nq + lpw - 1) / lpw < 256) lpw >>= 1;
     return lpw;
 }
 
@@ -612,6 +612,7 @@ hipError_t launch_window_loss(const SparseArgs &a, int lpw, const WinPlan &plan,
         case 32: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 32, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
         case 16: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 16, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
         case 8: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 8, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
+        case 4: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 4, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

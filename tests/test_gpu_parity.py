@@ -197,10 +197,10 @@ def test_accel_bounds_match_the_oracle():
     sim.close()
 
 
-@pytest.mark.parametrize("lpw", [8, 16, 32, 64])
+@pytest.mark.parametrize("lpw", [4, 8, 16, 32, 64])
 def test_sparse_rounds_for_every_workgroup_share(lpw, monkeypatch):
-    """The sparse kernel gives a workgroup 8, 16, 32 or 64 learners (chosen from R*K; small
-    cases always get 8).  OCO_SPARSE_LPW forces a share, read at every launch."""
+    """The sparse kernel gives a workgroup 4, 8, 16, 32 or 64 learners (chosen from R*K; small
+    cases always get 4).  OCO_SPARSE_LPW forces a share, read at every launch."""
     monkeypatch.setenv("OCO_SPARSE_LPW", str(lpw))
     for over in (dict(T=700, R=20, d=512, K=5, nnz=8, wstar_nnz=16),
                  dict(T=300, R=9, d=4096, K=8, wstar_nnz=64),
@@ -211,7 +211,7 @@ def test_sparse_rounds_for_every_workgroup_share(lpw, monkeypatch):
         _check(wl, data, _gpu(wl, data), norm_every=0, label="c5 lpw=%d %s" % (lpw, over))
 
 
-@pytest.mark.parametrize("lpw", [8, 64])
+@pytest.mark.parametrize("lpw", [4, 8, 64])
 def test_sparse_rounds_with_a_column_in_every_round(lpw, monkeypatch):
     """A feature present in every round (a bias column) makes every pair of rounds of a window
     collide and puts 64 equal columns next to each other in the scatter order."""
