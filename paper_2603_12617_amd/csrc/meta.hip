@@ -180,31 +180,59 @@ __global__ void __launch_bounds__(256) export_sparse_W_kernel(const ExportArgs a
     }
 }
 
+// p and wbar for a chunk of 16 runs and a tile of 64 coordinates per workgroup.  Threads walk
+// the tile with the run index fastest, so a wavefront reads whole row segments of V (the K
+// learners of 16 runs lie next to each other); the sums go through LDS and are written with
+// the coordinate fastest.  Sum over learners in the order i = 0..K-1, float64.
+constexpr int kExpRuns = 16, kExpRows = 64;
 __global__ void __launch_bounds__(256) export_sparse_p_wbar_kernel(const ExportArgs a)
 {
-    __shared__ double p_sh[64];
-    __shared__ double s_sh[64];
-    __shared__ float f_sh[64], h_sh[64];
-    const int r = blockIdx.y;
+    __shared__ double p_sh[kExpRuns][64];
+    __shared__ float s_sh[kExpRuns][64], f_sh[kExpRuns][64], h_sh[kExpRuns][64];
+    __shared__ float tile[kExpRows][kExpRuns + 1];
     const int K = a.K;
-    hedge_weights(a.L + (int64_t)r * K, K, a.eps, p_sh);
-    if (threadIdx.x < K) {
-        const double sg = static_cast<const double *>(a.sigma)[r * K + threadIdx.x];
-        s_sh[threadIdx.x] = sg;
-        played_scale(a, r * K + threadIdx.x, sg, f_sh[threadIdx.x], h_sh[threadIdx.x]);
+    const int r0 = blockIdx.y * kExpRuns;
+    const int64_t j0 = (int64_t)blockIdx.x * kExpRows;
+    if (threadIdx.x < kExpRuns && r0 + (int)threadIdx.x < a.R) {
+        const int rl = threadIdx.x, r = r0 + rl;
+        const double *L = a.L + (int64_t)r * K;
+        double Lmin = L[0];
+        for (int i = 1; i < K; ++i) Lmin = fmin(Lmin, L[i]);
+        double S = 0.0;
+        for (int i = 0; i < K; ++i) { p_sh[rl][i] = exp(-a.eps * (L[i] - Lmin)); S += p_sh[rl][i]; }
+        for (int i = 0; i < K; ++i) {
+            p_sh[rl][i] /= S;
+            const double sg = static_cast<const double *>(a.sigma)[r * K + i];
+            s_sh[rl][i] = (float)sg;
+            played_scale(a, r * K + i, sg, f_sh[rl][i], h_sh[rl][i]);
+            if (a.p && blockIdx.x == 0) a.p[(int64_t)r * K + i] = (float)p_sh[rl][i];
+        }
     }
     __syncthreads();
-    if (a.p && blockIdx.x == 0 && threadIdx.x < K) a.p[(int64_t)r * K + threadIdx.x] = (float)p_sh[threadIdx.x];
     if (!a.wbar) return;
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= a.d) return;
-    double acc = 0.0;
-    for (int i = 0; i < K; ++i) {
-        float w = (float)((double)a.V[j * a.RKp + r * K + i] * (double)(float)s_sh[i]);
-        if (a.optimistic) w = f_sh[i] * fmaf(-h_sh[i], a.xlast[j], w);
-        acc += p_sh[i] * (double)w;
+    for (int idx = threadIdx.x; idx < kExpRows * kExpRuns; idx += 256) {
+        const int rl = idx % kExpRuns, row = idx / kExpRuns;
+        const int r = r0 + rl;
+        const int64_t j = j0 + row;
+        double acc = 0.0;
+        if (r < a.R && j < a.d) {
+            const float xl = a.optimistic ? a.xlast[j] : 0.f;
+            const float *v = a.V + j * a.RKp + (int64_t)r * K;
+            for (int i = 0; i < K; ++i) {
+                float w = (float)((double)v[i] * (double)s_sh[rl][i]);
+                if (a.optimistic) w = f_sh[rl][i] * fmaf(-h_sh[rl][i], xl, w);
+                acc += p_sh[rl][i] * (double)w;
+            }
+        }
+        tile[row][rl] = (float)acc;
     }
-    a.wbar[(int64_t)r * a.d + j] = (float)acc;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < kExpRows * kExpRuns; idx += 256) {
+        const int row = idx % kExpRows, rl = idx / kExpRows;
+        const int r = r0 + rl;
+        const int64_t j = j0 + row;
+        if (r < a.R && j < a.d) a.wbar[(int64_t)r * a.d + j] = tile[row][rl];
+    }
 }
 
 __global__ void __launch_bounds__(256) zero_kernel(uint4 *p, size_t n16)
@@ -267,7 +295,8 @@ hipError_t launch_export(const ExportArgs &a, hipStream_t s)
         if (e != hipSuccess) return e;
     }
     if (a.p || a.wbar) {
-        dim3 grid(a.wbar ? (unsigned)(((int64_t)a.d + 255) / 256) : 1u, a.R);
+        dim3 grid(a.wbar ? (unsigned)(((int64_t)a.d + kExpRows - 1) / kExpRows) : 1u,
+                  (unsigned)((a.R + kExpRuns - 1) / kExpRuns));
         hipLaunchKernelGGL(export_sparse_p_wbar_kernel, grid, dim3(256), 0, s, a);
         return hipGetLastError();
     }

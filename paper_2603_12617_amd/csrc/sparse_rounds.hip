@@ -134,8 +134,7 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
 {
     __shared__ int cs[kWin * OCO_MAX_NNZ];
     __shared__ float vs[kWin * OCO_MAX_NNZ];
-    __shared__ unsigned long long key[kWin * OCO_MAX_NNZ];      // (column, position)
-    __shared__ unsigned short sorted[kWin * OCO_MAX_NNZ];
+    __shared__ unsigned long long key[kWin * OCO_MAX_NNZ];      // (column, position), sorted in place
     __shared__ unsigned int mk[kWin][2];
     __shared__ int rowoff[kWin + 1];
     __shared__ unsigned short pair_s[kWin * (kWin - 1) / 2], pair_t[kWin * (kWin - 1) / 2];
@@ -152,13 +151,23 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
     }
     for (int e = threadIdx.x; e < kWin * 2; e += blockDim.x) mk[e >> 1][e & 1] = 0u;
     __syncthreads();
-    // rank of every entry under the order (column, position): a stable sort by column
-    for (int e = threadIdx.x; e < total; e += blockDim.x) {
-        const unsigned long long ke = key[e];
-        int rank = 0;
-        for (int f = 0; f < total; ++f) rank += key[f] < ke ? 1 : 0;
-        sorted[rank] = (unsigned short)e;
-    }
+    // sort by (column, position) -- a stable sort by column -- with a bitonic network over the
+    // next power of two (padding keys are larger than any real key)
+    int P = 2;
+    while (P < total) P <<= 1;
+    for (int e = total + threadIdx.x; e < P; e += blockDim.x) key[e] = ~0ull;
+    __syncthreads();
+    for (int k = 2; k <= P; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = threadIdx.x; i < P / 2; i += blockDim.x) {
+                const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));      // i with a zero inserted at bit log2(j)
+                const int hi = lo | j;
+                const unsigned long long a0 = key[lo], a1 = key[hi];
+                const bool up = (lo & k) == 0;
+                if ((a0 > a1) == up) { key[lo] = a1; key[hi] = a0; }
+            }
+            __syncthreads();
+        }
     if (threadIdx.x < kWin) {
         float acc = 0.f;
         if (threadIdx.x < wl)
@@ -168,12 +177,13 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
     __syncthreads();
     // rounds that share a column sit next to each other in the sorted order
     for (int k = threadIdx.x; k < total; k += blockDim.x) {
-        const int e = sorted[k];
+        const unsigned long long kk = key[k];
+        const int e = (int)(kk & 0xFFF);
         rec.perm[k] = (unsigned short)e;
-        const int c = cs[e];
+        const unsigned long long c = kk >> 12;
         const int s = (int)(((unsigned)e * mdiv) >> 18);
-        for (int k2 = k + 1; k2 < total && cs[sorted[k2]] == c; ++k2) {
-            const int t = (int)(((unsigned)sorted[k2] * mdiv) >> 18);
+        for (int k2 = k + 1; k2 < total && (key[k2] >> 12) == c; ++k2) {
+            const int t = (int)(((unsigned)(key[k2] & 0xFFF) * mdiv) >> 18);
             if (t > s) atomicOr(&mk[s][t >> 5], 1u << (t & 31));
         }
     }
@@ -197,7 +207,7 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
     if (threadIdx.x <= kSpWaves) {
         // equal shares of the sorted entries, cut only where the column changes
         int k = (int)((int64_t)threadIdx.x * total / kSpWaves);
-        while (k > 0 && k < total && cs[sorted[k]] == cs[sorted[k - 1]]) ++k;
+        while (k > 0 && k < total && (key[k] >> 12) == (key[k - 1] >> 12)) ++k;
         rec.off[threadIdx.x] = k;
     }
     __syncthreads();
