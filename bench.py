@@ -6,9 +6,9 @@ HBM: reset the state, run all T rounds of all R runs (round kernel + meta kernel
 the final iterates / Hedge weights / combined iterate, and read back the regret.  The
 metric is learner-updates per second, R*K*T*d / time.
 
-Prints ONE JSON line.  `roofline` prices the dominant kernel (the round kernel, timed with
-HIP events on the library's stream inside the timed region) against the resource that
-bounds it; `cpu_baseline` times the fp64 reference on the host cores on a bounded sample.
+Prints ONE JSON line.  `roofline` prices the dominant kernel (the round kernel: all its launches
+of a step, timed with HIP events on the library's stream inside the timed region) against the
+resource that bounds it; `cpu_baseline` times the fp64 reference on the host cores on a bounded sample.
 """
 import argparse
 import json
@@ -32,7 +32,8 @@ DESCR = {
 
 
 def roofline_model(wl):
-    """Algorithmic work of ONE launch of the round kernel (all T rounds of all runs).
+    """Algorithmic work of the round kernels of ONE step (all T rounds of all runs; the library
+    enqueues a long call as several launches of the same kernel).
 
     dense: per learner-coordinate-round 7 flops (inner product 2, gradient step 2, norm of the
     stepped vector 2, projection scale 1) plus the comparator's inner product (2 per
@@ -229,7 +230,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 iterates, f64 losses/weights/regret", "data": "synthetic",
         "config": {"workload": DESCR[a.config], "R": wl.R, "K": wl.K, "d": wl.d, "T": wl.T,
-                   "loss": wl.loss, "nnz": wl.nnz, "rounds_per_launch": wl.T},
+                   "loss": wl.loss, "nnz": wl.nnz, "rounds_per_call": wl.T},
         "kernels_ms": {"round_kernel": main_res["round_kernel_ms"], "meta_kernel": main_res["meta_kernel_ms"]},
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                      "frac": achieved / peak, "traffic": traffic, "kernel": "round kernel (S0-S2,S4)"},

@@ -24,8 +24,11 @@
  *    device memory: the caller provides one workspace (oco_workspace_bytes)
  *    and owns every input and output buffer.  Device pointers must be at
  *    least 16-byte aligned; the workspace 256-byte aligned.
- *  - All GPU work is enqueued on the HIP stream given to oco_create.  Input
- *    buffers are borrowed until that work has finished.
+ *  - All GPU work is ordered on the HIP stream given to oco_create: a call may run
+ *    part of its work on a second stream of the library's own, which starts after
+ *    the work already on the caller's stream and which the caller's stream waits
+ *    for before the call's work counts as done.  Input buffers are borrowed until
+ *    that work has finished.
  *  - Results are a pure function of (config, inputs, call boundaries).  Dense
  *    configurations: splitting [0, T) into oco_run_rounds calls in any way
  *    gives bit-identical state and regret.  Sparse configurations work in
@@ -165,11 +168,15 @@ int oco_cum_losses(oco_state *st, double *out_host);
 int oco_reset(oco_state *st);
 
 /* Kernel timing for benchmarks.  After oco_set_timing(st, 1) every oco_run_rounds call records
- * HIP events on the state's stream around its two kernels; oco_last_timing waits for the most
- * recent call's events and writes the durations in milliseconds to ms_host: host [2],
- * [0] = the round kernel (steps S0-S2, S4 of a round: stream x, predict, slope, step, project),
- * [1] = the meta kernel (Hedge weights, losses, regret).  OCO_EINVAL if timing is off or no call
- * has been made since it was switched on. */
+ * HIP events on the state's stream; oco_last_timing waits for the most recent call's events and
+ * writes two durations in milliseconds to ms_host: host [2],
+ * [0] = the round kernels of the call (steps S0-S2, S4 of a round: stream x, predict, slope, step,
+ *       project; a long call goes to the GPU as several launches),
+ * [1] = from their end to the end of the call: the meta kernel (Hedge weights, losses, regret),
+ *       or, where the meta kernel of each piece of the call already ran beside the round kernels
+ *       of the next piece on a second stream, the part of it that was left.
+ * Timing changes nothing in what is enqueued.  OCO_EINVAL if timing is off or no call has been
+ * made since it was switched on. */
 int oco_set_timing(oco_state *st, int enable);
 int oco_last_timing(oco_state *st, float *ms_host);
 

@@ -32,6 +32,7 @@
 // regret are computed from Z by the meta kernel.
 #include "oco_internal.h"
 
+#include <algorithm>
 #include <cstdlib>
 
 namespace oco {
@@ -51,6 +52,10 @@ template <> struct DenseCfg<16> { static constexpr int MAXW = 16, RT = 2; };
 template <> struct DenseCfg<32> { static constexpr int MAXW = OCO_MAXW32, RT = 2; };
 template <> struct DenseCfg<64> { static constexpr int MAXW = 8,  RT = 2; };
 constexpr int kRing = 3;   // LDS tiles
+constexpr int64_t kStreamPieceBytes = 64ll << 20;  // shared round stream per launch of a multi-pass grid
+constexpr int64_t kPieceMinRounds = 512;           // no piece shorter than this
+constexpr int64_t kBesideMaxWaves = 1024;          // one wavefront per SIMD: the chip is mostly idle
+constexpr int64_t kBesidePieces = 4;
 
 template <int VW> struct VecT;
 template <> struct VecT<1> { using type = float; };
@@ -451,8 +456,17 @@ __global__ void __launch_bounds__(256) keep_last_row_kernel(const float *x, int6
     if (j == 0) x2last[rr] = x2[(int64_t)rr * x2_stride + n - 1];
 }
 
+// how one call's round kernel is launched: fixed for the call, used for each of its pieces
+struct DensePlan {
+    void (*kern)(const DenseArgs) = nullptr;
+    size_t smem = 0;
+    int wpb = 0;              // wavefronts per workgroup
+    int64_t nwg = 0;          // workgroups
+    int64_t batches = 0;      // passes the grid needs when the chip cannot hold it at once
+};
+
 template <int NPL>
-hipError_t launch_npl(const DenseArgs &a, int loss, hipStream_t s)
+hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
 {
     using C = DenseCfg<NPL>;
     const size_t smem = sizeof(float) * kRing * C::RT * NPL * kWave;
@@ -508,12 +522,28 @@ hipError_t launch_npl(const DenseArgs &a, int loss, hipStream_t s)
         if (w >= 1 && w <= C::MAXW) best = w;
     }
     if (best == 0) return hipErrorInvalidConfiguration;
+    int c = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, reinterpret_cast<const void *>(kern), best * kWave,
+                                                     smem) != hipSuccess || c <= 0)
+        c = 1;
+    plan->kern = kern;
+    plan->smem = smem;
+    plan->wpb = best;
+    plan->nwg = a.x_shared ? ((int64_t)a.R * per_run + best - 1) / best
+                           : (int64_t)a.R * ((per_run + best - 1) / best);
+    plan->batches = (plan->nwg + (int64_t)ncu * c - 1) / ((int64_t)ncu * c);
+    return hipSuccess;
+}
+
+hipError_t launch_piece(const DensePlan &p, const DenseArgs &a, hipStream_t s)
+{
+    const int per_run = a.K + 1;
     dim3 grid;
     if (a.x_shared)
-        grid = dim3((unsigned)(((int64_t)a.R * per_run + best - 1) / best), 1, 1);
+        grid = dim3((unsigned)p.nwg, 1, 1);
     else
-        grid = dim3((unsigned)((per_run + best - 1) / best), (unsigned)a.R, 1);
-    hipLaunchKernelGGL(kern, grid, dim3(best * kWave), smem, s, a);
+        grid = dim3((unsigned)((per_run + p.wpb - 1) / p.wpb), (unsigned)a.R, 1);
+    hipLaunchKernelGGL(p.kern, grid, dim3(p.wpb * kWave), p.smem, s, a);
     return hipGetLastError();
 }
 
@@ -521,32 +551,71 @@ hipError_t launch_npl(const DenseArgs &a, int loss, hipStream_t s)
 
 bool dense_supported(int64_t d) { return d >= 1 && d <= 64 * kWave; }
 
-hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s)
+// One piece of a call: the squared norms of its rows, its round kernel, and the row kept for the
+// next piece's hint terms.
+static hipError_t launch_dense_piece(const DensePlan &plan, const DenseArgs &a, hipStream_t s)
 {
-    if (a.n <= 0) return hipSuccess;
     const int nruns = a.x_shared ? 1 : a.R;
     const int64_t xstride = a.x_shared ? 0 : a.x_run_stride;
-    {
-        const int64_t rows = (int64_t)nruns * a.n;
-        hipLaunchKernelGGL(xnorm2_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a.x, xstride, nruns,
-                           a.n, a.d, a.x2, a.x2_run_stride, a.optimistic ? a.g01 : nullptr,
-                           a.optimistic ? a.xlast : nullptr);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    const int npl = (a.d + kWave - 1) / kWave;
-    hipError_t e = hipErrorInvalidValue;
-    if (npl <= 1) e = launch_npl<1>(a, loss, s);
-    else if (npl <= 2) e = launch_npl<2>(a, loss, s);
-    else if (npl <= 4) e = launch_npl<4>(a, loss, s);
-    else if (npl <= 8) e = launch_npl<8>(a, loss, s);
-    else if (npl <= 16) e = launch_npl<16>(a, loss, s);
-    else if (npl <= 32) e = launch_npl<32>(a, loss, s);
-    else if (npl <= 64) e = launch_npl<64>(a, loss, s);
+    const int64_t rows = (int64_t)nruns * a.n;
+    hipLaunchKernelGGL(xnorm2_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a.x, xstride, nruns,
+                       a.n, a.d, a.x2, a.x2_run_stride, a.optimistic ? a.g01 : nullptr,
+                       a.optimistic ? a.xlast : nullptr);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_piece(plan, a, s);
     if (e != hipSuccess || !a.optimistic) return e;
     hipLaunchKernelGGL(keep_last_row_kernel, dim3((unsigned)((a.d + 255) / 256), (unsigned)nruns), dim3(256), 0, s,
                        a.x, xstride, a.n, a.d, a.x2, a.x2_run_stride, a.xlast, a.x2last);
     return hipGetLastError();
+}
+
+hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s, const PieceHook *hook)
+{
+    if (a.n <= 0) return hipSuccess;
+    const int npl = (a.d + kWave - 1) / kWave;
+    DensePlan plan;
+    hipError_t e = hipErrorInvalidValue;
+    if (npl <= 1) e = plan_npl<1>(a, loss, &plan);
+    else if (npl <= 2) e = plan_npl<2>(a, loss, &plan);
+    else if (npl <= 4) e = plan_npl<4>(a, loss, &plan);
+    else if (npl <= 8) e = plan_npl<8>(a, loss, &plan);
+    else if (npl <= 16) e = plan_npl<16>(a, loss, &plan);
+    else if (npl <= 32) e = plan_npl<32>(a, loss, &plan);
+    else if (npl <= 64) e = plan_npl<64>(a, loss, &plan);
+    if (e != hipSuccess) return e;
+
+    // Rounds give the same bits under any split of a call, so a call may go as several launches:
+    //  - A grid that takes several passes over the chip has workgroups at unrelated positions of a
+    //    shared round stream, whose footprint is then the whole stream: pieces of at most
+    //    kStreamPieceBytes keep the stream of a piece in the last-level cache for every pass.
+    //  - A grid that leaves most of the chip idle lets the caller's per-piece work (the hook) run
+    //    beside the following pieces.
+    int64_t pieces = 1;
+    bool beside = false;
+    if (plan.batches > 1 && a.x_shared) {
+        const int64_t bytes = (int64_t)a.n * a.d * (int64_t)sizeof(float);
+        pieces = (bytes + kStreamPieceBytes - 1) / kStreamPieceBytes;
+    } else if (hook && plan.nwg * plan.wpb <= kBesideMaxWaves) {
+        pieces = kBesidePieces;
+        beside = true;
+    }
+    if (const char *ov = getenv("OCO_DENSE_PIECES")) pieces = atoi(ov);      // tuning override
+    pieces = std::max<int64_t>(1, std::min<int64_t>(pieces, a.n / kPieceMinRounds));
+    const int64_t step = (a.n / pieces + 63) / 64 * 64;
+    for (int64_t off = 0; off < a.n; off += step) {
+        const int64_t len = std::min<int64_t>(step, a.n - off);
+        DenseArgs b = a;
+        b.x = a.x + off * a.d; b.t0 = a.t0 + off; b.n = (int)len;
+        if (b.y) b.y = a.y + off;
+        b.x2 = a.x2 + off;
+        if (b.g01) b.g01 = a.g01 + off;
+        b.Z = a.Z + off * a.zl.zs_t;
+        e = launch_dense_piece(plan, b, s);
+        if (e == hipSuccess && beside) e = hook->fn(hook->ctx, (int)off, (int)len);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace oco

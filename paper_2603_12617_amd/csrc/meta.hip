@@ -56,7 +56,23 @@ __global__ void __launch_bounds__(256) meta_kernel(const MetaArgs a)
         }
         __syncthreads();
         if (j < K) {
-            for (int jj = 0; jj < cnt; ++jj) {
+            // running sums in round order; whole chunks issue their LDS reads together (one
+            // dependent LDS round trip per chunk instead of per round), the tail goes one by one
+            int jj = 0;
+            for (; jj + 16 <= cnt; jj += 16) {
+                double v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = lmat[(jj + u) * K + j];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const double l = v[u];
+                    v[u] = Lacc;
+                    Lacc += l;
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) lmat[(jj + u) * K + j] = v[u];
+            }
+            for (; jj < cnt; ++jj) {
                 const double l = lmat[jj * K + j];
                 lmat[jj * K + j] = Lacc;
                 Lacc += l;
@@ -79,7 +95,17 @@ __global__ void __launch_bounds__(256) meta_kernel(const MetaArgs a)
         }
         __syncthreads();
         if (j == 0)
-            for (int jj = 0; jj < cnt; ++jj) reg += diff[jj];
+        {
+            int jj = 0;
+            for (; jj + 16 <= cnt; jj += 16) {
+                double v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = diff[jj + u];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) reg += v[u];
+            }
+            for (; jj < cnt; ++jj) reg += diff[jj];
+        }
         // lmat/diff are rewritten only after the next tile's first barrier
     }
     if (j < K) a.L[(int64_t)r * K + j] = Lacc;

@@ -4,6 +4,7 @@
 #include "oco_internal.h"
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -119,8 +120,20 @@ struct oco_state {
     int64_t t_done = 0;
     bool timing = false, timed = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    // The meta kernel of a piece of a call depends on that piece's predictions only, and no
+    // round kernel depends on a meta kernel (every base learner steps at its own iterate): it
+    // runs on a second stream beside the round kernels of the following pieces, and the
+    // caller's stream waits for it at the end of the call.
+    hipStream_t side = nullptr;
+    std::vector<hipEvent_t> piece_ev;
+    hipEvent_t join_ev = nullptr;
 
-    ~oco_state() { for (auto e : ev) if (e) (void)hipEventDestroy(e); }
+    ~oco_state() {
+        for (auto e : ev) if (e) (void)hipEventDestroy(e);
+        for (auto e : piece_ev) if (e) (void)hipEventDestroy(e);
+        if (join_ev) (void)hipEventDestroy(join_ev);
+        if (side) { (void)hipStreamSynchronize(side); (void)hipStreamDestroy(side); }
+    }
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
     ZLayout zlayout() const {
         const int64_t nz = (int64_t)align_up((size_t)lay.n_max, 64);
@@ -190,6 +203,11 @@ int oco_create(const oco_config *cfg, void *dev_ws, size_t ws_bytes, void *hip_s
         delete st;
         return OCO_EHIP;
     }
+    if (hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&st->join_ev, hipEventDisableTiming) != hipSuccess) {
+        delete st;
+        return OCO_EHIP;
+    }
     rc = oco_reset(st);
     if (rc != OCO_OK) { delete st; return rc; }
     *out = st;
@@ -238,6 +256,44 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
     const ZLayout zl = st->zlayout();
     hipError_t e;
     if (st->timing && hipEventRecord(st->ev[0], st->stream) != hipSuccess) return OCO_EHIP;
+
+    // Meta kernel of the rounds [off, off + len) of this call, on the second stream.
+    struct MetaPipe {
+        oco_state *st; MetaArgs m; int loss; size_t used = 0;
+        static hipError_t piece(void *ctx, int off, int len) {
+            MetaPipe &p = *static_cast<MetaPipe *>(ctx);
+            oco_state *st = p.st;
+            if (p.used == st->piece_ev.size()) {
+                hipEvent_t ev;
+                hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+                if (e != hipSuccess) return e;
+                st->piece_ev.push_back(ev);
+            }
+            hipEvent_t ev = st->piece_ev[p.used++];
+            hipError_t e = hipEventRecord(ev, st->stream);
+            if (e == hipSuccess) e = hipStreamWaitEvent(st->side, ev, 0);
+            if (e != hipSuccess) return e;
+            MetaArgs m = p.m;
+            m.Z += (int64_t)off * m.zl.zs_t;
+            if (m.y) m.y += off;
+            m.n = len;
+            return launch_meta(m, p.loss, st->side);
+        }
+        hipError_t join() {
+            if (!used) return hipSuccess;
+            hipError_t e = hipEventRecord(st->join_ev, st->side);
+            if (e == hipSuccess) e = hipStreamWaitEvent(st->stream, st->join_ev, 0);
+            return e;
+        }
+    } pipe{st, {}, c.loss};
+    MetaArgs &m = pipe.m;
+    m.Z = st->at<float>(l.off_Z); m.zl = zl; m.y = rd->y; m.y_run_stride = yrs;
+    m.L = st->at<double>(l.off_L); m.regret = st->at<double>(l.off_regret);
+    m.eps = c.eps; m.K = (int)c.K; m.R = (int)c.R; m.n = (int)n;
+    const PieceHook hook{&MetaPipe::piece, &pipe};
+    bool overlap = true;
+    if (const char *ev = std::getenv("OCO_META_BESIDE")) overlap = std::atoi(ev) != 0;   // tuning override
+
     if (sparse) {
         SparseArgs a{};
         a.col = rd->col; a.val = rd->val; a.y = rd->y; a.y_run_stride = yrs;
@@ -253,7 +309,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
             a.last_col = st->at<int32_t>(l.off_lastcol); a.last_val = st->at<float>(l.off_lastval);
             a.xlast_dense = st->at<float>(l.off_xlast);
         }
-        e = launch_sparse_rounds(a, c.loss, st->stream);
+        e = launch_sparse_rounds(a, c.loss, st->stream, overlap ? &hook : nullptr);
     } else {
         DenseArgs a{};
         a.x = rd->x; a.x_run_stride = xrs; a.y = rd->y; a.y_run_stride = yrs;
@@ -271,16 +327,16 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
             a.g01 = st->at<float>(l.off_G01);
             a.xlast = st->at<float>(l.off_xlast); a.x2last = st->at<float>(l.off_x2last);
         }
-        e = launch_dense_rounds(a, c.loss, st->stream);
+        e = launch_dense_rounds(a, c.loss, st->stream, overlap ? &hook : nullptr);
     }
     if (e != hipSuccess) return OCO_EHIP;
+    // timing: [ev0, ev1] spans the round kernels, [ev1, ev2] whatever meta work is left after them
     if (st->timing && hipEventRecord(st->ev[1], st->stream) != hipSuccess) return OCO_EHIP;
-
-    MetaArgs m{};
-    m.Z = st->at<float>(l.off_Z); m.zl = zl; m.y = rd->y; m.y_run_stride = yrs;
-    m.L = st->at<double>(l.off_L); m.regret = st->at<double>(l.off_regret);
-    m.eps = c.eps; m.K = (int)c.K; m.R = (int)c.R; m.n = (int)n;
-    if (launch_meta(m, c.loss, st->stream) != hipSuccess) return OCO_EHIP;
+    if (pipe.used) {
+        if (pipe.join() != hipSuccess) return OCO_EHIP;
+    } else if (launch_meta(m, c.loss, st->stream) != hipSuccess) {
+        return OCO_EHIP;
+    }
     if (st->timing) {
         if (hipEventRecord(st->ev[2], st->stream) != hipSuccess) return OCO_EHIP;
         st->timed = true;

@@ -18,6 +18,13 @@ struct ZLayout {
     int64_t zs_r, zs_i, zs_t;
 };
 
+// Called after the round kernel of every piece of a call has been enqueued: rounds
+// [off, off + len) of the call have their predictions in Z once that kernel finishes.
+struct PieceHook {
+    hipError_t (*fn)(void *ctx, int off, int len);
+    void *ctx;
+};
+
 // ---- dense rounds -----------------------------------------------------------
 struct DenseArgs {
     const float *x;          // round stream (or gradient stream for the linear loss)
@@ -49,7 +56,7 @@ struct DenseArgs {
     float *xlast;            // [1 or R][d]  last round row of the previous call (0 before round 0)
     float *x2last;           // [1 or R]     its squared norm
 };
-hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s);
+hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s, const PieceHook *hook);
 bool dense_supported(int64_t d);
 
 // ---- sparse rounds ----------------------------------------------------------
@@ -82,7 +89,7 @@ struct SparseArgs {
     float *last_val;         // [OCO_MAX_NNZ]
     float *xlast_dense;      // [d]  the same row scattered into a dense vector (for the export)
 };
-hipError_t launch_sparse_rounds(const SparseArgs &a, int loss, hipStream_t s);
+hipError_t launch_sparse_rounds(const SparseArgs &a, int loss, hipStream_t s, const PieceHook *hook);
 size_t sparse_scratch_bytes(int64_t n_max);
 
 // ---- meta learner + regret --------------------------------------------------

@@ -98,6 +98,7 @@ constexpr double kSparseFoldSoft = OCO_FOLD_SOFT;  // fold between segments
 constexpr int kSegment = 2048;               // rounds per launch segment (absolute alignment)
 constexpr int kWin = 64;                     // rounds per window (absolute alignment)
 constexpr int kSpWaves = 16;                 // wavefronts per workgroup
+constexpr int kBesideMaxWorkgroups = 128;    // window grids up to this size leave half the chip idle
 
 // Pre-pass over the round stream, one workgroup per window of the launch:
 // G[s][t] = <x_s, x_t> for s < t, mask[s] = bit t set iff rounds s and t share a column,
@@ -645,7 +646,7 @@ size_t sparse_scratch_bytes(int64_t n_max)
     return (size_t)(n_max / kWin + 2) * sizeof(WinRec);
 }
 
-hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s)
+hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s, const PieceHook *hook)
 {
     SparseArgs a = a0;
     if (a.n <= 0) return hipSuccess;
@@ -664,6 +665,9 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s)
     // segments end at the multiples of kSegment of the horizon, which are window boundaries
     const int groups = a.RKp / kWave;
     const int lpw = sparse_learners_per_workgroup(a.R * a.K);
+    // the caller's per-segment work runs beside the following segments only while the window
+    // kernel's workgroups leave at least half of the compute units idle
+    if ((a.R * a.K + lpw - 1) / lpw > kBesideMaxWorkgroups) hook = nullptr;
     for (int wbeg = 0; wbeg < nwin;) {
         const int64_t seg_end = ((a.t0 + plan.start(wbeg)) / kSegment + 1) * kSegment;   // absolute
         int wend = wbeg + 1;
@@ -671,6 +675,11 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s)
         e = launch_window(a, loss, lpw, plan, wbeg, wend, s);
         if (e != hipSuccess) return e;
         const int64_t reached = a.t0 + plan.start(wend - 1) + plan.len(wend - 1);
+        if (hook) {
+            const int off = plan.start(wbeg);
+            e = hook->fn(hook->ctx, off, (int)(reached - a.t0) - off);
+            if (e != hipSuccess) return e;
+        }
         if (reached % kSegment == 0) {                        // a segment of the horizon ended
             hipLaunchKernelGGL(sparse_fold_kernel, dim3(1024, groups), dim3(256), 0, s, a.V, a.sigma, a.d, a.RKp);
             hipLaunchKernelGGL(sparse_fold_finish_kernel, dim3(groups), dim3(kWave), 0, s, a.sigma, a.n2);

@@ -257,6 +257,40 @@ def test_results_do_not_depend_on_how_the_horizon_is_cut(name, over, chunks):
                 assert np.array_equal(whole[k], part[k]), (k, c)
 
 
+@pytest.mark.parametrize("name,over", [
+    ("c3", dict(T=2600, R=2, d=256, K=5, seg_len=700)),
+    ("c2", dict(T=2100, R=3, d=100, K=15)),
+    ("c3", dict(T=2200, R=2, d=320, K=3, seg_len=500, optimistic=True)),
+    ("c5", dict(T=4500, R=3, d=4096, K=8, wstar_nnz=64)),
+])
+def test_results_do_not_depend_on_how_a_call_is_enqueued(name, over, monkeypatch):
+    """One call may go to the GPU as several launches, with the meta kernel of a piece on a
+    second stream beside the round kernels of the next: the state is bit-identical to the one
+    of a single launch followed by a single meta kernel, and to the timed path."""
+    wl = WL.make(name, **over)
+    data = WL.generate(wl)
+    _check(wl, data, _gpu(wl, data), norm_every=0 if wl.nnz else None, label="%s enqueue" % name)
+    base = _gpu(wl, data)
+    variants = [dict(OCO_META_BESIDE="0"), dict(OCO_DENSE_PIECES="1"), dict(OCO_DENSE_PIECES="5"),
+                dict(OCO_DENSE_PIECES="3", OCO_META_BESIDE="0")]
+    for env in variants:
+        for k, v in env.items():
+            monkeypatch.setenv(k, v)
+        print("case", name, over, env, flush=True)
+        got = _gpu(wl, data)
+        for k in env:
+            monkeypatch.delenv(k)
+        for k in ("regret", "L", "W", "p", "wbar"):
+            assert np.array_equal(base[k], got[k]), (k, env)
+    sim = B.Simulation(wl, data)
+    B.oco_set_timing(sim.h, True)
+    sim.run_all(0)
+    assert np.array_equal(sim.regret(), base["regret"])
+    assert np.array_equal(sim.cum_losses(), base["L"])
+    assert B.oco_last_timing(sim.h).min() > 0.0
+    sim.close()
+
+
 def test_degenerate_inputs():
     # T = 1
     wl = WL.make("c2", T=1, R=2, d=8, K=3)
