@@ -147,13 +147,13 @@ dense_rounds_kernel(const DenseArgs a)
     bool active;
     if (a.x_shared) {
         const int64_t q = (int64_t)blockIdx.x * wpb + wave;
-        active = q < (int64_t)a.R * (K + 1);
-        r = active ? (int)(q / (K + 1)) : 0;
-        i = active ? (int)(q % (K + 1)) : 0;
+        active = q < (int64_t)a.R * a.per_run;
+        r = active ? (int)(q / a.per_run) : 0;
+        i = active ? (int)(q % a.per_run) : 0;
     } else {
         r = blockIdx.y;
         i = blockIdx.x * wpb + wave;
-        active = i <= K;
+        active = i < a.per_run;
         if (!active) i = 0;
     }
     const bool is_cmp = active && i == K;
@@ -463,6 +463,7 @@ struct DensePlan {
     int wpb = 0;              // wavefronts per workgroup
     int64_t nwg = 0;          // workgroups
     int64_t batches = 0;      // passes the grid needs when the chip cannot hold it at once
+    double cost = 0.0;        // modelled duration, in units of one lightly loaded pass
 };
 
 template <int NPL>
@@ -497,7 +498,7 @@ hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
     // mostly fill each other's stalls (the round is a dependent chain), beyond that they
     // share the issue slots.
     auto g = [](double l) { return l <= 1.0 ? 1.0 : (l <= 4.0 ? 1.0 + 0.1 * (l - 1.0) : 1.3 + 0.35 * (l - 4.0)); };
-    const int per_run = a.K + 1;
+    const int per_run = a.per_run;
     int best = 0;
     double best_cost = 0.0;
     for (int w = C::MAXW; w >= 1; --w) {
@@ -522,6 +523,7 @@ hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
         if (w >= 1 && w <= C::MAXW) best = w;
     }
     if (best == 0) return hipErrorInvalidConfiguration;
+    plan->cost = best_cost;
     int c = 1;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, reinterpret_cast<const void *>(kern), best * kWave,
                                                      smem) != hipSuccess || c <= 0)
@@ -537,7 +539,7 @@ hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
 
 hipError_t launch_piece(const DensePlan &p, const DenseArgs &a, hipStream_t s)
 {
-    const int per_run = a.K + 1;
+    const int per_run = a.per_run;
     dim3 grid;
     if (a.x_shared)
         grid = dim3((unsigned)p.nwg, 1, 1);
@@ -563,6 +565,13 @@ static hipError_t launch_dense_piece(const DensePlan &plan, const DenseArgs &a, 
                        a.optimistic ? a.xlast : nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (a.per_run == a.K) {
+        ComparatorGemmArgs g{};
+        g.x = a.x; g.u = a.u; g.seg_start = a.seg_start; g.S = a.S; g.Z = a.Z; g.zl = a.zl;
+        g.d = a.d; g.K = a.K; g.R = a.R; g.t0 = a.t0; g.n = a.n; g.vec_ok = a.vec_ok;
+        e = launch_comparator_gemm(g, s);
+        if (e != hipSuccess) return e;
+    }
     e = launch_piece(plan, a, s);
     if (e != hipSuccess || !a.optimistic) return e;
     hipLaunchKernelGGL(keep_last_row_kernel, dim3((unsigned)((a.d + 255) / 256), (unsigned)nruns), dim3(256), 0, s,
@@ -570,19 +579,39 @@ static hipError_t launch_dense_piece(const DensePlan &plan, const DenseArgs &a, 
     return hipGetLastError();
 }
 
-hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s, const PieceHook *hook)
+hipError_t launch_dense_rounds(const DenseArgs &a0, int loss, hipStream_t s, const PieceHook *hook)
 {
-    if (a.n <= 0) return hipSuccess;
+    if (a0.n <= 0) return hipSuccess;
+    DenseArgs a = a0;
     const int npl = (a.d + kWave - 1) / kWave;
+    auto make_plan = [&](DensePlan *plan) {
+        if (npl <= 1) return plan_npl<1>(a, loss, plan);
+        if (npl <= 2) return plan_npl<2>(a, loss, plan);
+        if (npl <= 4) return plan_npl<4>(a, loss, plan);
+        if (npl <= 8) return plan_npl<8>(a, loss, plan);
+        if (npl <= 16) return plan_npl<16>(a, loss, plan);
+        if (npl <= 32) return plan_npl<32>(a, loss, plan);
+        if (npl <= 64) return plan_npl<64>(a, loss, plan);
+        return hipErrorInvalidValue;
+    };
+    // Each run has one more wavefront task than learners, the comparator's, which only takes
+    // inner products.  With a shared stream those are one contraction (U X^T per comparator
+    // segment) that a kernel of its own does on the matrix cores: worth it where the round
+    // kernel's grid gets cheaper without the extra tasks (fewer passes over the chip).
     DensePlan plan;
-    hipError_t e = hipErrorInvalidValue;
-    if (npl <= 1) e = plan_npl<1>(a, loss, &plan);
-    else if (npl <= 2) e = plan_npl<2>(a, loss, &plan);
-    else if (npl <= 4) e = plan_npl<4>(a, loss, &plan);
-    else if (npl <= 8) e = plan_npl<8>(a, loss, &plan);
-    else if (npl <= 16) e = plan_npl<16>(a, loss, &plan);
-    else if (npl <= 32) e = plan_npl<32>(a, loss, &plan);
-    else if (npl <= 64) e = plan_npl<64>(a, loss, &plan);
+    a.per_run = a.K + 1;
+    hipError_t e = make_plan(&plan);
+    if (e != hipSuccess) return e;
+    if (a.x_shared) {
+        int mode = -1;                                          // tuning override: 0 never, 1 always
+        if (const char *ov = getenv("OCO_COMPARATOR_GEMM")) mode = atoi(ov);
+        DensePlan alt;
+        a.per_run = a.K;
+        e = make_plan(&alt);
+        if (e != hipSuccess) return e;
+        if (mode == 1 || (mode != 0 && alt.cost < plan.cost * 0.98)) plan = alt;
+        else a.per_run = a.K + 1;
+    }
     if (e != hipSuccess) return e;
 
     // Rounds give the same bits under any split of a call, so a call may go as several launches:

@@ -48,6 +48,8 @@ struct DenseArgs {
     float D;
     int x_shared;
     int vec_ok;              // rows of x are 16-byte aligned and d % 4 == 0
+    int per_run;             // wavefront tasks per run: K + 1 with the comparator's, K when its
+                             // predictions come from the contraction kernel (set by the launcher)
     // optimistic two-step update (Eq. (3)); V then holds the intermediate model w^
     int optimistic;
     float *ha;               // [R][K]  eta_i c_{t-1}^i: the hint is ha * x_{t-1}
@@ -57,6 +59,21 @@ struct DenseArgs {
     float *x2last;           // [1 or R]     its squared norm
 };
 hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s, const PieceHook *hook);
+
+// comparator predictions of a shared dense stream as one contraction (rows K of Z)
+struct ComparatorGemmArgs {
+    const float *x;          // [n][d]
+    const float *u;          // [R][S][d]
+    const int64_t *seg_start;// device, [S]
+    int S;
+    float *Z;
+    ZLayout zl;
+    int d, K, R;
+    int64_t t0;
+    int n;
+    int vec_ok;              // rows of x and u are 16-byte aligned and d % 4 == 0
+};
+hipError_t launch_comparator_gemm(const ComparatorGemmArgs &a, hipStream_t s);
 bool dense_supported(int64_t d);
 
 // ---- sparse rounds ----------------------------------------------------------

@@ -79,6 +79,32 @@ def test_dense_rounds_match_the_oracle(name, over):
     _check(wl, data, _gpu(wl, data), label="%s %s" % (name, over))
 
 
+@pytest.mark.parametrize("name,over", [
+    ("c1", dict()),
+    ("c1", dict(T=130, d=3, R=2)),
+    ("c3", dict(T=1000, R=3, d=130, K=17, seg_len=100)),
+    ("c3", dict(T=777, R=70, d=1000, K=3, seg_len=100)),
+    ("c3", dict(T=300, R=2, d=261, K=3, seg_len=7)),
+    ("c4", dict(T=301, R=3, d=4096, K=16)),
+    ("c3", dict(T=400, R=130, d=64, K=2, seg_len=33, optimistic=True)),
+])
+@pytest.mark.parametrize("mode", ["0", "1"])
+def test_comparator_predictions_in_the_round_kernel_or_as_a_contraction(name, over, mode, monkeypatch):
+    """With a shared stream the comparators' predictions come either from an extra wavefront of
+    the round kernel or from the MFMA contraction kernel (the library picks by grid shape):
+    both, on every shape class (tiles ragged in runs, rounds and depth, unaligned rows, tiles
+    that straddle comparator segments), and both independent of how the horizon is cut."""
+    monkeypatch.setenv("OCO_COMPARATOR_GEMM", mode)
+    wl = WL.make(name, **over)
+    data = WL.generate(wl)
+    print("case", name, over, "contraction", mode, flush=True)
+    whole = _gpu(wl, data)
+    _check(wl, data, whole, runs=range(min(wl.R, 3)), label="%s %s gemm=%s" % (name, over, mode))
+    part = _gpu(wl, data, chunk=77, n_max=77)
+    for k in ("regret", "L", "W", "p", "wbar"):
+        assert np.array_equal(whole[k], part[k]), k
+
+
 SPARSE = [
     dict(T=2000, R=3, d=4096, K=8, wstar_nnz=64),
     dict(T=700, R=20, d=512, K=5, nnz=8, wstar_nnz=16),                     # R*K > 64: two wavefronts
