@@ -50,7 +50,14 @@ template <> struct DenseCfg<16> { static constexpr int MAXW = 16, RT = 2; };
 #define OCO_MAXW32 12
 #endif
 template <> struct DenseCfg<32> { static constexpr int MAXW = OCO_MAXW32, RT = 2; };
-template <> struct DenseCfg<64> { static constexpr int MAXW = 8,  RT = 2; };
+#ifndef OCO_MAXW64
+#define OCO_MAXW64 12
+#endif
+template <> struct DenseCfg<64> { static constexpr int MAXW = OCO_MAXW64,  RT = 2; };
+// One register set for the round row (x_t is replaced chunk by chunk with x_{t+1} as the step
+// consumes it) instead of two that swap roles: 64 fewer registers per lane, which at 64
+// coordinates per lane is the difference between two and three wavefronts per SIMD.
+template <int NPL> constexpr bool kOneRowSet = NPL >= 64;   // at 32 it measured 4 % slower
 constexpr int kRing = 3;   // LDS tiles
 constexpr int64_t kStreamPieceBytes = 64ll << 20;  // shared round stream per launch of a multi-pass grid
 constexpr int64_t kPieceMinRounds = 512;           // no piece shorter than this
@@ -328,6 +335,51 @@ dense_rounds_kernel(const DenseArgs a)
         }
     };
 
+    // The same pass with one register set: chunk c of x_t is dead once the step has used it and
+    // is refilled with chunk c of x_{t+1}; the dot runs kLag chunks behind so that the LDS
+    // latency of the refill is covered.  Same operations in the same order as `pass`.
+    auto pass_one = [&](float b, const V *xr, float (&xc)[NV][VW], float (&aq)[VW]) {
+        if constexpr (kOneRowSet<NPL>) {
+            static_assert(CH == 2 && VW == 4, "the ordering pin below lists the 8 values of a chunk");
+            constexpr int kLag = 3;
+            typedef float f4 __attribute__((ext_vector_type(4)));
+            typedef const __attribute__((address_space(3))) f4 *LdsRow;
+            LdsRow row = (LdsRow)(xr + lane);
+#pragma unroll
+            for (int e = 0; e < VW; ++e) aq[e] = 0.f;
+#pragma unroll
+            for (int c = 0; c < NCH + kLag; ++c) {
+                if (c < NCH) {
+                    const int m0 = c * CH;
+#pragma unroll
+                    for (int j = 0; j < CH; ++j)
+#pragma unroll
+                        for (int e = 0; e < VW; ++e) wv[m0 + j][e] = fmaf(-b, xc[m0 + j][e], wv[m0 + j][e]);
+                    // the refill may only be issued once the step has read the old chunk: without
+                    // this the LDS reads are hoisted to the top of the round (they do not depend
+                    // on b) and both rows are live at once
+                    asm volatile("" : "+v"(row)
+                                 : "v"(wv[m0][0]), "v"(wv[m0][1]), "v"(wv[m0][2]), "v"(wv[m0][3]),
+                                   "v"(wv[m0 + 1][0]), "v"(wv[m0 + 1][1]), "v"(wv[m0 + 1][2]), "v"(wv[m0 + 1][3]));
+#pragma unroll
+                    for (int j = 0; j < CH; ++j) {
+                        const f4 fresh = row[(m0 + j) * kWave];
+                        xc[m0 + j][0] = fresh.x; xc[m0 + j][1] = fresh.y;
+                        xc[m0 + j][2] = fresh.z; xc[m0 + j][3] = fresh.w;
+                    }
+                }
+                if (c >= kLag) {
+#pragma unroll
+                    for (int j = 0; j < CH; ++j) {
+                        const int m = (c - kLag) * CH + j;
+#pragma unroll
+                        for (int e = 0; e < VW; ++e) aq[e] = fmaf(wv[m][e], xc[m][e], aq[e]);
+                    }
+                }
+            }
+        }
+    };
+
     // one round: consumes xc = x_t, fills xn = x_{t+1}
     auto round = [&](int t, float (&xc)[NV][VW], float (&xn)[NV][VW]) {
         if ((t & 63) == 0) {
@@ -365,7 +417,8 @@ dense_rounds_kernel(const DenseArgs a)
         const float b = step * fast_rcp(sigma);
         const float qold = qv;
         float aq[VW];
-        pass(b, xrow(t + 1), xc, xn, aq);
+        if constexpr (kOneRowSet<NPL>) pass_one(b, xrow(t + 1), xc, aq);
+        else pass(b, xrow(t + 1), xc, xn, aq);
         if (((phase + t) & 63) == 63) {                  // re-measure ||v||^2 exactly
             float an[VW];
 #pragma unroll
@@ -398,11 +451,16 @@ dense_rounds_kernel(const DenseArgs a)
     for (int k = 0; k < ntiles; ++k) {
         if (k + 2 < ntiles) issue_tile(k + 2);
         const int rmax = min(RT, n - k * RT);
+        if constexpr (kOneRowSet<NPL>) {
 #pragma unroll 1
-        for (int rr = 0; rr < rmax; rr += 2) {
-            const int t = k * RT + rr;
-            round(t, xa, xb);
-            if (rr + 1 < rmax) round(t + 1, xb, xa);
+            for (int rr = 0; rr < rmax; ++rr) round(k * RT + rr, xa, xa);
+        } else {
+#pragma unroll 1
+            for (int rr = 0; rr < rmax; rr += 2) {
+                const int t = k * RT + rr;
+                round(t, xa, xb);
+                if (rr + 1 < rmax) round(t + 1, xb, xa);
+            }
         }
         __syncthreads();   // tile k+1 (and k+2) have landed; tile k may be overwritten
     }
