@@ -33,6 +33,7 @@
 #include "oco_internal.h"
 
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
 
 namespace oco {
@@ -550,31 +551,38 @@ hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
     if (ncu <= 0) ncu = 256;
 
     // Wavefronts per workgroup: the value that leaves the least work on the busiest compute
-    // unit.  With c workgroups resident per unit the grid is taken in ceil(nWG / (ncu*c))
-    // batches; a batch puts l = resident*wpb/4 wavefronts on each SIMD and its duration
-    // grows with l as g(l), fitted to sweeps on MI355X: up to about four wavefronts per SIMD
-    // mostly fill each other's stalls (the round is a dependent chain), beyond that they
-    // share the issue slots.
-    auto g = [](double l) { return l <= 1.0 ? 1.0 : (l <= 4.0 ? 1.0 + 0.1 * (l - 1.0) : 1.3 + 0.35 * (l - 4.0)); };
+    // unit.  A unit gets ceil(nWG / ncu) workgroups, c of them resident at a time: so many full
+    // passes plus a last, emptier one.  A pass puts l = resident*wpb/4 wavefronts on each SIMD
+    // and its duration grows with l as g(l), fitted to sweeps on MI355X: up to about four
+    // wavefronts per SIMD mostly fill each other's stalls (the round is a dependent chain),
+    // beyond that they share the issue slots.
+    auto g = [](double l) {
+        return l <= 1.0 ? 1.0 : l <= 4.0 ? 1.0 + 0.1 * (l - 1.0) : l <= 6.0 ? 1.3 + 0.2 * (l - 4.0) : 1.7 + 0.55 * (l - 6.0);
+    };
     const int per_run = a.per_run;
     int best = 0;
     double best_cost = 0.0;
     for (int w = C::MAXW; w >= 1; --w) {
-        // Candidates: multiples of four (a workgroup's wavefronts are dealt to the four SIMDs in
-        // turn, and with a barrier per tile the fullest SIMD sets the pace: other sizes measured
-        // 20-60 % slower), sizes that divide a run's tasks evenly, and tiny workgroups for tiny runs.
-        const bool candidate = w % 4 == 0 || (w >= 3 && per_run % w == 0) || (per_run < 4 && w == per_run);
-        if (!candidate) continue;
+        // A workgroup's wavefronts are dealt to the four SIMDs in turn and there is a barrier per
+        // tile, so sizes that are not a multiple of four leave SIMDs unevenly loaded (measured up
+        // to 20-60 % slower at equal occupancy): they pay a penalty and win only where they save a
+        // pass of the grid.  Tiny workgroups only for tiny runs.
+        if (w < 3 && !(per_run < 4 && w == per_run)) continue;
         int c = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, reinterpret_cast<const void *>(kern),
                                                          w * kWave, smem) != hipSuccess || c <= 0)
             continue;
         const int64_t nwg = a.x_shared ? ((int64_t)a.R * per_run + w - 1) / w
                                        : (int64_t)a.R * ((per_run + w - 1) / w);
-        const int64_t batches = (nwg + (int64_t)ncu * c - 1) / ((int64_t)ncu * c);
-        const int64_t resident = nwg < (int64_t)ncu * c ? (nwg + ncu - 1) / ncu : c;   // per unit
-        const double cost = (double)batches * g((double)(resident * w) / 4.0);
-        if (best == 0 || cost < best_cost * (1.0 - 1e-9)) { best = w; best_cost = cost; }
+        const int64_t per_cu = (nwg + ncu - 1) / ncu;
+        const int64_t full = per_cu / c, rem = per_cu % c;
+        double cost = (double)full * g((double)(c * w) / 4.0) + (rem ? g((double)(rem * w) / 4.0) : 0.0);
+        if (w % 4 != 0 && per_run % w != 0) cost *= 1.1;
+        // on equal cost prefer more, smaller workgroups per unit (fewer wavefronts held up by one
+        // barrier), down to eight wavefronts (below that the per-workgroup staging of x shows)
+        const bool better = best == 0 || cost < best_cost * (1.0 - 1e-9) ||
+                            (w >= 8 && cost <= best_cost * (1.0 + 1e-9));
+        if (better) { best = w; best_cost = cost; }
     }
     if (const char *ov = getenv("OCO_DENSE_WPB")) {      // tuning override: wavefronts per workgroup
         const int w = atoi(ov);
@@ -582,6 +590,8 @@ hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
     }
     if (best == 0) return hipErrorInvalidConfiguration;
     plan->cost = best_cost;
+    if (getenv("OCO_DENSE_VERBOSE"))
+        fprintf(stderr, "dense plan: NPL %d per_run %d -> wpb %d cost %.3f\n", NPL, per_run, best, best_cost);
     int c = 1;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, reinterpret_cast<const void *>(kern), best * kWave,
                                                      smem) != hipSuccess || c <= 0)
@@ -591,7 +601,7 @@ hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
     plan->wpb = best;
     plan->nwg = a.x_shared ? ((int64_t)a.R * per_run + best - 1) / best
                            : (int64_t)a.R * ((per_run + best - 1) / best);
-    plan->batches = (plan->nwg + (int64_t)ncu * c - 1) / ((int64_t)ncu * c);
+    plan->batches = ((plan->nwg + ncu - 1) / ncu + c - 1) / c;
     return hipSuccess;
 }
 
