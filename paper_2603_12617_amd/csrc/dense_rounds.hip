@@ -133,6 +133,12 @@ dense_rounds_kernel(const DenseArgs a)
     constexpr int RING_ROUNDS = kRing * RT;
     constexpr int NI = TILE / 4 / kWave;        // 1 KB copy instructions per tile
     constexpr int CH = NV >= 2 ? 2 : 1;         // LDS reads per chunk
+#ifndef OCO_NACC64
+#define OCO_NACC64 4
+#endif
+    // partial sums of the next-round dot: two chains (one add to combine them), four where the
+    // chains would get 32 FMAs long
+    constexpr int NACC = NPL >= 64 ? OCO_NACC64 : (VW >= 2 ? 2 : 1);
     constexpr int NCH = NV / CH;
     static_assert(TILE % (4 * kWave) == 0, "tile must be a whole number of 1 KB copies");
     static_assert(RT % 2 == 0, "the round loop is unrolled by two");
@@ -267,6 +273,11 @@ dense_rounds_kernel(const DenseArgs a)
     }
 
     // ---- learner wavefront ---------------------------------------------------------------
+    auto dot_total = [](const float (&p)[VW]) {
+        if constexpr (NACC == 4) return (p[0] + p[1]) + (p[2] + p[3]);
+        else if constexpr (NACC == 2) return p[0] + p[1];
+        else return p[0];
+    };
     float wv[NV][VW];           // v = iterate / sigma
     float xa[NV][VW], xb[NV][VW];   // x_t / x_{t+1}, swapping roles every round
     float sigma = a.sigma[(int64_t)r * K + i];
@@ -292,11 +303,11 @@ dense_rounds_kernel(const DenseArgs a)
             for (int e = 0; e < VW; ++e) {
                 const int j = (m * kWave + lane) * VW + e;
                 wv[m][e] = j < d ? src[j] : 0.f;
-                acc[e] = fmaf(wv[m][e], xa[m][e], acc[e]);
+                acc[e & (NACC - 1)] = fmaf(wv[m][e], xa[m][e], acc[e & (NACC - 1)]);   // same order as the passes
                 xb[m][e] = 0.f;
             }
         }
-        qv = wave_sum(combine<VW>(acc));
+        qv = wave_sum(dot_total(acc));
         z = sigma * qv;                               // z_0 = <w_0, x_0>
     }
     const float *x2row = a.x2 + (a.x_shared ? 0 : (int64_t)r * a.x2_run_stride);
@@ -306,6 +317,12 @@ dense_rounds_kernel(const DenseArgs a)
     const float D = a.D;
     const float D2 = D * D;
     float *zrow = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)i * a.zl.zs_i;
+    // sigma changes only when a projection is active (and only downwards): its reciprocal and
+    // the threshold D^2 / sigma^2 on ||v||^2 are functions of sigma alone, recomputed with it,
+    // so that a round that does not project pays one compare for the projection
+    float isig = fast_rcp(sigma);
+    float thr = D2 * isig * isig;
+    const float eta2 = 2.0f * eta;
 
     // the pass over the registers: step and next-round dot
     auto pass = [&](float b, const V *xr, float (&xc)[NV][VW], float (&xn)[NV][VW], float (&aq)[VW]) {
@@ -329,7 +346,7 @@ dense_rounds_kernel(const DenseArgs a)
                 for (int e = 0; e < VW; ++e) {
                     const float w1 = fmaf(-b, xc[m][e], wv[m][e]);
                     wv[m][e] = w1;
-                    aq[e] = fmaf(w1, xn[m][e], aq[e]);
+                    aq[e & (NACC - 1)] = fmaf(w1, xn[m][e], aq[e & (NACC - 1)]);
                 }
             }
             if (NCH > 2) __builtin_amdgcn_sched_barrier(0);
@@ -374,7 +391,7 @@ dense_rounds_kernel(const DenseArgs a)
                     for (int j = 0; j < CH; ++j) {
                         const int m = (c - kLag) * CH + j;
 #pragma unroll
-                        for (int e = 0; e < VW; ++e) aq[e] = fmaf(wv[m][e], xc[m][e], aq[e]);
+                        for (int e = 0; e < VW; ++e) aq[e & (NACC - 1)] = fmaf(wv[m][e], xc[m][e], aq[e & (NACC - 1)]);
                     }
                 }
             }
@@ -405,7 +422,7 @@ dense_rounds_kernel(const DenseArgs a)
         if (lane == (t & 63)) zreg = zp;
         // fold sigma into v first (never between computing z and using it, so that z is
         // the same whether or not a call boundary falls here)
-        if (sigma < kFoldLo || sigma > kFoldHi) {
+        if (sigma < kFoldLo) {                           // (sigma never grows: no upper test)
 #pragma unroll
             for (int m = 0; m < NV; ++m)
 #pragma unroll
@@ -413,9 +430,12 @@ dense_rounds_kernel(const DenseArgs a)
             n2 *= (double)sigma * (double)sigma;
             qv = z;
             sigma = 1.f;
+            isig = 1.f;
+            thr = D2;
         }
-        const float step = eta * slope<LOSS>(zp, yt);       // w-space step along x_t
-        const float b = step * fast_rcp(sigma);
+        // w-space step along x_t; for the squared loss eta * 2 (z - y) = (2 eta) (z - y) exactly
+        const float step = LOSS == 1 ? eta2 * (zp - yt) : eta * slope<LOSS>(zp, yt);
+        const float b = step * isig;
         const float qold = qv;
         float aq[VW];
         if constexpr (kOneRowSet<NPL>) pass_one(b, xrow(t + 1), xc, aq);
@@ -434,9 +454,14 @@ dense_rounds_kernel(const DenseArgs a)
             n2 = fma(bd * bd, (double)x2t, fma(-2.0 * bd, (double)qv, n2));
             n2 = n2 > 0.0 ? n2 : 0.0;
         }
-        qv = wave_sum(combine<VW>(aq));                  // <v, x_{t+1}>
+        qv = wave_sum(dot_total(aq));                      // <v, x_{t+1}>
         const float nrm = (float)n2;                     // ||v||^2
-        if (sigma * sigma * nrm > D2) sigma = D * __builtin_amdgcn_rsqf(nrm);   // projection
+        if (__builtin_amdgcn_ballot_w64(nrm > thr) != 0) {   // projection (the same in every lane)
+            asm volatile("" ::: "memory");    // keeps the branch: its body is not to be run speculatively
+            sigma = D * __builtin_amdgcn_rsqf(nrm);
+            isig = fast_rcp(sigma);
+            thr = D2 * isig * isig;
+        }
         z = sigma * qv;
         if (OPT) {                                       // next round's hint and <w^_{t+1}, x_t>
             hp = sigma * fmaf(-b, x2t, qold);
