@@ -48,8 +48,11 @@
 // horizon; after each segment a grid-wide kernel folds the 64-learner column
 // groups whose smallest sigma has dropped below 2^-64 (a streaming pass at HBM
 // speed, and a no-op otherwise).  Should a sigma fall below 2^-100 inside a
-// segment (steps many orders of magnitude larger than the ball), the chain
-// wavefront folds its own columns in place, slowly but safely.  Windows are
+// segment (steps larger than the ball: sigma then shrinks by a constant factor
+// every round), the chain stops after that round and the workgroup folds its
+// own columns: all wavefronts apply the window's steps so far, scale the
+// columns, measure ||v||^2 exactly (fixed order) and gather the remaining
+// rounds' <v, x_t> afresh; then the chain goes on.  Windows are
 // aligned to multiples of 64 rounds of the horizon and all fold decisions
 // depend on the state and the absolute round index only.
 //
@@ -58,6 +61,8 @@
 // <x_{t-1}, x_t> and ||x_{t-1}||^2, so V holds the intermediate model and the
 // memory phases are unchanged.
 #include "oco_internal.h"
+
+#include <type_traits>
 #include <stddef.h>
 #include <stdlib.h>
 #include "../../include/oco.h"
@@ -302,6 +307,11 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     constexpr int EPI = kWave / LPW;
     __shared__ Chain<LPW> ch;
     __shared__ __align__(16) WinStage stage[2];
+    // in-kernel fold: round after which the chain stopped (-1: none), the learners' scales, and
+    // one partial squared norm per wavefront and learner
+    __shared__ int fold_t, fold_gp;
+    __shared__ float fold_sf[LPW];
+    __shared__ double fold_part[kSpWaves][LPW];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -336,6 +346,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     const float Df = (float)a.D, D2f = Df * Df;
 
     stage_window(stage[0], a, recs[wbeg], plan.start(wbeg), plan.len(wbeg) * nnz, threadIdx.x, blockDim.x);
+    if (threadIdx.x == 0) fold_t = -1;
     wg_sync();
     for (int w = wbeg; w < wend; ++w) {
         WinStage &st = stage[(w - wbeg) & 1];
@@ -349,9 +360,8 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         const int ws = plan.start(w), wl = plan.len(w);
         // ---- A: q0_t = <v_start, x_t>; a wavefront takes rounds wave, wave + 16, ..., RA at a
         // time; slot e of the wavefront takes the entries j = e, e + EPI, ... of a round ----------
-        {
-            constexpr int RA = LPW == 64 ? 2 : 4;
-            constexpr int BK = LPW == 64 ? 16 : (LPW >= 16 ? 8 : (LPW == 8 ? 4 : 2));   // RA * BK gathers in flight
+        auto gather_q0 = [&](auto ra_tag, auto bk_tag) {
+            constexpr int RA = decltype(ra_tag)::value, BK = decltype(bk_tag)::value;   // RA * BK gathers in flight
             const int NL = (nnz + EPI - 1) / EPI;
             for (int tg = wave; tg < wl; tg += RA * kSpWaves) {
                 float acc[RA][4], yl[RA];
@@ -397,15 +407,56 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                     }
                 }
             }
-        }
+        };
+        // ---- C: V[col] += -b_t x_t[col] for the rounds t <= tmax.  All entries of a column belong
+        // to one wavefront, which walks its share of the column-sorted list EPI entries per
+        // instruction; entries of one column that meet in an instruction are summed across slots
+        // first (fixed order) -------------------------------------------------------------------
+        auto apply_steps = [&](int tmax, auto partial) {         // partial: only rounds t <= tmax (else all)
+            const int beg = __builtin_amdgcn_readfirstlane(offs[wave]);
+            const int end = __builtin_amdgcn_readfirstlane(offs[wave + 1]);
+            constexpr int NI = 4;                                // instructions per batch
+            for (int k0 = beg; k0 < end; k0 += NI * EPI) {
+                int cc[NI];
+                float xv[NI];
+#pragma unroll
+                for (int n = 0; n < NI; ++n) {
+                    const int k = k0 + n * EPI + e;
+                    const bool act = k < end;
+                    const int ee = perm[act ? k : end - 1];
+                    const int t = (int)(((unsigned)ee * mdiv) >> 18);
+                    cc[n] = act ? cw[ee] : -1;
+                    xv[n] = act && (!decltype(partial)::value || t <= tmax) ? -ch.bw[t][l] * vw[ee] : 0.f;
+                }
+#pragma unroll
+                for (int n = 0; n < NI; ++n) {
+                    bool last = true;
+                    if (EPI > 1) {
+#pragma unroll
+                        for (int sh = 1; sh < EPI; sh <<= 1) {
+                            const float ox = __shfl_up(xv[n], sh * LPW);
+                            const int oc = __shfl_up(cc[n], sh * LPW);
+                            if (e >= sh && oc == cc[n]) xv[n] += ox;
+                        }
+                        const int nc = __shfl_down(cc[n], LPW);
+                        last = e == EPI - 1 || nc != cc[n];
+                    }
+                    if (cc[n] >= 0 && last) unsafeAtomicAdd(a.V + (int64_t)cc[n] * a.RKp + uq, xv[n]);
+                }
+            }
+        };
+        gather_q0(std::integral_constant<int, LPW == 64 ? 2 : 4>(),
+                  std::integral_constant<int, LPW == 64 ? 16 : (LPW >= 16 ? 8 : (LPW == 8 ? 4 : 2))>());
         wg_sync();
-        // ---- B: the dependent rounds, scalars and LDS only (LPW lanes of wavefront 0) ----------
-        if (chain) {
-            int gp = 0;                                          // next Gram value of the window
-            float qn = ch.q0[0][l], yn = ch.yv[0][l];
-            RoundRec rn = rr[0];
-            float *zs = a.Z + (int64_t)ws * a.zl.zs_t;
-            for (int t = 0; t < wl; ++t) {
+        // ---- B: the dependent rounds, scalars and LDS only (LPW lanes of wavefront 0).  If a
+        // learner's sigma falls below the fold threshold the chain stops after that round, the
+        // whole workgroup folds (below) and the chain goes on from the next round ---------------
+        auto run_chain = [&](int tstart, int gp) {               // gp: next Gram value of the window
+            float qn = ch.q0[tstart][l], yn = ch.yv[tstart][l];
+            RoundRec rn = rr[tstart];
+            float *zs = a.Z + (int64_t)(ws + tstart) * a.zl.zs_t;
+            int tend = wl;                                       // a fold request ends the loop early
+            for (int t = tstart; t < tend; ++t) {
                 const float qv = qn, yy = yn;                    // <v_t, x_t>, y_t
                 const RoundRec rc = rn;                          // collisions with later rounds, ||x_t||^2
                 qn = ch.q0[t + 1][l]; yn = ch.yv[t + 1][l]; rn = rr[t + 1];        // next round, early
@@ -452,31 +503,14 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                     x2p = (float)rc.x2;
                 }
                 if (__any(sigma < kSparseFoldLo)) {
-                    // emergency fold.  v = v_start - sum_{r<=t} b_r x_r is not in memory yet:
-                    // apply the window's steps so far, fold, and restart the window after t.
-                    for (int rd = 0; rd <= t; ++rd)
-                        for (int j = 0; j < nnz; ++j) {
-                            float *p = Vq + (int64_t)cw[rd * nnz + j] * a.RKp;
-                            *p = ldv(p) + (-ch.bw[rd][l] * vw[rd * nnz + j]);
-                        }
-                    double m2 = 0.0;
-                    for (int64_t j = 0; j < a.d; ++j) {
-                        const float wv = ldv(Vq + j * a.RKp) * sf;
-                        Vq[j * a.RKp] = wv;
-                        m2 += (double)wv * (double)wv;
-                    }
-                    n2 = m2;
-                    sigma = 1.0; sd2 = 1.0; sf = 1.f; isf = 1.f;
-                    for (int rd = 0; rd <= t; ++rd) ch.bw[rd][l] = 0.f;      // already applied
-                    for (int t2 = t + 1; t2 < wl; ++t2) {                    // fresh <v, x_t2>
-                        float acc = 0.f;
-                        for (int j = 0; j < nnz; ++j)
-                            acc = fmaf(ldv(Vq + (int64_t)cw[t2 * nnz + j] * a.RKp), vw[t2 * nnz + j], acc);
-                        ch.q0[t2][l] = acc;
-                    }
-                    qn = ch.q0[t + 1][l];
+                    if (lane == 0) { fold_t = t; fold_gp = gp; }
+                    fold_sf[l] = sf;
+                    tend = t + 1;
                 }
             }
+        };
+        if (chain) {
+            run_chain(0, 0);
         } else if (wave != 0 && w + 1 < wend) {
             // ---- meanwhile the other wavefronts stage the next window -------------------------
             stage_window(stage[(w + 1 - wbeg) & 1], a, recs[w + 1], plan.start(w + 1), plan.len(w + 1) * nnz,
@@ -491,42 +525,51 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             }
         }
         wg_sync();
-        // ---- C: V[col] += -b_t x_t[col].  All entries of a column belong to one wavefront, which
-        // walks its share of the column-sorted list EPI entries per instruction; entries of one
-        // column that meet in an instruction are summed across slots first (fixed order) ---------
+        for (int ft = fold_t; ft >= 0; ft = fold_t) {
+        const int gp0 = fold_gp;
+        // ---- fold inside the window (sigma below 2^-100 before the segment ended): apply the
+        // steps taken so far, scale the workgroup's columns of V by sigma with all wavefronts,
+        // measure ||v||^2 exactly, and take the remaining rounds' <v, x_t> afresh ----------------
+        apply_steps(ft, std::true_type());
+        wg_sync();
         {
-            const int beg = __builtin_amdgcn_readfirstlane(offs[wave]);
-            const int end = __builtin_amdgcn_readfirstlane(offs[wave + 1]);
-            constexpr int NI = 4;                                // instructions per batch
-            for (int k0 = beg; k0 < end; k0 += NI * EPI) {
-                int cc[NI];
-                float xv[NI];
+            for (int rd = (int)threadIdx.x / LPW; rd <= ft; rd += kSpWaves * EPI) ch.bw[rd][l] = 0.f;   // applied
+            const float fs = fold_sf[l];
+            const int64_t nslots = kSpWaves * EPI;
+            double m2 = 0.0;
+            for (int64_t j0 = wave * EPI + e; j0 < a.d; j0 += 4 * nslots) {
+                float vv[4];
 #pragma unroll
-                for (int n = 0; n < NI; ++n) {
-                    const int k = k0 + n * EPI + e;
-                    const bool act = k < end;
-                    const int ee = perm[act ? k : end - 1];
-                    const int t = (int)(((unsigned)ee * mdiv) >> 18);
-                    cc[n] = act ? cw[ee] : -1;
-                    xv[n] = act ? -ch.bw[t][l] * vw[ee] : 0.f;
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t j = j0 + u * nslots;
+                    vv[u] = j < a.d ? ldv(Vq + j * a.RKp) : 0.f;
                 }
 #pragma unroll
-                for (int n = 0; n < NI; ++n) {
-                    bool last = true;
-                    if (EPI > 1) {
-#pragma unroll
-                        for (int sh = 1; sh < EPI; sh <<= 1) {
-                            const float ox = __shfl_up(xv[n], sh * LPW);
-                            const int oc = __shfl_up(cc[n], sh * LPW);
-                            if (e >= sh && oc == cc[n]) xv[n] += ox;
-                        }
-                        const int nc = __shfl_down(cc[n], LPW);
-                        last = e == EPI - 1 || nc != cc[n];
-                    }
-                    if (cc[n] >= 0 && last) unsafeAtomicAdd(a.V + (int64_t)cc[n] * a.RKp + uq, xv[n]);
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t j = j0 + u * nslots;
+                    const float wv = vv[u] * fs;
+                    if (j < a.d) Vq[j * a.RKp] = wv;
+                    m2 += (double)wv * (double)wv;
                 }
             }
+#pragma unroll
+            for (int sh = 32; sh >= LPW; sh >>= 1) m2 += __shfl_xor(m2, sh);
+            if (lane < LPW) fold_part[wave][l] = m2;
         }
+        wg_sync();
+        if (chain) {
+            double m2 = 0.0;
+            for (int wv = 0; wv < kSpWaves; ++wv) m2 += fold_part[wv][l];
+            n2 = m2;
+            sigma = 1.0; sd2 = 1.0; sf = 1.f; isf = 1.f;
+        }
+        if (threadIdx.x == 0) fold_t = -1;
+        gather_q0(std::integral_constant<int, 1>(), std::integral_constant<int, 2>());   // rare: few registers
+        wg_sync();
+        if (chain) run_chain(ft + 1, gp0);
+        wg_sync();
+        }
+        apply_steps(wl - 1, std::false_type());
         wg_sync();
     }
     if (chain) { a.sigma[q] = sigma; a.n2[q] = n2; }

@@ -237,6 +237,26 @@ def test_sparse_rounds_for_every_workgroup_share(lpw, monkeypatch):
         _check(wl, data, _gpu(wl, data), norm_every=0, label="c5 lpw=%d %s" % (lpw, over))
 
 
+@pytest.mark.parametrize("lpw", [4, 16, 64])
+def test_sparse_rounds_with_steps_far_larger_than_the_ball(lpw, monkeypatch):
+    """Steps hundreds of times the radius make the lazy scale shrink by a constant factor every
+    round: it falls below the in-kernel fold threshold many times inside one launch segment, and
+    the workgroup folds its columns (all wavefronts, ragged row count) and goes on.  Same state
+    whether the rounds come in one call or in calls of 128."""
+    monkeypatch.setenv("OCO_SPARSE_LPW", str(lpw))
+    wl = WL.make("c5", T=500, R=5, d=6007, K=4, wstar_nnz=64, eta=(0.5, 8.0, 100.0, 2000.0))
+    data = WL.generate(wl)
+    print("case c5 big steps lpw", lpw, flush=True)
+    whole = _gpu(wl, data)
+    _check(wl, data, whole, norm_every=0, label="c5 big steps lpw=%d" % lpw)
+    part = _gpu(wl, data, chunk=128, n_max=128)
+    for k in ("regret", "L", "W", "p", "wbar"):
+        assert np.array_equal(whole[k], part[k]), k
+    wl = WL.make("c5", T=300, R=2, d=400, K=3, nnz=16, wstar_nnz=30, eta=(1.0, 50.0, 3000.0), optimistic=True)
+    data = WL.generate(wl)
+    _check_sparse_optimistic(wl, data, _gpu(wl, data), "c5 optimistic big steps lpw=%d" % lpw)
+
+
 @pytest.mark.parametrize("lpw", [4, 8, 64])
 def test_sparse_rounds_with_a_column_in_every_round(lpw, monkeypatch):
     """A feature present in every round (a bias column) makes every pair of rounds of a window
