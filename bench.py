@@ -235,6 +235,28 @@ def main():
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                      "frac": achieved / peak, "traffic": traffic, "kernel": "round kernel (S0-S2,S4)"},
     }
+    # what rocprofv3 counted behind L2 for the round kernels of one step, as a rate, against the
+    # nominal peak and against a plain device copy timed here
+    if traffic:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dst.copy_(src)
+        ev0.record()
+        for _ in range(3):
+            dst.copy_(src)
+        ev1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 3 * 2 * src.numel() * 4 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+        del src, dst
+        torch.cuda.empty_cache()
+        gbs = traffic / (main_res["round_kernel_ms"] * 1e-3) / 1e9
+        line["hbm_counters"] = {"traffic_bytes_per_step": traffic, "rate_GBps": gbs, "frac_of_peak": gbs / PEAK_HBM_GBS,
+                                "copy_ceiling_GBps": copy_gbs, "frac_of_copy_ceiling": gbs / copy_gbs,
+                                "source": "profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE)"}
+    bpath = os.path.join(ROOT, "profiles", "binding_resource.json")
+    if os.path.exists(bpath):
+        line["binding_resource"] = json.load(open(bpath)).get(a.config)
     ab = keep["accel"]
     line["accel_bounds_k4_alpha0.05"] = {"gamma_lower_mean": float(ab[:, 2].mean()), "gamma_upper": float(ab[0, 3]),
                                          "note": "Theorem 1 from the regret of each run, mean over runs"}
