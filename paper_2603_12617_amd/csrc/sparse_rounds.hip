@@ -327,10 +327,17 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     const float eta = valid ? a.eta[i] : 0.f;
     float *Vq = a.V + q;
     const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
-    const unsigned zoff = (unsigned)(r * a.zl.zs_r + i * a.zl.zs_i);
+    const unsigned zoff4 = 4u * (unsigned)(r * a.zl.zs_r + i * a.zl.zs_i);    // byte offset inside a round's slice of Z
+    const int64_t zstep = 4 * a.zl.zs_t;
     const double D2 = a.D * a.D;
     const WinRec *recs = static_cast<const WinRec *>(a.scratch);
-    const bool chain = wave == 0 && lane < LPW;     // the lanes that run the dependent rounds
+    // the lanes that run the dependent rounds (padding learners of the last workgroup take no part:
+    // their step sizes stay zero and their scale stays one)
+    const bool chain = wave == 0 && lane < LPW && valid;
+    if (wave == 0 && lane < LPW && !valid) {
+        for (int rd = 0; rd < kWin; ++rd) ch.bw[rd][l] = 0.f;
+    }
+    if (wave == 0 && lane < LPW) fold_sf[l] = 1.f;
     double sigma = 1.0, n2 = 0.0;
     if (chain) { sigma = a.sigma[q]; n2 = a.n2[q]; }
     // Wait for these loads here.  Left to the compiler, the wait lands at their first use inside
@@ -454,7 +461,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         auto run_chain = [&](int tstart, int gp) {               // gp: next Gram value of the window
             float qn = ch.q0[tstart][l], yn = ch.yv[tstart][l];
             RoundRec rn = rr[tstart];
-            float *zs = a.Z + (int64_t)(ws + tstart) * a.zl.zs_t;
+            char *zs = reinterpret_cast<char *>(a.Z + (int64_t)(ws + tstart) * a.zl.zs_t);
             int tend = wl;                                       // a fold request ends the loop early
             for (int t = tstart; t < tend; ++t) {
                 const float qv = qn, yy = yn;                    // <v_t, x_t>, y_t
@@ -469,8 +476,8 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                     const float sp = mf > D2f ? Df * __builtin_amdgcn_rsqf(mf) : 1.f;
                     z = sp * fmaf(-ha, g01[t], z);
                 }
-                if (valid) zs[zoff] = z;
-                zs += a.zl.zs_t;
+                *reinterpret_cast<float *>(zs + zoff4) = z;
+                zs += zstep;
                 const float step = eta_r * slope<LOSS>(z, yy);
                 const float b = step * isf;
                 ch.bw[t][l] = b;
