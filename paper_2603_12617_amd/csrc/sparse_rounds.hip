@@ -344,6 +344,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     // the round loop, where it also waits for the previous round's store, every round.
     float eta_r = eta;
     asm volatile("" : "+v"(eta_r), "+v"(sigma), "+v"(n2));
+    const float eta2_r = 2.f * eta_r;
     double sd2 = sigma * sigma;
     float sf = (float)sigma, isf = __builtin_amdgcn_rcpf(sf);
     // optimistic update (Eq. (3)): hint ha * x_{t-1}, hp = <w^_t, x_{t-1}>, x2p = ||x_{t-1}||^2
@@ -478,7 +479,8 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                 }
                 *reinterpret_cast<float *>(zs + zoff4) = z;
                 zs += zstep;
-                const float step = eta_r * slope<LOSS>(z, yy);
+                // for the squared loss eta * 2 (z - y) = (2 eta) (z - y) exactly
+                const float step = LOSS == 1 ? eta2_r * (z - yy) : eta_r * slope<LOSS>(z, yy);
                 const float b = step * isf;
                 ch.bw[t][l] = b;
                 // (readfirstlane returns int: go through unsigned, or the low word sign-extends)
@@ -498,12 +500,13 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                 const double bd = (double)b;
                 n2 = fma(bd, fma(bd, rc.x2, (double)(-2.f * qv)), n2);
                 n2 = n2 > 0.0 ? n2 : 0.0;
-                if (n2 * sd2 > D2) {                             // projection: sigma = D / ||v||
-                    sigma = a.D * rsqrt_pos(n2);
-                    sd2 = sigma * sigma;
-                    sf = (float)sigma;
-                    isf = __builtin_amdgcn_rcpf(sf);
-                }
+                // projection: sigma = D / ||v||.  One select, then the values that follow from sigma
+                // (the chain is bound by the number of instructions a single wavefront can issue)
+                const double snew = a.D * rsqrt_pos(n2);
+                sigma = n2 * sd2 > D2 ? snew : sigma;
+                sd2 = sigma * sigma;
+                sf = (float)sigma;
+                isf = __builtin_amdgcn_rcpf(sf);
                 if (OPT) {                                      // next round's hint and <w^_{t+1}, x_t>
                     hp = sf * fmaf(-b, (float)rc.x2, qv);
                     ha = step;
