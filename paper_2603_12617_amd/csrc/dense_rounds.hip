@@ -19,9 +19,10 @@
 // and the norm needed by the projection follows from scalars already at hand,
 //     ||v - b x_t||^2 = ||v||^2 - 2 b <v, x_t> + b^2 ||x_t||^2
 // (<v, x_t> is the previous round's q, ||x_t||^2 comes from a small pre-pass
-// over the round stream), carried in float64 and re-measured exactly, as
-// sum_j v_j^2 inside the pass, at every 64th round of the horizon so that
-// rounding cannot accumulate.  Then sigma <- D/||v|| if sigma ||v|| > D, and
+// over the round stream), carried in float32 like its inputs (float64 for the
+// three scalars changed no result: the error is that of <v, x_t>) and
+// re-measured exactly, as sum_j v_j^2 inside the pass, at every 64th round of
+// the horizon so that rounding cannot accumulate.  Then sigma <- D/||v|| if sigma ||v|| > D, and
 // z_{t+1} = sigma q.  x_{t+1} is
 // read from LDS during the pass, one chunk ahead of the arithmetic, and stays
 // in registers as the next round's x_t (two register sets that swap roles, the
@@ -281,7 +282,7 @@ dense_rounds_kernel(const DenseArgs a)
     float wv[NV][VW];           // v = iterate / sigma
     float xa[NV][VW], xb[NV][VW];   // x_t / x_{t+1}, swapping roles every round
     float sigma = a.sigma[(int64_t)r * K + i];
-    double n2 = a.n2[(int64_t)r * K + i];       // ||v||^2
+    float n2 = (float)a.n2[(int64_t)r * K + i];  // ||v||^2 (kept as float64 in the state)
     const float eta = a.eta[i];
     float qv, z, zreg = 0.f, yreg = 0.f, x2reg = 0.f;   // qv = <v, x_t>, z = sigma qv
     // optimistic update: the hint is ha * x_{t-1}; hp = <w^_t, x_{t-1}>; g01 = <x_{t-1}, x_t>
@@ -414,7 +415,7 @@ dense_rounds_kernel(const DenseArgs a)
             const float g01t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g01reg), t & 63));
             const double had = (double)ha;
             const double m = fma(had * had, (double)x2prev,
-                                 fma(-2.0 * had, (double)hp, (double)sigma * (double)sigma * n2));
+                                 fma(-2.0 * had, (double)hp, (double)sigma * (double)sigma * (double)n2));
             const float mf = (float)m;
             const float sp = mf > D2 ? D * __builtin_amdgcn_rsqf(mf) : 1.f;
             zp = sp * fmaf(-ha, g01t, z);
@@ -427,7 +428,7 @@ dense_rounds_kernel(const DenseArgs a)
             for (int m = 0; m < NV; ++m)
 #pragma unroll
                 for (int e = 0; e < VW; ++e) wv[m][e] *= sigma;
-            n2 *= (double)sigma * (double)sigma;
+            n2 *= sigma * sigma;
             qv = z;
             sigma = 1.f;
             isig = 1.f;
@@ -448,14 +449,12 @@ dense_rounds_kernel(const DenseArgs a)
             for (int m = 0; m < NV; ++m)
 #pragma unroll
                 for (int e = 0; e < VW; ++e) an[e] = fmaf(wv[m][e], wv[m][e], an[e]);
-            n2 = (double)wave_sum(combine<VW>(an));
+            n2 = wave_sum(combine<VW>(an));
         } else {
-            const double bd = (double)b;
-            n2 = fma(bd * bd, (double)x2t, fma(-2.0 * bd, (double)qv, n2));
-            n2 = n2 > 0.0 ? n2 : 0.0;
+            n2 = fmaxf(fmaf(b, fmaf(b, x2t, -2.f * qv), n2), 0.f);
         }
         qv = wave_sum(dot_total(aq));                      // <v, x_{t+1}>
-        const float nrm = (float)n2;                     // ||v||^2
+        const float nrm = n2;                            // ||v||^2
         if (__builtin_amdgcn_ballot_w64(nrm > thr) != 0) {   // projection (the same in every lane)
             asm volatile("" ::: "memory");    // keeps the branch: its body is not to be run speculatively
             sigma = D * __builtin_amdgcn_rsqf(nrm);
@@ -500,7 +499,7 @@ dense_rounds_kernel(const DenseArgs a)
                 const int j = (m * kWave + lane) * VW + e;
                 if (j < d) dst[j] = wv[m][e];
             }
-        if (lane == 0) { a.sigma[(int64_t)r * K + i] = sigma; a.n2[(int64_t)r * K + i] = n2; }
+        if (lane == 0) { a.sigma[(int64_t)r * K + i] = sigma; a.n2[(int64_t)r * K + i] = (double)n2; }
         if (OPT && lane == 0) { a.ha[(int64_t)r * K + i] = ha; a.hp[(int64_t)r * K + i] = hp; }
     }
 }
