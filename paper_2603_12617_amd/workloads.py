@@ -128,7 +128,12 @@ def _csr_rows(wl: Workload) -> tuple:
     """T rows of exactly nnz distinct column indices, ascending, with values
     N(0, 1/nnz)."""
     rng = _rng(wl, 0, _S_COL)
-    col = np.sort(rng.integers(0, wl.d, size=(wl.T, wl.nnz), dtype=np.int64), axis=1)
+    if wl.nnz > wl.d:
+        raise ValueError("a sparse row cannot have more entries than columns")
+    if wl.nnz * 8 > wl.d:       # rows that fill much of the width: a random subset (redrawing would not end)
+        col = np.sort(np.argsort(rng.random((wl.T, wl.d)), axis=1)[:, :wl.nnz], axis=1).astype(np.int64)
+    else:
+        col = np.sort(rng.integers(0, wl.d, size=(wl.T, wl.nnz), dtype=np.int64), axis=1)
     while True:
         bad = np.nonzero((col[:, 1:] == col[:, :-1]).any(axis=1))[0]
         if bad.size == 0:
