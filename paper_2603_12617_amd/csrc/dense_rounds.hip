@@ -65,6 +65,8 @@ constexpr int64_t kStreamPieceBytes = 64ll << 20;  // shared round stream per la
 constexpr int64_t kPieceMinRounds = 512;           // no piece shorter than this
 constexpr int64_t kBesideMaxWaves = 1024;          // one wavefront per SIMD: the chip is mostly idle
 constexpr int64_t kBesidePieces = 4;
+constexpr int64_t kHalfMinTasks = 8192;           // two learners per wavefront from this many learners on:
+                                                   // four wavefronts per SIMD (with 4352 it measured 13 % slower)
 
 template <int VW> struct VecT;
 template <> struct VecT<1> { using type = float; };
@@ -504,6 +506,278 @@ dense_rounds_kernel(const DenseArgs a)
     }
 }
 
+// ---- two learners per wavefront ------------------------------------------------------------
+// For d <= 1024 more than half of a round's instructions are its scalar section (slope, norm
+// identity, reduction, projection), which every lane executes alike.  Here each half of a
+// wavefront (32 lanes) owns one learner, so that section serves two learners at once; a lane
+// keeps d/32 coordinates.  Shared round stream only; the comparators' predictions come from the
+// contraction kernel, so every task is a learner.  Same arithmetic per learner as above except
+// that sums run over 32 lanes.
+template <int NPL> struct HalfCfg {
+    static constexpr int RT = DenseCfg<NPL / 2>::RT;   // same tile bytes as the kernel above at equal d
+    static constexpr int MAXW = NPL >= 32 ? 12 : 16;   // register budget
+};
+
+// Sum over the 32 lanes of each half of the wavefront (fixed order: xor-butterfly inside each row
+// of 16 lanes, then row 1 += row 0 and row 3 += row 2); every lane gets the sum of its half.
+__device__ __forceinline__ float half_sum(float v, bool upper)
+{
+    v += dpp_term<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v += dpp_term<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v += dpp_term<0x141, 0xF>(v);   // row_half_mirror
+    v += dpp_term<0x140, 0xF>(v);   // row_mirror
+    asm("s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 0"
+        : "+v"(v));
+    const float lo = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31));
+    const float hi = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+    return upper ? hi : lo;
+}
+
+template <int NPL, int LOSS, bool OPT>
+__global__ void __launch_bounds__(HalfCfg<NPL>::MAXW * kWave)
+dense_rounds_half_kernel(const DenseArgs a)
+{
+    constexpr int LW = 32;                      // lanes per learner
+    constexpr int VW = 4;
+    constexpr int NV = NPL / VW;
+    constexpr int DP = NPL * LW;                // padded dimension
+    constexpr int RT = HalfCfg<NPL>::RT;
+    constexpr int TILE = RT * DP;
+    constexpr int RING_ROUNDS = kRing * RT;
+    constexpr int NI = TILE / 4 / kWave;
+    constexpr int CH = NV >= 2 ? 2 : 1;
+    constexpr int NCH = NV / CH;
+    static_assert(NPL % 4 == 0 && TILE % (4 * kWave) == 0 && RT % 2 == 0, "tile shape");
+    using V = float4;
+
+    extern __shared__ float4 smem4[];
+    float *ring = reinterpret_cast<float *>(smem4);
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int wpb = nthreads >> 6;
+    const int lane = tid & 63;
+    const int ll = lane & (LW - 1);             // lane inside the half
+    const bool upper = lane >= LW;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = a.n;
+    const int d = a.d;
+    const int K = a.K;
+
+    // task = learner (run r, index i); the upper half of the last wavefront may have none: it
+    // then repeats the last task and stores nothing
+    const int64_t ntask = (int64_t)a.R * K;
+    const int64_t q0 = 2 * ((int64_t)blockIdx.x * wpb + wave);
+    const bool active = q0 < ntask;             // per wavefront
+    const int64_t qraw = q0 + (upper ? 1 : 0);
+    const bool store = qraw < ntask;
+    const int64_t q = store ? qraw : ntask - 1;
+    const int r = (int)(q / K), i = (int)(q % K);
+    const float *xg = a.x;
+
+    auto issue_tile = [&](int k) {
+        float *dst = ring + (k % kRing) * TILE;
+        if (a.vec_ok) {
+            for (int ii = wave; ii < NI; ii += wpb) {
+                const int e = ii * kWave + lane;               // float4 index in the tile
+                const int rr = e / (DP / 4), j4 = e % (DP / 4);
+                const int tt = k * RT + rr;
+                if (tt < n && j4 * 4 < d)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(xg + (int64_t)tt * d + j4 * 4),
+                        (__attribute__((address_space(3))) void *)(dst + ii * 4 * kWave), 16, 0, 0);
+            }
+        } else {
+            for (int e = tid; e < TILE; e += nthreads) {
+                const int rr = e / DP, j = e % DP;
+                const int tt = k * RT + rr;
+                if (tt < n && j < d) dst[e] = xg[(int64_t)tt * d + j];
+            }
+        }
+    };
+
+    for (int e = tid; e < kRing * TILE / 4; e += nthreads) smem4[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+    const int ntiles = (n + RT - 1) / RT;
+    issue_tile(0);
+    if (ntiles > 1) issue_tile(1);
+    __syncthreads();
+
+    auto xrow = [&](int t) { return reinterpret_cast<const V *>(ring + (t % RING_ROUNDS) * DP); };
+
+    if (!active) {
+        for (int k = 0; k < ntiles; ++k) {
+            if (k + 2 < ntiles) issue_tile(k + 2);
+            __syncthreads();
+        }
+        return;
+    }
+
+    const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
+    float wv[NV][VW];
+    float xa[NV][VW], xb[NV][VW];
+    float sigma = a.sigma[(int64_t)r * K + i];
+    float n2 = (float)a.n2[(int64_t)r * K + i];
+    const float eta = a.eta[i];
+    float qv, z, zreg = 0.f, yreg = 0.f, x2reg = 0.f;
+    float ha = 0.f, hp = 0.f, x2prev = 0.f, g01reg = 0.f;
+    if (OPT) {
+        ha = a.ha[(int64_t)r * K + i];
+        hp = a.hp[(int64_t)r * K + i];
+        x2prev = a.x2last[0];
+    }
+    {
+        const float *src = a.V + ((int64_t)r * K + i) * d;
+        float acc[2] = {0.f, 0.f};
+#pragma unroll
+        for (int m = 0; m < NV; ++m) {
+            unpack<VW>(xrow(0)[m * LW + ll], xa[m]);
+#pragma unroll
+            for (int e = 0; e < VW; ++e) {
+                const int j = (m * LW + ll) * VW + e;
+                wv[m][e] = j < d ? src[j] : 0.f;
+                acc[e & 1] = fmaf(wv[m][e], xa[m][e], acc[e & 1]);     // same order as the passes
+                xb[m][e] = 0.f;
+            }
+        }
+        qv = half_sum(acc[0] + acc[1], upper);
+        z = sigma * qv;
+    }
+    const float *x2row = a.x2;
+    const float *g01row = OPT ? a.g01 : nullptr;
+    const int phase = (int)(a.t0 & 63);
+    const float D = a.D;
+    const float D2 = D * D;
+    float *zrow = a.Z + (int64_t)r * a.zl.zs_r + (int64_t)i * a.zl.zs_i;
+    float isig = fast_rcp(sigma);
+    float thr = D2 * isig * isig;
+    const float eta2 = 2.0f * eta;
+
+    auto pass = [&](float b, const V *xr, float (&xc)[NV][VW], float (&xn)[NV][VW], float (&aq)[2]) {
+        aq[0] = aq[1] = 0.f;
+#pragma unroll
+        for (int j = 0; j < CH; ++j) unpack<VW>(xr[j * LW + ll], xn[j]);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if (c + 1 < NCH) {
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    const int m = (c + 1) * CH + j;
+                    unpack<VW>(xr[m * LW + ll], xn[m]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                const int m = c * CH + j;
+#pragma unroll
+                for (int e = 0; e < VW; ++e) {
+                    const float w1 = fmaf(-b, xc[m][e], wv[m][e]);
+                    wv[m][e] = w1;
+                    aq[e & 1] = fmaf(w1, xn[m][e], aq[e & 1]);
+                }
+            }
+            if (NCH > 2) __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    auto round = [&](int t, float (&xc)[NV][VW], float (&xn)[NV][VW]) {
+        if ((t & (LW - 1)) == 0 && yrow) yreg = (t + ll < n) ? yrow[t + ll] : 0.f;   // per half: the runs may differ
+        if ((t & 63) == 0) {
+            x2reg = (t + lane < n) ? x2row[t + lane] : 0.f;
+            if (OPT) g01reg = (t + lane < n) ? g01row[t + lane] : 0.f;
+        }
+        const float ylo = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(yreg), t & (LW - 1)));
+        const float yhi = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(yreg), LW + (t & (LW - 1))));
+        const float yt = upper ? yhi : ylo;
+        const float x2t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x2reg), t & 63));
+        float zp = z;
+        if (OPT) {
+            const float g01t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g01reg), t & 63));
+            const double had = (double)ha;
+            const double m = fma(had * had, (double)x2prev,
+                                 fma(-2.0 * had, (double)hp, (double)sigma * (double)sigma * (double)n2));
+            const float mf = (float)m;
+            const float sp = mf > D2 ? D * __builtin_amdgcn_rsqf(mf) : 1.f;
+            zp = sp * fmaf(-ha, g01t, z);
+        }
+        if (ll == (t & (LW - 1))) zreg = zp;
+        if (sigma < kFoldLo) {                           // per learner: the halves may differ
+#pragma unroll
+            for (int m = 0; m < NV; ++m)
+#pragma unroll
+                for (int e = 0; e < VW; ++e) wv[m][e] *= sigma;
+            n2 *= sigma * sigma;
+            qv = z;
+            sigma = 1.f;
+            isig = 1.f;
+            thr = D2;
+        }
+        const float step = LOSS == 1 ? eta2 * (zp - yt) : eta * slope<LOSS>(zp, yt);
+        const float b = step * isig;
+        const float qold = qv;
+        float aq[2];
+        pass(b, xrow(t + 1), xc, xn, aq);
+        if (((phase + t) & 63) == 63) {                  // re-measure ||v||^2 exactly
+            float an[2] = {0.f, 0.f};
+#pragma unroll
+            for (int m = 0; m < NV; ++m)
+#pragma unroll
+                for (int e = 0; e < VW; ++e) an[e & 1] = fmaf(wv[m][e], wv[m][e], an[e & 1]);
+            n2 = half_sum(an[0] + an[1], upper);
+        } else {
+            n2 = fmaxf(fmaf(b, fmaf(b, x2t, -2.f * qv), n2), 0.f);
+        }
+        qv = half_sum(aq[0] + aq[1], upper);             // <v, x_{t+1}>
+        const float nrm = n2;
+        const bool pj = nrm > thr;                       // projection, per learner
+        if (__builtin_amdgcn_ballot_w64(pj) != 0) {
+            asm volatile("" ::: "memory");               // keeps the branch
+            const float s2 = D * __builtin_amdgcn_rsqf(nrm);
+            const float i2 = fast_rcp(s2);
+            sigma = pj ? s2 : sigma;
+            isig = pj ? i2 : isig;
+            thr = pj ? D2 * i2 * i2 : thr;
+        }
+        z = sigma * qv;
+        if (OPT) {
+            hp = sigma * fmaf(-b, x2t, qold);
+            ha = step;
+            x2prev = x2t;
+        }
+        if ((t & (LW - 1)) == LW - 1 || t == n - 1) {    // flush the z of rounds (t & ~31) .. t
+            const int tb = t & ~(LW - 1);
+            if (tb + ll <= t && store) zrow[(int64_t)(tb + ll) * a.zl.zs_t] = zreg;
+        }
+    };
+
+    for (int k = 0; k < ntiles; ++k) {
+        if (k + 2 < ntiles) issue_tile(k + 2);
+        const int rmax = min(RT, n - k * RT);
+#pragma unroll 1
+        for (int rr = 0; rr < rmax; rr += 2) {
+            const int t = k * RT + rr;
+            round(t, xa, xb);
+            if (rr + 1 < rmax) round(t + 1, xb, xa);
+        }
+        __syncthreads();
+    }
+
+    if (store) {
+        float *dst = a.V + ((int64_t)r * K + i) * d;
+#pragma unroll
+        for (int m = 0; m < NV; ++m)
+#pragma unroll
+            for (int e = 0; e < VW; ++e) {
+                const int j = (m * LW + ll) * VW + e;
+                if (j < d) dst[j] = wv[m][e];
+            }
+        if (ll == 0) { a.sigma[(int64_t)r * K + i] = sigma; a.n2[(int64_t)r * K + i] = (double)n2; }
+        if (OPT && ll == 0) { a.ha[(int64_t)r * K + i] = ha; a.hp[(int64_t)r * K + i] = hp; }
+    }
+}
+
 // ||x_t||^2 of every round row and, if g01 is given, <x_{t-1}, x_t> (x_{-1} = the last row of the
 // previous call, kept in xlast): one wavefront per row, fixed summation order.
 __global__ void __launch_bounds__(256) xnorm2_kernel(const float *x, int64_t run_stride, int nruns,
@@ -537,6 +811,14 @@ __global__ void __launch_bounds__(256) keep_last_row_kernel(const float *x, int6
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j < d) xlast[(int64_t)rr * d + j] = x[(int64_t)rr * run_stride + (int64_t)(n - 1) * d + j];
     if (j == 0) x2last[rr] = x2[(int64_t)rr * x2_stride + n - 1];
+}
+
+// Duration of one pass of the grid with l wavefronts on each SIMD, in units of a pass with one,
+// fitted to sweeps on MI355X: up to about four wavefronts per SIMD mostly fill each other's
+// stalls (the round is a dependent chain), beyond that they share the issue slots.
+static double pass_cost(double l)
+{
+    return l <= 1.0 ? 1.0 : l <= 4.0 ? 1.0 + 0.1 * (l - 1.0) : l <= 6.0 ? 1.3 + 0.2 * (l - 4.0) : 1.7 + 0.55 * (l - 6.0);
 }
 
 // how one call's round kernel is launched: fixed for the call, used for each of its pieces
@@ -580,9 +862,6 @@ hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
     // and its duration grows with l as g(l), fitted to sweeps on MI355X: up to about four
     // wavefronts per SIMD mostly fill each other's stalls (the round is a dependent chain),
     // beyond that they share the issue slots.
-    auto g = [](double l) {
-        return l <= 1.0 ? 1.0 : l <= 4.0 ? 1.0 + 0.1 * (l - 1.0) : l <= 6.0 ? 1.3 + 0.2 * (l - 4.0) : 1.7 + 0.55 * (l - 6.0);
-    };
     const int per_run = a.per_run;
     int best = 0;
     double best_cost = 0.0;
@@ -600,7 +879,7 @@ hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
                                        : (int64_t)a.R * ((per_run + w - 1) / w);
         const int64_t per_cu = (nwg + ncu - 1) / ncu;
         const int64_t full = per_cu / c, rem = per_cu % c;
-        double cost = (double)full * g((double)(c * w) / 4.0) + (rem ? g((double)(rem * w) / 4.0) : 0.0);
+        double cost = (double)full * pass_cost((double)(c * w) / 4.0) + (rem ? pass_cost((double)(rem * w) / 4.0) : 0.0);
         if (w % 4 != 0 && per_run % w != 0) cost *= 1.1;
         // on equal cost prefer more, smaller workgroups per unit (fewer wavefronts held up by one
         // barrier), down to eight wavefronts (below that the per-workgroup staging of x shows)
@@ -626,6 +905,63 @@ hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
     plan->nwg = a.x_shared ? ((int64_t)a.R * per_run + best - 1) / best
                            : (int64_t)a.R * ((per_run + best - 1) / best);
     plan->batches = ((plan->nwg + ncu - 1) / ncu + c - 1) / c;
+    return hipSuccess;
+}
+
+// the same for the kernel with two learners per wavefront (shared stream, learners only)
+template <int NPL>
+hipError_t plan_half(const DenseArgs &a, int loss, DensePlan *plan)
+{
+    using C = HalfCfg<NPL>;
+    const size_t smem = sizeof(float) * kRing * C::RT * NPL * 32;
+    void (*kern)(const DenseArgs) = nullptr;
+    switch (loss * 2 + (a.optimistic ? 1 : 0)) {
+        case 0: kern = dense_rounds_half_kernel<NPL, 0, false>; break;
+        case 1: kern = dense_rounds_half_kernel<NPL, 0, true>; break;
+        case 2: kern = dense_rounds_half_kernel<NPL, 1, false>; break;
+        case 3: kern = dense_rounds_half_kernel<NPL, 1, true>; break;
+        case 4: kern = dense_rounds_half_kernel<NPL, 2, false>; break;
+        case 5: kern = dense_rounds_half_kernel<NPL, 2, true>; break;
+        default: return hipErrorInvalidValue;
+    }
+    if (smem > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    int dev = 0, ncu = 256;
+    if (hipGetDevice(&dev) == hipSuccess)
+        (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (ncu <= 0) ncu = 256;
+    const int64_t nwaves = ((int64_t)a.R * a.K + 1) / 2;
+    int best = 0, best_c = 1;
+    double best_cost = 0.0;
+    for (int w = C::MAXW; w >= 3; --w) {
+        int c = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, reinterpret_cast<const void *>(kern),
+                                                         w * kWave, smem) != hipSuccess || c <= 0)
+            continue;
+        const int64_t nwg = (nwaves + w - 1) / w;
+        const int64_t per_cu = (nwg + ncu - 1) / ncu;
+        const int64_t full = per_cu / c, rem = per_cu % c;
+        double cost = (double)full * pass_cost((double)(c * w) / 4.0) + (rem ? pass_cost((double)(rem * w) / 4.0) : 0.0);
+        if (w % 4 != 0) cost *= 1.1;
+        const bool better = best == 0 || cost < best_cost * (1.0 - 1e-9) || (w >= 8 && cost <= best_cost * (1.0 + 1e-9));
+        if (better) { best = w; best_cost = cost; best_c = c; }
+    }
+    if (const char *ov = getenv("OCO_DENSE_WPB")) {      // tuning override
+        const int w = atoi(ov);
+        if (w >= 1 && w <= C::MAXW) best = w;
+    }
+    if (best == 0) return hipErrorInvalidConfiguration;
+    plan->kern = kern;
+    plan->smem = smem;
+    plan->wpb = best;
+    plan->nwg = (nwaves + best - 1) / best;
+    plan->batches = ((plan->nwg + ncu - 1) / ncu + best_c - 1) / best_c;
+    plan->cost = best_cost;
+    if (getenv("OCO_DENSE_VERBOSE"))
+        fprintf(stderr, "dense plan (two learners per wavefront): NPL %d -> wpb %d cost %.3f\n", NPL, best, best_cost);
     return hipSuccess;
 }
 
@@ -705,6 +1041,23 @@ hipError_t launch_dense_rounds(const DenseArgs &a0, int loss, hipStream_t s, con
         else a.per_run = a.K + 1;
     }
     if (e != hipSuccess) return e;
+
+    // Two learners per wavefront where a round is mostly its scalar section (d <= 1024) and the
+    // grid is large enough to be bound by instruction issue rather than by the latency of a round.
+    {
+        bool half = a.x_shared && a.d > 96 && a.d <= 1024 && (int64_t)a.R * a.K >= kHalfMinTasks;
+        if (const char *ov = getenv("OCO_DENSE_HALF"))        // tuning override: 0 never, 1 wherever it can run
+            half = atoi(ov) != 0 && a.x_shared && a.d <= 1024;
+        if (half) {
+            const int nplh = (a.d + 31) / 32;
+            a.per_run = a.K;                                // comparators: contraction kernel
+            if (nplh <= 4) e = plan_half<4>(a, loss, &plan);
+            else if (nplh <= 8) e = plan_half<8>(a, loss, &plan);
+            else if (nplh <= 16) e = plan_half<16>(a, loss, &plan);
+            else e = plan_half<32>(a, loss, &plan);
+            if (e != hipSuccess) return e;
+        }
+    }
 
     // Rounds give the same bits under any split of a call, so a call may go as several launches:
     //  - A grid that takes several passes over the chip has workgroups at unrelated positions of a

@@ -105,6 +105,41 @@ def test_comparator_predictions_in_the_round_kernel_or_as_a_contraction(name, ov
         assert np.array_equal(whole[k], part[k]), k
 
 
+@pytest.mark.parametrize("name,over", [
+    ("c3", dict(T=300, R=3, d=130, K=5, seg_len=100)),
+    ("c3", dict(T=333, R=5, d=1000, K=17, seg_len=100)),
+    ("c3", dict(T=200, R=2, d=97, K=3, seg_len=7)),
+    ("c4", dict(T=257, R=5, d=512, K=16)),
+    ("c4", dict(T=150, R=3, d=1024, K=2)),
+    ("c1", dict(T=130, d=3, R=2)),
+    ("c3", dict(T=260, R=3, d=700, K=7, seg_len=64, optimistic=True)),
+    ("c4", dict(T=200, R=3, d=300, K=3, optimistic=True)),
+])
+def test_two_learners_per_wavefront(name, over, monkeypatch):
+    """For d <= 1024 and at least 8192 learners on a shared stream each half of a wavefront owns a
+    learner.  OCO_DENSE_HALF=1 forces that kernel on small cases (odd learner counts leave the
+    last upper half without a task): parity with the oracle, and the same bits under any cut."""
+    monkeypatch.setenv("OCO_DENSE_HALF", "1")
+    wl = WL.make(name, **over)
+    data = WL.generate(wl)
+    print("case", name, over, flush=True)
+    whole = _gpu(wl, data)
+    _check(wl, data, whole, label="%s %s two per wavefront" % (name, over))
+    for c in (1, 37, 64):
+        part = _gpu(wl, data, chunk=c, n_max=c)
+        for k in ("regret", "L", "W", "p", "wbar"):
+            assert np.array_equal(whole[k], part[k]), (k, c)
+
+
+def test_two_learners_per_wavefront_is_chosen_for_many_learners(monkeypatch, capfd):
+    monkeypatch.setenv("OCO_DENSE_VERBOSE", "1")           # the launcher reports its plan on stderr
+    wl = WL.make("c4", T=130, R=700, d=200, K=12)          # 8400 learners
+    data = WL.generate(wl)
+    got = _gpu(wl, data)
+    assert "two learners per wavefront" in capfd.readouterr().err
+    _check(wl, data, got, runs=[0, 350, 699], label="c4 8400 learners")
+
+
 SPARSE = [
     dict(T=2000, R=3, d=4096, K=8, wstar_nnz=64),
     dict(T=700, R=20, d=512, K=5, nnz=8, wstar_nnz=16),                     # R*K > 64: two wavefronts
