@@ -47,7 +47,10 @@ template <> struct DenseCfg<1>  { static constexpr int MAXW = 16, RT = 32; };
 template <> struct DenseCfg<2>  { static constexpr int MAXW = 16, RT = 16; };
 template <> struct DenseCfg<4>  { static constexpr int MAXW = 16, RT = 16; };
 template <> struct DenseCfg<8>  { static constexpr int MAXW = 16, RT = 8; };
-template <> struct DenseCfg<16> { static constexpr int MAXW = 16, RT = 2; };
+#ifndef OCO_RT16
+#define OCO_RT16 2
+#endif
+template <> struct DenseCfg<16> { static constexpr int MAXW = 16, RT = OCO_RT16; };
 #ifndef OCO_MAXW32
 #define OCO_MAXW32 12
 #endif
