@@ -418,10 +418,9 @@ dense_rounds_kernel(const DenseArgs a)
         float zp = z;
         if (OPT) {
             const float g01t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g01reg), t & 63));
-            const double had = (double)ha;
-            const double m = fma(had * had, (double)x2prev,
-                                 fma(-2.0 * had, (double)hp, (double)sigma * (double)sigma * (double)n2));
-            const float mf = (float)m;
+            // ||w^_t - ha x_{t-1}||^2 in float32 like its inputs: it only matters where it exceeds D^2,
+            // and there no term is much larger than the result
+            const float mf = fmaf(ha * ha, x2prev, fmaf(-2.f * ha, hp, sigma * sigma * n2));
             const float sp = mf > D2 ? D * __builtin_amdgcn_rsqf(mf) : 1.f;
             zp = sp * fmaf(-ha, g01t, z);
         }
@@ -698,10 +697,9 @@ dense_rounds_half_kernel(const DenseArgs a)
         float zp = z;
         if (OPT) {
             const float g01t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g01reg), t & 63));
-            const double had = (double)ha;
-            const double m = fma(had * had, (double)x2prev,
-                                 fma(-2.0 * had, (double)hp, (double)sigma * (double)sigma * (double)n2));
-            const float mf = (float)m;
+            // ||w^_t - ha x_{t-1}||^2 in float32 like its inputs: it only matters where it exceeds D^2,
+            // and there no term is much larger than the result
+            const float mf = fmaf(ha * ha, x2prev, fmaf(-2.f * ha, hp, sigma * sigma * n2));
             const float sp = mf > D2 ? D * __builtin_amdgcn_rsqf(mf) : 1.f;
             zp = sp * fmaf(-ha, g01t, z);
         }
