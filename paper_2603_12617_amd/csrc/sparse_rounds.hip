@@ -471,9 +471,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                 float z = sf * qv;
                 if (OPT) {
                     // played iterate w_t = s (w^_t - ha x_{t-1}), s from ||w^_t - ha x_{t-1}||^2: scalars only
-                    const double had = (double)ha;
-                    const double m = fma(had * had, (double)x2p, fma(-2.0 * had, (double)hp, sd2 * n2));
-                    const float mf = (float)m;
+                    const float mf = fmaf(ha * ha, x2p, fmaf(-2.f * ha, hp, (float)(sd2 * n2)));
                     const float sp = mf > D2f ? Df * __builtin_amdgcn_rsqf(mf) : 1.f;
                     z = sp * fmaf(-ha, g01[t], z);
                 }
