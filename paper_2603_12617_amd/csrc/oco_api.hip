@@ -56,7 +56,10 @@ int validate_and_layout(const oco_config *c, Layout *lay)
     size_t off = 0;
     l.off_V = off;
     if (c->sparse_nnz > 0) {
-        l.RKp = (int)align_up((size_t)RK, kWave);
+        // row length of V: the learners padded to whole wavefronts, plus 32 floats, which makes
+        // it an odd number of 128-byte lines.  A workgroup touches the same few bytes of many rows;
+        // with a power-of-two row length all of them would sit in one L2 channel.
+        l.RKp = (int)align_up((size_t)RK, kWave) + 32;
         off += align_up(sizeof(float) * (size_t)c->d * l.RKp, 256);
         l.off_sigma = off; l.n_sigma = l.RKp;
         off += align_up(sizeof(double) * l.RKp, 256);
@@ -301,7 +304,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
         a.V = st->at<float>(l.off_V); a.sigma = st->at<double>(l.off_sigma); a.n2 = st->at<double>(l.off_n2);
         a.eta = st->at<float>(l.off_eta); a.Z = st->at<float>(l.off_Z); a.zl = zl;
         a.d = (int)c.d; a.K = (int)c.K; a.R = (int)c.R; a.nnz = c.sparse_nnz; a.RKp = l.RKp;
-        a.t0 = t0; a.n = (int)n; a.D = c.D; a.prefetch = 1;
+        a.t0 = t0; a.n = (int)n; a.D = c.D;
         a.scratch = st->at<char>(l.off_gram);
         a.optimistic = c.optimistic;
         if (c.optimistic) {

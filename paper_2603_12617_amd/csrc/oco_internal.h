@@ -85,7 +85,7 @@ struct SparseArgs {
     const float *u;          // [R][S][d]
     const int64_t *seg_start;
     int S;
-    float *V;                // [d][RKp]: coordinate-major, the R*K learners interleaved
+    float *V;                // [d][RKp]: coordinate-major, the R*K learners interleaved (RKp: padded row length)
     double *sigma;           // [RKp]
     double *n2;              // [RKp]  ||V column||^2
     const float *eta;        // [K]
@@ -95,7 +95,6 @@ struct SparseArgs {
     int64_t t0;
     int n;
     double D;
-    int prefetch;            // 1: idle wavefronts warm L2 with the next window's rows
     void *scratch;           // sparse_scratch_bytes(n_max) bytes: per-window Gram data of the call
     // optimistic two-step update (Eq. (3)); V then holds the intermediate model w^
     int optimistic;

@@ -13,7 +13,8 @@
 // run touches the SAME coordinates in a round.  V is stored coordinate-major
 // with the R*K learners interleaved, V[j][q], q = r*K + i: a lane is a learner,
 // one coordinate of the learners of a workgroup is one contiguous row segment
-// (256 bytes for 64 learners), every gather and scatter is coalesced and all
+// (256 bytes for 64 learners; rows are padded to an odd number of 128-byte
+// lines, see oco_create), every gather and scatter is coalesced and all
 // the per-learner scalar work (slope, step, norm, projection) runs
 // lane-parallel with no reduction.  A workgroup owns 64, 32, 16, 8 or 4 learners:
 // few learners per workgroup spread a small problem over more compute units,
@@ -26,17 +27,20 @@
 // In v-space the step is linear, v_t = v_s - sum_{s<=r<t} b_r x_r, hence inside
 // a window of 64 rounds
 //     <v_t, x_t> = <v_window_start, x_t> - sum_{r<t in window} b_r <x_r, x_t>.
-// Per window the kernel therefore runs three phases:
-//   A  all wavefronts: q0_t = <v_start, x_t> for the 64 rounds (bulk gathers);
+// Per window the kernel therefore has three pieces of work:
+//   A  q0_t = <v_start, x_t> for the 64 rounds (bulk gathers);
 //   B  one wavefront: the 64 dependent rounds on scalars and LDS only
 //      (prediction, slope, step size b_t, norm, projection); the Gram terms
 //      <x_r, x_t> come from a pre-pass over the round stream and are almost
-//      all zero (two sparse rows rarely share a column); meanwhile the other
-//      wavefronts stage the next window's stream and pre-pass record into a
-//      second LDS buffer and pull its rows of V into L2;
-//   C  all wavefronts: V[col] += -b_t x_t[col] as no-return float atomics, the
-//      entries split over wavefronts by column so that the adds to one address
-//      are issued by one wavefront in round order (bitwise reproducible).
+//      all zero (two sparse rows rarely share a column); predictions go to LDS;
+//   C  V[col] += -b_t x_t[col] as no-return float atomics, the entries split
+//      over wavefronts by column so that the adds to one address are issued
+//      by one wavefront in round order (bitwise reproducible), and the
+//      window's predictions to Z.
+// B is the critical path.  Where the LDS has room for the buffers of three
+// windows, A of the next window and C of the previous one run beside B of the
+// current one (the kernel below says how); otherwise A, B, C of a window
+// follow one another and only the staging of the next window runs beside B.
 //
 // The comparator's predictions <u_t, x_t> do not depend on the learners and
 // are taken by a separate, fully parallel kernel (one thread per run-round).
@@ -83,7 +87,7 @@ template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
 // goes to L2 as well (a device-scope relaxed load never hits in the per-CU cache).
 __device__ __forceinline__ float ldv(const float *p)
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // Workgroup barrier that first waits for every global access of this wavefront (loads,
@@ -94,6 +98,17 @@ __device__ __forceinline__ void wg_sync()
     __syncthreads();
 }
 
+// The same barrier where wavefront 0 (the dependent rounds) has nothing in flight that the
+// others read: it does not wait for its stores of predictions to be acknowledged.
+__device__ __forceinline__ void wg_sync_chain(int wave)
+{
+    if (wave != 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
+
+#ifndef OCO_KMID
+#define OCO_KMID 32
+#endif
 #ifndef OCO_FOLD_LO
 #define OCO_FOLD_LO 0x1p-100
 #define OCO_FOLD_SOFT 0x1p-64
@@ -104,6 +119,9 @@ constexpr int kSegment = 2048;               // rounds per launch segment (absol
 constexpr int kWin = 64;                     // rounds per window (absolute alignment)
 constexpr int kSpWaves = 16;                 // wavefronts per workgroup
 constexpr int kBesideMaxWorkgroups = 128;    // window grids up to this size leave half the chip idle
+constexpr size_t kLdsBytes = 160 * 1024;     // LDS of a gfx950 compute unit
+constexpr int kMaxCross = 64;                // most round pairs across a window boundary that are corrected
+constexpr int kMid = OCO_KMID;                     // round of a window at which the pipelined kernel's two halves meet
 
 // Pre-pass over the round stream, one workgroup per window of the launch:
 // G[s][t] = <x_s, x_t> for s < t, mask[s] = bit t set iff rounds s and t share a column,
@@ -128,7 +146,11 @@ struct WinRec {
     int ng;                             // number of set mask bits
     int pad[32 - kSpWaves - 2];
     float g01[kWin];                    // <x_{t-1}, x_t> (optimistic update only; x_{-1}: previous call's last row)
-    unsigned short perm[kWin * OCO_MAX_NNZ];   // entries of the window sorted by column (stable)
+    int nx;                             // pairs (round s of the previous window, round t of this one) that share
+    int padx[31];                       //   a column; -1: too many, or no previous window in this call
+    unsigned short xs[kMaxCross], xt[kMaxCross];
+    float xg[kMaxCross];                // their <x_s, x_t>, in (s, t) order
+    unsigned short perm[kWin * OCO_MAX_NNZ];   // entries of the window sorted by column (stable); bit 15: column not unique
     float g[kWin * (kWin - 1) / 2];     // <x_s, x_t> of the set mask bits, in (s, t) order
 };
 static_assert(sizeof(WinRec) % 128 == 0, "window records stay 256-byte aligned");
@@ -136,8 +158,12 @@ constexpr int kRecHeadInts = (int)(offsetof(WinRec, perm) / 4);
 
 __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, const float *val, int nnz,
                                                           WinPlan plan, WinRec *recs, int optimistic,
-                                                          const int32_t *last_col, const float *last_val)
+                                                          const int32_t *last_col, const float *last_val, int shares)
 {
+    __shared__ int csp[kWin * OCO_MAX_NNZ];                     // the previous window's entries
+    __shared__ float vsp[kWin * OCO_MAX_NNZ];
+    __shared__ unsigned int xm[kWin][2];
+    __shared__ int xrowoff[kWin + 1];
     __shared__ int cs[kWin * OCO_MAX_NNZ];
     __shared__ float vs[kWin * OCO_MAX_NNZ];
     __shared__ unsigned long long key[kWin * OCO_MAX_NNZ];      // (column, position), sorted in place
@@ -155,7 +181,12 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
         vs[e] = val[(int64_t)ws * nnz + e];
         key[e] = ((unsigned long long)(unsigned)c << 12) | (unsigned)e;
     }
-    for (int e = threadIdx.x; e < kWin * 2; e += blockDim.x) mk[e >> 1][e & 1] = 0u;
+    const int pws = w > 0 ? plan.start(w - 1) : 0, ptotal = w > 0 ? plan.len(w - 1) * nnz : 0;
+    for (int e = threadIdx.x; e < ptotal; e += blockDim.x) {
+        csp[e] = col[(int64_t)pws * nnz + e];
+        vsp[e] = val[(int64_t)pws * nnz + e];
+    }
+    for (int e = threadIdx.x; e < kWin * 2; e += blockDim.x) { mk[e >> 1][e & 1] = 0u; xm[e >> 1][e & 1] = 0u; }
     __syncthreads();
     // sort by (column, position) -- a stable sort by column -- with a bitonic network over the
     // next power of two (padding keys are larger than any real key)
@@ -185,8 +216,10 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
     for (int k = threadIdx.x; k < total; k += blockDim.x) {
         const unsigned long long kk = key[k];
         const int e = (int)(kk & 0xFFF);
-        rec.perm[k] = (unsigned short)e;
         const unsigned long long c = kk >> 12;
+        // bit 15: another entry of the window has the same column
+        const bool dup = (k > 0 && (key[k - 1] >> 12) == c) || (k + 1 < total && (key[k + 1] >> 12) == c);
+        rec.perm[k] = (unsigned short)(e | (dup ? 0x8000 : 0));
         const int s = (int)(((unsigned)e * mdiv) >> 18);
         for (int k2 = k + 1; k2 < total && (key[k2] >> 12) == c; ++k2) {
             const int t = (int)(((unsigned)(key[k2] & 0xFFF) * mdiv) >> 18);
@@ -212,9 +245,25 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
     }
     if (threadIdx.x <= kSpWaves) {
         // equal shares of the sorted entries, cut only where the column changes
-        int k = (int)((int64_t)threadIdx.x * total / kSpWaves);
+        const int sh = (int)threadIdx.x < shares ? (int)threadIdx.x : shares;
+        int k = (int)((int64_t)sh * total / shares);
         while (k > 0 && k < total && (key[k] >> 12) == (key[k - 1] >> 12)) ++k;
         rec.off[threadIdx.x] = k;
+    }
+    // rounds of the previous window that share a column with a round of this one: look every
+    // entry of the previous window up in the sorted list
+    for (int ep = threadIdx.x; ep < ptotal; ep += blockDim.x) {
+        const unsigned long long c = (unsigned long long)(unsigned)csp[ep];
+        int lo = 0, hi = total;                                // first k with column(key[k]) >= c
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if ((key[mid] >> 12) < c) lo = mid + 1; else hi = mid;
+        }
+        const int s = (int)(((unsigned)ep * mdiv) >> 18);
+        for (int k2 = lo; k2 < total && (key[k2] >> 12) == c; ++k2) {
+            const int t = (int)(((unsigned)(key[k2] & 0xFFF) * mdiv) >> 18);
+            atomicOr(&xm[s][t >> 5], 1u << (t & 31));
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -225,8 +274,36 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
         }
         rowoff[kWin] = acc;
         rec.ng = acc;
+        int xacc = 0;
+        for (int s2 = 0; s2 < kWin; ++s2) {
+            xrowoff[s2] = xacc;
+            xacc += __popc(xm[s2][0]) + __popc(xm[s2][1]);
+        }
+        xrowoff[kWin] = xacc;
+        rec.nx = (w == 0 || xacc > kMaxCross) ? -1 : xacc;
     }
     __syncthreads();
+    if (w > 0 && xrowoff[kWin] <= kMaxCross && threadIdx.x >= 64 && threadIdx.x < 64 + kWin) {
+        // one thread per round of the previous window: its pairs in order of t, each <x_s, x_t>
+        // summed in a fixed order
+        const int s2 = threadIdx.x - 64;
+        unsigned long long m = (unsigned long long)xm[s2][0] | ((unsigned long long)xm[s2][1] << 32);
+        int o = xrowoff[s2];
+        while (m) {
+            const int t = __builtin_ctzll(m);
+            m &= m - 1;
+            float g = 0.f;
+            for (int a2 = 0; a2 < nnz; ++a2) {
+                const int ca = csp[s2 * nnz + a2];
+                for (int b2 = 0; b2 < nnz; ++b2)
+                    if (cs[t * nnz + b2] == ca) g = fmaf(vsp[s2 * nnz + a2], vs[t * nnz + b2], g);
+            }
+            rec.xs[o] = (unsigned short)s2;
+            rec.xt[o] = (unsigned short)t;
+            rec.xg[o] = g;
+            ++o;
+        }
+    }
     if (threadIdx.x < kWin) {
         const int s2 = threadIdx.x;
         unsigned long long m = (unsigned long long)mk[s2][0] | ((unsigned long long)mk[s2][1] << 32);
@@ -261,30 +338,106 @@ __device__ __forceinline__ float bcast_f(float v, int l)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
 }
 
-// LDS of the rounds kernel that is staged per window (two copies: the next window is
-// staged while the dependent rounds of the current one run)
+// LDS of the rounds kernel that is staged per window, sized by the entries per round of the
+// launch: cw | vw | head | perm2 | gl, each a multiple of 16 bytes.
+constexpr int kGramInts = kWin * (kWin - 1) / 2;
+__host__ __device__ inline int stage_perm_ints(int nnz) { return ((kWin * nnz + 1) / 2 + 3) & ~3; }
+__host__ __device__ inline int stage_ints(int nnz) { return 2 * kWin * nnz + kRecHeadInts + stage_perm_ints(nnz) + kGramInts; }
 struct WinStage {
-    int cw[kWin * OCO_MAX_NNZ];
-    float vw[kWin * OCO_MAX_NNZ];
-    int head[kRecHeadInts];                      // rr | off | ng (rr[kWin] may be read, never used)
-    unsigned int perm2[kWin * OCO_MAX_NNZ / 2];
-    float gl[kWin * (kWin - 1) / 2];
+    int *cw;
+    float *vw;
+    int *head;                                   // rr | off | ng | g01 | cross-window pairs (rr[kWin] may be read, never used)
+    unsigned int *perm2;
+    float *gl;
+};
+__device__ __forceinline__ WinStage stage_at(int *base, int nnz)
+{
+    WinStage st;
+    st.cw = base;
+    st.vw = reinterpret_cast<float *>(base + kWin * nnz);
+    st.head = base + 2 * kWin * nnz;
+    st.perm2 = reinterpret_cast<unsigned int *>(st.head + kRecHeadInts);
+    st.gl = reinterpret_cast<float *>(st.head + kRecHeadInts + stage_perm_ints(nnz));
+    return st;
+}
+
+// A window's stream entries and pre-pass record on their way into LDS, held in registers by
+// the threads of at least 15 wavefronts: all loads are issued before the first is waited for
+// (one memory round trip, not one per loop iteration; the trip counts are bounded by the sizes of
+// the record), and other memory work can be issued between load() and store().
+struct StageRegs {
+    static constexpr int kMinThr = (kSpWaves - 1) * kWave;
+    static constexpr int NE = (kWin * OCO_MAX_NNZ + kMinThr - 1) / kMinThr;
+    static constexpr int NP = (kWin * OCO_MAX_NNZ / 2 + kMinThr - 1) / kMinThr;
+    static constexpr int NG = (kGramInts + kMinThr - 1) / kMinThr;
+    static constexpr int NH = (kRecHeadInts + kMinThr - 1) / kMinThr;
+    int c[NE], h[NH];
+    float x[NE], g[NG];
+    unsigned int pp[NP];
+    const int *ngp;
+
+    __device__ __forceinline__ void load(const SparseArgs &a, const WinRec &rec, int ws, int total, int tid, int nthr)
+    {
+        const int nnz = a.nnz;
+        const int *hsrc = reinterpret_cast<const int *>(&rec);
+        const unsigned int *psrc = reinterpret_cast<const unsigned int *>(rec.perm);
+        const int np = (total + 1) / 2;
+        ngp = &rec.ng;
+#pragma unroll
+        for (int u = 0; u < NE; ++u) {
+            const int e = tid + u * nthr;
+            c[u] = e < total ? a.col[(int64_t)ws * nnz + e] : 0;
+            x[u] = e < total ? a.val[(int64_t)ws * nnz + e] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < NH; ++u) {
+            const int e = tid + u * nthr;
+            h[u] = e < kRecHeadInts ? hsrc[e] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < NP; ++u) {
+            const int e = tid + u * nthr;
+            pp[u] = e < np ? psrc[e] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < NG; ++u) {
+            const int e = tid + u * nthr;
+            g[u] = e < kGramInts ? rec.g[e] : 0.f;           // not gated by ng: no load waits for another
+        }
+    }
+    __device__ __forceinline__ void store(const WinStage &st, int total, int tid, int nthr) const
+    {
+        const int np = (total + 1) / 2;
+        const int ng = *ngp;
+#pragma unroll
+        for (int u = 0; u < NE; ++u) {
+            const int e = tid + u * nthr;
+            if (e < total) { st.cw[e] = c[u]; st.vw[e] = x[u]; }
+        }
+#pragma unroll
+        for (int u = 0; u < NH; ++u) {
+            const int e = tid + u * nthr;
+            if (e < kRecHeadInts) st.head[e] = h[u];
+        }
+#pragma unroll
+        for (int u = 0; u < NP; ++u) {
+            const int e = tid + u * nthr;
+            if (e < np) st.perm2[e] = pp[u];
+        }
+#pragma unroll
+        for (int u = 0; u < NG; ++u) {
+            const int e = tid + u * nthr;
+            if (e < ng) st.gl[e] = g[u];
+        }
+    }
 };
 
-__device__ __forceinline__ void stage_window(WinStage &st, const SparseArgs &a, const WinRec &rec, int ws, int total,
+__device__ __forceinline__ void stage_window(const WinStage &st, const SparseArgs &a, const WinRec &rec, int ws, int total,
                                              int tid, int nthr)
 {
-    const int ng = rec.ng;
-    const int nnz = a.nnz;
-    for (int e = tid; e < total; e += nthr) {
-        st.cw[e] = a.col[(int64_t)ws * nnz + e];
-        st.vw[e] = a.val[(int64_t)ws * nnz + e];
-    }
-    const int *hsrc = reinterpret_cast<const int *>(&rec);
-    for (int e = tid; e < kRecHeadInts; e += nthr) st.head[e] = hsrc[e];
-    const unsigned int *psrc = reinterpret_cast<const unsigned int *>(rec.perm);
-    for (int e = tid; e < (total + 1) / 2; e += nthr) st.perm2[e] = psrc[e];
-    for (int e = tid; e < ng; e += nthr) st.gl[e] = rec.g[e];
+    StageRegs sr;
+    sr.load(a, rec, ws, total, tid, nthr);
+    sr.store(st, total, tid, nthr);
 }
 
 // 1/sqrt(x) for a finite x > 0: the hardware estimate (relative error < 6e-8, measured over
@@ -299,14 +452,50 @@ template <int LPW> struct Chain {
     float q0[kWin + 1][LPW];       // <v_start, x_t>, then corrected in place (row kWin: read ahead only)
     float yv[kWin + 1][LPW];       // labels
     float bw[kWin][LPW];           // step sizes b_t of the window
+    float zb[kWin][LPW];           // predictions of the window, written to Z with the window's steps
+};
+// LDS the kernel declares itself, rounded up, and one chain buffer
+constexpr int sparse_static_lds(int lpw) { return kSpWaves * lpw * 8 + lpw * 4 + 256; }
+constexpr size_t sparse_chain_bytes(int lpw) { return (size_t)(2 * (kWin + 1) + 2 * kWin) * 4 * lpw; }
+static_assert(sizeof(Chain<64>) == sparse_chain_bytes(64) && sizeof(Chain<4>) == sparse_chain_bytes(4), "chain buffer size");
+
+// A staged window as the phases see it.
+struct WinView {
+    const int *cw;
+    const float *vw;
+    const RoundRec *rr;
+    const int *offs;
+    const float *g01;
+    const int *xh;                 // nx | pad | xs | xt | xg
+    const unsigned short *perm;
+    const float *gl;
+    int ws, wl;
 };
 
+// Where the LDS has room for it (pipe) the windows are pipelined: while wavefront 0 runs the
+// dependent rounds of window w, the other fifteen first apply the steps of window w - 1 and
+// stage window w + 1 and then, once those atomics are acknowledged (a workgroup barrier that
+// wavefront 0 meets after round kMid), gather <v, x_t> for window w + 1.  That gather sees V
+// without the steps of window w; they enter as Gram terms over the window boundary,
+//     <v_start(w+1), x_t> = <v_start(w), x_t> - sum_{s in w} b_s <x_s, x_t>,
+// which the pre-pass lists (a handful of pairs for columns drawn at random).  The first window
+// of a launch, a window with more than kMaxCross such pairs and the window after a fold inside
+// the kernel are gathered after all earlier steps have been applied, as without the pipeline.
+// Otherwise (64 learners per workgroup, or 64 entries per round with 32 learners) the LDS holds
+// one set of buffers and every window runs gather, rounds, steps one after the other.
 template <int LOSS, int LPW, bool OPT>
-__global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const SparseArgs a, WinPlan plan, int wbeg, int wend)
+__global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const SparseArgs a, WinPlan plan, int wbeg, int wend,
+                                                                         int pipe)
 {
     constexpr int EPI = kWave / LPW;
-    __shared__ Chain<LPW> ch;
-    __shared__ __align__(16) WinStage stage[2];
+    constexpr int kCWaves = kSpWaves - 1;           // wavefronts that apply steps (all but the chain's)
+    const bool PIPE = pipe != 0;
+    const int NB = PIPE ? 2 : 1;                    // chain buffers: window w (, w + 1)
+    extern __shared__ __align__(16) int smem_i[];   // NB chain buffers, then the staged windows (w - 1,) w, w + 1
+    Chain<LPW> *chs = reinterpret_cast<Chain<LPW> *>(smem_i);
+    int *stage0 = smem_i + NB * (int)(sizeof(Chain<LPW>) / 4);
+    const int stage_n = stage_ints(a.nnz);
+    auto stage_of = [&](int w) { return stage_at(stage0 + (PIPE ? (w - wbeg) % 3 : (w - wbeg) & 1) * stage_n, a.nnz); };
     // in-kernel fold: round after which the chain stopped (-1: none), the learners' scales, and
     // one partial squared norm per wavefront and learner
     __shared__ int fold_t, fold_gp;
@@ -318,7 +507,11 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     const int l = lane % LPW, e = lane / LPW;       // learner and slot of this lane
     const int nnz = a.nnz;
     const unsigned mdiv = ((1u << 18) + nnz - 1) / nnz;       // e / nnz == (e * mdiv) >> 18 for e < 4096
-    const int q = blockIdx.x * LPW + l;             // learner (column of V) of this lane
+    // Workgroups go to the eight XCDs in turn, each with an L2 of its own: the workgroups of one
+    // XCD take neighbouring learners, whose segments of a row of V share cache lines.
+    const int nblk = (int)gridDim.x;
+    const int blk = nblk % 8 == 0 ? ((int)blockIdx.x % 8) * (nblk / 8) + (int)blockIdx.x / 8 : (int)blockIdx.x;
+    const int q = blk * LPW + l;                    // learner (column of V) of this lane
     const unsigned uq = (unsigned)q;
     const int nq = a.R * a.K;
     const bool valid = q < nq;
@@ -335,7 +528,8 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     // their step sizes stay zero and their scale stays one)
     const bool chain = wave == 0 && lane < LPW && valid;
     if (wave == 0 && lane < LPW && !valid) {
-        for (int rd = 0; rd < kWin; ++rd) ch.bw[rd][l] = 0.f;
+        for (int nb = 0; nb < NB; ++nb)
+            for (int rd = 0; rd < kWin; ++rd) chs[nb].bw[rd][l] = 0.f;
     }
     if (wave == 0 && lane < LPW) fold_sf[l] = 1.f;
     double sigma = 1.0, n2 = 0.0;
@@ -353,195 +547,281 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     if (OPT) asm volatile("" : "+v"(ha), "+v"(hp), "+v"(x2p));
     const float Df = (float)a.D, D2f = Df * Df;
 
-    stage_window(stage[0], a, recs[wbeg], plan.start(wbeg), plan.len(wbeg) * nnz, threadIdx.x, blockDim.x);
-    if (threadIdx.x == 0) fold_t = -1;
-    wg_sync();
-    for (int w = wbeg; w < wend; ++w) {
-        WinStage &st = stage[(w - wbeg) & 1];
-        const int *cw = st.cw;
-        const float *vw = st.vw;
-        const RoundRec *rr = reinterpret_cast<const RoundRec *>(st.head);
-        const int *offs = st.head + 4 * kWin;
-        const float *g01 = reinterpret_cast<const float *>(st.head + 4 * kWin + 32);
-        const unsigned short *perm = reinterpret_cast<const unsigned short *>(st.perm2);
-        const float *gl = st.gl;
-        const int ws = plan.start(w), wl = plan.len(w);
-        // ---- A: q0_t = <v_start, x_t>; a wavefront takes rounds wave, wave + 16, ..., RA at a
-        // time; slot e of the wavefront takes the entries j = e, e + EPI, ... of a round ----------
-        auto gather_q0 = [&](auto ra_tag, auto bk_tag) {
-            constexpr int RA = decltype(ra_tag)::value, BK = decltype(bk_tag)::value;   // RA * BK gathers in flight
-            const int NL = (nnz + EPI - 1) / EPI;
-            for (int tg = wave; tg < wl; tg += RA * kSpWaves) {
-                float acc[RA][4], yl[RA];
+    auto view = [&](int w) {
+        const WinStage st = stage_of(w);
+        WinView v;
+        v.cw = st.cw;
+        v.vw = st.vw;
+        v.rr = reinterpret_cast<const RoundRec *>(st.head);
+        v.offs = st.head + 4 * kWin;
+        v.g01 = reinterpret_cast<const float *>(st.head + 4 * kWin + 32);
+        v.xh = st.head + 4 * kWin + 32 + kWin;
+        v.perm = reinterpret_cast<const unsigned short *>(st.perm2);
+        v.gl = st.gl;
+        v.ws = plan.start(w);
+        v.wl = plan.len(w);
+        return v;
+    };
+    // ---- A: q0_t = <v, x_t> for the rounds of a window.  Wavefront wv of nwv takes the rounds
+    // wv, wv + nwv, ..., RA at a time; slot e of the wavefront takes the entries j = e, e + EPI, ...
+    // of a round -----------------------------------------------------------------------------
+    auto gather_q0 = [&](auto ra_tag, auto bk_tag, const WinView &v, int wv, int nwv, float (*q0d)[LPW],
+                         float (*yvd)[LPW]) {
+        constexpr int RA = decltype(ra_tag)::value, BK = decltype(bk_tag)::value;   // RA * BK gathers in flight
+        const int NL = (nnz + EPI - 1) / EPI;
+        const int wl = v.wl;
+        for (int tg = wv; tg < wl; tg += RA * nwv) {
+            float acc[RA][4], yl[RA];
+#pragma unroll
+            for (int ra = 0; ra < RA; ++ra) {
+                acc[ra][0] = acc[ra][1] = acc[ra][2] = acc[ra][3] = 0.f;
+                const int t = tg + ra * nwv < wl ? tg + ra * nwv : tg;
+                yl[ra] = yrow ? yrow[v.ws + t] : 0.f;               // in flight with the gathers
+            }
+            for (int k0 = 0; k0 < NL; k0 += BK) {
+                float vv[RA][BK];
 #pragma unroll
                 for (int ra = 0; ra < RA; ++ra) {
-                    acc[ra][0] = acc[ra][1] = acc[ra][2] = acc[ra][3] = 0.f;
-                    const int t = tg + ra * kSpWaves < wl ? tg + ra * kSpWaves : tg;
-                    yl[ra] = yrow ? yrow[ws + t] : 0.f;             // in flight with the gathers
-                }
-                for (int k0 = 0; k0 < NL; k0 += BK) {
-                    float vv[RA][BK];
+                    const int t = tg + ra * nwv < wl ? tg + ra * nwv : tg;
 #pragma unroll
-                    for (int ra = 0; ra < RA; ++ra) {
-                        const int t = tg + ra * kSpWaves < wl ? tg + ra * kSpWaves : tg;
-#pragma unroll
-                        for (int u = 0; u < BK; ++u) {
-                            const int j = (k0 + u) * EPI + e;
-                            const bool in = k0 + u < NL && j < nnz;
-                            vv[ra][u] = ldv(a.V + (int64_t)cw[t * nnz + (in ? j : 0)] * a.RKp + uq);
-                        }
-                    }
-#pragma unroll
-                    for (int ra = 0; ra < RA; ++ra) {
-                        const int t = tg + ra * kSpWaves < wl ? tg + ra * kSpWaves : tg;
-#pragma unroll
-                        for (int u = 0; u < BK; ++u) {
-                            const int j = (k0 + u) * EPI + e;
-                            const bool in = k0 + u < NL && j < nnz;
-                            const float xv = in ? vw[t * nnz + (in ? j : 0)] : 0.f;
-                            acc[ra][u & 3] = fmaf(vv[ra][u], xv, acc[ra][u & 3]);
-                        }
+                    for (int u = 0; u < BK; ++u) {
+                        const int j = (k0 + u) * EPI + e;
+                        const bool in = k0 + u < NL && j < nnz;
+                        vv[ra][u] = ldv(a.V + (int64_t)v.cw[t * nnz + (in ? j : 0)] * a.RKp + uq);
                     }
                 }
 #pragma unroll
                 for (int ra = 0; ra < RA; ++ra) {
-                    const int t = tg + ra * kSpWaves;
-                    float sum = (acc[ra][0] + acc[ra][1]) + (acc[ra][2] + acc[ra][3]);
+                    const int t = tg + ra * nwv < wl ? tg + ra * nwv : tg;
 #pragma unroll
-                    for (int sh = 32; sh >= LPW; sh >>= 1) sum += __shfl_xor(sum, sh);
-                    if (t < wl && lane < LPW) {
-                        ch.q0[t][l] = sum;
-                        ch.yv[t][l] = yl[ra];
+                    for (int u = 0; u < BK; ++u) {
+                        const int j = (k0 + u) * EPI + e;
+                        const bool in = k0 + u < NL && j < nnz;
+                        const float xv = in ? v.vw[t * nnz + (in ? j : 0)] : 0.f;
+                        acc[ra][u & 3] = fmaf(vv[ra][u], xv, acc[ra][u & 3]);
                     }
                 }
             }
-        };
-        // ---- C: V[col] += -b_t x_t[col] for the rounds t <= tmax.  All entries of a column belong
-        // to one wavefront, which walks its share of the column-sorted list EPI entries per
-        // instruction; entries of one column that meet in an instruction are summed across slots
-        // first (fixed order) -------------------------------------------------------------------
-        auto apply_steps = [&](int tmax, auto partial) {         // partial: only rounds t <= tmax (else all)
-            const int beg = __builtin_amdgcn_readfirstlane(offs[wave]);
-            const int end = __builtin_amdgcn_readfirstlane(offs[wave + 1]);
-            constexpr int NI = 4;                                // instructions per batch
-            for (int k0 = beg; k0 < end; k0 += NI * EPI) {
-                int cc[NI];
-                float xv[NI];
 #pragma unroll
-                for (int n = 0; n < NI; ++n) {
-                    const int k = k0 + n * EPI + e;
-                    const bool act = k < end;
-                    const int ee = perm[act ? k : end - 1];
-                    const int t = (int)(((unsigned)ee * mdiv) >> 18);
-                    cc[n] = act ? cw[ee] : -1;
-                    xv[n] = act && (!decltype(partial)::value || t <= tmax) ? -ch.bw[t][l] * vw[ee] : 0.f;
-                }
+            for (int ra = 0; ra < RA; ++ra) {
+                const int t = tg + ra * nwv;
+                float sum = (acc[ra][0] + acc[ra][1]) + (acc[ra][2] + acc[ra][3]);
 #pragma unroll
-                for (int n = 0; n < NI; ++n) {
-                    bool last = true;
-                    if (EPI > 1) {
-#pragma unroll
-                        for (int sh = 1; sh < EPI; sh <<= 1) {
-                            const float ox = __shfl_up(xv[n], sh * LPW);
-                            const int oc = __shfl_up(cc[n], sh * LPW);
-                            if (e >= sh && oc == cc[n]) xv[n] += ox;
-                        }
-                        const int nc = __shfl_down(cc[n], LPW);
-                        last = e == EPI - 1 || nc != cc[n];
-                    }
-                    if (cc[n] >= 0 && last) unsafeAtomicAdd(a.V + (int64_t)cc[n] * a.RKp + uq, xv[n]);
+                for (int sh = 32; sh >= LPW; sh >>= 1) sum += __shfl_xor(sum, sh);
+                if (t < wl && lane < LPW) {
+                    q0d[t][l] = sum;
+                    yvd[t][l] = yl[ra];
                 }
-            }
-        };
-        gather_q0(std::integral_constant<int, LPW == 64 ? 2 : 4>(),
-                  std::integral_constant<int, LPW == 64 ? 16 : (LPW >= 16 ? 8 : (LPW == 8 ? 4 : 2))>());
-        wg_sync();
-        // ---- B: the dependent rounds, scalars and LDS only (LPW lanes of wavefront 0).  If a
-        // learner's sigma falls below the fold threshold the chain stops after that round, the
-        // whole workgroup folds (below) and the chain goes on from the next round ---------------
-        auto run_chain = [&](int tstart, int gp) {               // gp: next Gram value of the window
-            float qn = ch.q0[tstart][l], yn = ch.yv[tstart][l];
-            RoundRec rn = rr[tstart];
-            char *zs = reinterpret_cast<char *>(a.Z + (int64_t)(ws + tstart) * a.zl.zs_t);
-            int tend = wl;                                       // a fold request ends the loop early
-            for (int t = tstart; t < tend; ++t) {
-                const float qv = qn, yy = yn;                    // <v_t, x_t>, y_t
-                const RoundRec rc = rn;                          // collisions with later rounds, ||x_t||^2
-                qn = ch.q0[t + 1][l]; yn = ch.yv[t + 1][l]; rn = rr[t + 1];        // next round, early
-                float z = sf * qv;
-                if (OPT) {
-                    // played iterate w_t = s (w^_t - ha x_{t-1}), s from ||w^_t - ha x_{t-1}||^2: scalars only
-                    const float mf = fmaf(ha * ha, x2p, fmaf(-2.f * ha, hp, (float)(sd2 * n2)));
-                    const float sp = mf > D2f ? Df * __builtin_amdgcn_rsqf(mf) : 1.f;
-                    z = sp * fmaf(-ha, g01[t], z);
-                }
-                *reinterpret_cast<float *>(zs + zoff4) = z;
-                zs += zstep;
-                // for the squared loss eta * 2 (z - y) = (2 eta) (z - y) exactly
-                const float step = LOSS == 1 ? eta2_r * (z - yy) : eta_r * slope<LOSS>(z, yy);
-                const float b = step * isf;
-                ch.bw[t][l] = b;
-                // (readfirstlane returns int: go through unsigned, or the low word sign-extends)
-                unsigned long long m =
-                    (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)rc.mask) |
-                    ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(rc.mask >> 32)) << 32);
-                if (m) {
-                    const bool next_hit = (m >> (t + 1)) & 1;
-                    while (m) {
-                        const int t2 = __builtin_ctzll(m);
-                        m &= m - 1;
-                        ch.q0[t2][l] = fmaf(-b, gl[gp++], ch.q0[t2][l]);
-                    }
-                    if (next_hit) qn = ch.q0[t + 1][l];
-                }
-                // ||v - b x||^2 = ||v||^2 + b (b ||x||^2 - 2 <v, x>)
-                const double bd = (double)b;
-                n2 = fma(bd, fma(bd, rc.x2, (double)(-2.f * qv)), n2);
-                n2 = n2 > 0.0 ? n2 : 0.0;
-                // projection: sigma = D / ||v||.  One select, then the values that follow from sigma
-                // (the chain is bound by the number of instructions a single wavefront can issue)
-                const double snew = a.D * rsqrt_pos(n2);
-                sigma = n2 * sd2 > D2 ? snew : sigma;
-                sd2 = sigma * sigma;
-                sf = (float)sigma;
-                isf = __builtin_amdgcn_rcpf(sf);
-                if (OPT) {                                      // next round's hint and <w^_{t+1}, x_t>
-                    hp = sf * fmaf(-b, (float)rc.x2, qv);
-                    ha = step;
-                    x2p = (float)rc.x2;
-                }
-                if (__any(sigma < kSparseFoldLo)) {
-                    if (lane == 0) { fold_t = t; fold_gp = gp; }
-                    fold_sf[l] = sf;
-                    tend = t + 1;
-                }
-            }
-        };
-        if (chain) {
-            run_chain(0, 0);
-        } else if (wave != 0 && w + 1 < wend) {
-            // ---- meanwhile the other wavefronts stage the next window -------------------------
-            stage_window(stage[(w + 1 - wbeg) & 1], a, recs[w + 1], plan.start(w + 1), plan.len(w + 1) * nnz,
-                         (int)threadIdx.x - kWave, (kSpWaves - 1) * kWave);
-            if (a.prefetch) {
-                // ... and pull its rows of V towards L2 (one lane per row segment of this workgroup)
-                const int ns = plan.start(w + 1), ntot = plan.len(w + 1) * nnz;
-                float sink = 0.f;
-                for (int en = (int)threadIdx.x - kWave; en < ntot; en += (kSpWaves - 1) * kWave)
-                    sink += ldv(a.V + (int64_t)a.col[(int64_t)ns * nnz + en] * a.RKp + blockIdx.x * LPW);
-                if (sink == 1.2345e30f) a.Z[0] = sink;          // never true; keeps the loads alive
             }
         }
-        wg_sync();
+    };
+    // the predictions of a window go from LDS to Z (wavefronts 1 .. 15, a lane stores for its own learner)
+    auto flush_z = [&](const WinView &v, const float (*zbp)[LPW]) {
+        if (wave == 0 || !valid) return;
+        char *zs = reinterpret_cast<char *>(a.Z) + zoff4;
+        for (int t = (wave - 1) * EPI + e; t < v.wl; t += kCWaves * EPI)
+            *reinterpret_cast<float *>(zs + (int64_t)(v.ws + t) * zstep) = zbp[t][l];
+    };
+    // ---- C: V[col] += -b_t x_t[col] for the rounds t <= tmax of a window, as no-return float
+    // atomics.  All entries of a column belong to one wavefront (1 .. 15; wavefront 0 runs the
+    // dependent rounds), which walks its share of the column-sorted list EPI entries per
+    // instruction, so the adds to one address are issued in round order.  Entries of one column
+    // that meet in an instruction are summed across slots first (fixed order); the pre-pass
+    // marks them, and an instruction without any (nearly all, for columns drawn at random)
+    // skips the exchange ------------------------------------------------------------------------
+    auto apply_steps = [&](const WinView &v, const float (*bwp)[LPW], int tmax, auto partial) {   // partial: only t <= tmax
+        if (wave == 0) return;
+        const int beg = __builtin_amdgcn_readfirstlane(v.offs[wave - 1]);
+        const int end = __builtin_amdgcn_readfirstlane(v.offs[wave]);
+        constexpr int NI = 4;                                // instructions per batch
+        for (int k0 = beg; k0 < end; k0 += NI * EPI) {
+            int cc[NI];
+            float xv[NI];
+            bool dup[NI];
+#pragma unroll
+            for (int n = 0; n < NI; ++n) {
+                const int k = k0 + n * EPI + e;
+                const bool act = k < end;
+                const int pe = v.perm[act ? k : end - 1];
+                const int ee = pe & 0xFFF;
+                const int t = (int)(((unsigned)ee * mdiv) >> 18);
+                cc[n] = act ? v.cw[ee] : -1;
+                dup[n] = act && (pe & 0x8000);
+                xv[n] = act && (!decltype(partial)::value || t <= tmax) ? -bwp[t][l] * v.vw[ee] : 0.f;
+            }
+#pragma unroll
+            for (int n = 0; n < NI; ++n) {
+                bool last = true;
+                if (EPI > 1 && __builtin_amdgcn_ballot_w64(dup[n]) != 0) {
+#pragma unroll
+                    for (int sh = 1; sh < EPI; sh <<= 1) {
+                        const float ox = __shfl_up(xv[n], sh * LPW);
+                        const int oc = __shfl_up(cc[n], sh * LPW);
+                        if (e >= sh && oc == cc[n]) xv[n] += ox;
+                    }
+                    const int nc = __shfl_down(cc[n], LPW);
+                    last = e == EPI - 1 || nc != cc[n];
+                }
+                if (cc[n] >= 0 && last) unsafeAtomicAdd(a.V + (int64_t)cc[n] * a.RKp + uq, xv[n]);
+            }
+        }
+    };
+    // ---- B: the dependent rounds tstart .. tstop - 1 of a window, scalars and LDS only (LPW
+    // lanes of wavefront 0).  If a learner's sigma falls below the fold threshold the chain stops
+    // after that round (fold_t), the whole workgroup folds and the chain goes on from the next
+    // round.  gp: next Gram value of the window; returns the one after the rounds taken -----------
+    auto run_chain = [&](const WinView &v, float (*q0)[LPW], const float (*yv)[LPW], float (*bw)[LPW], float (*zb)[LPW],
+                         int tstart, int tstop, int gp) {
+        float qn = q0[tstart][l], yn = yv[tstart][l];
+        const RoundRec *rr = v.rr;
+        const float *gl = v.gl, *g01 = v.g01;
+        RoundRec rn = rr[tstart];
+        int tend = tstop;                                    // a fold request ends the loop early
+        for (int t = tstart; t < tend; ++t) {
+            const float qv = qn, yy = yn;                    // <v_t, x_t>, y_t
+            const RoundRec rc = rn;                          // collisions with later rounds, ||x_t||^2
+            qn = q0[t + 1][l]; yn = yv[t + 1][l]; rn = rr[t + 1];        // next round, early
+            float z = sf * qv;
+            if (OPT) {
+                // played iterate w_t = s (w^_t - ha x_{t-1}), s from ||w^_t - ha x_{t-1}||^2: scalars only
+                const float mf = fmaf(ha * ha, x2p, fmaf(-2.f * ha, hp, (float)(sd2 * n2)));
+                const float sp = mf > D2f ? Df * __builtin_amdgcn_rsqf(mf) : 1.f;
+                z = sp * fmaf(-ha, g01[t], z);
+            }
+            zb[t][l] = z;         // not to Z from here: a global store would queue behind the other wavefronts' memory work
+            // for the squared loss eta * 2 (z - y) = (2 eta) (z - y) exactly
+            const float step = LOSS == 1 ? eta2_r * (z - yy) : eta_r * slope<LOSS>(z, yy);
+            const float b = step * isf;
+            bw[t][l] = b;
+            // (readfirstlane returns int: go through unsigned, or the low word sign-extends)
+            unsigned long long m =
+                (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)rc.mask) |
+                ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(rc.mask >> 32)) << 32);
+            if (m) {
+                const bool next_hit = (m >> (t + 1)) & 1;
+                while (m) {
+                    const int t2 = __builtin_ctzll(m);
+                    m &= m - 1;
+                    q0[t2][l] = fmaf(-b, gl[gp++], q0[t2][l]);
+                }
+                if (next_hit) qn = q0[t + 1][l];
+            }
+            // ||v - b x||^2 = ||v||^2 + b (b ||x||^2 - 2 <v, x>)
+            const double bd = (double)b;
+            n2 = fma(bd, fma(bd, rc.x2, (double)(-2.f * qv)), n2);
+            n2 = n2 > 0.0 ? n2 : 0.0;
+            // projection: sigma = D / ||v||.  One select, then the values that follow from sigma
+            // (the chain is bound by the number of instructions a single wavefront can issue)
+            const double snew = a.D * rsqrt_pos(n2);
+            sigma = n2 * sd2 > D2 ? snew : sigma;
+            sd2 = sigma * sigma;
+            sf = (float)sigma;
+            isf = __builtin_amdgcn_rcpf(sf);
+            if (OPT) {                                      // next round's hint and <w^_{t+1}, x_t>
+                hp = sf * fmaf(-b, (float)rc.x2, qv);
+                ha = step;
+                x2p = (float)rc.x2;
+            }
+            if (__any(sigma < kSparseFoldLo)) {
+                if (lane == 0) { fold_t = t; fold_gp = gp; }
+                fold_sf[l] = sf;
+                tend = t + 1;
+            }
+        }
+        return gp;
+    };
+    // What the wavefronts 1 .. 15 do beside the dependent rounds: the loads of window wn (on their
+    // way into LDS) are issued first, then the steps and predictions of window wc, and only then
+    // are the loads waited for; the next barrier waits for the atomics.
+    auto work_beside = [&](int wn, bool steps, const WinView &vc, const float (*bwc)[LPW], const float (*zbc)[LPW]) {
+        const int tid = (int)threadIdx.x - kWave;
+        StageRegs sr;
+        if (wn < wend) sr.load(a, recs[wn], plan.start(wn), plan.len(wn) * nnz, tid, kCWaves * kWave);
+        if (steps) { apply_steps(vc, bwc, 0, std::false_type()); flush_z(vc, zbc); }
+        if (wn < wend) sr.store(stage_of(wn), plan.len(wn) * nnz, tid, kCWaves * kWave);
+    };
+
+    // the dependent rounds are the critical path: their wavefront issues ahead of the three that
+    // share its SIMD
+    if (wave == 0) __builtin_amdgcn_s_setprio(3);
+    stage_window(stage_of(wbeg), a, recs[wbeg], plan.start(wbeg), plan.len(wbeg) * nnz, threadIdx.x, blockDim.x);
+    if (threadIdx.x == 0) fold_t = -1;
+    wg_sync();
+    bool have_q0 = false;          // PIPE: this window's <v, x_t> were gathered beside the previous window's rounds
+    bool pending = false;          // PIPE: the previous window's steps are not in V yet
+    for (int w = wbeg; w < wend; ++w) {
+        const WinView v = view(w);
+        const int cb = PIPE ? (w - wbeg) & 1 : 0;
+        Chain<LPW> &ch = chs[cb];                            // this window's buffers
+        Chain<LPW> &cho = chs[cb ^ (NB - 1)];                // PIPE: the previous window's, then the next one's
+        float (*q0)[LPW] = ch.q0;
+        float (*yv)[LPW] = ch.yv;
+        float (*bw)[LPW] = ch.bw;
+        float (*zb)[LPW] = ch.zb;
+        const int wl = v.wl;
+        if (!have_q0) {
+            if (PIPE && pending) {
+                apply_steps(view(w - 1), cho.bw, 0, std::false_type());
+                flush_z(view(w - 1), cho.zb);
+                wg_sync();
+                pending = false;
+            }
+            gather_q0(std::integral_constant<int, LPW == 64 ? 2 : 4>(),
+                      std::integral_constant<int, LPW == 64 ? 16 : (LPW >= 16 ? 8 : (LPW == 8 ? 4 : 2))>(), v, wave,
+                      kSpWaves, q0, yv);
+            wg_sync();
+        }
+        int gp = 0;
+        if (PIPE) {
+            // ---- first part: rounds 0 .. kMid - 1 | steps of window w - 1, staging of window w + 1
+            const int tmid = wl < kMid ? wl : kMid;
+            if (wave == 0) {
+                if (chain) {
+                    if (have_q0) {
+                        // steps of window w - 1 that the early gather has not seen
+                        const int nx = v.xh[0];
+                        const unsigned short *xs = reinterpret_cast<const unsigned short *>(v.xh + 32);
+                        const unsigned short *xt = xs + kMaxCross;
+                        const float *xg = reinterpret_cast<const float *>(v.xh + 32 + kMaxCross);
+                        const float (*bwprev)[LPW] = cho.bw;
+                        for (int p = 0; p < nx; ++p) q0[xt[p]][l] = fmaf(-bwprev[xs[p]][l], xg[p], q0[xt[p]][l]);
+                    }
+                    gp = run_chain(v, q0, yv, bw, zb, 0, tmid, 0);
+                }
+            } else {
+                work_beside(w + 1, pending, pending ? view(w - 1) : v, cho.bw, cho.zb);
+            }
+            wg_sync_chain(wave);
+            // ---- second part: the other rounds | <v, x_t> of window w + 1 (V holds the steps up to
+            // window w - 1) ----------------------------------------------------------------------
+            const bool early = w + 1 < wend && stage_of(w + 1).head[4 * kWin + 32 + kWin] >= 0;
+            if (wave == 0) {
+                if (chain && fold_t < 0 && tmid < wl) gp = run_chain(v, q0, yv, bw, zb, tmid, wl, gp);
+            } else if (early) {
+                gather_q0(std::integral_constant<int, 5>(), std::integral_constant<int, LPW >= 16 ? 4 : (LPW == 8 ? 4 : 2)>(),
+                          view(w + 1), wave - 1, kCWaves, cho.q0, cho.yv);
+            }
+            wg_sync_chain(wave);
+            pending = false;
+            have_q0 = early;
+        } else {
+            if (chain) {
+                run_chain(v, q0, yv, bw, zb, 0, wl, 0);
+            } else if (wave != 0 && w + 1 < wend) {
+                work_beside(w + 1, false, v, bw, zb);
+            }
+            wg_sync_chain(wave);
+        }
         for (int ft = fold_t; ft >= 0; ft = fold_t) {
         const int gp0 = fold_gp;
+        have_q0 = false;           // what was gathered for the next window is void after a fold
         // ---- fold inside the window (sigma below 2^-100 before the segment ended): apply the
         // steps taken so far, scale the workgroup's columns of V by sigma with all wavefronts,
         // measure ||v||^2 exactly, and take the remaining rounds' <v, x_t> afresh ----------------
-        apply_steps(ft, std::true_type());
+        apply_steps(v, bw, ft, std::true_type());
         wg_sync();
         {
-            for (int rd = (int)threadIdx.x / LPW; rd <= ft; rd += kSpWaves * EPI) ch.bw[rd][l] = 0.f;   // applied
+            for (int rd = (int)threadIdx.x / LPW; rd <= ft; rd += kSpWaves * EPI) bw[rd][l] = 0.f;   // applied
             const float fs = fold_sf[l];
             const int64_t nslots = kSpWaves * EPI;
             double m2 = 0.0;
@@ -572,12 +852,22 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             sigma = 1.0; sd2 = 1.0; sf = 1.f; isf = 1.f;
         }
         if (threadIdx.x == 0) fold_t = -1;
-        gather_q0(std::integral_constant<int, 1>(), std::integral_constant<int, 2>());   // rare: few registers
+        gather_q0(std::integral_constant<int, 1>(), std::integral_constant<int, 2>(), v, wave, kSpWaves, q0, yv);   // rare: few registers
         wg_sync();
-        if (chain) run_chain(ft + 1, gp0);
+        if (chain) run_chain(v, q0, yv, bw, zb, ft + 1, wl, gp0);
         wg_sync();
         }
-        apply_steps(wl - 1, std::false_type());
+        if (PIPE) {
+            pending = true;                                  // applied beside the next window's rounds
+        } else {
+            apply_steps(v, bw, 0, std::false_type());
+            flush_z(v, zb);
+            wg_sync();
+        }
+    }
+    if (PIPE && pending) {
+        apply_steps(view(wend - 1), chs[(wend - 1 - wbeg) & 1].bw, 0, std::false_type());
+        flush_z(view(wend - 1), chs[(wend - 1 - wbeg) & 1].zb);
         wg_sync();
     }
     if (chain) { a.sigma[q] = sigma; a.n2[q] = n2; }
@@ -661,20 +951,38 @@ int sparse_learners_per_workgroup(int nq)
     return lpw;
 }
 
+template <int LOSS, int LPW, bool OPT>
+hipError_t launch_window_lpw(const SparseArgs &a, const WinPlan &plan, int wbeg, int wend, hipStream_t s)
+{
+    const int nq = a.R * a.K;
+    const dim3 grid((unsigned)((nq + LPW - 1) / LPW)), block(kSpWaves * kWave);
+    const size_t stage_b = (size_t)stage_ints(a.nnz) * 4, chain_b = sizeof(Chain<LPW>);
+    // the pipelined kernel keeps two chain buffers and three staged windows
+    int pipe = 2 * chain_b + 3 * stage_b + sparse_static_lds(LPW) <= kLdsBytes;
+    if (const char *f = getenv("OCO_SPARSE_PIPE")) pipe = pipe && atoi(f) != 0;
+    const size_t smem = pipe ? 2 * chain_b + 3 * stage_b : chain_b + 2 * stage_b;
+    if (smem + sparse_static_lds(LPW) > kLdsBytes) return hipErrorInvalidValue;
+    const auto kern = sparse_window_kernel<LOSS, LPW, OPT>;
+    if (smem > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, grid, block, smem, s, a, plan, wbeg, wend, pipe);
+    return hipGetLastError();
+}
+
 template <int LOSS, bool OPT>
 hipError_t launch_window_loss(const SparseArgs &a, int lpw, const WinPlan &plan, int wbeg, int wend, hipStream_t s)
 {
-    const int nq = a.R * a.K;
-    const dim3 grid((unsigned)((nq + lpw - 1) / lpw)), block(kSpWaves * kWave);
     switch (lpw) {
-        case 64: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 64, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
-        case 32: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 32, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
-        case 16: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 16, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
-        case 8: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 8, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
-        case 4: hipLaunchKernelGGL((sparse_window_kernel<LOSS, 4, OPT>), grid, block, 0, s, a, plan, wbeg, wend); break;
+        case 64: return launch_window_lpw<LOSS, 64, OPT>(a, plan, wbeg, wend, s);
+        case 32: return launch_window_lpw<LOSS, 32, OPT>(a, plan, wbeg, wend, s);
+        case 16: return launch_window_lpw<LOSS, 16, OPT>(a, plan, wbeg, wend, s);
+        case 8: return launch_window_lpw<LOSS, 8, OPT>(a, plan, wbeg, wend, s);
+        case 4: return launch_window_lpw<LOSS, 4, OPT>(a, plan, wbeg, wend, s);
         default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 hipError_t launch_window(const SparseArgs &a, int loss, int lpw, const WinPlan &plan, int wbeg, int wend, hipStream_t s)
@@ -709,13 +1017,16 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s, c
     const WinPlan plan{a.t0, a.n};
     const int nwin = plan.count();
     hipLaunchKernelGGL(sparse_gram_kernel, dim3(nwin), dim3(256), 0, s, a.col, a.val, a.nnz, plan,
-                       static_cast<WinRec *>(a.scratch), a.optimistic, a.last_col, a.last_val);
+                       static_cast<WinRec *>(a.scratch), a.optimistic, a.last_col, a.last_val, kSpWaves - 1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
     // segments end at the multiples of kSegment of the horizon, which are window boundaries
-    const int groups = a.RKp / kWave;
-    const int lpw = sparse_learners_per_workgroup(a.R * a.K);
+    const int groups = (a.R * a.K + kWave - 1) / kWave;
+    int lpw = sparse_learners_per_workgroup(a.R * a.K);
+    // one chain buffer and two staged windows have to fit the LDS (64 learners with more than 40
+    // entries per round do not)
+    while (lpw > 4 && sparse_chain_bytes(lpw) + 2 * (size_t)stage_ints(a.nnz) * 4 + sparse_static_lds(lpw) > kLdsBytes) lpw >>= 1;
     // the caller's per-segment work runs beside the following segments only while the window
     // kernel's workgroups leave at least half of the compute units idle
     if ((a.R * a.K + lpw - 1) / lpw > kBesideMaxWorkgroups) hook = nullptr;

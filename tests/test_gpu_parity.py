@@ -272,6 +272,30 @@ def test_sparse_rounds_for_every_workgroup_share(lpw, monkeypatch):
         _check(wl, data, _gpu(wl, data), norm_every=0, label="c5 lpw=%d %s" % (lpw, over))
 
 
+@pytest.mark.parametrize("lpw", [4, 32])
+def test_sparse_rounds_without_the_window_pipeline(lpw, monkeypatch):
+    """Where the LDS has no room for three staged windows (64 learners per workgroup, or many
+    entries per round) the windows run gather, rounds, steps one after the other;
+    OCO_SPARSE_PIPE=0 takes that path for any share.  Both paths agree with the oracle; between
+    them only float32 rounding differs (a window's inner products are taken before or after
+    the previous window's steps)."""
+    monkeypatch.setenv("OCO_SPARSE_LPW", str(lpw))
+    for over in (dict(T=700, R=5, d=512, K=5, nnz=8, wstar_nnz=16),
+                 dict(T=2300, R=3, d=4096, K=8, wstar_nnz=64),
+                 dict(T=300, R=2, d=300, K=2, nnz=64, wstar_nnz=30, eta=(2.0, 400.0))):
+        wl = WL.make("c5", **over)
+        data = WL.generate(wl)
+        piped = _gpu(wl, data)
+        monkeypatch.setenv("OCO_SPARSE_PIPE", "0")
+        print("case c5 no pipeline lpw", lpw, over, flush=True)
+        plain = _gpu(wl, data)
+        monkeypatch.delenv("OCO_SPARSE_PIPE")
+        _check(wl, data, plain, norm_every=0, label="c5 no pipeline lpw=%d %s" % (lpw, over))
+        for k in ("regret", "L", "W", "p", "wbar"):
+            scale = max(1.0, float(np.abs(plain[k]).max()))
+            np.testing.assert_allclose(piped[k], plain[k], rtol=0, atol=2e-6 * scale, err_msg=k)
+
+
 @pytest.mark.parametrize("lpw", [4, 16, 64])
 def test_sparse_rounds_with_steps_far_larger_than_the_ball(lpw, monkeypatch):
     """Steps hundreds of times the radius make the lazy scale shrink by a constant factor every
@@ -315,12 +339,13 @@ def test_sparse_rounds_with_a_column_in_every_round(lpw, monkeypatch):
     ("c4", dict(T=200, R=2, d=4096, K=4), (3, 100)),
     ("c5", dict(T=600, R=3, d=4096, K=8, wstar_nnz=64), (128, 1, 250)),
     ("c5", dict(T=300, R=2, d=300, K=2, nnz=64, wstar_nnz=30, eta=(2.0, 400.0)), (64, 7)),
+    ("c5", dict(T=4300, R=2, d=2048, K=4, wstar_nnz=64), (2048, 64)),
 ])
 def test_results_do_not_depend_on_how_the_horizon_is_cut(name, over, chunks):
     """State after T rounds is bit-identical whether the rounds arrive in one call or many
     (also the practical race detector: any unordered reduction would show up here).  The
-    sparse path works in windows of 64 rounds of the horizon: calls that end on a multiple
-    of 64 are bit-identical, other cuts regroup float sums and agree to rounding."""
+    sparse path is launched in segments that end at the multiples of 2048 rounds of the horizon:
+    calls that end there are bit-identical, other cuts regroup float sums and agree to rounding."""
     wl = WL.make(name, **over)
     data = WL.generate(wl)
     whole = _gpu(wl, data)
@@ -331,7 +356,7 @@ def test_results_do_not_depend_on_how_the_horizon_is_cut(name, over, chunks):
         print("case", name, over, "chunk", c, flush=True)
         part = _gpu(wl, data, chunk=c, n_max=c)
         for k in ("regret", "L", "W", "p", "wbar"):
-            if wl.nnz and c % 64:
+            if wl.nnz and c % 2048:
                 scale = max(1.0, float(np.abs(whole[k]).max()))
                 np.testing.assert_allclose(part[k], whole[k], rtol=0, atol=2e-6 * scale, err_msg="%s %d" % (k, c))
             else:
