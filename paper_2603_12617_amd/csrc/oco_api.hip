@@ -263,18 +263,28 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
     // Meta kernel of the rounds [off, off + len) of this call, on the second stream.
     struct MetaPipe {
         oco_state *st; MetaArgs m; int loss; size_t used = 0;
-        static hipError_t piece(void *ctx, int off, int len) {
-            MetaPipe &p = *static_cast<MetaPipe *>(ctx);
-            oco_state *st = p.st;
-            if (p.used == st->piece_ev.size()) {
+        // the second stream waits for what is on the call's stream now
+        hipError_t follow() {
+            if (used == st->piece_ev.size()) {
                 hipEvent_t ev;
                 hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
                 if (e != hipSuccess) return e;
                 st->piece_ev.push_back(ev);
             }
-            hipEvent_t ev = st->piece_ev[p.used++];
+            hipEvent_t ev = st->piece_ev[used++];
             hipError_t e = hipEventRecord(ev, st->stream);
             if (e == hipSuccess) e = hipStreamWaitEvent(st->side, ev, 0);
+            return e;
+        }
+        static hipError_t beside(void *ctx, hipStream_t *out) {
+            MetaPipe &p = *static_cast<MetaPipe *>(ctx);
+            *out = p.st->side;
+            return p.follow();
+        }
+        static hipError_t piece(void *ctx, int off, int len) {
+            MetaPipe &p = *static_cast<MetaPipe *>(ctx);
+            oco_state *st = p.st;
+            hipError_t e = p.follow();
             if (e != hipSuccess) return e;
             MetaArgs m = p.m;
             m.Z += (int64_t)off * m.zl.zs_t;
@@ -293,7 +303,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
     m.Z = st->at<float>(l.off_Z); m.zl = zl; m.y = rd->y; m.y_run_stride = yrs;
     m.L = st->at<double>(l.off_L); m.regret = st->at<double>(l.off_regret);
     m.eps = c.eps; m.K = (int)c.K; m.R = (int)c.R; m.n = (int)n;
-    const PieceHook hook{&MetaPipe::piece, &pipe};
+    const PieceHook hook{&MetaPipe::piece, &pipe, &MetaPipe::beside};
     bool overlap = true;
     if (const char *ev = std::getenv("OCO_META_BESIDE")) overlap = std::atoi(ev) != 0;   // tuning override
 

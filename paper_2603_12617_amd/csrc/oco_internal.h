@@ -23,6 +23,9 @@ struct ZLayout {
 struct PieceHook {
     hipError_t (*fn)(void *ctx, int off, int len);
     void *ctx;
+    // Optional: a stream for work of the call that the round kernels neither wait for nor feed
+    // (it starts after the work already on the call's stream, and what fn enqueues follows it).
+    hipError_t (*beside)(void *ctx, hipStream_t *out) = nullptr;
 };
 
 // ---- dense rounds -----------------------------------------------------------

@@ -156,12 +156,10 @@ struct WinRec {
 static_assert(sizeof(WinRec) % 128 == 0, "window records stay 256-byte aligned");
 constexpr int kRecHeadInts = (int)(offsetof(WinRec, perm) / 4);
 
-__global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, const float *val, int nnz,
+__global__ void __launch_bounds__(1024) sparse_gram_kernel(const int32_t *col, const float *val, int nnz,
                                                           WinPlan plan, WinRec *recs, int optimistic,
                                                           const int32_t *last_col, const float *last_val, int shares)
 {
-    __shared__ int csp[kWin * OCO_MAX_NNZ];                     // the previous window's entries
-    __shared__ float vsp[kWin * OCO_MAX_NNZ];
     __shared__ unsigned int xm[kWin][2];
     __shared__ int xrowoff[kWin + 1];
     __shared__ int cs[kWin * OCO_MAX_NNZ];
@@ -181,11 +179,10 @@ __global__ void __launch_bounds__(256) sparse_gram_kernel(const int32_t *col, co
         vs[e] = val[(int64_t)ws * nnz + e];
         key[e] = ((unsigned long long)(unsigned)c << 12) | (unsigned)e;
     }
+    // the previous window's entries are read where they lie (once each, but for the rare pairs)
     const int pws = w > 0 ? plan.start(w - 1) : 0, ptotal = w > 0 ? plan.len(w - 1) * nnz : 0;
-    for (int e = threadIdx.x; e < ptotal; e += blockDim.x) {
-        csp[e] = col[(int64_t)pws * nnz + e];
-        vsp[e] = val[(int64_t)pws * nnz + e];
-    }
+    const int32_t *csp = col + (int64_t)pws * nnz;
+    const float *vsp = val + (int64_t)pws * nnz;
     for (int e = threadIdx.x; e < kWin * 2; e += blockDim.x) { mk[e >> 1][e & 1] = 0u; xm[e >> 1][e & 1] = 0u; }
     __syncthreads();
     // sort by (column, position) -- a stable sort by column -- with a bitonic network over the
@@ -1010,13 +1007,11 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s, c
     SparseArgs a = a0;
     if (a.n <= 0) return hipSuccess;
     if (a.nnz > OCO_MAX_NNZ) return hipErrorInvalidValue;
-    const int64_t nthr = (int64_t)a.n * a.R;
-    hipLaunchKernelGGL(sparse_comparator_kernel, dim3((unsigned)((nthr + 255) / 256)), dim3(256), 0, s, a);
 
     // scratch: one record per window of the call
     const WinPlan plan{a.t0, a.n};
     const int nwin = plan.count();
-    hipLaunchKernelGGL(sparse_gram_kernel, dim3(nwin), dim3(256), 0, s, a.col, a.val, a.nnz, plan,
+    hipLaunchKernelGGL(sparse_gram_kernel, dim3(nwin), dim3(1024), 0, s, a.col, a.val, a.nnz, plan,
                        static_cast<WinRec *>(a.scratch), a.optimistic, a.last_col, a.last_val, kSpWaves - 1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -1030,6 +1025,19 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s, c
     // the caller's per-segment work runs beside the following segments only while the window
     // kernel's workgroups leave at least half of the compute units idle
     if ((a.R * a.K + lpw - 1) / lpw > kBesideMaxWorkgroups) hook = nullptr;
+    // the comparator's predictions feed the meta kernel only: beside the round kernels where
+    // those leave room, else ahead of them
+    {
+        hipStream_t cs = s;
+        if (hook && hook->beside) {
+            e = hook->beside(hook->ctx, &cs);
+            if (e != hipSuccess) return e;
+        }
+        const int64_t nthr = (int64_t)a.n * a.R;
+        hipLaunchKernelGGL(sparse_comparator_kernel, dim3((unsigned)((nthr + 255) / 256)), dim3(256), 0, cs, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     for (int wbeg = 0; wbeg < nwin;) {
         const int64_t seg_end = ((a.t0 + plan.start(wbeg)) / kSegment + 1) * kSegment;   // absolute
         int wend = wbeg + 1;
