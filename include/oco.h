@@ -32,7 +32,7 @@
  *  - Results are a pure function of (config, inputs, call boundaries).  Dense
  *    configurations: splitting [0, T) into oco_run_rounds calls in any way
  *    gives bit-identical state and regret.  Sparse configurations work in
- *    segments of 2048 rounds of the horizon: splits at multiples of 2048 are
+ *    segments of 4096 rounds of the horizon: splits at multiples of 4096 are
  *    bit-identical, other splits regroup float32 sums and agree to rounding.
  *  - Arithmetic: iterates, inner products and the projection in float32;
  *    losses, cumulative losses, Hedge weights and regret in float64.

@@ -48,7 +48,7 @@
 // On the boundary of the ball sigma shrinks geometrically (every projection
 // multiplies it by a factor < 1) and v grows, so sigma has to be folded back
 // into v now and then: V[:, q] *= sigma_q, ||v||^2 *= sigma_q^2, sigma_q = 1.
-// The rounds are launched in segments that end at every 2048th round of the
+// The rounds are launched in segments that end at every 4096th round of the
 // horizon; after each segment a grid-wide kernel folds the 64-learner column
 // groups whose smallest sigma has dropped below 2^-64 (a streaming pass at HBM
 // speed, and a no-op otherwise).  Should a sigma fall below 2^-100 inside a
@@ -115,7 +115,10 @@ __device__ __forceinline__ void wg_sync_chain(int wave)
 #endif
 constexpr double kSparseFoldLo = OCO_FOLD_LO;    // in-kernel emergency fold
 constexpr double kSparseFoldSoft = OCO_FOLD_SOFT;  // fold between segments
-constexpr int kSegment = 2048;               // rounds per launch segment (absolute alignment)
+#ifndef OCO_SEGMENT
+#define OCO_SEGMENT 4096
+#endif
+constexpr int kSegment = OCO_SEGMENT;        // rounds per launch segment (absolute alignment)
 constexpr int kWin = 64;                     // rounds per window (absolute alignment)
 constexpr int kSpWaves = 16;                 // wavefronts per workgroup
 constexpr int kBesideMaxWorkgroups = 128;    // window grids up to this size leave half the chip idle

@@ -339,12 +339,12 @@ def test_sparse_rounds_with_a_column_in_every_round(lpw, monkeypatch):
     ("c4", dict(T=200, R=2, d=4096, K=4), (3, 100)),
     ("c5", dict(T=600, R=3, d=4096, K=8, wstar_nnz=64), (128, 1, 250)),
     ("c5", dict(T=300, R=2, d=300, K=2, nnz=64, wstar_nnz=30, eta=(2.0, 400.0)), (64, 7)),
-    ("c5", dict(T=4300, R=2, d=2048, K=4, wstar_nnz=64), (2048, 64)),
+    ("c5", dict(T=8500, R=2, d=2048, K=4, wstar_nnz=64), (4096, 64)),
 ])
 def test_results_do_not_depend_on_how_the_horizon_is_cut(name, over, chunks):
     """State after T rounds is bit-identical whether the rounds arrive in one call or many
     (also the practical race detector: any unordered reduction would show up here).  The
-    sparse path is launched in segments that end at the multiples of 2048 rounds of the horizon:
+    sparse path is launched in segments that end at the multiples of 4096 rounds of the horizon:
     calls that end there are bit-identical, other cuts regroup float sums and agree to rounding."""
     wl = WL.make(name, **over)
     data = WL.generate(wl)
@@ -356,7 +356,7 @@ def test_results_do_not_depend_on_how_the_horizon_is_cut(name, over, chunks):
         print("case", name, over, "chunk", c, flush=True)
         part = _gpu(wl, data, chunk=c, n_max=c)
         for k in ("regret", "L", "W", "p", "wbar"):
-            if wl.nnz and c % 2048:
+            if wl.nnz and c % 4096:
                 scale = max(1.0, float(np.abs(whole[k]).max()))
                 np.testing.assert_allclose(part[k], whole[k], rtol=0, atol=2e-6 * scale, err_msg="%s %d" % (k, c))
             else:
