@@ -146,6 +146,11 @@ SPARSE = [
     dict(T=500, R=3, d=4096, K=3, wstar_nnz=64, eta=(0.5, 5.0, 50.0)),       # projection every round
     dict(T=300, R=2, d=300, K=2, nnz=64, wstar_nnz=30, eta=(2.0, 400.0)),    # sigma folds
     dict(T=100, R=1, d=64, K=1, nnz=1, wstar_nnz=4),
+    # few enough columns shared by neighbouring windows (about 16 round pairs) that the windows are
+    # pipelined and the inner products gathered ahead are corrected across the window boundary
+    dict(T=900, R=3, d=1 << 16, K=4, nnz=16, wstar_nnz=64),
+    dict(T=700, R=2, d=1 << 18, K=8, wstar_nnz=64),
+    dict(T=500, R=2, d=1 << 17, K=3, wstar_nnz=64, eta=(0.5, 5.0, 50.0)),
 ]
 
 
@@ -236,6 +241,22 @@ def test_sparse_optimistic_rounds_match_the_oracle(over, monkeypatch):
         np.testing.assert_allclose(odd[k], whole[k], rtol=0, atol=2e-6 * scale, err_msg=k)
     monkeypatch.setenv("OCO_SPARSE_LPW", "64")
     _check_sparse_optimistic(wl, data, _gpu(wl, data), "c5 optimistic lpw=64 %s" % over)
+
+
+def test_sparse_optimistic_rounds_with_pipelined_windows():
+    """Columns spread widely enough that neighbouring windows share only a few: the windows are
+    pipelined (inner products of the next window gathered ahead and corrected across the
+    boundary).  Cuts of the horizon inside a launch segment then regroup float sums."""
+    over = dict(T=500, R=2, d=1 << 16, K=4, nnz=16, wstar_nnz=64)
+    wl = WL.make("c5", optimistic=True, **over)
+    data = WL.generate(wl)
+    print("case c5 optimistic pipelined", over, flush=True)
+    whole = _gpu(wl, data)
+    _check_sparse_optimistic(wl, data, whole, "c5 optimistic pipelined %s" % over)
+    part = _gpu(wl, data, chunk=128, n_max=128)
+    for k in ("regret", "L", "W", "p", "wbar"):
+        scale = max(1.0, float(np.abs(whole[k]).max()))
+        np.testing.assert_allclose(part[k], whole[k], rtol=0, atol=2e-6 * scale, err_msg=k)
 
 
 def test_accel_bounds_match_the_oracle():
