@@ -23,8 +23,12 @@ template <int LOSS> __device__ __forceinline__ double phi(double z, double y)
 {
     if (LOSS == 0) return z;
     if (LOSS == 1) { const double e = z - y; return e * e; }
-    const double m = y * z;                       // log(1 + exp(-m)) without overflow
-    return m > 0.0 ? log1p(exp(-m)) : log1p(exp(m)) - m;
+    // log(1 + exp(-m)) without overflow: log1p(exp(-|m|)) + max(-m, 0).  One exp and one log1p
+    // for every lane (a branch on the sign of m would run both sides in most wavefronts).
+    const double m = y * z;
+    const double am = fabs(m);
+    const double lp = log1p(exp(-am));
+    return m > 0.0 ? lp : lp + am;
 }
 
 template <int LOSS>
