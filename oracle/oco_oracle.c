@@ -26,7 +26,8 @@
  * Also here: the accepted-length / acceleration-rate bounds of Lemma 1 and
  * Theorem 1 (closed forms) and the optimistic two-step update of Eq. (3).
  * Every function is pinned by tests that do not call it to produce their
- * expectation (tests/test_oracle_pins.py, tests/test_oracle_pins_next.py).
+ * expectation (tests/test_oracle_pins.py, tests/test_oracle_pins_next.py),
+ * the many-run wrappers and the sparse form of Eq. (3) included.
  *
  * Losses are generalised-linear: f_t(w) = phi(<w, x_t>; y_t), so the
  * gradient is phi'(z; y) x_t.  For the linear loss x_t is the gradient g_t.
@@ -425,13 +426,182 @@ int oco_oracle_run_optimistic(int64_t d, int64_t K, int64_t T, double D, const d
     return 0;
 }
 
-/* R independent optimistic runs, one per thread at a time; layout as oco_oracle_run_many. */
+/*
+ * The same optimistic update (Eq. (3), last-gradient hint) on SPARSE rounds:
+ * col/val[T][nnz], columns distinct within a round.  The intermediate model w^
+ * is kept as a dense double vector per learner; the hint h_t is the previous
+ * round's row times that learner's previous slope, so it is held as
+ * (column, value) of the previous round plus one slope per learner.
+ *   norm_every == 0: the definition.  Every round the played iterate
+ *                    w_t = Proj[w^_t - eta h_t] is formed over all d
+ *                    coordinates and projected by its recomputed norm, and the
+ *                    norm of the stepped w^ is recomputed over all d.
+ *   norm_every  > 0: ||w^||^2 is carried forward by adding w'_j^2 - w_j^2 over
+ *                    the touched coordinates and recomputed over all d every
+ *                    norm_every rounds (largest relative gap -> *max_drift); the
+ *                    norm of w^_t - eta h_t is ||w^_t||^2 plus the same kind of
+ *                    difference over the hint's coordinates, and the played
+ *                    iterate is only evaluated at the coordinates round t reads.
+ * Outputs as oco_oracle_run_optimistic.
+ */
+int oco_oracle_run_optimistic_sparse(int64_t d, int64_t K, int64_t T, double D, const double *eta,
+                                     double eps, int loss, const int32_t *col, const float *val,
+                                     int64_t nnz, const float *y, const float *u,
+                                     const int64_t *seg_start, int64_t S, int64_t norm_every,
+                                     double *W, double *What, double *L, double *p, double *wbar,
+                                     double *regret, double *delta, double *max_drift,
+                                     const oco_oracle_trace *tr)
+{
+    if (d <= 0 || K <= 0 || T < 0 || S <= 0 || nnz <= 0 || !eta || !u || !seg_start || !col || !val)
+        return -1;
+    if (loss != LOSS_LINEAR && !y) return -1;
+    double *hat = calloc(K * d, sizeof(double));       /* w^_t, dense */
+    double *cprev = calloc(K, sizeof(double));         /* slope of the previous round: h_t = cprev x_{t-1} */
+    double *n2 = calloc(K, sizeof(double));            /* carried ||w^_t||^2 */
+    double *z = malloc(sizeof(double) * K), *ell = malloc(sizeof(double) * K);
+    double *wc = malloc(sizeof(double) * K * nnz);     /* played iterates at round t's columns */
+    double *saved = malloc(sizeof(double) * nnz);
+    double *tmp = calloc(d, sizeof(double));           /* dense scratch, all zero between uses */
+    if (!hat || !cprev || !n2 || !z || !ell || !wc || !saved || !tmp) return -1;
+    for (int64_t i = 0; i < K; ++i) { L[i] = 0.0; if (delta) delta[i] = 0.0; }
+    double reg = 0.0, drift = 0.0;
+    int64_t seg = 0;
+
+    for (int64_t t = 0; t < T; ++t) {
+        while (seg + 1 < S && t >= seg_start[seg + 1]) ++seg;
+        const float *ut = u + seg * d;
+        double yt = y ? (double)y[t] : 0.0;
+        const int32_t *ct = col + t * nnz, *cp = t > 0 ? col + (t - 1) * nnz : NULL;
+        const float *vt = val + t * nnz, *vp = t > 0 ? val + (t - 1) * nnz : NULL;
+        oco_oracle_hedge(L, K, eps, p);
+
+        /* the played iterates w_t^i = Proj[w^_t - eta_i h_t] and their predictions */
+        for (int64_t i = 0; i < K; ++i) {
+            double *hi = hat + i * d;
+            double a = eta[i] * cprev[i];
+            double f = 1.0;
+            if (norm_every == 0) {
+                double *w = W + i * d;
+                memcpy(w, hi, sizeof(double) * d);
+                if (cp) for (int64_t k = 0; k < nnz; ++k) w[cp[k]] -= a * (double)vp[k];
+                oco_oracle_project(w, d, D);
+                for (int64_t k = 0; k < nnz; ++k) wc[i * nnz + k] = w[ct[k]];
+            } else {
+                double m2 = n2[i];
+                if (cp) for (int64_t k = 0; k < nnz; ++k) {     /* w^ - eta h, in place for now */
+                    saved[k] = hi[cp[k]];
+                    double nw = saved[k] - a * (double)vp[k];
+                    hi[cp[k]] = nw;
+                    m2 += nw * nw - saved[k] * saved[k];
+                }
+                double nrm = sqrt(m2 > 0.0 ? m2 : 0.0);
+                if (nrm > D) f = D / nrm;
+                for (int64_t k = 0; k < nnz; ++k) wc[i * nnz + k] = f * hi[ct[k]];
+                if (cp) for (int64_t k = 0; k < nnz; ++k) hi[cp[k]] = saved[k];   /* back to w^ */
+            }
+            double sdot = 0.0;
+            for (int64_t k = 0; k < nnz; ++k) sdot += wc[i * nnz + k] * (double)vt[k];
+            z[i] = sdot;
+            ell[i] = oco_oracle_loss(loss, z[i], yt);
+        }
+        double zu = 0.0, zw = 0.0, zmix = 0.0;
+        for (int64_t k = 0; k < nnz; ++k) {
+            zu += (double)ut[ct[k]] * (double)vt[k];
+            double wj = 0.0;
+            for (int64_t i = 0; i < K; ++i) wj += p[i] * wc[i * nnz + k];
+            zw += wj * (double)vt[k];
+        }
+        for (int64_t i = 0; i < K; ++i) zmix += p[i] * z[i];
+        double ft = oco_oracle_loss(loss, zw, yt), fu = oco_oracle_loss(loss, zu, yt);
+        reg += ft - fu;
+        if (tr) {
+            for (int64_t i = 0; i < K; ++i) {
+                if (tr->p) tr->p[t * K + i] = p[i];
+                if (tr->z) tr->z[t * K + i] = z[i];
+                if (tr->loss) tr->loss[t * K + i] = ell[i];
+            }
+            if (tr->f) tr->f[t] = ft;
+            if (tr->fu) tr->fu[t] = fu;
+            if (tr->zmix) tr->zmix[t] = zmix;
+        }
+
+        /* w^_{t+1} = Proj[w^_t - eta g_t], g_t = c x_t at the played iterate; h_{t+1} = g_t */
+        for (int64_t i = 0; i < K; ++i) {
+            double *hi = hat + i * d;
+            double c = oco_oracle_slope(loss, z[i], yt);
+            if (delta) {                                   /* ||h_t - g_t||^2 over the union of columns */
+                double dsum = 0.0;
+                if (cp) for (int64_t k = 0; k < nnz; ++k) tmp[cp[k]] += cprev[i] * (double)vp[k];
+                for (int64_t k = 0; k < nnz; ++k) tmp[ct[k]] -= c * (double)vt[k];
+                if (cp) for (int64_t k = 0; k < nnz; ++k) { dsum += tmp[cp[k]] * tmp[cp[k]]; tmp[cp[k]] = 0.0; }
+                for (int64_t k = 0; k < nnz; ++k) { dsum += tmp[ct[k]] * tmp[ct[k]]; tmp[ct[k]] = 0.0; }
+                delta[i] += dsum;
+            }
+            double a = eta[i] * c, dl = 0.0, s2;
+            for (int64_t k = 0; k < nnz; ++k) {
+                double old = hi[ct[k]];
+                double nw = old - a * (double)vt[k];
+                hi[ct[k]] = nw;
+                dl += nw * nw - old * old;
+            }
+            if (norm_every == 0) {
+                s2 = 0.0;
+                for (int64_t j = 0; j < d; ++j) s2 += hi[j] * hi[j];
+            } else {
+                s2 = n2[i] + dl;
+                if ((t + 1) % norm_every == 0) {
+                    double full = 0.0;
+                    for (int64_t j = 0; j < d; ++j) full += hi[j] * hi[j];
+                    double gap = fabs(full - s2) / (full > 1e-300 ? full : 1e-300);
+                    if (full > 0 && gap > drift) drift = gap;
+                    s2 = full;
+                }
+            }
+            double nrm = sqrt(s2 > 0.0 ? s2 : 0.0);
+            if (nrm > D) {
+                double f = D / nrm;
+                for (int64_t j = 0; j < d; ++j) hi[j] *= f;
+                s2 = D * D;
+            }
+            n2[i] = s2;
+            cprev[i] = c;
+            L[i] += ell[i];
+        }
+    }
+
+    /* the iterates that would be played next, formed over all d coordinates */
+    for (int64_t i = 0; i < K; ++i) {
+        double *w = W + i * d;
+        memcpy(w, hat + i * d, sizeof(double) * d);
+        if (T > 0) {
+            const int32_t *cp = col + (T - 1) * nnz;
+            const float *vp = val + (T - 1) * nnz;
+            for (int64_t k = 0; k < nnz; ++k) w[cp[k]] -= eta[i] * cprev[i] * (double)vp[k];
+        }
+        oco_oracle_project(w, d, D);
+    }
+    oco_oracle_hedge(L, K, eps, p);
+    for (int64_t j = 0; j < d; ++j) {
+        double wj = 0.0;
+        for (int64_t i = 0; i < K; ++i) wj += p[i] * W[i * d + j];
+        wbar[j] = wj;
+    }
+    if (What) memcpy(What, hat, sizeof(double) * K * d);
+    *regret = reg;
+    if (max_drift) *max_drift = drift;
+    free(hat); free(cprev); free(n2); free(z); free(ell); free(wc); free(saved); free(tmp);
+    return 0;
+}
+
+/* R independent optimistic runs, one per thread at a time; layout as oco_oracle_run_many
+ * (dense x[T][d] shared or x[R][T][d]; or, with nnz > 0, shared col/val[T][nnz] and x == NULL). */
 int oco_oracle_run_many_optimistic(int64_t R, int64_t d, int64_t K, int64_t T, double D,
                                    const double *eta, double eps, int loss, int x_shared,
-                                   const float *x, const float *y, const float *u,
-                                   const int64_t *seg_start, int64_t S, int threads,
+                                   const float *x, const int32_t *col, const float *val, int64_t nnz,
+                                   const float *y, const float *u,
+                                   const int64_t *seg_start, int64_t S, int64_t norm_every, int threads,
                                    double *W, double *L, double *p, double *wbar, double *regret,
-                                   int *threads_used)
+                                   double *max_drift, int *threads_used)
 {
     int bad = 0, used = 1;
 #ifdef _OPENMP
@@ -443,10 +613,19 @@ int oco_oracle_run_many_optimistic(int64_t R, int64_t d, int64_t K, int64_t T, d
 #endif
 #pragma omp parallel for schedule(dynamic, 1) reduction(+ : bad)
     for (int64_t r = 0; r < R; ++r) {
-        int rc = oco_oracle_run_optimistic(d, K, T, D, eta, eps, loss, x_shared ? x : x + r * T * d,
+        int rc;
+        double dr = 0.0;
+        if (nnz > 0)
+            rc = oco_oracle_run_optimistic_sparse(d, K, T, D, eta, eps, loss, col, val, nnz,
+                                                  y ? y + r * T : NULL, u + r * S * d, seg_start, S,
+                                                  norm_every, W + r * K * d, NULL, L + r * K, p + r * K,
+                                                  wbar + r * d, regret + r, NULL, &dr, NULL);
+        else
+            rc = oco_oracle_run_optimistic(d, K, T, D, eta, eps, loss, x_shared ? x : x + r * T * d,
                                            y ? y + r * T : NULL, u + r * S * d, seg_start, S,
                                            W + r * K * d, NULL, L + r * K, p + r * K, wbar + r * d,
                                            regret + r, NULL, NULL);
+        if (max_drift) max_drift[r] = dr;
         if (rc) bad += 1;
     }
     if (threads_used) *threads_used = used;

@@ -57,11 +57,17 @@ def lib() -> C.CDLL:
             [C.c_int64, C.c_int64, C.c_int64, d, C.c_void_p, d, C.c_int]
             + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
             + [C.c_void_p] * 7 + [C.c_void_p])
+        _lib.oco_oracle_run_optimistic_sparse.restype = C.c_int
+        _lib.oco_oracle_run_optimistic_sparse.argtypes = (
+            [C.c_int64, C.c_int64, C.c_int64, d, C.c_void_p, d, C.c_int]
+            + [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64]
+            + [C.c_void_p] * 8 + [C.c_void_p])
         _lib.oco_oracle_run_many_optimistic.restype = C.c_int
         _lib.oco_oracle_run_many_optimistic.argtypes = (
             [C.c_int64] * 4 + [d, C.c_void_p, d, C.c_int, C.c_int]
-            + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int]
-            + [C.c_void_p] * 5 + [C.c_void_p])
+            + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
+            + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int]
+            + [C.c_void_p] * 5 + [C.c_void_p, C.c_void_p])
     return _lib
 
 
@@ -145,18 +151,26 @@ def accel_bounds(reg: float, T: int, k: int, alpha: float) -> np.ndarray:
 
 
 def run_optimistic(d: int, K: int, T: int, D: float, eta, eps: float, loss: str, *,
-                   x, y=None, u=None, seg_start=None, trace: bool = False) -> Dict[str, np.ndarray]:
-    """One run of K optimistic learners (Eq. (3), last-gradient hint) on a dense stream."""
+                   x=None, col=None, val=None, y=None, u=None, seg_start=None, norm_every: int = 0,
+                   trace: bool = False) -> Dict[str, np.ndarray]:
+    """One run of K optimistic learners (Eq. (3), last-gradient hint) on a dense stream x [T][d]
+    or on sparse rounds col/val [T][nnz]."""
     eta = np.ascontiguousarray(eta, dtype=np.float64)
     assert eta.size == K
-    x, y, u = _f32(x), _f32(y), _f32(u)
+    x, val, y, u = _f32(x), _f32(val), _f32(y), _f32(u)
+    col = None if col is None else np.ascontiguousarray(col, dtype=np.int32)
     u = u.reshape(-1, d)
     S = u.shape[0]
     seg_start = (np.zeros(1, np.int64) if seg_start is None
                  else np.ascontiguousarray(seg_start, dtype=np.int64))
-    assert seg_start.size == S and x.shape == (T, d)
+    assert seg_start.size == S
+    assert (x is None) != (col is None)
+    if x is not None:
+        assert x.shape == (T, d)
+    else:
+        assert col.shape == val.shape and col.shape[0] == T
     W = np.empty((K, d)); What = np.empty((K, d)); L = np.empty(K); p = np.empty(K); wbar = np.empty(d)
-    reg = np.zeros(1); delta = np.zeros(K)
+    reg = np.zeros(1); delta = np.zeros(K); drift = np.zeros(1)
     tr = None
     res: Dict[str, np.ndarray] = {}
     if trace:
@@ -166,13 +180,21 @@ def run_optimistic(d: int, K: int, T: int, D: float, eta, eps: float, loss: str,
             arr = np.zeros(shape)
             res["tr_" + name] = arr
             setattr(tr, name, arr.ctypes.data)
-    rc = lib().oco_oracle_run_optimistic(d, K, T, float(D), _ptr(eta), float(eps), LOSS_ID[loss],
-                                         _ptr(x), _ptr(y), _ptr(u), _ptr(seg_start), S,
-                                         _ptr(W), _ptr(What), _ptr(L), _ptr(p), _ptr(wbar), _ptr(reg),
-                                         _ptr(delta), C.byref(tr) if tr is not None else None)
+    if col is not None:
+        rc = lib().oco_oracle_run_optimistic_sparse(
+            d, K, T, float(D), _ptr(eta), float(eps), LOSS_ID[loss], _ptr(col), _ptr(val), col.shape[1],
+            _ptr(y), _ptr(u), _ptr(seg_start), S, int(norm_every),
+            _ptr(W), _ptr(What), _ptr(L), _ptr(p), _ptr(wbar), _ptr(reg), _ptr(delta), _ptr(drift),
+            C.byref(tr) if tr is not None else None)
+    else:
+        rc = lib().oco_oracle_run_optimistic(d, K, T, float(D), _ptr(eta), float(eps), LOSS_ID[loss],
+                                             _ptr(x), _ptr(y), _ptr(u), _ptr(seg_start), S,
+                                             _ptr(W), _ptr(What), _ptr(L), _ptr(p), _ptr(wbar), _ptr(reg),
+                                             _ptr(delta), C.byref(tr) if tr is not None else None)
     if rc != 0:
         raise ValueError("oco_oracle_run_optimistic rejected its arguments")
-    res.update(W=W, What=What, L=L, p=p, wbar=wbar, regret=float(reg[0]), delta=delta)
+    res.update(W=W, What=What, L=L, p=p, wbar=wbar, regret=float(reg[0]), delta=delta,
+               max_drift=float(drift[0]))
     return res
 
 
@@ -194,12 +216,13 @@ def run_workload(wl, data, *, threads: int = 0, norm_every: Optional[int] = None
     W = np.empty((R, K, d)); L = np.empty((R, K)); p = np.empty((R, K)); wbar = np.empty((R, d))
     reg = np.zeros(R); drift = np.zeros(R); used = C.c_int(0)
     if getattr(wl, "optimistic", False):
-        assert nnz == 0, "the optimistic update is defined here for dense streams"
         bad = lib().oco_oracle_run_many_optimistic(R, d, K, T, float(wl.D), _ptr(eta), float(wl.eps),
                                                    LOSS_ID[wl.loss], int(bool(wl.x_shared)),
-                                                   _ptr(x), _ptr(y), _ptr(u), _ptr(seg_start), S,
-                                                   int(threads), _ptr(W), _ptr(L), _ptr(p), _ptr(wbar),
-                                                   _ptr(reg), C.byref(used))
+                                                   _ptr(x), _ptr(col), _ptr(val), nnz,
+                                                   _ptr(y), _ptr(u), _ptr(seg_start), S,
+                                                   int(norm_every), int(threads),
+                                                   _ptr(W), _ptr(L), _ptr(p), _ptr(wbar),
+                                                   _ptr(reg), _ptr(drift), C.byref(used))
         if bad:
             raise ValueError("oco_oracle_run_many_optimistic: %d runs failed" % bad)
         return dict(W=W, L=L, p=p, wbar=wbar, regret=reg, max_drift=drift, threads=used.value)

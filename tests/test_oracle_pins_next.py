@@ -163,3 +163,96 @@ def test_optimistic_learners_are_independent_and_hedge_combines_them():
     np.testing.assert_allclose(r["tr_f"], f, rtol=0, atol=1e-13)
     assert r["regret"] == pytest.approx(float((f - r["tr_fu"]).sum()), abs=1e-11)
     np.testing.assert_allclose(r["wbar"], p[-1] @ r["W"], rtol=0, atol=1e-14)
+
+
+# ------------------------------------------ optimistic OGD on sparse rounds ----
+@pytest.mark.parametrize("norm_every", [0, 1, 2])
+def test_sparse_optimistic_hand_computed_trajectory(golden, norm_every):
+    g = golden("optimistic_sparse_squared_d3.txt")
+    d, K, T = int(g["d"]), int(g["K"]), int(g["T"])
+    r = O.run_optimistic(d, K, T, g["D"], [g["eta"]], g["eps"], g["loss"],
+                         col=g["col"].astype(np.int32), val=g["val"], y=g["y"], u=g["u"].reshape(1, d),
+                         seg_start=np.atleast_1d(g["seg_start"]).astype(np.int64), norm_every=norm_every,
+                         trace=True)
+    tol = 5e-7
+    assert abs(r["regret"] - g["regret"]) < tol
+    np.testing.assert_allclose(r["tr_f"], g["f"], atol=tol)
+    np.testing.assert_allclose(r["tr_fu"], g["fu"], atol=tol)
+    np.testing.assert_allclose(r["W"].ravel(), g["W"], atol=tol)
+    np.testing.assert_allclose(r["What"].ravel(), g["What"], atol=tol)
+    assert abs(r["delta"][0] - g["delta"]) < 5e-6
+
+
+def _sparse_instance(rng, d, T, nnz, S=2, noise=0.05):
+    col = np.stack([np.sort(rng.choice(d, size=nnz, replace=False)) for _ in range(T)]).astype(np.int32)
+    val = (rng.standard_normal((T, nnz)) / np.sqrt(nnz)).astype(np.float32)
+    x = np.zeros((T, d), np.float32)
+    x[np.arange(T)[:, None], col] = val
+    ws = rng.standard_normal((S, d)); ws = (0.6 * ws / np.linalg.norm(ws, axis=1, keepdims=True)).astype(np.float32)
+    seg_start = np.array([s * (T // S) for s in range(S)], np.int64)
+    seg = np.searchsorted(seg_start, np.arange(T), side="right") - 1
+    zt = np.einsum("td,td->t", x.astype(np.float64), ws[seg].astype(np.float64))
+    return col, val, x, ws, seg_start, zt
+
+
+@pytest.mark.parametrize("loss", ["squared", "logistic", "linear"])
+@pytest.mark.parametrize("norm_every", [0, 1, 7, 1000])
+def test_sparse_optimistic_equals_its_dense_expansion(loss, norm_every):
+    """The sparse form must give what the dense form of Eq. (3) gives on the same rounds written
+    out as dense rows -- steps small (never projected), moderate, and far larger than the ball
+    (both projections active every round); consecutive rounds share columns (d is small), so the
+    hint overlaps the current row in some coordinates and not in others."""
+    rng = np.random.default_rng(23 + norm_every)
+    d, T, nnz, K, D, eps = 12, 90, 3, 4, 0.9, 0.2
+    eta = [0.01, 0.3, 4.0, 300.0]
+    col, val, x, ws, seg_start, zt = _sparse_instance(rng, d, T, nnz)
+    if loss == "logistic":
+        y = np.where(zt >= 0, 1.0, -1.0).astype(np.float32)
+    elif loss == "squared":
+        y = (zt + 0.05 * rng.standard_normal(T)).astype(np.float32)
+    else:
+        y = None
+    assert any(len(set(col[t]) & set(col[t - 1])) not in (0, nnz) for t in range(1, T))
+    dense = O.run_optimistic(d, K, T, D, eta, eps, loss, x=x, y=y, u=ws, seg_start=seg_start, trace=True)
+    sp = O.run_optimistic(d, K, T, D, eta, eps, loss, col=col, val=val, y=y, u=ws, seg_start=seg_start,
+                          norm_every=norm_every, trace=True)
+    for k in ("W", "What", "L", "p", "wbar", "tr_z", "tr_p", "tr_loss", "tr_f", "tr_fu", "tr_zmix"):
+        np.testing.assert_allclose(sp[k], dense[k], rtol=0, atol=2e-12, err_msg=k)
+    np.testing.assert_allclose(sp["delta"], dense["delta"], rtol=1e-12)
+    assert sp["regret"] == pytest.approx(dense["regret"], abs=1e-11)
+    assert sp["max_drift"] < 1e-12
+    # the projections were exercised: the large steps sit on the boundary, the small one inside
+    assert np.linalg.norm(dense["What"][3]) == pytest.approx(D, rel=1e-12)
+    assert np.linalg.norm(dense["What"][0]) < 0.5 * D
+
+
+def test_many_run_wrappers_equal_single_runs_for_the_optimistic_update():
+    """run_workload(optimistic) -- the layout arithmetic of the many-run wrapper (run strides of x,
+    y and u, shared against per-run streams, dense against sparse rounds) -- against one
+    run_optimistic call per run on that run's own arrays."""
+    from paper_2603_12617_amd import workloads as WL
+    cases = [("c3", dict(T=230, R=4, d=9, K=3, seg_len=60)),                   # shared dense stream, 4 segments
+             ("c2", dict(T=150, R=3, d=7, K=4, seg_len=50)),                   # one dense stream per run
+             ("c4", dict(T=120, R=3, d=11, K=2, seg_len=40)),                  # logistic
+             ("c1", dict(T=100, R=3, d=5, x_shared=False)),                    # linear, per run, no labels
+             ("c5", dict(T=200, R=4, d=40, K=3, nnz=4, wstar_nnz=8, seg_len=70, eta=(0.05, 1.0, 30.0)))]
+    for name, over in cases:
+        wl = WL.make(name, optimistic=True, **over)
+        data = WL.generate(wl)
+        assert data["u"].shape[1] >= 1 and wl.R >= 3
+        for norm_every in ((0, 13) if wl.nnz else (0,)):
+            many = O.run_workload(wl, data, norm_every=norm_every, threads=2)
+            for r in range(wl.R):
+                kw = dict(y=None if data["y"] is None else data["y"][r], u=data["u"][r],
+                          seg_start=data["seg_start"])
+                if wl.nnz:
+                    kw.update(col=data["col"], val=data["val"], norm_every=norm_every)
+                else:
+                    kw.update(x=data["x"] if wl.x_shared else data["x"][r])
+                one = O.run_optimistic(wl.d, wl.K, wl.T, wl.D, wl.eta, wl.eps, wl.loss, **kw)
+                for k in ("W", "L", "p", "wbar"):
+                    assert np.array_equal(many[k][r], one[k]), (name, k, r)
+                assert many["regret"][r] == one["regret"]
+                assert many["max_drift"][r] == one["max_drift"]
+        # runs differ from each other (a wrapper that reused run 0's arrays would pass otherwise)
+        assert len({float(v) for v in many["regret"]}) == wl.R
