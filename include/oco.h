@@ -22,18 +22,27 @@
  *    kernel is launched.
  *  - "host" / "device" is stated for every pointer.  The library allocates no
  *    device memory: the caller provides one workspace (oco_workspace_bytes)
- *    and owns every input and output buffer.  Device pointers must be at
- *    least 16-byte aligned; the workspace 256-byte aligned.
+ *    and owns every input and output buffer.  Device pointers to float32 /
+ *    int32 data must be 4-byte aligned (OCO_EINVAL otherwise); round streams
+ *    whose rows are 16-byte aligned (pointer and run stride multiples of 16 bytes,
+ *    d a multiple of 4) take the kernels' vector-load path, others a slower
+ *    scalar one with the same results.  The comparator array must be 16-byte
+ *    aligned, float64 outputs 8-byte, the workspace 256-byte aligned.
+ *  - A HIP error in the middle of oco_run_rounds (after part of the call's work
+ *    was enqueued) leaves the device state undefined: the state is marked failed
+ *    and every later call on it returns OCO_EHIP until oco_reset.
  *  - All GPU work is ordered on the HIP stream given to oco_create: a call may run
  *    part of its work on a second stream of the library's own, which starts after
  *    the work already on the caller's stream and which the caller's stream waits
  *    for before the call's work counts as done.  Input buffers are borrowed until
  *    that work has finished.
- *  - Results are a pure function of (config, inputs, call boundaries).  Dense
- *    configurations: splitting [0, T) into oco_run_rounds calls in any way
- *    gives bit-identical state and regret.  Sparse configurations work in
- *    segments of 4096 rounds of the horizon: splits at multiples of 4096 are
- *    bit-identical, other splits regroup float32 sums and agree to rounding.
+ *  - Results are a pure function of (config, options, inputs, call boundaries).
+ *    Dense configurations on the register kernel: splitting [0, T) into
+ *    oco_run_rounds calls in any way gives bit-identical state and regret; on the
+ *    windowed kernel (OCO_OPT_DENSE_PATH) the rounds are worked in windows that
+ *    end at the multiples of 64 of the horizon: splits there are bit-identical,
+ *    other splits regroup float32 sums and agree to rounding.  Sparse
+ *    configurations work in segments of 4096 rounds of the horizon in the same way.
  *  - Arithmetic: iterates, inner products and the projection in float32;
  *    losses, cumulative losses, Hedge weights and regret in float64.
  */
@@ -68,11 +77,13 @@ typedef enum {
 
 #define OCO_MAX_SEGMENTS 4096   /* comparator segments per run */
 #define OCO_MAX_K 64            /* base learners per run */
-#define OCO_MAX_DENSE_D 4096    /* dense rounds keep a learner's iterate in one wavefront's registers */
+#define OCO_MAX_DENSE_D 65536   /* dense rounds: per-run streams need d <= 4096 (the iterate lives in one
+                                   wavefront's registers); a shared stream may go up to this (iterates in
+                                   registers up to 4096, beyond that streamed from HBM once per 64 rounds) */
 #define OCO_MAX_NNZ 64          /* entries per sparse round */
 
 typedef struct {
-    int64_t d;            /* dimension of w; dense rounds need d <= OCO_MAX_DENSE_D   */
+    int64_t d;            /* dimension of w; dense rounds: see OCO_MAX_DENSE_D        */
     int64_t K;            /* base learners per run (the paper's N), 1..OCO_MAX_K      */
     int64_t T;            /* horizon: total rounds                                    */
     int64_t R;            /* independent runs                                         */
@@ -127,6 +138,29 @@ size_t oco_workspace_bytes(const oco_config *cfg);
 int oco_create(const oco_config *cfg, void *dev_ws, size_t ws_bytes, void *hip_stream,
                oco_state **out);
 
+/* Tuning choices of a state: which of several equivalent kernels or launch shapes a call uses.
+ * value -1 (the default of every key) leaves the choice to the library.  Results agree with the
+ * reference to the stated tolerances under every choice; choices that change how float32 sums
+ * are grouped are marked (~).  OCO_EINVAL for an unknown key or a value the key does not take. */
+typedef enum {
+    OCO_OPT_META_BESIDE = 0,     /* 0: meta kernel after the round kernels, on the call's stream;
+                                    1: beside them on the library's second stream where the launcher allows */
+    OCO_OPT_DENSE_PATH = 1,      /* (~) 1: one wavefront per learner, iterate in registers;
+                                    2: windows of 64 rounds as contractions on the matrix cores (shared stream) */
+    OCO_OPT_DENSE_WPB = 2,       /* wavefronts per workgroup of the register kernel */
+    OCO_OPT_COMPARATOR_GEMM = 3, /* (~) comparator predictions of a shared stream: 0 in the round kernel, 1 as a contraction */
+    OCO_OPT_DENSE_HALF = 4,      /* (~) 1: two learners per wavefront (shared stream, d <= 1024); 0: never */
+    OCO_OPT_DENSE_PIECES = 5,    /* launches a dense call is cut into */
+    OCO_OPT_SPARSE_LPW = 6,      /* (~) learners per workgroup of the sparse kernel: 4, 8, 16, 32, 64 */
+    OCO_OPT_SPARSE_PIPE = 7,     /* (~) 0: sparse windows one after the other, no pipeline */
+    OCO_OPT_VERBOSE = 8,         /* 1: launch plans on stderr */
+    OCO_OPT_WINDOW_RESIDENT = 9, /* windowed dense path: 0 streams the iterates from HBM every window even
+                                    where they would fit in registers */
+    OCO_OPT_WINDOW_WAVES = 10,   /* windowed dense path: wavefronts per workgroup (4 or 8) */
+    OCO_OPT_COUNT = 11
+} oco_option;
+int oco_set_option(oco_state *st, int key, int64_t value);
+
 /* Comparator sequence of Eq. (2): u_dev device [R][S][d] float32 (borrowed until the last
  * oco_run_rounds has finished), segment s of every run is active for rounds
  * seg_start[s] <= t < seg_start[s+1] (last segment to T).  seg_start: host [S], copied,
@@ -164,7 +198,8 @@ int oco_accel_bounds(oco_state *st, int64_t k, double alpha, double *out_dev);
  * Synchronises the stream. */
 int oco_cum_losses(oco_state *st, double *out_host);
 
-/* Back to round 0 (w = 0, L = 0, regret = 0); keeps the comparator.  Asynchronous. */
+/* Back to round 0 (w = 0, L = 0, regret = 0); keeps the comparator and the options, clears a
+ * failed mark.  Asynchronous. */
 int oco_reset(oco_state *st);
 
 /* Kernel timing for benchmarks.  After oco_set_timing(st, 1) every oco_run_rounds call records

@@ -18,7 +18,11 @@ LIB_PATH = os.environ.get("OCO_LIB") or os.path.join(HERE, "liboco.so")
 OCO_OK, OCO_EINVAL, OCO_ESEQ, OCO_ERANGE, OCO_ENOMEM, OCO_EHIP, OCO_ENOCOMP, OCO_EUNSUPPORTED = (
     0, -1, -2, -3, -4, -5, -6, -7)
 LOSS_ID = {"linear": 0, "squared": 1, "logistic": 2}
+# oco_option keys (include/oco.h)
+OPT = dict(meta_beside=0, dense_path=1, dense_wpb=2, comparator_gemm=3, dense_half=4, dense_pieces=5,
+           sparse_lpw=6, sparse_pipe=7, verbose=8, window_resident=9, window_waves=10)
 EXPORTS = ("oco_step_grid", "oco_paper_num_learners", "oco_workspace_bytes", "oco_create",
+           "oco_set_option",
            "oco_set_comparator", "oco_run_rounds", "oco_regret", "oco_get_state",
            "oco_cum_losses", "oco_accel_bounds", "oco_reset", "oco_set_timing", "oco_last_timing", "oco_rounds_done", "oco_destroy", "oco_strerror",
            "sd_verify", "sd_acceptance", "sd_strerror")
@@ -66,6 +70,8 @@ def lib() -> C.CDLL:
         L.oco_workspace_bytes.argtypes = [C.POINTER(OcoConfig)]
         L.oco_create.restype = C.c_int
         L.oco_create.argtypes = [C.POINTER(OcoConfig), vp, C.c_size_t, vp, C.POINTER(vp)]
+        L.oco_set_option.restype = C.c_int
+        L.oco_set_option.argtypes = [vp, C.c_int, i64]
         L.oco_set_comparator.restype = C.c_int
         L.oco_set_comparator.argtypes = [vp, vp, vp, i64]
         L.oco_run_rounds.restype = C.c_int
@@ -151,6 +157,12 @@ def oco_create(cfg: OcoConfig, ws, stream=None) -> int:
     return h.value
 
 
+def oco_set_option(h: int, key, value: int) -> None:
+    """key: an oco_option number or its name in OPT."""
+    k = OPT[key] if isinstance(key, str) else int(key)
+    _check(lib().oco_set_option(h, k, int(value)), "oco_set_option")
+
+
 def oco_set_comparator(h: int, u, seg_start) -> None:
     seg = np.ascontiguousarray(seg_start, dtype=np.int64)
     _check(lib().oco_set_comparator(h, _dptr(u), seg.ctypes.data, seg.size), "oco_set_comparator")
@@ -220,7 +232,7 @@ class Simulation:
     arithmetic happens inside oco_run_rounds / oco_get_state; this class only uploads the
     arrays, slices them by pointer arithmetic and downloads results."""
 
-    def __init__(self, wl, data, n_max: int = 0, device: str = "cuda:0", stream=None):
+    def __init__(self, wl, data, n_max: int = 0, device: str = "cuda:0", stream=None, options=None):
         import torch
         self.torch = torch
         self.wl = wl
@@ -237,6 +249,8 @@ class Simulation:
             raise OcoError(OCO_EINVAL, "oco_workspace_bytes")
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
         self.h = oco_create(self.cfg, self.ws, stream)
+        for k, v in (options or {}).items():
+            oco_set_option(self.h, k, v)
         oco_set_comparator(self.h, self.u, self.seg_start)
 
     def run(self, t0: int, n: int) -> None:

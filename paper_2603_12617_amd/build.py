@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liboco.so")
 SOURCES = ["oco_api.hip", "dense_rounds.hip", "sparse_rounds.hip", "meta.hip", "specdec.hip",
-           "comparator_gemm.hip"]
+           "comparator_gemm.hip", "dense_window.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -46,7 +46,7 @@ def build(verbose: bool = False, extra_flags=(), lib: str = LIB, tag: str = "") 
             raise RuntimeError("hipcc failed on " + src)
         return obj
 
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(one, SOURCES))
     cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)

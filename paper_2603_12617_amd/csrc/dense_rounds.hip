@@ -32,6 +32,7 @@
 // The kernel writes z_t^i for every round to Z; losses, Hedge weights and
 // regret are computed from Z by the meta kernel.
 #include "oco_internal.h"
+#include "../../include/oco.h"
 
 #include <algorithm>
 #include <cstdio>
@@ -110,6 +111,17 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
+// Workgroup barrier that publishes the tiles copied global -> LDS.  Those copies complete
+// asynchronously and are counted by vmcnt of the wavefront that issued them; a plain barrier
+// does not wait for them (a workgroup-scope fence leaves vmcnt alone), and a wavefront that never
+// reads the ring (padding wavefronts) would otherwise meet the barrier with its share of a tile
+// still in flight.  Every wavefront therefore drains its own copies before it arrives.
+__device__ __forceinline__ void tile_sync()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
 
 template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
 {
@@ -203,11 +215,11 @@ dense_rounds_kernel(const DenseArgs a)
 
     // padding coordinates (j >= d) of the ring are never written again: zero them once
     for (int e = tid; e < kRing * TILE / 4; e += nthreads) smem4[e] = make_float4(0.f, 0.f, 0.f, 0.f);
-    __syncthreads();
+    tile_sync();
     const int ntiles = (n + RT - 1) / RT;
     issue_tile(0);
     if (ntiles > 1) issue_tile(1);
-    __syncthreads();
+    tile_sync();
 
     auto xrow = [&](int t) { return reinterpret_cast<const V *>(ring + (t % RING_ROUNDS) * DP); };
     const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
@@ -217,7 +229,7 @@ dense_rounds_kernel(const DenseArgs a)
     if (!active) {
         for (int k = 0; k < ntiles; ++k) {
             if (k + 2 < ntiles) issue_tile(k + 2);
-            __syncthreads();
+            tile_sync();
         }
         return;
     }
@@ -273,7 +285,7 @@ dense_rounds_kernel(const DenseArgs a)
                     if (tb + lane <= t) zrow[(int64_t)(tb + lane) * a.zl.zs_t] = zreg;
                 }
             }
-            __syncthreads();
+            tile_sync();
         }
         return;
     }
@@ -491,7 +503,7 @@ dense_rounds_kernel(const DenseArgs a)
                 if (rr + 1 < rmax) round(t + 1, xb, xa);
             }
         }
-        __syncthreads();   // tile k+1 (and k+2) have landed; tile k may be overwritten
+        tile_sync();   // every wavefront has drained its copies: tile k+1 is complete; tile k may be overwritten
     }
 
     {
@@ -601,18 +613,18 @@ dense_rounds_half_kernel(const DenseArgs a)
     };
 
     for (int e = tid; e < kRing * TILE / 4; e += nthreads) smem4[e] = make_float4(0.f, 0.f, 0.f, 0.f);
-    __syncthreads();
+    tile_sync();
     const int ntiles = (n + RT - 1) / RT;
     issue_tile(0);
     if (ntiles > 1) issue_tile(1);
-    __syncthreads();
+    tile_sync();
 
     auto xrow = [&](int t) { return reinterpret_cast<const V *>(ring + (t % RING_ROUNDS) * DP); };
 
     if (!active) {
         for (int k = 0; k < ntiles; ++k) {
             if (k + 2 < ntiles) issue_tile(k + 2);
-            __syncthreads();
+            tile_sync();
         }
         return;
     }
@@ -762,7 +774,7 @@ dense_rounds_half_kernel(const DenseArgs a)
             round(t, xa, xb);
             if (rr + 1 < rmax) round(t + 1, xb, xa);
         }
-        __syncthreads();
+        tile_sync();
     }
 
     if (store) {
@@ -888,13 +900,13 @@ hipError_t plan_npl(const DenseArgs &a, int loss, DensePlan *plan)
                             (w >= 8 && cost <= best_cost * (1.0 + 1e-9));
         if (better) { best = w; best_cost = cost; }
     }
-    if (const char *ov = getenv("OCO_DENSE_WPB")) {      // tuning override: wavefronts per workgroup
-        const int w = atoi(ov);
+    {                                                     // tuning choice: wavefronts per workgroup
+        const int w = (int)a.tune->get(OCO_OPT_DENSE_WPB);
         if (w >= 1 && w <= C::MAXW) best = w;
     }
     if (best == 0) return hipErrorInvalidConfiguration;
     plan->cost = best_cost;
-    if (getenv("OCO_DENSE_VERBOSE"))
+    if (a.tune->get(OCO_OPT_VERBOSE) == 1)
         fprintf(stderr, "dense plan: NPL %d per_run %d -> wpb %d cost %.3f\n", NPL, per_run, best, best_cost);
     int c = 1;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, reinterpret_cast<const void *>(kern), best * kWave,
@@ -950,8 +962,8 @@ hipError_t plan_half(const DenseArgs &a, int loss, DensePlan *plan)
         const bool better = best == 0 || cost < best_cost * (1.0 - 1e-9) || (w >= 8 && cost <= best_cost * (1.0 + 1e-9));
         if (better) { best = w; best_cost = cost; best_c = c; }
     }
-    if (const char *ov = getenv("OCO_DENSE_WPB")) {      // tuning override
-        const int w = atoi(ov);
+    {                                                     // tuning choice
+        const int w = (int)a.tune->get(OCO_OPT_DENSE_WPB);
         if (w >= 1 && w <= C::MAXW) best = w;
     }
     if (best == 0) return hipErrorInvalidConfiguration;
@@ -961,7 +973,7 @@ hipError_t plan_half(const DenseArgs &a, int loss, DensePlan *plan)
     plan->nwg = (nwaves + best - 1) / best;
     plan->batches = ((plan->nwg + ncu - 1) / ncu + best_c - 1) / best_c;
     plan->cost = best_cost;
-    if (getenv("OCO_DENSE_VERBOSE"))
+    if (a.tune->get(OCO_OPT_VERBOSE) == 1)
         fprintf(stderr, "dense plan (two learners per wavefront): NPL %d -> wpb %d cost %.3f\n", NPL, best, best_cost);
     return hipSuccess;
 }
@@ -980,7 +992,7 @@ hipError_t launch_piece(const DensePlan &p, const DenseArgs &a, hipStream_t s)
 
 }  // namespace
 
-bool dense_supported(int64_t d) { return d >= 1 && d <= 64 * kWave; }
+bool dense_supported(int64_t d, int x_shared) { return d >= 1 && d <= (x_shared ? OCO_MAX_DENSE_D : 64 * kWave); }
 
 // One piece of a call: the squared norms of its rows, its round kernel, and the row kept for the
 // next piece's hint terms.
@@ -1008,10 +1020,10 @@ static hipError_t launch_dense_piece(const DensePlan &plan, const DenseArgs &a, 
     return hipGetLastError();
 }
 
-hipError_t launch_dense_rounds(const DenseArgs &a0, int loss, hipStream_t s, const PieceHook *hook)
+// Works out how the round kernel of this configuration is launched (kernel, workgroup size,
+// who takes the comparators' predictions).
+static hipError_t make_dense_plan(DenseArgs &a, int loss, DensePlan *out)
 {
-    if (a0.n <= 0) return hipSuccess;
-    DenseArgs a = a0;
     const int npl = (a.d + kWave - 1) / kWave;
     auto make_plan = [&](DensePlan *plan) {
         if (npl <= 1) return plan_npl<1>(a, loss, plan);
@@ -1032,8 +1044,7 @@ hipError_t launch_dense_rounds(const DenseArgs &a0, int loss, hipStream_t s, con
     hipError_t e = make_plan(&plan);
     if (e != hipSuccess) return e;
     if (a.x_shared) {
-        int mode = -1;                                          // tuning override: 0 never, 1 always
-        if (const char *ov = getenv("OCO_COMPARATOR_GEMM")) mode = atoi(ov);
+        const int mode = (int)a.tune->get(OCO_OPT_COMPARATOR_GEMM);     // 0 never, 1 always
         DensePlan alt;
         a.per_run = a.K;
         e = make_plan(&alt);
@@ -1041,14 +1052,13 @@ hipError_t launch_dense_rounds(const DenseArgs &a0, int loss, hipStream_t s, con
         if (mode == 1 || (mode != 0 && alt.cost < plan.cost * 0.98)) plan = alt;
         else a.per_run = a.K + 1;
     }
-    if (e != hipSuccess) return e;
 
     // Two learners per wavefront where a round is mostly its scalar section (d <= 1024) and the
     // grid is large enough to be bound by instruction issue rather than by the latency of a round.
     {
         bool half = a.x_shared && a.d > 96 && a.d <= 1024 && (int64_t)a.R * a.K >= kHalfMinTasks;
-        if (const char *ov = getenv("OCO_DENSE_HALF"))        // tuning override: 0 never, 1 wherever it can run
-            half = atoi(ov) != 0 && a.x_shared && a.d <= 1024;
+        const int hv = (int)a.tune->get(OCO_OPT_DENSE_HALF);          // 0 never, 1 wherever it can run
+        if (hv >= 0) half = hv != 0 && a.x_shared && a.d <= 1024;
         if (half) {
             const int nplh = (a.d + 31) / 32;
             a.per_run = a.K;                                // comparators: contraction kernel
@@ -1059,6 +1069,32 @@ hipError_t launch_dense_rounds(const DenseArgs &a0, int loss, hipStream_t s, con
             if (e != hipSuccess) return e;
         }
     }
+    *out = plan;
+    return hipSuccess;
+}
+
+hipError_t launch_dense_rounds(const DenseArgs &a0, int loss, hipStream_t s, const PieceHook *hook)
+{
+    if (a0.n <= 0) return hipSuccess;
+    if (dense_window_wanted(a0)) return launch_dense_window(a0, loss, s, hook);
+    if (a0.d > 64 * kWave) return hipErrorInvalidValue;
+    DenseArgs a = a0;
+    // the plan depends on the configuration and the tuning choices only: made once per state
+    DensePlan plan;
+    if (a.plan->valid) {
+        plan.kern = reinterpret_cast<void (*)(const DenseArgs)>(const_cast<void *>(a.plan->kern));
+        plan.smem = a.plan->smem; plan.wpb = a.plan->wpb; plan.nwg = a.plan->nwg;
+        plan.batches = a.plan->batches;
+        a.per_run = a.plan->per_run;
+    } else {
+        hipError_t e = make_dense_plan(a, loss, &plan);
+        if (e != hipSuccess) return e;
+        a.plan->kern = reinterpret_cast<const void *>(plan.kern);
+        a.plan->smem = plan.smem; a.plan->wpb = plan.wpb; a.plan->nwg = plan.nwg;
+        a.plan->batches = plan.batches; a.plan->per_run = a.per_run;
+        a.plan->valid = true;
+    }
+    hipError_t e = hipSuccess;
 
     // Rounds give the same bits under any split of a call, so a call may go as several launches:
     //  - A grid that takes several passes over the chip has workgroups at unrelated positions of a
@@ -1075,7 +1111,7 @@ hipError_t launch_dense_rounds(const DenseArgs &a0, int loss, hipStream_t s, con
         pieces = kBesidePieces;
         beside = true;
     }
-    if (const char *ov = getenv("OCO_DENSE_PIECES")) pieces = atoi(ov);      // tuning override
+    if (a.tune->get(OCO_OPT_DENSE_PIECES) >= 1) pieces = a.tune->get(OCO_OPT_DENSE_PIECES);   // tuning choice
     pieces = std::max<int64_t>(1, std::min<int64_t>(pieces, a.n / kPieceMinRounds));
     const int64_t step = (a.n / pieces + 63) / 64 * 64;
     for (int64_t off = 0; off < a.n; off += step) {

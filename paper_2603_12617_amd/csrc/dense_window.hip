@@ -1,0 +1,597 @@
+// Dense rounds of the base learners on a shared round stream, worked in windows of 64 rounds as
+// contractions on the matrix cores (Sec. 3.1 update inside the ensemble of Sec. 3.3).
+//
+// The update of a base learner, w_{t+1} = Proj[w_t - eta c_t x_t] with c_t = phi'(<w_t, x_t>; y_t),
+// keeps the iterate in the span of the window's start w_s and the window's round rows, whatever
+// the projections do (a projection onto the ball only rescales):
+//     w_t = A_t w_s - sum_{s <= r < t} a_r rho_{r,t} x_r,   a_r = eta c_r,
+//     rho_{r,t} = f_r f_{r+1} ... f_{t-1},   A_t = f_s ... f_{t-1},   f_r = min(1, D / ||w_r - a_r x_r||).
+// So for a window of B = 64 rounds and a tile of M = 16 learners (any 16 learners: the stream is
+// shared), with W the M x d matrix of iterates and X_w the B x d block of round rows:
+//   (1) Q0 = W X_w^T                                  (M x B contraction over d, matrix cores)
+//   (2) the 64 dependent rounds on scalars only: with G = X_w X_w^T (once per window for all
+//       learners, pre-pass), p_{t2} = <w_t, x_{t2}> for the rounds t2 >= t still to come obeys
+//           p_{t2} <- f_t (p_{t2} - a_t G[t][t2]),
+//       the prediction of round t is p_t itself, and the squared norm follows from
+//           ||w_t - a_t x_t||^2 = ||w_t||^2 - 2 a_t <w_t, x_t> + a_t^2 G[t][t]
+//       (float64 scalars; one wavefront, a quad of lanes per learner, each lane of the quad
+//       carrying every fourth pending round);
+//   (3) W <- F W - Bm X_w,  F = A_end,  Bm[r] = a_r rho_{r,end}   (M x d contraction over B).
+// (3) of window w and (1) of window w + 1 are taken block by block in one sweep over the
+// coordinates, so the iterates are touched once per window.  ||w||^2 is re-measured from the
+// new iterates in that sweep (no drift across windows).
+//
+// Where the tile's iterates fit in the registers of a workgroup (d <= 4096: eight wavefronts,
+// each with every eighth block of 16 coordinates, in the layout the matrix instruction writes:
+// a lane holds 4 coordinates of one learner) they stay there for the whole call and the only
+// memory traffic is the round stream (from L2: every tile reads the same rows).  Otherwise the
+// same sweep loads each 16 x 16 block from HBM, updates it, takes its share of the next
+// window's inner products and writes it back: 8 bytes per coordinate, learner and window, all
+// in full 64-byte segments.
+//
+// v_mfma_f32_16x16x4_f32 computes D = A B + C with A 16x4, B 4x16: lane l supplies
+// A[l % 16][l / 16] and B[l / 16][l % 16] and holds D[4 (l / 16) + r][l % 16] in register r.
+// A block of iterates is kept as the transposed 16 coordinates x 16 learners D tile, so that
+// register r of it is at once the B operand of (1) for the depth indices k <-> coordinate 4 k + r
+// (the order of the terms of an inner product is free; the round rows are loaded to match).
+//
+// Windows end at the multiples of 64 of the horizon; a call that starts or ends elsewhere has
+// shorter first / last windows.
+#include "oco_internal.h"
+#include "../../include/oco.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <type_traits>
+#include <utility>
+
+namespace oco {
+namespace {
+
+constexpr int kB = 64;            // rounds per window
+constexpr int kM = 16;            // learners per tile
+constexpr int kNW = 8;            // wavefronts per workgroup
+constexpr int kGStride = 18;      // doubles per (round, quad lane) row of the masked Gram table (16 + padding)
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+struct WinPlanD {
+    int64_t t0;      // absolute round of the call's first round
+    int n;           // rounds in the call
+    __host__ __device__ int first_len() const { const int f = (int)(kB - t0 % kB); return f < n ? f : n; }
+    __host__ __device__ int count() const { const int f = first_len(); return 1 + (n - f + kB - 1) / kB; }
+    __host__ __device__ int start(int w) const { return w == 0 ? 0 : first_len() + (w - 1) * kB; }
+    __host__ __device__ int len(int w) const { const int s = start(w); const int l = w == 0 ? first_len() : kB; return l < n - s ? l : n - s; }
+};
+
+template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
+{
+    if (LOSS == 0) return 1.0f;
+    if (LOSS == 1) return 2.0f * (z - y);
+    return -y * __builtin_amdgcn_rcpf(1.0f + __expf(y * z));
+}
+
+// ---- pre-pass: G = X_w X_w^T of every window of the call --------------------------------------
+// One workgroup of four wavefronts per window; wavefront v computes rows 16 v .. 16 v + 15 of G
+// (four 16 x 16 blocks), depth in steps of 16 coordinates.  Rows past the window's length and
+// coordinates past d enter as zeros.  Fixed summation order.
+__global__ void __launch_bounds__(256) dense_gram_kernel(const float *x, int d, WinPlanD plan, float *gram)
+{
+    const int w = blockIdx.x;
+    const int ws = plan.start(w), wl = plan.len(w);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lr = lane & 15, lk = lane >> 4;
+    f4 acc[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[b] = f4{0.f, 0.f, 0.f, 0.f};
+    const int rowa = wave * 16 + lr;
+    const float *xa = x + (int64_t)(ws + (rowa < wl ? rowa : 0)) * d;
+    const float *xb[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int rowb = b * 16 + lr;
+        xb[b] = x + (int64_t)(ws + (rowb < wl ? rowb : 0)) * d;
+    }
+    for (int c0 = 0; c0 < d; c0 += 16) {
+        const int c = c0 + 4 * lk;
+        const bool in = c < d;
+        f4 av = f4{0.f, 0.f, 0.f, 0.f}, bv[4];
+        if (in && rowa < wl) av = *reinterpret_cast<const f4 *>(xa + c);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            bv[b] = f4{0.f, 0.f, 0.f, 0.f};
+            if (in && b * 16 + lr < wl) bv[b] = *reinterpret_cast<const f4 *>(xb[b] + c);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[r], bv[b][r], acc[b], 0, 0, 0);
+    }
+    float *g = gram + (int64_t)w * kB * kB;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) g[(wave * 16 + 4 * lk + r) * kB + b * 16 + lr] = acc[b][r];
+}
+
+// LDS of the window kernel (dynamic), in bytes from the base
+struct Lds {
+    static constexpr int gd = 0;                                   // double [64][4][kGStride]: G[t][t2], zero for t2 <= t
+    static constexpr int x2 = gd + kB * 4 * kGStride * 8;          // double [64]: G[t][t]
+    static constexpr int q0 = x2 + kB * 8;                         // double [64][16]: <w_s, x_t>
+    static constexpr int fl = q0 + kB * kM * 8;                    // double [64][16]: f_t
+    static constexpr int part = fl + kB * kM * 8;                  // float [kNW][64][16]: per-wavefront shares of Q0
+    static constexpr int yb = part + kNW * kB * kM * 4;            // float [64][16]: labels
+    static constexpr int zb = yb + kB * kM * 4;                    // float [64][16]: predictions
+    static constexpr int st = zb + kB * kM * 4;                    // float [64][16]: a_t
+    static constexpr int bm = st + kB * kM * 4;                    // float [64][16]: -Bm
+    static constexpr int fv = bm + kB * kM * 4;                    // float [16]: F
+    static constexpr int n2 = fv + kM * 4;                         // float [kNW][4][16]: shares of ||w||^2
+    static constexpr int total = n2 + kNW * 4 * kM * 4;
+};
+
+// every lane of a quad gets the value of the quad's lane SEL
+template <int SEL> __device__ __forceinline__ double quad_bcast(double v)
+{
+    constexpr int ctrl = SEL * 0x55;                             // quad_perm [SEL, SEL, SEL, SEL]
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), ctrl, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), ctrl, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a
+// compile-time constant in every iteration (register arrays indexed by it stay in registers)
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// The 64 dependent rounds of one window for the tile's 16 learners: wavefront 0, lane = 4 learner
+// + quad lane s; quad lane s carries the pending predictions of the rounds t2 = 4 j + s.
+// In: q0 (times the scale `sig` of the stored iterates), labels, G, n2 = ||w||^2.  Out: predictions,
+// -Bm and F in LDS; n2 is left to the sweep (it re-measures it).
+// Straight-line code: a window shorter than 64 rounds (first / last window of a call) runs its
+// missing rounds as rounds without a step (a = 0, so f = 1 and no pending prediction moves; their
+// rows of G are zero).
+template <int LOSS>
+__device__ __forceinline__ void chain_window(char *lds, int lane, int wl, float eta, double D, double sig, double n2)
+{
+    const int lc = lane >> 2, s = lane & 3;
+    const double *gd = reinterpret_cast<const double *>(lds + Lds::gd) + s * kGStride;
+    const double *x2d = reinterpret_cast<const double *>(lds + Lds::x2);
+    const double *q0d = reinterpret_cast<const double *>(lds + Lds::q0) + s * kM + lc;
+    double *fl = reinterpret_cast<double *>(lds + Lds::fl) + lc;
+    const float *yb = reinterpret_cast<const float *>(lds + Lds::yb) + lc;
+    float *zb = reinterpret_cast<float *>(lds + Lds::zb) + lc;
+    float *stl = reinterpret_cast<float *>(lds + Lds::st) + lc;
+    const double D2 = D * D;
+    const float eta2 = 2.f * eta;
+
+    double p[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) p[j] = sig * q0d[4 * j * kM];
+
+    static_for<kB>([&](auto tc) __attribute__((always_inline)) {
+        constexpr int t = decltype(tc)::value;
+        constexpr int j0 = t >> 2;
+        // this round's row of G first: it does not depend on the scalars below
+        double gr[16 - j0];
+#pragma unroll
+        for (int j = j0; j < 16; ++j) gr[j - j0] = gd[t * 4 * kGStride + j];
+        const float yt = yb[t * kM];
+        const double x2t = x2d[t];
+        const double zt = quad_bcast<(t & 3)>(p[j0]);               // <w_t, x_t>
+        const float z32 = (float)zt;
+        // a_t = eta c_t; for the squared loss eta * 2 (z - y) = (2 eta) (z - y) exactly
+        float a32 = LOSS == 1 ? eta2 * (z32 - yt) : eta * slope<LOSS>(z32, yt);
+        a32 = t < wl ? a32 : 0.f;
+        const double at = (double)a32;
+        // ||w_t - a_t x_t||^2 and the projection factor
+        double m2 = fma(at, fma(at, x2t, -2.0 * zt), n2);
+        m2 = m2 > 0.0 ? m2 : 0.0;
+        const bool pj = m2 > D2;
+        const double f = pj ? D * __builtin_amdgcn_rsq(m2) : 1.0;
+        n2 = pj ? D2 : m2;
+        zb[t * kM] = z32;                                            // (the quad's four lanes write the same value)
+        stl[t * kM] = a32;
+        fl[t * kM] = f;
+#pragma unroll
+        for (int j = j0; j < 16; ++j) p[j] = f * fma(-at, gr[j - j0], p[j]);
+        __builtin_amdgcn_sched_barrier(0);                           // rounds are not interleaved: registers
+    });
+
+    // Bm[r] = a_r f_r f_{r+1} ... f_63 and F = sig f_0 ... f_63: quad lane s takes the rounds
+    // 16 s .. 16 s + 15 backwards, then the quad's products are combined
+    float *bm = reinterpret_cast<float *>(lds + Lds::bm) + lc;
+    float *fv = reinterpret_cast<float *>(lds + Lds::fv);
+    double loc[16];
+    double acc = 1.0;
+#pragma unroll
+    for (int k = 15; k >= 0; --k) {
+        acc *= fl[(16 * s + k) * kM];
+        loc[k] = acc;
+    }
+    const double P0 = quad_bcast<0>(acc), P1 = quad_bcast<1>(acc), P2 = quad_bcast<2>(acc), P3 = quad_bcast<3>(acc);
+    const double tail = s == 3 ? 1.0 : s == 2 ? P3 : s == 1 ? P2 * P3 : P1 * (P2 * P3);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const int r = 16 * s + k;
+        bm[r * kM] = -(float)((double)stl[r * kM] * (loc[k] * tail));
+    }
+    if (s == 0) fv[lc] = (float)(sig * (P0 * (P1 * (P2 * P3))));
+}
+
+// What a thread is in the sweep, derived from its index.  The window loop re-derives it every
+// iteration from an index the compiler cannot see through, so that none of it (nor the many
+// addresses that follow from it) is kept alive across the dependent rounds.
+struct Geo {
+    int tid, lane, wave, lr, lk;
+    int qofs, uofs;            // per-lane offsets of the round-row loads (floats)
+    bool q_ok;                 // this lane's learner exists
+    float *vrow;               // its row of the iterates, at this lane's 4 coordinates of a block
+};
+__device__ __forceinline__ Geo make_geo(int tid, const DenseArgs &a)
+{
+    Geo g;
+    g.tid = tid;
+    g.lane = tid & 63;
+    g.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    g.lr = g.lane & 15;
+    g.lk = g.lane >> 4;
+    g.qofs = g.lr * a.d + 4 * g.lk;
+    g.uofs = g.lk * a.d + g.lr;
+    const int q = (int)blockIdx.x * kM + g.lr;
+    g.q_ok = q < a.R * a.K;
+    g.vrow = a.V + (int64_t)(g.q_ok ? q : 0) * a.d + 4 * g.lk;
+    return g;
+}
+
+// RES: the tile's iterates stay in registers for the whole call (d <= 16 * kNW * NB); otherwise
+// every block is loaded and stored in the sweep.
+template <int LOSS, int NB, bool RES>
+__global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArgs a, const float *gram, WinPlanD plan)
+{
+    constexpr bool BMR = !(RES && NB > 8);     // -Bm in registers for the whole sweep, or re-read from LDS per block
+    extern __shared__ __align__(16) char lds[];
+    const int d = a.d, K = a.K;
+    const int nq = a.R * K;
+    const int nblk = (d + 15) / 16;                             // blocks of 16 coordinates
+    const int nwin = plan.count();
+    const float *x = a.x;
+
+    // the tile's iterates: block (wave + 8 b) of 16 coordinates x 16 learners, transposed
+    auto ld_block = [&](const Geo &g, int blk) __attribute__((always_inline)) {
+        f4 v = f4{0.f, 0.f, 0.f, 0.f};
+        if (g.q_ok && blk * 16 + 4 * g.lk < d) v = *reinterpret_cast<const f4 *>(g.vrow + blk * 16);
+        return v;
+    };
+    auto st_block = [&](const Geo &g, int blk, const f4 &v) __attribute__((always_inline)) {
+        if (g.q_ok && blk * 16 + 4 * g.lk < d) *reinterpret_cast<f4 *>(g.vrow + blk * 16) = v;
+    };
+    // round rows as the matrix instruction wants them
+    //   for (1): lane (round l % 16 of a group of 16, coordinates 4 (l / 16) .. + 3 of the block)
+    //   for (3): lane (coordinate l % 16 of the block, round l / 16 of a group of 4)
+    // A full window and a block inside d need no guards: one address per wavefront (scalar) plus a
+    // fixed per-lane offset.  Ragged windows / the last block of a d that is no multiple of 16 take
+    // the guarded loads (rows past the window and coordinates past d enter as zeros).
+    auto ldq = [&](const Geo &g, int ws, int wl, int blk, f4 (&o)[4]) __attribute__((always_inline)) {
+        if (wl == kB && blk * 16 + 16 <= d) {
+            const float *base = x + (int64_t)ws * d + blk * 16;
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) o[rb] = *reinterpret_cast<const f4 *>(base + (int64_t)(rb * 16) * d + g.qofs);
+        } else {
+            const int c = blk * 16 + 4 * g.lk;
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                const int t = rb * 16 + g.lr;
+                o[rb] = f4{0.f, 0.f, 0.f, 0.f};
+                if (c < d && t < wl) o[rb] = *reinterpret_cast<const f4 *>(x + (int64_t)(ws + t) * d + c);
+            }
+        }
+    };
+    auto ldu = [&](const Geo &g, int ws, int wl, int blk, float (&o)[16]) __attribute__((always_inline)) {
+        if (wl == kB && blk * 16 + 16 <= d) {
+            const float *base = x + (int64_t)ws * d + blk * 16;
+#pragma unroll
+            for (int rs = 0; rs < 16; ++rs) o[rs] = base[(int64_t)(rs * 4) * d + g.uofs];
+        } else {
+            const int c = blk * 16 + g.lr;
+#pragma unroll
+            for (int rs = 0; rs < 16; ++rs) {
+                const int t = rs * 4 + g.lk;
+                o[rs] = (c < d && t < wl) ? x[(int64_t)(ws + t) * d + c] : 0.f;
+            }
+        }
+    };
+    // LDS inputs of window w's dependent rounds: labels, masked Gram table, its diagonal
+    auto stage_chain_inputs = [&](const Geo &g, int w) __attribute__((always_inline)) {
+        const int ws = plan.start(w), wl = plan.len(w);
+        float *yb = reinterpret_cast<float *>(lds + Lds::yb);
+        double *gd = reinterpret_cast<double *>(lds + Lds::gd);
+        double *x2d = reinterpret_cast<double *>(lds + Lds::x2);
+        {
+            const int l16 = g.tid >> 5, t = g.tid & 31;         // 16 learners x 32 lanes, two rounds each
+            const int q = (int)blockIdx.x * kM + l16;
+            const float *yrow = (a.y && q < nq) ? a.y + (int64_t)(q / K) * a.y_run_stride + ws : nullptr;
+            yb[t * kM + l16] = (yrow && t < wl) ? yrow[t] : 0.f;
+            yb[(t + 32) * kM + l16] = (yrow && t + 32 < wl) ? yrow[t + 32] : 0.f;
+        }
+        const float *gsrc = gram + (int64_t)w * kB * kB;
+#pragma unroll
+        for (int u = 0; u < kB * kB / (kNW * kWave); ++u) {
+            const int e = g.tid + u * kNW * kWave;
+            const int t = e >> 6, t2 = e & 63;
+            const float gv = gsrc[e];
+            gd[(t * 4 + (t2 & 3)) * kGStride + (t2 >> 2)] = t2 > t ? (double)gv : 0.0;
+            if (t2 == t) x2d[t] = (double)gv;
+        }
+    };
+    // Q0 shares of this wavefront for one window -> LDS
+    auto put_part = [&](const Geo &g, const f4 (&acc)[4]) __attribute__((always_inline)) {
+        float *part = reinterpret_cast<float *>(lds + Lds::part);
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[(g.wave * kB + rb * 16 + 4 * g.lk + r) * kM + g.lr] = acc[rb][r];
+    };
+
+    // ---- per-learner state of the dependent rounds (wavefront 0: lane = 4 learner + quad lane) ----
+    float eta = 0.f;
+    double sig = 1.0, n2 = 0.0;
+    f4 V[RES ? NB : 1];
+    {
+        const Geo g = make_geo((int)threadIdx.x, a);
+        const int q_ch = (int)blockIdx.x * kM + (g.lane >> 2);
+        if (g.wave == 0 && q_ch < nq) {
+            eta = a.eta[q_ch % K];
+            sig = (double)a.sigma[q_ch];
+            n2 = a.n2[q_ch] * sig * sig;                        // ||w||^2 of the iterate itself
+        }
+        if (RES) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) V[b] = ld_block(g, g.wave + kNW * b);
+        }
+        // ---- prologue: inner products of the first window ----------------------------------------
+        const int ws = plan.start(0), wl = plan.len(0);
+        f4 acc[4];
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
+        auto q_of = [&](const f4 &vb, int blk) __attribute__((always_inline)) {
+            f4 xq[4];
+            ldq(g, ws, wl, blk, xq);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb)
+                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq[rb][r], vb[r], acc[rb], 0, 0, 0);
+        };
+        if constexpr (RES) {
+            static_for<NB>([&](auto bc) __attribute__((always_inline)) {
+                constexpr int b = decltype(bc)::value;
+                const int blk = g.wave + kNW * b;
+                if (blk < nblk) q_of(V[b], blk);
+            });
+        } else {
+            for (int blk = g.wave; blk < nblk; blk += kNW) q_of(ld_block(g, blk), blk);
+        }
+        put_part(g, acc);
+        stage_chain_inputs(g, 0);
+    }
+
+    for (int w = 0; w < nwin; ++w) {
+        const int ws = plan.start(w), wl = plan.len(w);
+        __syncthreads();                                         // (A) shares of Q0, labels, G in LDS
+        int tid_w = (int)threadIdx.x;
+        asm volatile("" : "+v"(tid_w));                          // see Geo
+        {
+            // Q0 = sum of the eight shares, fixed order, as float64
+            const float *part = reinterpret_cast<const float *>(lds + Lds::part);
+            double *q0d = reinterpret_cast<double *>(lds + Lds::q0);
+#pragma unroll
+            for (int u = 0; u < kB * kM / (kNW * kWave); ++u) {
+                const int e = tid_w + u * kNW * kWave;
+                double sum = 0.0;
+#pragma unroll
+                for (int v = 0; v < kNW; ++v) sum += (double)part[v * kB * kM + e];
+                q0d[e] = sum;
+            }
+        }
+        __syncthreads();                                         // (B)
+        if (__builtin_amdgcn_readfirstlane(tid_w >> 6) == 0) {
+            const int lane = tid_w & 63;
+            if (w > 0) {
+                // ||w||^2 as the last sweep measured it: 32 shares per learner, fixed order
+                const float *n2s = reinterpret_cast<const float *>(lds + Lds::n2);
+                double m = 0.0;
+                const int lc = lane >> 2;
+#pragma unroll
+                for (int v = 0; v < kNW; ++v)
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4) m += (double)n2s[(v * 4 + g4) * kM + lc];
+                n2 = m;
+                sig = 1.0;
+            }
+            chain_window<LOSS>(lds, lane, wl, eta, (double)a.D, sig, n2);
+        }
+        __syncthreads();                                         // (C) predictions, -Bm, F in LDS
+        asm volatile("" : "+v"(tid_w));
+        const Geo g = make_geo(tid_w, a);
+        const int lr = g.lr, lk = g.lk;
+
+        // predictions of the window to Z
+        {
+            const float *zb = reinterpret_cast<const float *>(lds + Lds::zb);
+            const int l16 = g.tid >> 5, t = g.tid & 31;
+            const int q = (int)blockIdx.x * kM + l16;
+            if (q < nq) {
+                float *zrow = a.Z + (int64_t)(q / K) * a.zl.zs_r + (int64_t)(q % K) * a.zl.zs_i + (int64_t)ws * a.zl.zs_t;
+                if (t < wl) zrow[(int64_t)t * a.zl.zs_t] = zb[t * kM + l16];
+                if (t + 32 < wl) zrow[(int64_t)(t + 32) * a.zl.zs_t] = zb[(t + 32) * kM + l16];
+            }
+        }
+
+        // ---- sweep: (3) of window w and (1) of window w + 1, block by block ----------------------
+        // The round rows (and, where the iterates live in HBM, the block itself) of the next block
+        // are on their way while the matrix instructions of the current block run.
+        const float *bml = reinterpret_cast<const float *>(lds + Lds::bm);
+        float bmr[BMR ? 16 : 1];
+        if (BMR) {
+#pragma unroll
+            for (int rs = 0; rs < 16; ++rs) bmr[rs] = bml[(rs * 4 + lk) * kM + lr];
+        }
+        const float F = reinterpret_cast<const float *>(lds + Lds::fv)[lr];
+        const bool more = w + 1 < nwin;
+        const int ws1 = more ? plan.start(w + 1) : 0, wl1 = more ? plan.len(w + 1) : 0;
+        f4 acc[4];
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
+        float nn = 0.f;
+        struct BlkIn { float xu[16]; f4 xq[4]; f4 vb; };
+        auto load_in = [&](BlkIn &in, int blk) __attribute__((always_inline)) {
+            ldu(g, ws, wl, blk, in.xu);
+            if (more) ldq(g, ws1, wl1, blk, in.xq);
+            if (!RES) in.vb = ld_block(g, blk);
+        };
+        auto compute = [&](BlkIn &in, f4 &vreg, int blk) __attribute__((always_inline)) {
+            f4 vb = RES ? vreg : in.vb;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) vb[r] *= F;
+#pragma unroll
+            for (int rs = 0; rs < 16; ++rs)
+                vb = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs], BMR ? bmr[BMR ? rs : 0] : bml[(rs * 4 + lk) * kM + lr], vb, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) nn = fmaf(vb[r], vb[r], nn);
+            if (RES) vreg = vb; else st_block(g, blk, vb);
+            if (more) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb)
+                        acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xq[rb][r], vb[r], acc[rb], 0, 0, 0);
+            }
+        };
+        BlkIn in[2];
+        load_in(in[0], g.wave);
+        if constexpr (RES) {
+            static_for<NB>([&](auto bc) __attribute__((always_inline)) {
+                constexpr int b = decltype(bc)::value;
+                const int blk = g.wave + kNW * b;
+                if (b + 1 < NB) load_in(in[(b + 1) & 1], blk + kNW);     // lanes past d load nothing
+                __builtin_amdgcn_sched_barrier(0);
+                if (blk < nblk) compute(in[b & 1], V[b], blk);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        } else {
+            f4 none;
+            for (int blk = g.wave; blk < nblk; blk += 2 * kNW) {
+                load_in(in[1], blk + kNW);
+                __builtin_amdgcn_sched_barrier(0);
+                compute(in[0], none, blk);
+                __builtin_amdgcn_sched_barrier(0);
+                load_in(in[0], blk + 2 * kNW);
+                __builtin_amdgcn_sched_barrier(0);
+                if (blk + kNW < nblk) compute(in[1], none, blk + kNW);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        reinterpret_cast<float *>(lds + Lds::n2)[(g.wave * 4 + lk) * kM + lr] = nn;
+        if (more) {
+            put_part(g, acc);
+            stage_chain_inputs(g, w + 1);
+        }
+    }
+
+    // ---- state out: the iterates themselves (scale 1) and their squared norms ---------------------
+    {
+        const Geo g = make_geo((int)threadIdx.x, a);
+        if (RES) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) st_block(g, g.wave + kNW * b, V[b]);
+        }
+        __syncthreads();
+        const int q_ch = (int)blockIdx.x * kM + (g.lane >> 2);
+        if (g.wave == 0 && (g.lane & 3) == 0 && q_ch < nq) {
+            const float *n2s = reinterpret_cast<const float *>(lds + Lds::n2);
+            double m = 0.0;
+            const int lc = g.lane >> 2;
+            for (int v = 0; v < kNW; ++v)
+                for (int g4 = 0; g4 < 4; ++g4) m += (double)n2s[(v * 4 + g4) * kM + lc];
+            a.sigma[q_ch] = 1.f;
+            a.n2[q_ch] = m;
+        }
+    }
+}
+
+template <int LOSS>
+hipError_t launch_window_kernel(const DenseArgs &a, const float *gram, const WinPlanD &plan, bool resident, hipStream_t s)
+{
+    const int ntiles = (a.R * a.K + kM - 1) / kM;
+    const dim3 grid((unsigned)ntiles), block(kNW * kWave);
+    const int nblk = (a.d + 15) / 16;
+    void (*kern)(const DenseArgs, const float *, WinPlanD) = nullptr;
+    if (resident && nblk <= 8 * kNW) kern = dense_window_kernel<LOSS, 8, true>;
+    else if (resident && nblk <= 32 * kNW) kern = dense_window_kernel<LOSS, 32, true>;
+    else kern = dense_window_kernel<LOSS, 1, false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       Lds::total);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, block, Lds::total, s, a, gram, plan);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t dense_gram_bytes(int64_t n_max) { return (size_t)(n_max / kB + 2) * kB * kB * sizeof(float); }
+
+bool dense_window_supported(const DenseArgs &a)
+{
+    // a shared stream whose rows can be read 16 bytes at a time; the optimistic update is not built here
+    return a.x_shared && !a.optimistic && a.vec_ok && a.gram != nullptr;
+}
+
+bool dense_window_wanted(const DenseArgs &a)
+{
+    if (!dense_window_supported(a)) return false;
+    const int64_t path = a.tune->get(OCO_OPT_DENSE_PATH);
+    if (path == 1) return a.d > 64 * kWave;                     // the register kernel cannot hold more
+    if (path == 2) return true;
+    return a.d > 64 * kWave || ((int64_t)a.R * a.K >= 1024 && a.d >= 256);
+}
+
+hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, const PieceHook *hook)
+{
+    (void)hook;
+    DenseArgs a = a0;
+    if (a.n <= 0) return hipSuccess;
+    if (!dense_window_supported(a)) return hipErrorInvalidValue;
+    const WinPlanD plan{a.t0, a.n};
+    const int nwin = plan.count();
+    hipLaunchKernelGGL(dense_gram_kernel, dim3((unsigned)nwin), dim3(256), 0, s, a.x, a.d, plan, a.gram);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    {
+        ComparatorGemmArgs g{};
+        g.x = a.x; g.u = a.u; g.seg_start = a.seg_start; g.S = a.S; g.Z = a.Z; g.zl = a.zl;
+        g.d = a.d; g.K = a.K; g.R = a.R; g.t0 = a.t0; g.n = a.n; g.vec_ok = a.vec_ok;
+        e = launch_comparator_gemm(g, s);
+        if (e != hipSuccess) return e;
+    }
+    const bool resident = a.d <= 16 * kNW * 32 && a.tune->get(OCO_OPT_WINDOW_RESIDENT) != 0;
+    if (a.tune->get(OCO_OPT_VERBOSE) == 1)
+        fprintf(stderr, "dense plan: windowed contraction kernel, %d windows, %d tiles, iterates %s\n", nwin,
+                (a.R * a.K + kM - 1) / kM, resident ? "in registers" : "streamed from HBM");
+    switch (loss) {
+        case 0: return launch_window_kernel<0>(a, a.gram, plan, resident, s);
+        case 1: return launch_window_kernel<1>(a, a.gram, plan, resident, s);
+        case 2: return launch_window_kernel<2>(a, a.gram, plan, resident, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace oco

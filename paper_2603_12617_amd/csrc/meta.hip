@@ -341,6 +341,17 @@ hipError_t launch_accel_bounds(const double *regret, int R, int64_t t, int64_t k
     return hipGetLastError();
 }
 
+__global__ void __launch_bounds__(64) set_eta_kernel(float *eta, const EtaTable tab, int K)
+{
+    if ((int)threadIdx.x < K) eta[threadIdx.x] = tab.v[threadIdx.x];
+}
+
+hipError_t launch_set_eta(float *eta_dev, const EtaTable &tab, int K, hipStream_t s)
+{
+    hipLaunchKernelGGL(set_eta_kernel, dim3(1), dim3(64), 0, s, eta_dev, tab, K);
+    return hipGetLastError();
+}
+
 hipError_t launch_init_state(void *zero_base, size_t zero_bytes, void *sigma, int64_t n_sigma,
                              int sigma_is_double, hipStream_t s)
 {

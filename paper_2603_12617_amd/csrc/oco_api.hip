@@ -48,8 +48,10 @@ int validate_and_layout(const oco_config *c, Layout *lay)
     if (c->sparse_nnz > 0) {
         if (c->sparse_nnz > OCO_MAX_NNZ || c->sparse_nnz > c->d) return OCO_EUNSUPPORTED;
         if (!c->x_shared) return OCO_EUNSUPPORTED;
-    } else if (!dense_supported(c->d)) {
+    } else if (!dense_supported(c->d, c->x_shared)) {
         return OCO_EUNSUPPORTED;
+    } else if (c->d > 4096 && (c->d % 4 != 0 || c->optimistic)) {
+        return OCO_EUNSUPPORTED;      // beyond one wavefront's registers only the windowed kernel runs
     }
     Layout l;
     l.n_max = n_max;
@@ -99,6 +101,10 @@ int validate_and_layout(const oco_config *c, Layout *lay)
             l.off_G01 = off;
             off += align_up(sizeof(float) * (size_t)(c->x_shared ? 1 : c->R) * align_up(n_max, 64), 256);
         }
+        if (c->x_shared) {
+            l.off_gram = off;
+            off += align_up(dense_gram_bytes(n_max), 256);
+        }
     } else {
         l.off_gram = off;
         off += align_up(sparse_scratch_bytes(n_max), 256);
@@ -112,17 +118,20 @@ int validate_and_layout(const oco_config *c, Layout *lay)
 
 struct oco_state {
     oco_config cfg;
-    std::vector<double> eta;
-    std::vector<float> eta_f;
-    std::vector<int64_t> seg_start;
+    double eta[OCO_MAX_K];
+    int64_t seg_start[OCO_MAX_SEGMENTS];
     Layout lay;
     char *ws = nullptr;
     hipStream_t stream = nullptr;
     const float *u_dev = nullptr;
     int64_t S = 0;
     int64_t t_done = 0;
+    bool failed = false;       // a HIP error hit a call half-way: the device state is undefined until oco_reset
+    bool is_static = false;    // created by oco_create_static: no second stream, no events
     bool timing = false, timed = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    Tuning tune;
+    DensePlanCache dense_plan;
     // The meta kernel of a piece of a call depends on that piece's predictions only, and no
     // round kernel depends on a meta kernel (every base learner steps at its own iterate): it
     // runs on a second stream beside the round kernels of the following pieces, and the
@@ -144,6 +153,36 @@ struct oco_state {
         return ZLayout{(cfg.K + 1) * nz, nz, 1};
     }
 };
+
+namespace {
+
+// Builds the host object on a validated layout: `side_stream` says whether the state gets a
+// second stream (and the event that joins it) for work beside the round kernels.
+int create_on(const oco_config *cfg, const Layout &l, void *dev_ws, void *hip_stream, bool side_stream,
+              oco_state **out)
+{
+    oco_state *st = new (std::nothrow) oco_state();
+    if (!st) return OCO_ENOMEM;
+    st->cfg = *cfg;
+    for (int64_t i = 0; i < cfg->K; ++i) st->eta[i] = cfg->eta[i];
+    st->cfg.eta = st->eta;
+    st->lay = l;
+    st->ws = static_cast<char *>(dev_ws);
+    st->stream = static_cast<hipStream_t>(hip_stream);
+    st->is_static = !side_stream;
+    if (side_stream &&
+        (hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking) != hipSuccess ||
+         hipEventCreateWithFlags(&st->join_ev, hipEventDisableTiming) != hipSuccess)) {
+        delete st;
+        return OCO_EHIP;
+    }
+    int rc = oco_reset(st);
+    if (rc != OCO_OK) { delete st; return rc; }
+    *out = st;
+    return OCO_OK;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -174,7 +213,13 @@ int oco_reset(oco_state *st)
                                      st->at<void>(st->lay.off_sigma), st->lay.n_sigma,
                                      st->cfg.sparse_nnz > 0, st->stream);
     if (e != hipSuccess) return OCO_EHIP;
+    // the step sizes travel as a kernel argument (no host buffer has to outlive the call)
+    EtaTable tab;
+    for (int64_t i = 0; i < OCO_MAX_K; ++i) tab.v[i] = i < st->cfg.K ? (float)st->eta[i] : 0.f;
+    if (launch_set_eta(st->at<float>(st->lay.off_eta), tab, (int)st->cfg.K, st->stream) != hipSuccess)
+        return OCO_EHIP;
     st->t_done = 0;
+    st->failed = false;
     return OCO_OK;
 }
 
@@ -189,31 +234,33 @@ int oco_create(const oco_config *cfg, void *dev_ws, size_t ws_bytes, void *hip_s
     if (ws_bytes < l.total) return OCO_ENOMEM;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return OCO_EHIP;
+    return create_on(cfg, l, dev_ws, hip_stream, true, out);
+}
 
-    oco_state *st = new (std::nothrow) oco_state();
-    if (!st) return OCO_ENOMEM;
-    st->cfg = *cfg;
-    st->eta.assign(cfg->eta, cfg->eta + cfg->K);
-    st->eta_f.resize(cfg->K);
-    for (int64_t i = 0; i < cfg->K; ++i) st->eta_f[i] = (float)cfg->eta[i];
-    st->cfg.eta = st->eta.data();
-    st->lay = l;
-    st->ws = static_cast<char *>(dev_ws);
-    st->stream = static_cast<hipStream_t>(hip_stream);
-
-    if (hipMemcpyAsync(st->at<float>(l.off_eta), st->eta_f.data(), sizeof(float) * cfg->K,
-                       hipMemcpyHostToDevice, st->stream) != hipSuccess) {
-        delete st;
-        return OCO_EHIP;
+int oco_set_option(oco_state *st, int key, int64_t value)
+{
+    if (!st || key < 0 || key >= OCO_OPT_COUNT || value < -1) return OCO_EINVAL;
+    bool ok = true;
+    switch (key) {
+        case OCO_OPT_META_BESIDE: case OCO_OPT_COMPARATOR_GEMM: case OCO_OPT_DENSE_HALF:
+        case OCO_OPT_SPARSE_PIPE: case OCO_OPT_VERBOSE: case OCO_OPT_WINDOW_RESIDENT:
+            ok = value <= 1; break;
+        case OCO_OPT_DENSE_PATH:
+            ok = value == -1 || value == 1 || value == 2;
+            if (value == 2 && (st->cfg.sparse_nnz > 0 || !st->cfg.x_shared || st->cfg.optimistic || st->cfg.d % 4 != 0))
+                return OCO_EUNSUPPORTED;
+            if (value == 1 && st->cfg.sparse_nnz == 0 && st->cfg.d > 4096) return OCO_EUNSUPPORTED;
+            break;
+        case OCO_OPT_DENSE_WPB: ok = value == -1 || (value >= 1 && value <= 16); break;
+        case OCO_OPT_DENSE_PIECES: ok = value == -1 || (value >= 1 && value <= (1 << 20)); break;
+        case OCO_OPT_SPARSE_LPW:
+            ok = value == -1 || value == 4 || value == 8 || value == 16 || value == 32 || value == 64; break;
+        case OCO_OPT_WINDOW_WAVES: ok = value == -1 || value == 4 || value == 8; break;
+        default: ok = false;
     }
-    if (hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking) != hipSuccess ||
-        hipEventCreateWithFlags(&st->join_ev, hipEventDisableTiming) != hipSuccess) {
-        delete st;
-        return OCO_EHIP;
-    }
-    rc = oco_reset(st);
-    if (rc != OCO_OK) { delete st; return rc; }
-    *out = st;
+    if (!ok) return OCO_EINVAL;
+    st->tune.v[key] = value;
+    st->dense_plan.valid = false;
     return OCO_OK;
 }
 
@@ -225,11 +272,11 @@ int oco_set_comparator(oco_state *st, const float *u_dev, const int64_t *seg_sta
     if (seg_start_host[0] != 0) return OCO_EINVAL;
     for (int64_t s = 1; s < S; ++s)
         if (seg_start_host[s] <= seg_start_host[s - 1]) return OCO_EINVAL;
-    st->seg_start.assign(seg_start_host, seg_start_host + S);
-    if (hipMemcpyAsync(st->at<int64_t>(st->lay.off_seg), st->seg_start.data(), sizeof(int64_t) * S,
+    std::memcpy(st->seg_start, seg_start_host, sizeof(int64_t) * (size_t)S);
+    if (hipMemcpyAsync(st->at<int64_t>(st->lay.off_seg), st->seg_start, sizeof(int64_t) * S,
                        hipMemcpyHostToDevice, st->stream) != hipSuccess)
         return OCO_EHIP;
-    // the host vector may be reassigned by a later call: make sure the copy has left it
+    // the host copy may be rewritten by a later call: make sure the transfer has left it
     if (hipStreamSynchronize(st->stream) != hipSuccess) return OCO_EHIP;
     st->u_dev = u_dev;
     st->S = S;
@@ -239,6 +286,7 @@ int oco_set_comparator(oco_state *st, const float *u_dev, const int64_t *seg_sta
 int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
 {
     if (!st || !rd || n < 0 || t0 < 0) return OCO_EINVAL;
+    if (st->failed) return OCO_EHIP;
     if (t0 != st->t_done) return OCO_ESEQ;
     if (t0 + n > st->cfg.T || n > st->lay.n_max) return OCO_ERANGE;
     if (!st->u_dev) return OCO_ENOCOMP;
@@ -254,11 +302,14 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
     if (rd->y && yrs < n) return OCO_EINVAL;
     auto mis = [](const void *p, unsigned a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
     if (mis(rd->x, 4) || mis(rd->y, 4) || mis(rd->col, 4) || mis(rd->val, 4)) return OCO_EINVAL;
+    if (!sparse && c.d > 4096 && mis(rd->x, 16)) return OCO_EUNSUPPORTED;
 
     const Layout &l = st->lay;
     const ZLayout zl = st->zlayout();
     hipError_t e;
     if (st->timing && hipEventRecord(st->ev[0], st->stream) != hipSuccess) return OCO_EHIP;
+    // from here on part of the call's work may be on the device when an error comes back
+    auto fail = [st]() { st->failed = true; return (int)OCO_EHIP; };
 
     // Meta kernel of the rounds [off, off + len) of this call, on the second stream.
     struct MetaPipe {
@@ -269,7 +320,12 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
                 hipEvent_t ev;
                 hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
                 if (e != hipSuccess) return e;
-                st->piece_ev.push_back(ev);
+                try {
+                    st->piece_ev.push_back(ev);          // nothing may throw across the C boundary
+                } catch (...) {
+                    (void)hipEventDestroy(ev);
+                    return hipErrorOutOfMemory;
+                }
             }
             hipEvent_t ev = st->piece_ev[used++];
             hipError_t e = hipEventRecord(ev, st->stream);
@@ -304,8 +360,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
     m.L = st->at<double>(l.off_L); m.regret = st->at<double>(l.off_regret);
     m.eps = c.eps; m.K = (int)c.K; m.R = (int)c.R; m.n = (int)n;
     const PieceHook hook{&MetaPipe::piece, &pipe, &MetaPipe::beside};
-    bool overlap = true;
-    if (const char *ev = std::getenv("OCO_META_BESIDE")) overlap = std::atoi(ev) != 0;   // tuning override
+    const bool overlap = st->side != nullptr && st->tune.get(OCO_OPT_META_BESIDE) != 0;
 
     if (sparse) {
         SparseArgs a{};
@@ -322,6 +377,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
             a.last_col = st->at<int32_t>(l.off_lastcol); a.last_val = st->at<float>(l.off_lastval);
             a.xlast_dense = st->at<float>(l.off_xlast);
         }
+        a.tune = &st->tune;
         e = launch_sparse_rounds(a, c.loss, st->stream, overlap ? &hook : nullptr);
     } else {
         DenseArgs a{};
@@ -340,18 +396,20 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
             a.g01 = st->at<float>(l.off_G01);
             a.xlast = st->at<float>(l.off_xlast); a.x2last = st->at<float>(l.off_x2last);
         }
+        a.tune = &st->tune; a.plan = &st->dense_plan;
+        a.gram = l.off_gram ? st->at<float>(l.off_gram) : nullptr;
         e = launch_dense_rounds(a, c.loss, st->stream, overlap ? &hook : nullptr);
     }
-    if (e != hipSuccess) return OCO_EHIP;
+    if (e != hipSuccess) return fail();
     // timing: [ev0, ev1] spans the round kernels, [ev1, ev2] whatever meta work is left after them
-    if (st->timing && hipEventRecord(st->ev[1], st->stream) != hipSuccess) return OCO_EHIP;
+    if (st->timing && hipEventRecord(st->ev[1], st->stream) != hipSuccess) return fail();
     if (pipe.used) {
-        if (pipe.join() != hipSuccess) return OCO_EHIP;
+        if (pipe.join() != hipSuccess) return fail();
     } else if (launch_meta(m, c.loss, st->stream) != hipSuccess) {
-        return OCO_EHIP;
+        return fail();
     }
     if (st->timing) {
-        if (hipEventRecord(st->ev[2], st->stream) != hipSuccess) return OCO_EHIP;
+        if (hipEventRecord(st->ev[2], st->stream) != hipSuccess) return fail();
         st->timed = true;
     }
     st->t_done = t0 + n;
@@ -361,6 +419,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
 int oco_regret(oco_state *st, double *out_host)
 {
     if (!st || !out_host) return OCO_EINVAL;
+    if (st->failed) return OCO_EHIP;
     if (hipMemcpyAsync(out_host, st->at<double>(st->lay.off_regret), sizeof(double) * st->cfg.R,
                        hipMemcpyDeviceToHost, st->stream) != hipSuccess)
         return OCO_EHIP;
@@ -371,6 +430,7 @@ int oco_accel_bounds(oco_state *st, int64_t k, double alpha, double *out_dev)
 {
     if (!st || !out_dev || k < 1 || !std::isfinite(alpha) || alpha < 0.0) return OCO_EINVAL;
     if (reinterpret_cast<uintptr_t>(out_dev) & 7u) return OCO_EINVAL;
+    if (st->failed) return OCO_EHIP;
     if (st->t_done <= 0) return OCO_ESEQ;
     return launch_accel_bounds(st->at<double>(st->lay.off_regret), (int)st->cfg.R, st->t_done, k, alpha,
                                out_dev, st->stream) == hipSuccess ? OCO_OK : OCO_EHIP;
@@ -379,6 +439,7 @@ int oco_accel_bounds(oco_state *st, int64_t k, double alpha, double *out_dev)
 int oco_cum_losses(oco_state *st, double *out_host)
 {
     if (!st || !out_host) return OCO_EINVAL;
+    if (st->failed) return OCO_EHIP;
     if (hipMemcpyAsync(out_host, st->at<double>(st->lay.off_L), sizeof(double) * st->cfg.R * st->cfg.K,
                        hipMemcpyDeviceToHost, st->stream) != hipSuccess)
         return OCO_EHIP;
@@ -388,6 +449,7 @@ int oco_cum_losses(oco_state *st, double *out_host)
 int oco_get_state(oco_state *st, float *W_dev, float *p_dev, float *wbar_dev)
 {
     if (!st) return OCO_EINVAL;
+    if (st->failed) return OCO_EHIP;
     auto mis = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; };
     if (mis(W_dev) || mis(p_dev) || mis(wbar_dev)) return OCO_EINVAL;
     ExportArgs a{};

@@ -18,6 +18,25 @@ struct ZLayout {
     int64_t zs_r, zs_i, zs_t;
 };
 
+// Tuning choices of a state (oco_set_option), indexed by oco_option; -1 = the library decides.
+constexpr int kNumOptions = 12;
+struct Tuning {
+    int64_t v[kNumOptions];
+    __host__ Tuning() { for (auto &e : v) e = -1; }
+    int64_t get(int key) const { return v[key]; }
+};
+
+// How the dense round kernel of a state is launched: depends on the configuration and the
+// tuning choices only (not on n or t0), so it is worked out once and kept in the state.
+struct DensePlanCache {
+    bool valid = false;
+    const void *kern = nullptr;
+    size_t smem = 0;
+    int wpb = 0;
+    int64_t nwg = 0, batches = 0;
+    int per_run = 0;
+};
+
 // Called after the round kernel of every piece of a call has been enqueued: rounds
 // [off, off + len) of the call have their predictions in Z once that kernel finishes.
 struct PieceHook {
@@ -60,8 +79,15 @@ struct DenseArgs {
     float *g01;              // scratch like x2: <x_{t-1}, x_t> per round of this call
     float *xlast;            // [1 or R][d]  last round row of the previous call (0 before round 0)
     float *x2last;           // [1 or R]     its squared norm
+    const Tuning *tune;      // never null
+    DensePlanCache *plan;    // never null
+    float *gram;             // shared streams: dense_gram_bytes(n_max) of scratch for the windowed path
 };
 hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s, const PieceHook *hook);
+// the windowed path (dense_window.hip): whether a configuration takes it, and its launcher
+bool dense_window_wanted(const DenseArgs &a);
+hipError_t launch_dense_window(const DenseArgs &a, int loss, hipStream_t s, const PieceHook *hook);
+size_t dense_gram_bytes(int64_t n_max);
 
 // comparator predictions of a shared dense stream as one contraction (rows K of Z)
 struct ComparatorGemmArgs {
@@ -77,7 +103,7 @@ struct ComparatorGemmArgs {
     int vec_ok;              // rows of x and u are 16-byte aligned and d % 4 == 0
 };
 hipError_t launch_comparator_gemm(const ComparatorGemmArgs &a, hipStream_t s);
-bool dense_supported(int64_t d);
+bool dense_supported(int64_t d, int x_shared);
 
 // ---- sparse rounds ----------------------------------------------------------
 struct SparseArgs {
@@ -107,6 +133,7 @@ struct SparseArgs {
     int32_t *last_col;       // [OCO_MAX_NNZ]  last round row of the previous call (zeros before round 0)
     float *last_val;         // [OCO_MAX_NNZ]
     float *xlast_dense;      // [d]  the same row scattered into a dense vector (for the export)
+    const Tuning *tune;      // never null
 };
 hipError_t launch_sparse_rounds(const SparseArgs &a, int loss, hipStream_t s, const PieceHook *hook);
 size_t sparse_scratch_bytes(int64_t n_max);
@@ -144,6 +171,10 @@ struct ExportArgs {
 hipError_t launch_export(const ExportArgs &a, hipStream_t s);
 hipError_t launch_accel_bounds(const double *regret, int R, int64_t t, int64_t k, double alpha, double *out,
                                hipStream_t s);
+
+// step sizes as a kernel argument
+struct EtaTable { float v[64]; };
+hipError_t launch_set_eta(float *eta_dev, const EtaTable &tab, int K, hipStream_t s);
 
 // fills `bytes` (a multiple of 16) of device memory with zero using a kernel,
 // and sets every sigma to 1

@@ -940,11 +940,11 @@ __global__ void __launch_bounds__(64) sparse_fold_finish_kernel(double *sigma, d
 namespace {
 
 // The largest share that still gives every compute unit a workgroup, at least 4.
-int sparse_learners_per_workgroup(int nq)
+int sparse_learners_per_workgroup(int nq, const Tuning &tune)
 {
     int lpw = 64;
-    if (const char *f = getenv("OCO_SPARSE_LPW")) {
-        const int v = atoi(f);
+    {
+        const int v = (int)tune.get(OCO_OPT_SPARSE_LPW);
         if (v == 4 || v == 8 || v == 16 || v == 32 || v == 64) return v;
     }
     while (lpw > 4 && (nq + lpw - 1) / lpw < 256) lpw >>= 1;
@@ -959,7 +959,7 @@ hipError_t launch_window_lpw(const SparseArgs &a, const WinPlan &plan, int wbeg,
     const size_t stage_b = (size_t)stage_ints(a.nnz) * 4, chain_b = sizeof(Chain<LPW>);
     // the pipelined kernel keeps two chain buffers and three staged windows
     int pipe = 2 * chain_b + 3 * stage_b + sparse_static_lds(LPW) <= kLdsBytes;
-    if (const char *f = getenv("OCO_SPARSE_PIPE")) pipe = pipe && atoi(f) != 0;
+    if (a.tune->get(OCO_OPT_SPARSE_PIPE) == 0) pipe = 0;
     const size_t smem = pipe ? 2 * chain_b + 3 * stage_b : chain_b + 2 * stage_b;
     if (smem + sparse_static_lds(LPW) > kLdsBytes) return hipErrorInvalidValue;
     const auto kern = sparse_window_kernel<LOSS, LPW, OPT>;
@@ -1021,7 +1021,7 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s, c
 
     // segments end at the multiples of kSegment of the horizon, which are window boundaries
     const int groups = (a.R * a.K + kWave - 1) / kWave;
-    int lpw = sparse_learners_per_workgroup(a.R * a.K);
+    int lpw = sparse_learners_per_workgroup(a.R * a.K, *a.tune);
     // one chain buffer and two staged windows have to fit the LDS (64 learners with more than 40
     // entries per round do not)
     while (lpw > 4 && sparse_chain_bytes(lpw) + 2 * (size_t)stage_ints(a.nnz) * 4 + sparse_static_lds(lpw) > kLdsBytes) lpw >>= 1;

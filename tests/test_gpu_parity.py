@@ -22,8 +22,8 @@ def _oracle():
     return O
 
 
-def _gpu(wl, data, chunk=0, n_max=0):
-    sim = B.Simulation(wl, data, n_max=n_max)
+def _gpu(wl, data, chunk=0, n_max=0, options=None):
+    sim = B.Simulation(wl, data, n_max=n_max, options=options)
     sim.run_all(chunk)
     reg = sim.regret()
     L = sim.cum_losses()
@@ -90,19 +90,19 @@ def test_dense_rounds_match_the_oracle(name, over):
     ("c4", dict(T=301, R=3, d=4096, K=16)),
     ("c3", dict(T=400, R=130, d=64, K=2, seg_len=33, optimistic=True)),
 ])
-@pytest.mark.parametrize("mode", ["0", "1"])
-def test_comparator_predictions_in_the_round_kernel_or_as_a_contraction(name, over, mode, monkeypatch):
+@pytest.mark.parametrize("mode", [0, 1])
+def test_comparator_predictions_in_the_round_kernel_or_as_a_contraction(name, over, mode):
     """With a shared stream the comparators' predictions come either from an extra wavefront of
     the round kernel or from the MFMA contraction kernel (the library picks by grid shape):
     both, on every shape class (tiles ragged in runs, rounds and depth, unaligned rows, tiles
     that straddle comparator segments), and both independent of how the horizon is cut."""
-    monkeypatch.setenv("OCO_COMPARATOR_GEMM", mode)
+    opt = dict(comparator_gemm=mode, dense_path=1)
     wl = WL.make(name, **over)
     data = WL.generate(wl)
     print("case", name, over, "contraction", mode, flush=True)
-    whole = _gpu(wl, data)
+    whole = _gpu(wl, data, options=opt)
     _check(wl, data, whole, runs=range(min(wl.R, 3)), label="%s %s gemm=%s" % (name, over, mode))
-    part = _gpu(wl, data, chunk=77, n_max=77)
+    part = _gpu(wl, data, chunk=77, n_max=77, options=opt)
     for k in ("regret", "L", "W", "p", "wbar"):
         assert np.array_equal(whole[k], part[k]), k
 
@@ -117,27 +117,26 @@ def test_comparator_predictions_in_the_round_kernel_or_as_a_contraction(name, ov
     ("c3", dict(T=260, R=3, d=700, K=7, seg_len=64, optimistic=True)),
     ("c4", dict(T=200, R=3, d=300, K=3, optimistic=True)),
 ])
-def test_two_learners_per_wavefront(name, over, monkeypatch):
+def test_two_learners_per_wavefront(name, over):
     """For d <= 1024 and at least 8192 learners on a shared stream each half of a wavefront owns a
-    learner.  OCO_DENSE_HALF=1 forces that kernel on small cases (odd learner counts leave the
-    last upper half without a task): parity with the oracle, and the same bits under any cut."""
-    monkeypatch.setenv("OCO_DENSE_HALF", "1")
+    learner.  The option dense_half=1 forces that kernel on small cases (odd learner counts leave
+    the last upper half without a task): parity with the oracle, and the same bits under any cut."""
+    opt = dict(dense_half=1, dense_path=1)
     wl = WL.make(name, **over)
     data = WL.generate(wl)
     print("case", name, over, flush=True)
-    whole = _gpu(wl, data)
+    whole = _gpu(wl, data, options=opt)
     _check(wl, data, whole, label="%s %s two per wavefront" % (name, over))
     for c in (1, 37, 64):
-        part = _gpu(wl, data, chunk=c, n_max=c)
+        part = _gpu(wl, data, chunk=c, n_max=c, options=opt)
         for k in ("regret", "L", "W", "p", "wbar"):
             assert np.array_equal(whole[k], part[k]), (k, c)
 
 
-def test_two_learners_per_wavefront_is_chosen_for_many_learners(monkeypatch, capfd):
-    monkeypatch.setenv("OCO_DENSE_VERBOSE", "1")           # the launcher reports its plan on stderr
+def test_two_learners_per_wavefront_is_chosen_for_many_learners(capfd):
     wl = WL.make("c4", T=130, R=700, d=200, K=12)          # 8400 learners
     data = WL.generate(wl)
-    got = _gpu(wl, data)
+    got = _gpu(wl, data, options=dict(verbose=1, dense_path=1))   # the launcher reports its plan on stderr
     assert "two learners per wavefront" in capfd.readouterr().err
     _check(wl, data, got, runs=[0, 350, 699], label="c4 8400 learners")
 
@@ -246,7 +245,7 @@ def _check_sparse_optimistic(wl, data, got, label):
     dict(T=400, R=2, d=300, K=2, nnz=64, wstar_nnz=30, eta=(2.0, 400.0)),      # folds of the lazy scale
     dict(T=130, R=1, d=64, K=1, nnz=1, wstar_nnz=4),
 ])
-def test_sparse_optimistic_rounds_match_the_oracle(over, monkeypatch):
+def test_sparse_optimistic_rounds_match_the_oracle(over):
     wl = WL.make("c5", optimistic=True, **over)
     data = WL.generate(wl)
     print("case c5 optimistic", over, flush=True)
@@ -260,8 +259,7 @@ def test_sparse_optimistic_rounds_match_the_oracle(over, monkeypatch):
     for k in ("regret", "L", "W", "p", "wbar"):
         scale = max(1.0, float(np.abs(whole[k]).max()))
         np.testing.assert_allclose(odd[k], whole[k], rtol=0, atol=2e-6 * scale, err_msg=k)
-    monkeypatch.setenv("OCO_SPARSE_LPW", "64")
-    _check_sparse_optimistic(wl, data, _gpu(wl, data), "c5 optimistic lpw=64 %s" % over)
+    _check_sparse_optimistic(wl, data, _gpu(wl, data, options=dict(sparse_lpw=64)), "c5 optimistic lpw=64 %s" % over)
 
 
 def test_sparse_optimistic_rounds_with_pipelined_windows():
@@ -301,10 +299,10 @@ def test_accel_bounds_match_the_oracle():
 
 
 @pytest.mark.parametrize("lpw", [4, 8, 16, 32, 64])
-def test_sparse_rounds_for_every_workgroup_share(lpw, monkeypatch):
+def test_sparse_rounds_for_every_workgroup_share(lpw):
     """The sparse kernel gives a workgroup 4, 8, 16, 32 or 64 learners (chosen from R*K; small
-    cases always get 4).  OCO_SPARSE_LPW forces a share, read at every launch."""
-    monkeypatch.setenv("OCO_SPARSE_LPW", str(lpw))
+    cases always get 4).  The option sparse_lpw forces a share."""
+    opt = dict(sparse_lpw=lpw)
     for over in (dict(T=700, R=20, d=512, K=5, nnz=8, wstar_nnz=16),
                  dict(T=300, R=9, d=4096, K=8, wstar_nnz=64),
                  dict(T=200, R=2, d=300, K=2, nnz=64, wstar_nnz=30, eta=(2.0, 400.0)),
@@ -312,27 +310,24 @@ def test_sparse_rounds_for_every_workgroup_share(lpw, monkeypatch):
         wl = WL.make("c5", **over)
         data = WL.generate(wl)
         print("case c5 lpw", lpw, over, flush=True)
-        _check(wl, data, _gpu(wl, data), norm_every=0, label="c5 lpw=%d %s" % (lpw, over))
+        _check(wl, data, _gpu(wl, data, options=opt), norm_every=0, label="c5 lpw=%d %s" % (lpw, over))
 
 
 @pytest.mark.parametrize("lpw", [4, 32])
-def test_sparse_rounds_without_the_window_pipeline(lpw, monkeypatch):
+def test_sparse_rounds_without_the_window_pipeline(lpw):
     """Where the LDS has no room for three staged windows (64 learners per workgroup, or many
-    entries per round) the windows run gather, rounds, steps one after the other;
-    OCO_SPARSE_PIPE=0 takes that path for any share.  Both paths agree with the oracle; between
+    entries per round) the windows run gather, rounds, steps one after the other; the option
+    sparse_pipe=0 takes that path for any share.  Both paths agree with the oracle; between
     them only float32 rounding differs (a window's inner products are taken before or after
     the previous window's steps)."""
-    monkeypatch.setenv("OCO_SPARSE_LPW", str(lpw))
     for over in (dict(T=700, R=5, d=512, K=5, nnz=8, wstar_nnz=16),
                  dict(T=2300, R=3, d=4096, K=8, wstar_nnz=64),
                  dict(T=300, R=2, d=300, K=2, nnz=64, wstar_nnz=30, eta=(2.0, 400.0))):
         wl = WL.make("c5", **over)
         data = WL.generate(wl)
-        piped = _gpu(wl, data)
-        monkeypatch.setenv("OCO_SPARSE_PIPE", "0")
+        piped = _gpu(wl, data, options=dict(sparse_lpw=lpw))
         print("case c5 no pipeline lpw", lpw, over, flush=True)
-        plain = _gpu(wl, data)
-        monkeypatch.delenv("OCO_SPARSE_PIPE")
+        plain = _gpu(wl, data, options=dict(sparse_lpw=lpw, sparse_pipe=0))
         _check(wl, data, plain, norm_every=0, label="c5 no pipeline lpw=%d %s" % (lpw, over))
         for k in ("regret", "L", "W", "p", "wbar"):
             scale = max(1.0, float(np.abs(plain[k]).max()))
@@ -340,30 +335,29 @@ def test_sparse_rounds_without_the_window_pipeline(lpw, monkeypatch):
 
 
 @pytest.mark.parametrize("lpw", [4, 16, 64])
-def test_sparse_rounds_with_steps_far_larger_than_the_ball(lpw, monkeypatch):
+def test_sparse_rounds_with_steps_far_larger_than_the_ball(lpw):
     """Steps hundreds of times the radius make the lazy scale shrink by a constant factor every
     round: it falls below the in-kernel fold threshold many times inside one launch segment, and
     the workgroup folds its columns (all wavefronts, ragged row count) and goes on.  Same state
     whether the rounds come in one call or in calls of 128."""
-    monkeypatch.setenv("OCO_SPARSE_LPW", str(lpw))
+    opt = dict(sparse_lpw=lpw)
     wl = WL.make("c5", T=500, R=5, d=6007, K=4, wstar_nnz=64, eta=(0.5, 8.0, 100.0, 2000.0))
     data = WL.generate(wl)
     print("case c5 big steps lpw", lpw, flush=True)
-    whole = _gpu(wl, data)
+    whole = _gpu(wl, data, options=opt)
     _check(wl, data, whole, norm_every=0, label="c5 big steps lpw=%d" % lpw)
-    part = _gpu(wl, data, chunk=128, n_max=128)
+    part = _gpu(wl, data, chunk=128, n_max=128, options=opt)
     for k in ("regret", "L", "W", "p", "wbar"):
         assert np.array_equal(whole[k], part[k]), k
     wl = WL.make("c5", T=300, R=2, d=400, K=3, nnz=16, wstar_nnz=30, eta=(1.0, 50.0, 3000.0), optimistic=True)
     data = WL.generate(wl)
-    _check_sparse_optimistic(wl, data, _gpu(wl, data), "c5 optimistic big steps lpw=%d" % lpw)
+    _check_sparse_optimistic(wl, data, _gpu(wl, data, options=opt), "c5 optimistic big steps lpw=%d" % lpw)
 
 
 @pytest.mark.parametrize("lpw", [4, 8, 64])
-def test_sparse_rounds_with_a_column_in_every_round(lpw, monkeypatch):
+def test_sparse_rounds_with_a_column_in_every_round(lpw):
     """A feature present in every round (a bias column) makes every pair of rounds of a window
     collide and puts 64 equal columns next to each other in the scatter order."""
-    monkeypatch.setenv("OCO_SPARSE_LPW", str(lpw))
     wl = WL.make("c5", T=400, R=3, d=2048, K=4, wstar_nnz=32)
     data = WL.generate(wl)
     col = data["col"]
@@ -373,7 +367,7 @@ def test_sparse_rounds_with_a_column_in_every_round(lpw, monkeypatch):
         col[t, t % wl.nnz] = wl.d - 1
     assert all(len(np.unique(col[t])) == wl.nnz for t in range(wl.T))
     print("case c5 bias column lpw", lpw, flush=True)
-    _check(wl, data, _gpu(wl, data), norm_every=0, label="c5 bias column lpw=%d" % lpw)
+    _check(wl, data, _gpu(wl, data, options=dict(sparse_lpw=lpw)), norm_every=0, label="c5 bias column lpw=%d" % lpw)
 
 
 @pytest.mark.parametrize("name,over,chunks", [
@@ -412,7 +406,7 @@ def test_results_do_not_depend_on_how_the_horizon_is_cut(name, over, chunks):
     ("c3", dict(T=2200, R=2, d=320, K=3, seg_len=500, optimistic=True)),
     ("c5", dict(T=4500, R=3, d=4096, K=8, wstar_nnz=64)),
 ])
-def test_results_do_not_depend_on_how_a_call_is_enqueued(name, over, monkeypatch):
+def test_results_do_not_depend_on_how_a_call_is_enqueued(name, over):
     """One call may go to the GPU as several launches, with the meta kernel of a piece on a
     second stream beside the round kernels of the next: the state is bit-identical to the one
     of a single launch followed by a single meta kernel, and to the timed path."""
@@ -420,17 +414,13 @@ def test_results_do_not_depend_on_how_a_call_is_enqueued(name, over, monkeypatch
     data = WL.generate(wl)
     _check(wl, data, _gpu(wl, data), norm_every=0 if wl.nnz else None, label="%s enqueue" % name)
     base = _gpu(wl, data)
-    variants = [dict(OCO_META_BESIDE="0"), dict(OCO_DENSE_PIECES="1"), dict(OCO_DENSE_PIECES="5"),
-                dict(OCO_DENSE_PIECES="3", OCO_META_BESIDE="0")]
-    for env in variants:
-        for k, v in env.items():
-            monkeypatch.setenv(k, v)
-        print("case", name, over, env, flush=True)
-        got = _gpu(wl, data)
-        for k in env:
-            monkeypatch.delenv(k)
+    variants = [dict(meta_beside=0), dict(dense_pieces=1), dict(dense_pieces=5),
+                dict(dense_pieces=3, meta_beside=0)]
+    for opt in variants:
+        print("case", name, over, opt, flush=True)
+        got = _gpu(wl, data, options=opt)
         for k in ("regret", "L", "W", "p", "wbar"):
-            assert np.array_equal(base[k], got[k]), (k, env)
+            assert np.array_equal(base[k], got[k]), (k, opt)
     sim = B.Simulation(wl, data)
     B.oco_set_timing(sim.h, True)
     sim.run_all(0)
@@ -537,28 +527,35 @@ def test_user_stream_is_honoured():
 
 # ---------------------------------------------------------------- full sizes ----
 FULL = [
-    ("c1", None, None, False),
-    ("c2", None, None, False),
-    ("c3", [0, 37, 101, 128, 199, 255], None, False),
-    ("c4", [0, 1, 333, 512, 800, 1023], None, False),
-    ("c5", [0, 15], 1000, False),
-    ("c2", None, None, True),
-    ("c3", [0, 64, 255], None, True),
-    ("c4", [0, 511, 1023], None, True),
-    ("c5", [3, 12], 1000, True),
+    ("c1", None, None, False, None),
+    ("c2", None, None, False, None),
+    ("c3", [0, 37, 101, 128, 199, 255], None, False, None),
+    ("c4", [0, 1, 333, 512, 800, 1023], None, False, None),
+    ("c5", [0, 15], 1000, False, None),
+    ("c2", None, None, True, None),
+    ("c3", [0, 64, 255], None, True, None),
+    ("c4", [0, 511, 1023], None, True, None),
+    ("c5", [3, 12], 1000, True, None),
+    # c3 and c4 on each of the dense kernels by name (the default picks one of them), and c4 with
+    # its iterates streamed from HBM every window
+    ("c3", [5, 250], None, False, dict(dense_path=1)),
+    ("c3", [5, 250], None, False, dict(dense_path=2)),
+    ("c4", [7, 1000], None, False, dict(dense_path=1)),
+    ("c4", [7, 1000], None, False, dict(dense_path=2)),
+    ("c4", [7, 1000], None, False, dict(dense_path=2, window_resident=0)),
 ]
 
 
-@pytest.mark.parametrize("name,runs,norm_every,optimistic", FULL)
-def test_benchmark_configurations_match_the_oracle(name, runs, norm_every, optimistic):
+@pytest.mark.parametrize("name,runs,norm_every,optimistic,options", FULL)
+def test_benchmark_configurations_match_the_oracle(name, runs, norm_every, optimistic, options):
     """The five benchmark configurations at full size, in the launch configuration the bench
     times (one oco_run_rounds call for the whole horizon); the oracle recomputes every output
     of the listed runs.  Every configuration the bench reports, also with the optimistic update."""
     wl = WL.make(name, optimistic=optimistic)
     print("generating", name, flush=True)
     data = WL.generate(wl)
-    print("gpu", name, flush=True)
-    got = _gpu(wl, data)
+    print("gpu", name, options, flush=True)
+    got = _gpu(wl, data, options=options)
     print("oracle", name, runs, flush=True)
     _check(wl, data, got, runs=runs, norm_every=norm_every, label=name)
     if name == "c1":
