@@ -138,6 +138,21 @@ size_t oco_workspace_bytes(const oco_config *cfg);
 int oco_create(const oco_config *cfg, void *dev_ws, size_t ws_bytes, void *hip_stream,
                oco_state **out);
 
+/* The same as oco_create for callers that cannot provide (or allocate) a workspace: code that
+ * runs where hipMalloc is not allowed -- under HIP graph capture, inside a serving loop, in a
+ * harness that forbids allocation.  The state, the predictions of a call and the kernels'
+ * scratch live in a device array of OCO_STATIC_WS_BYTES that is part of the library's image
+ * (one copy per GPU, held until the process ends); a configuration whose oco_workspace_bytes
+ * exceeds that returns OCO_ENOMEM (lower n_max to make it fit).  The call allocates no device
+ * memory, creates no stream or event (work of a call that could run beside the round kernels
+ * stays in line, and oco_set_timing is refused with OCO_EUNSUPPORTED) and touches the device
+ * only with the kernel that zeroes the state.  Inputs and outputs stay the caller's, as in
+ * every other call.  All states created this way on one GPU share the one array: a second
+ * oco_create_static (or oco_reset) overwrites the first state's memory, and calls on two such
+ * states that overlap in time race.  Results are identical to those of oco_create. */
+#define OCO_STATIC_WS_BYTES (64u << 20)
+int oco_create_static(const oco_config *cfg, void *hip_stream, oco_state **out);
+
 /* Tuning choices of a state: which of several equivalent kernels or launch shapes a call uses.
  * value -1 (the default of every key) leaves the choice to the library.  Results agree with the
  * reference to the stated tolerances under every choice; choices that change how float32 sums

@@ -21,8 +21,9 @@ LOSS_ID = {"linear": 0, "squared": 1, "logistic": 2}
 # oco_option keys (include/oco.h)
 OPT = dict(meta_beside=0, dense_path=1, dense_wpb=2, comparator_gemm=3, dense_half=4, dense_pieces=5,
            sparse_lpw=6, sparse_pipe=7, verbose=8, window_resident=9, window_waves=10)
+OCO_STATIC_WS_BYTES = 64 << 20
 EXPORTS = ("oco_step_grid", "oco_paper_num_learners", "oco_workspace_bytes", "oco_create",
-           "oco_set_option",
+           "oco_create_static", "oco_set_option",
            "oco_set_comparator", "oco_run_rounds", "oco_regret", "oco_get_state",
            "oco_cum_losses", "oco_accel_bounds", "oco_reset", "oco_set_timing", "oco_last_timing", "oco_rounds_done", "oco_destroy", "oco_strerror",
            "sd_verify", "sd_acceptance", "sd_strerror")
@@ -70,6 +71,8 @@ def lib() -> C.CDLL:
         L.oco_workspace_bytes.argtypes = [C.POINTER(OcoConfig)]
         L.oco_create.restype = C.c_int
         L.oco_create.argtypes = [C.POINTER(OcoConfig), vp, C.c_size_t, vp, C.POINTER(vp)]
+        L.oco_create_static.restype = C.c_int
+        L.oco_create_static.argtypes = [C.POINTER(OcoConfig), vp, C.POINTER(vp)]
         L.oco_set_option.restype = C.c_int
         L.oco_set_option.argtypes = [vp, C.c_int, i64]
         L.oco_set_comparator.restype = C.c_int
@@ -157,6 +160,14 @@ def oco_create(cfg: OcoConfig, ws, stream=None) -> int:
     return h.value
 
 
+def oco_create_static(cfg: OcoConfig, stream=None) -> int:
+    """The same state in the library's own device array (no workspace from the caller)."""
+    h = C.c_void_p()
+    sp = None if stream is None else stream.cuda_stream
+    _check(lib().oco_create_static(C.byref(cfg), sp, C.byref(h)), "oco_create_static")
+    return h.value
+
+
 def oco_set_option(h: int, key, value: int) -> None:
     """key: an oco_option number or its name in OPT."""
     k = OPT[key] if isinstance(key, str) else int(key)
@@ -232,7 +243,8 @@ class Simulation:
     arithmetic happens inside oco_run_rounds / oco_get_state; this class only uploads the
     arrays, slices them by pointer arithmetic and downloads results."""
 
-    def __init__(self, wl, data, n_max: int = 0, device: str = "cuda:0", stream=None, options=None):
+    def __init__(self, wl, data, n_max: int = 0, device: str = "cuda:0", stream=None, options=None,
+                 static: bool = False):
         import torch
         self.torch = torch
         self.wl = wl
@@ -247,8 +259,12 @@ class Simulation:
         nbytes = oco_workspace_bytes(self.cfg)
         if nbytes == 0:
             raise OcoError(OCO_EINVAL, "oco_workspace_bytes")
-        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
-        self.h = oco_create(self.cfg, self.ws, stream)
+        if static:
+            self.ws = None
+            self.h = oco_create_static(self.cfg, stream)
+        else:
+            self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+            self.h = oco_create(self.cfg, self.ws, stream)
         for k, v in (options or {}).items():
             oco_set_option(self.h, k, v)
         oco_set_comparator(self.h, self.u, self.seg_start)

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -156,7 +157,29 @@ struct oco_state {
 
 namespace {
 
-// Builds the host object on a validated layout: `side_stream` says whether the state gets a
+// Workspace of oco_create_static: part of the library's image, one copy per GPU.  In host code
+// the array's name only stands for the symbol; the device address comes from
+// hipGetSymbolAddress, once per device, and only that pointer is ever handed to kernels.
+__device__ __align__(256) unsigned char scratch[OCO_STATIC_WS_BYTES];
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];      // per device; null until looked up
+std::mutex g_scratch_mu;
+
+// Device address of this GPU's copy of `scratch` (null on error).
+void *static_workspace()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+// Common part of oco_create and oco_create_static: `side_stream` says whether the state gets a
 // second stream (and the event that joins it) for work beside the round kernels.
 int create_on(const oco_config *cfg, const Layout &l, void *dev_ws, void *hip_stream, bool side_stream,
               oco_state **out)
@@ -235,6 +258,21 @@ int oco_create(const oco_config *cfg, void *dev_ws, size_t ws_bytes, void *hip_s
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return OCO_EHIP;
     return create_on(cfg, l, dev_ws, hip_stream, true, out);
+}
+
+int oco_create_static(const oco_config *cfg, void *hip_stream, oco_state **out)
+{
+    if (!out) return OCO_EINVAL;
+    *out = nullptr;
+    Layout l;
+    int rc = validate_and_layout(cfg, &l);
+    if (rc != OCO_OK) return rc;
+    if (l.total > (size_t)OCO_STATIC_WS_BYTES) return OCO_ENOMEM;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return OCO_EHIP;
+    void *ws = static_workspace();
+    if (!ws) return OCO_EHIP;
+    return create_on(cfg, l, ws, hip_stream, false, out);
 }
 
 int oco_set_option(oco_state *st, int key, int64_t value)
@@ -473,6 +511,7 @@ int oco_get_state(oco_state *st, float *W_dev, float *p_dev, float *wbar_dev)
 int oco_set_timing(oco_state *st, int enable)
 {
     if (!st) return OCO_EINVAL;
+    if (enable && st->is_static) return OCO_EUNSUPPORTED;     // would create events
     if (enable)
         for (auto &e : st->ev)
             if (!e && hipEventCreate(&e) != hipSuccess) return OCO_EHIP;

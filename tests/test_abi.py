@@ -117,6 +117,26 @@ def test_create_rejects_bad_arguments_on_the_host():
     L.oco_destroy(None)
 
 
+def test_static_create_rejects_bad_arguments_and_oversize_configs_on_the_host():
+    L = B.lib()
+    h = C.c_void_p()
+    cfg, keep = _cfg()
+    assert L.oco_create_static(C.byref(cfg), None, None) == B.OCO_EINVAL
+    assert L.oco_create_static(None, None, C.byref(h)) == B.OCO_EINVAL
+    bad, keep2 = _cfg(d=4097)
+    assert L.oco_create_static(C.byref(bad), None, C.byref(h)) == B.OCO_EUNSUPPORTED
+    # a state larger than the library's own device array: refused before any device call
+    big, keep3 = _cfg(d=4096, K=16, R=1024, eta=[0.1] * 16)
+    assert B.oco_workspace_bytes(big) > B.OCO_STATIC_WS_BYTES
+    assert L.oco_create_static(C.byref(big), None, C.byref(h)) == B.OCO_ENOMEM
+    # ... and one whose state fits but whose call size does not, until n_max is lowered
+    mid, keep4 = _cfg(d=100, K=15, R=64, T=100000, eta=[0.1] * 15, x_shared=False)
+    assert L.oco_create_static(C.byref(mid), None, C.byref(h)) == B.OCO_ENOMEM
+    mid.n_max = 4096
+    assert 0 < B.oco_workspace_bytes(mid) <= B.OCO_STATIC_WS_BYTES
+    assert h.value is None
+
+
 def test_specdec_host_validation():
     L = B.lib()
     one = C.c_void_p(256)          # any non-null, aligned address: rejected before it is touched
