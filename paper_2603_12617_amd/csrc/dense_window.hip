@@ -23,7 +23,7 @@
 //
 // Where the tile's iterates fit in the registers of a workgroup (d <= 4096: eight wavefronts,
 // each with every eighth block of 16 coordinates, in the layout the matrix instruction writes:
-// a lane holds 4 coordinates of one learner) they stay there for the whole call and the only
+// a lane holds 4 coordinates of one learner) they stay there for a whole launch and the only
 // memory traffic is the round stream (from L2: every tile reads the same rows).  Otherwise the
 // same sweep loads each 16 x 16 block from HBM, updates it, takes its share of the next
 // window's inner products and writes it back: 8 bytes per coordinate, learner and window, all
@@ -33,7 +33,16 @@
 // A[l % 16][l / 16] and B[l / 16][l % 16] and holds D[4 (l / 16) + r][l % 16] in register r.
 // A block of iterates is kept as the transposed 16 coordinates x 16 learners D tile, so that
 // register r of it is at once the B operand of (1) for the depth indices k <-> coordinate 4 k + r
-// (the order of the terms of an inner product is free; the round rows are loaded to match).
+// (the order of the terms of an inner product is free; the round rows are laid out to match).
+//
+// The round rows as operands.  In (1) a lane holds (round l % 16, four coordinates): read from
+// the stream, neighbouring lanes would sit in different rows, 16 bytes each.  A pre-pass
+// therefore re-tiles the stream once per launch: per window and block of 16 coordinates, 4 KB in
+// the order the lanes of (1) want them and 4 KB in the order the lanes of (3) want them (lane:
+// coordinate l % 16, sixteen rounds), so that every load of the sweep is 16 bytes per lane and
+// 1 KB contiguous per instruction, rows past a window's length and coordinates past d already
+// zero.  A call is worked in pieces of at most 64 MB of stream so that the two copies stay a
+// bounded scratch (and, with the piece itself, inside the last-level cache for every tile).
 //
 // Windows end at the multiples of 64 of the horizon; a call that starts or ends elsewhere has
 // shorter first / last windows.
@@ -52,8 +61,17 @@ constexpr int kB = 64;            // rounds per window
 constexpr int kM = 16;            // learners per tile
 constexpr int kNW = 8;            // wavefronts per workgroup
 constexpr int kGStride = 18;      // doubles per (round, quad lane) row of the masked Gram table (16 + padding)
+constexpr int64_t kPieceBytes = 64ll << 20;   // stream per launch (each tiled copy is as large)
+constexpr int kTileFloats = kB * 16;          // one window x one block of 16 coordinates
 
 typedef float f4 __attribute__((ext_vector_type(4)));
+
+#ifdef OCO_WIN_PROF
+__device__ unsigned long long g_win_prof[8];
+#define PROF_T(i) do { if (threadIdx.x == 0) { const unsigned long long now_ = wall_clock64(); prof_[i] += now_ - last_; last_ = now_; } } while (0)
+#else
+#define PROF_T(i) do { } while (0)
+#endif
 
 struct WinPlanD {
     int64_t t0;      // absolute round of the call's first round
@@ -71,65 +89,92 @@ template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
     return -y * __builtin_amdgcn_rcpf(1.0f + __expf(y * z));
 }
 
-// ---- pre-pass: G = X_w X_w^T of every window of the call --------------------------------------
-// One workgroup of four wavefronts per window; wavefront v computes rows 16 v .. 16 v + 15 of G
-// (four 16 x 16 blocks), depth in steps of 16 coordinates.  Rows past the window's length and
-// coordinates past d enter as zeros.  Fixed summation order.
-__global__ void __launch_bounds__(256) dense_gram_kernel(const float *x, int d, WinPlanD plan, float *gram)
+// ---- pre-pass 1: the round rows of the windows w0 .. w0 + gridDim.y - 1, re-tiled ----------------
+// One wavefront per (window, block of 16 coordinates).  xq[((w - w0) nblk + blk) 1024 + (rb 64 + l) 4 + r]
+// = x[round 16 rb + l % 16][coordinate 16 blk + 4 (l / 16) + r], xu[... + (k 64 + l) 4 + r]
+// = x[round 4 (4 k + r) + l / 16][coordinate 16 blk + l % 16]; zero past the window or past d.
+__global__ void __launch_bounds__(64) dense_tile_kernel(const float *x, int d, WinPlanD plan, int w0, float *xq, float *xu)
 {
-    const int w = blockIdx.x;
+    const int blk = blockIdx.x, w = w0 + blockIdx.y;
+    const int nblk = gridDim.x;
     const int ws = plan.start(w), wl = plan.len(w);
+    const int l = threadIdx.x, lr = l & 15, lk = l >> 4;
+    const int64_t tile = ((int64_t)blockIdx.y * nblk + blk) * kTileFloats;
+    const float *xw = x + (int64_t)ws * d + blk * 16;
+    {
+        const int c = blk * 16 + 4 * lk;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            const int t = rb * 16 + lr;
+            f4 v = f4{0.f, 0.f, 0.f, 0.f};
+            if (c < d && t < wl) v = *reinterpret_cast<const f4 *>(xw + (int64_t)t * d + 4 * lk);
+            *reinterpret_cast<f4 *>(xq + tile + (rb * 64 + l) * 4) = v;
+        }
+    }
+    {
+        const int c = blk * 16 + lr;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            f4 v;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int t = 4 * (4 * k + r) + lk;
+                v[r] = (c < d && t < wl) ? xw[(int64_t)t * d + lr] : 0.f;
+            }
+            *reinterpret_cast<f4 *>(xu + tile + (k * 64 + l) * 4) = v;
+        }
+    }
+}
+
+// ---- pre-pass 2: G = X_w X_w^T of the same windows, from the tiled rows ------------------------------
+// One workgroup of four wavefronts per window; wavefront v computes rows 16 v .. 16 v + 15 of G
+// (four 16 x 16 blocks), depth block by block.  Fixed summation order.
+__global__ void __launch_bounds__(256) dense_gram_kernel(const float *xq, int nblk, float *gram)
+{
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lr = lane & 15, lk = lane >> 4;
     f4 acc[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[b] = f4{0.f, 0.f, 0.f, 0.f};
-    const int rowa = wave * 16 + lr;
-    const float *xa = x + (int64_t)(ws + (rowa < wl ? rowa : 0)) * d;
-    const float *xb[4];
+    const float *xw = xq + (int64_t)blockIdx.x * nblk * kTileFloats + lane * 4;
+    for (int blk = 0; blk < nblk; ++blk) {
+        f4 bv[4];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        const int rowb = b * 16 + lr;
-        xb[b] = x + (int64_t)(ws + (rowb < wl ? rowb : 0)) * d;
-    }
-    for (int c0 = 0; c0 < d; c0 += 16) {
-        const int c = c0 + 4 * lk;
-        const bool in = c < d;
-        f4 av = f4{0.f, 0.f, 0.f, 0.f}, bv[4];
-        if (in && rowa < wl) av = *reinterpret_cast<const f4 *>(xa + c);
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            bv[b] = f4{0.f, 0.f, 0.f, 0.f};
-            if (in && b * 16 + lr < wl) bv[b] = *reinterpret_cast<const f4 *>(xb[b] + c);
-        }
+        for (int b = 0; b < 4; ++b) bv[b] = *reinterpret_cast<const f4 *>(xw + (int64_t)blk * kTileFloats + b * 256);
+        const f4 av = wave == 0 ? bv[0] : wave == 1 ? bv[1] : wave == 2 ? bv[2] : bv[3];
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int b = 0; b < 4; ++b)
                 acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[r], bv[b][r], acc[b], 0, 0, 0);
     }
-    float *g = gram + (int64_t)w * kB * kB;
+    float *g = gram + (int64_t)blockIdx.x * kB * kB;
 #pragma unroll
     for (int b = 0; b < 4; ++b)
 #pragma unroll
         for (int r = 0; r < 4; ++r) g[(wave * 16 + 4 * lk + r) * kB + b * 16 + lr] = acc[b][r];
 }
 
-// LDS of the window kernel (dynamic), in bytes from the base
+// LDS of the window kernel (dynamic), in bytes from the base.  The Gram table, its diagonal and
+// the labels have two buffers: the next window's are staged while this window's are in use.
 struct Lds {
-    static constexpr int gd = 0;                                   // double [64][4][kGStride]: G[t][t2], zero for t2 <= t
-    static constexpr int x2 = gd + kB * 4 * kGStride * 8;          // double [64]: G[t][t]
-    static constexpr int q0 = x2 + kB * 8;                         // double [64][16]: <w_s, x_t>
+    static constexpr int gd_bytes = kB * 4 * kGStride * 8;         // double [64][4][kGStride]: G[t][t2], zero for t2 <= t
+    static constexpr int x2_bytes = kB * 8;                        // double [64]: G[t][t]
+    static constexpr int yb_bytes = kB * kM * 4;                   // float [64][16]: labels
+    static constexpr int gd = 0;
+    static constexpr int x2 = gd + 2 * gd_bytes;
+    static constexpr int yb = x2 + 2 * x2_bytes;
+    static constexpr int q0 = yb + 2 * yb_bytes;                   // double [64][16]: <w_s, x_t>
     static constexpr int fl = q0 + kB * kM * 8;                    // double [64][16]: f_t
     static constexpr int part = fl + kB * kM * 8;                  // float [kNW][64][16]: per-wavefront shares of Q0
-    static constexpr int yb = part + kNW * kB * kM * 4;            // float [64][16]: labels
-    static constexpr int zb = yb + kB * kM * 4;                    // float [64][16]: predictions
+    static constexpr int zb = part + kNW * kB * kM * 4;            // float [64][16]: predictions
     static constexpr int st = zb + kB * kM * 4;                    // float [64][16]: a_t
     static constexpr int bm = st + kB * kM * 4;                    // float [64][16]: -Bm
     static constexpr int fv = bm + kB * kM * 4;                    // float [16]: F
     static constexpr int n2 = fv + kM * 4;                         // float [kNW][4][16]: shares of ||w||^2
     static constexpr int total = n2 + kNW * 4 * kM * 4;
 };
+static_assert(Lds::total <= 160 * 1024, "LDS of a gfx950 compute unit");
 
 // every lane of a quad gets the value of the quad's lane SEL
 template <int SEL> __device__ __forceinline__ double quad_bcast(double v)
@@ -160,14 +205,14 @@ template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
 // missing rounds as rounds without a step (a = 0, so f = 1 and no pending prediction moves; their
 // rows of G are zero).
 template <int LOSS>
-__device__ __forceinline__ void chain_window(char *lds, int lane, int wl, float eta, double D, double sig, double n2)
+__device__ __forceinline__ void chain_window(char *lds, int buf, int lane, int wl, float eta, double D, double sig, double n2)
 {
     const int lc = lane >> 2, s = lane & 3;
-    const double *gd = reinterpret_cast<const double *>(lds + Lds::gd) + s * kGStride;
-    const double *x2d = reinterpret_cast<const double *>(lds + Lds::x2);
+    const double *gd = reinterpret_cast<const double *>(lds + Lds::gd + buf * Lds::gd_bytes) + s * kGStride;
+    const double *x2d = reinterpret_cast<const double *>(lds + Lds::x2 + buf * Lds::x2_bytes);
     const double *q0d = reinterpret_cast<const double *>(lds + Lds::q0) + s * kM + lc;
     double *fl = reinterpret_cast<double *>(lds + Lds::fl) + lc;
-    const float *yb = reinterpret_cast<const float *>(lds + Lds::yb) + lc;
+    const float *yb = reinterpret_cast<const float *>(lds + Lds::yb + buf * Lds::yb_bytes) + lc;
     float *zb = reinterpret_cast<float *>(lds + Lds::zb) + lc;
     float *stl = reinterpret_cast<float *>(lds + Lds::st) + lc;
     const double D2 = D * D;
@@ -232,7 +277,6 @@ __device__ __forceinline__ void chain_window(char *lds, int lane, int wl, float 
 // addresses that follow from it) is kept alive across the dependent rounds.
 struct Geo {
     int tid, lane, wave, lr, lk;
-    int qofs, uofs;            // per-lane offsets of the round-row loads (floats)
     bool q_ok;                 // this lane's learner exists
     float *vrow;               // its row of the iterates, at this lane's 4 coordinates of a block
 };
@@ -244,26 +288,24 @@ __device__ __forceinline__ Geo make_geo(int tid, const DenseArgs &a)
     g.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     g.lr = g.lane & 15;
     g.lk = g.lane >> 4;
-    g.qofs = g.lr * a.d + 4 * g.lk;
-    g.uofs = g.lk * a.d + g.lr;
     const int q = (int)blockIdx.x * kM + g.lr;
     g.q_ok = q < a.R * a.K;
     g.vrow = a.V + (int64_t)(g.q_ok ? q : 0) * a.d + 4 * g.lk;
     return g;
 }
 
-// RES: the tile's iterates stay in registers for the whole call (d <= 16 * kNW * NB); otherwise
+// The windows w0 .. w0 + nw - 1 of the call's plan; xq / xu / gram hold those windows only.
+// RES: the tile's iterates stay in registers for the whole launch (d <= 16 * kNW * NB); otherwise
 // every block is loaded and stored in the sweep.
 template <int LOSS, int NB, bool RES>
-__global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArgs a, const float *gram, WinPlanD plan)
+__global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArgs a, const float *gram, const float *xq,
+                                                                   const float *xu, WinPlanD plan, int w0, int nw)
 {
     constexpr bool BMR = !(RES && NB > 8);     // -Bm in registers for the whole sweep, or re-read from LDS per block
     extern __shared__ __align__(16) char lds[];
     const int d = a.d, K = a.K;
     const int nq = a.R * K;
     const int nblk = (d + 15) / 16;                             // blocks of 16 coordinates
-    const int nwin = plan.count();
-    const float *x = a.x;
 
     // the tile's iterates: block (wave + 8 b) of 16 coordinates x 16 learners, transposed
     auto ld_block = [&](const Geo &g, int blk) __attribute__((always_inline)) {
@@ -274,58 +316,34 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
     auto st_block = [&](const Geo &g, int blk, const f4 &v) __attribute__((always_inline)) {
         if (g.q_ok && blk * 16 + 4 * g.lk < d) *reinterpret_cast<f4 *>(g.vrow + blk * 16) = v;
     };
-    // round rows as the matrix instruction wants them
-    //   for (1): lane (round l % 16 of a group of 16, coordinates 4 (l / 16) .. + 3 of the block)
-    //   for (3): lane (coordinate l % 16 of the block, round l / 16 of a group of 4)
-    // A full window and a block inside d need no guards: one address per wavefront (scalar) plus a
-    // fixed per-lane offset.  Ragged windows / the last block of a d that is no multiple of 16 take
-    // the guarded loads (rows past the window and coordinates past d enter as zeros).
-    auto ldq = [&](const Geo &g, int ws, int wl, int blk, f4 (&o)[4]) __attribute__((always_inline)) {
-        if (wl == kB && blk * 16 + 16 <= d) {
-            const float *base = x + (int64_t)ws * d + blk * 16;
+    // the tiled round rows of window wi (relative to w0), block blk: four 16-byte loads per lane each
+    auto ldq = [&](const Geo &g, int wi, int blk, f4 (&o)[4]) __attribute__((always_inline)) {
+        const float *t = xq + ((int64_t)wi * nblk + blk) * kTileFloats + g.lane * 4;
 #pragma unroll
-            for (int rb = 0; rb < 4; ++rb) o[rb] = *reinterpret_cast<const f4 *>(base + (int64_t)(rb * 16) * d + g.qofs);
-        } else {
-            const int c = blk * 16 + 4 * g.lk;
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const int t = rb * 16 + g.lr;
-                o[rb] = f4{0.f, 0.f, 0.f, 0.f};
-                if (c < d && t < wl) o[rb] = *reinterpret_cast<const f4 *>(x + (int64_t)(ws + t) * d + c);
-            }
-        }
+        for (int rb = 0; rb < 4; ++rb) o[rb] = *reinterpret_cast<const f4 *>(t + rb * 256);
     };
-    auto ldu = [&](const Geo &g, int ws, int wl, int blk, float (&o)[16]) __attribute__((always_inline)) {
-        if (wl == kB && blk * 16 + 16 <= d) {
-            const float *base = x + (int64_t)ws * d + blk * 16;
+    auto ldu = [&](const Geo &g, int wi, int blk, f4 (&o)[4]) __attribute__((always_inline)) {
+        const float *t = xu + ((int64_t)wi * nblk + blk) * kTileFloats + g.lane * 4;
 #pragma unroll
-            for (int rs = 0; rs < 16; ++rs) o[rs] = base[(int64_t)(rs * 4) * d + g.uofs];
-        } else {
-            const int c = blk * 16 + g.lr;
-#pragma unroll
-            for (int rs = 0; rs < 16; ++rs) {
-                const int t = rs * 4 + g.lk;
-                o[rs] = (c < d && t < wl) ? x[(int64_t)(ws + t) * d + c] : 0.f;
-            }
-        }
+        for (int k = 0; k < 4; ++k) o[k] = *reinterpret_cast<const f4 *>(t + k * 256);
     };
-    // LDS inputs of window w's dependent rounds: labels, masked Gram table, its diagonal
-    auto stage_chain_inputs = [&](const Geo &g, int w) __attribute__((always_inline)) {
+    // LDS inputs of the dependent rounds of window wi: labels, masked Gram table, its diagonal.
+    // `nthr` threads numbered tid share the work.
+    auto stage_chain_inputs = [&](int tid, int nthr, int wi) __attribute__((always_inline)) {
+        const int w = w0 + wi, buf = wi & 1;
         const int ws = plan.start(w), wl = plan.len(w);
-        float *yb = reinterpret_cast<float *>(lds + Lds::yb);
-        double *gd = reinterpret_cast<double *>(lds + Lds::gd);
-        double *x2d = reinterpret_cast<double *>(lds + Lds::x2);
-        {
-            const int l16 = g.tid >> 5, t = g.tid & 31;         // 16 learners x 32 lanes, two rounds each
+        float *yb = reinterpret_cast<float *>(lds + Lds::yb + buf * Lds::yb_bytes);
+        double *gd = reinterpret_cast<double *>(lds + Lds::gd + buf * Lds::gd_bytes);
+        double *x2d = reinterpret_cast<double *>(lds + Lds::x2 + buf * Lds::x2_bytes);
+        for (int e = tid; e < kB * kM; e += nthr) {
+            const int l16 = e >> 6, t = e & 63;                 // a learner's 64 labels are contiguous
             const int q = (int)blockIdx.x * kM + l16;
-            const float *yrow = (a.y && q < nq) ? a.y + (int64_t)(q / K) * a.y_run_stride + ws : nullptr;
-            yb[t * kM + l16] = (yrow && t < wl) ? yrow[t] : 0.f;
-            yb[(t + 32) * kM + l16] = (yrow && t + 32 < wl) ? yrow[t + 32] : 0.f;
+            float yv = 0.f;
+            if (a.y && q < nq && t < wl) yv = a.y[(int64_t)(q / K) * a.y_run_stride + ws + t];
+            yb[t * kM + l16] = yv;
         }
-        const float *gsrc = gram + (int64_t)w * kB * kB;
-#pragma unroll
-        for (int u = 0; u < kB * kB / (kNW * kWave); ++u) {
-            const int e = g.tid + u * kNW * kWave;
+        const float *gsrc = gram + (int64_t)wi * kB * kB;
+        for (int e = tid; e < kB * kB; e += nthr) {
             const int t = e >> 6, t2 = e & 63;
             const float gv = gsrc[e];
             gd[(t * 4 + (t2 & 3)) * kGStride + (t2 >> 2)] = t2 > t ? (double)gv : 0.0;
@@ -358,18 +376,17 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
             for (int b = 0; b < NB; ++b) V[b] = ld_block(g, g.wave + kNW * b);
         }
         // ---- prologue: inner products of the first window ----------------------------------------
-        const int ws = plan.start(0), wl = plan.len(0);
         f4 acc[4];
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
         auto q_of = [&](const f4 &vb, int blk) __attribute__((always_inline)) {
-            f4 xq[4];
-            ldq(g, ws, wl, blk, xq);
+            f4 xr[4];
+            ldq(g, 0, blk, xr);
 #pragma unroll
             for (int r = 0; r < 4; ++r)
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb)
-                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xq[rb][r], vb[r], acc[rb], 0, 0, 0);
+                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[rb][r], vb[r], acc[rb], 0, 0, 0);
         };
         if constexpr (RES) {
             static_for<NB>([&](auto bc) __attribute__((always_inline)) {
@@ -381,12 +398,17 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
             for (int blk = g.wave; blk < nblk; blk += kNW) q_of(ld_block(g, blk), blk);
         }
         put_part(g, acc);
-        stage_chain_inputs(g, 0);
+        stage_chain_inputs(g.tid, kNW * kWave, 0);
     }
 
-    for (int w = 0; w < nwin; ++w) {
+#ifdef OCO_WIN_PROF
+    unsigned long long prof_[8] = {0, 0, 0, 0, 0, 0, 0, 0}, last_ = wall_clock64();
+#endif
+    for (int wi = 0; wi < nw; ++wi) {
+        const int w = w0 + wi;
         const int ws = plan.start(w), wl = plan.len(w);
         __syncthreads();                                         // (A) shares of Q0, labels, G in LDS
+        PROF_T(0);
         int tid_w = (int)threadIdx.x;
         asm volatile("" : "+v"(tid_w));                          // see Geo
         {
@@ -403,9 +425,11 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
             }
         }
         __syncthreads();                                         // (B)
+        PROF_T(1);
+        const bool more = wi + 1 < nw;
         if (__builtin_amdgcn_readfirstlane(tid_w >> 6) == 0) {
             const int lane = tid_w & 63;
-            if (w > 0) {
+            if (wi > 0) {
                 // ||w||^2 as the last sweep measured it: 32 shares per learner, fixed order
                 const float *n2s = reinterpret_cast<const float *>(lds + Lds::n2);
                 double m = 0.0;
@@ -417,9 +441,14 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
                 n2 = m;
                 sig = 1.0;
             }
-            chain_window<LOSS>(lds, lane, wl, eta, (double)a.D, sig, n2);
+            chain_window<LOSS>(lds, wi & 1, lane, wl, eta, (double)a.D, sig, n2);
+        } else if (more) {
+            // beside the dependent rounds: the next window's labels and Gram table into the other buffer
+            stage_chain_inputs(tid_w - kWave, (kNW - 1) * kWave, wi + 1);
         }
+        PROF_T(2);
         __syncthreads();                                         // (C) predictions, -Bm, F in LDS
+        PROF_T(3);
         asm volatile("" : "+v"(tid_w));
         const Geo g = make_geo(tid_w, a);
         const int lr = g.lr, lk = g.lk;
@@ -446,25 +475,34 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
             for (int rs = 0; rs < 16; ++rs) bmr[rs] = bml[(rs * 4 + lk) * kM + lr];
         }
         const float F = reinterpret_cast<const float *>(lds + Lds::fv)[lr];
-        const bool more = w + 1 < nwin;
-        const int ws1 = more ? plan.start(w + 1) : 0, wl1 = more ? plan.len(w + 1) : 0;
         f4 acc[4];
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
         float nn = 0.f;
-        struct BlkIn { float xu[16]; f4 xq[4]; f4 vb; };
+        struct BlkIn { f4 xu[4]; f4 xq[4]; f4 vb; };
         auto load_in = [&](BlkIn &in, int blk) __attribute__((always_inline)) {
-            ldu(g, ws, wl, blk, in.xu);
-            if (more) ldq(g, ws1, wl1, blk, in.xq);
-            if (!RES) in.vb = ld_block(g, blk);
+#ifdef OCO_WIN_NOLOAD
+            if (blk < 0) {
+#else
+            if (blk < nblk) {
+#endif
+                ldu(g, wi, blk, in.xu);
+                if (more) ldq(g, wi + 1, blk, in.xq);
+                if (!RES) in.vb = ld_block(g, blk);
+            }
         };
         auto compute = [&](BlkIn &in, f4 &vreg, int blk) __attribute__((always_inline)) {
             f4 vb = RES ? vreg : in.vb;
+            f4 vo = f4{0.f, 0.f, 0.f, 0.f};                      // two chains of eight dependent instructions
 #pragma unroll
             for (int r = 0; r < 4; ++r) vb[r] *= F;
 #pragma unroll
-            for (int rs = 0; rs < 16; ++rs)
-                vb = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs], BMR ? bmr[BMR ? rs : 0] : bml[(rs * 4 + lk) * kM + lr], vb, 0, 0, 0);
+            for (int rs = 0; rs < 16; rs += 2) {
+                vb = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs >> 2][rs & 3], BMR ? bmr[BMR ? rs : 0] : bml[(rs * 4 + lk) * kM + lr], vb, 0, 0, 0);
+                vo = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs >> 2][(rs & 3) + 1], BMR ? bmr[BMR ? rs + 1 : 0] : bml[((rs + 1) * 4 + lk) * kM + lr], vo, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) vb[r] += vo[r];
 #pragma unroll
             for (int r = 0; r < 4; ++r) nn = fmaf(vb[r], vb[r], nn);
             if (RES) vreg = vb; else st_block(g, blk, vb);
@@ -482,7 +520,7 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
             static_for<NB>([&](auto bc) __attribute__((always_inline)) {
                 constexpr int b = decltype(bc)::value;
                 const int blk = g.wave + kNW * b;
-                if (b + 1 < NB) load_in(in[(b + 1) & 1], blk + kNW);     // lanes past d load nothing
+                if (b + 1 < NB) load_in(in[(b + 1) & 1], blk + kNW);
                 __builtin_amdgcn_sched_barrier(0);
                 if (blk < nblk) compute(in[b & 1], V[b], blk);
                 __builtin_amdgcn_sched_barrier(0);
@@ -500,12 +538,15 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        PROF_T(4);
         reinterpret_cast<float *>(lds + Lds::n2)[(g.wave * 4 + lk) * kM + lr] = nn;
-        if (more) {
-            put_part(g, acc);
-            stage_chain_inputs(g, w + 1);
-        }
+        if (more) put_part(g, acc);
+        PROF_T(5);
     }
+#ifdef OCO_WIN_PROF
+    if (threadIdx.x == 0 && blockIdx.x == 0)
+        for (int i = 0; i < 8; ++i) g_win_prof[i] = prof_[i];
+#endif
 
     // ---- state out: the iterates themselves (scale 1) and their squared norms ---------------------
     {
@@ -528,26 +569,42 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
     }
 }
 
-template <int LOSS>
-hipError_t launch_window_kernel(const DenseArgs &a, const float *gram, const WinPlanD &plan, bool resident, hipStream_t s)
+using WindowKernel = void (*)(const DenseArgs, const float *, const float *, const float *, WinPlanD, int, int);
+
+template <int LOSS> WindowKernel pick_window_kernel(int nblk, bool resident)
 {
-    const int ntiles = (a.R * a.K + kM - 1) / kM;
-    const dim3 grid((unsigned)ntiles), block(kNW * kWave);
-    const int nblk = (a.d + 15) / 16;
-    void (*kern)(const DenseArgs, const float *, WinPlanD) = nullptr;
-    if (resident && nblk <= 8 * kNW) kern = dense_window_kernel<LOSS, 8, true>;
-    else if (resident && nblk <= 32 * kNW) kern = dense_window_kernel<LOSS, 32, true>;
-    else kern = dense_window_kernel<LOSS, 1, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       Lds::total);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, grid, block, Lds::total, s, a, gram, plan);
-    return hipGetLastError();
+    if (resident && nblk <= 8 * kNW) return dense_window_kernel<LOSS, 8, true>;
+    if (resident && nblk <= 32 * kNW) return dense_window_kernel<LOSS, 32, true>;
+    return dense_window_kernel<LOSS, 1, false>;
+}
+
+// scratch: Gram matrices of the windows of a piece, then the two tiled copies of its rows
+struct Scratch {
+    int64_t piece_windows;      // windows per launch
+    size_t gram_floats, tile_floats;
+    size_t total_floats() const { return gram_floats + 2 * tile_floats; }
+};
+Scratch scratch_layout(int64_t n_max, int64_t d)
+{
+    const int64_t nblk = (d + 15) / 16;
+    const int64_t win_bytes = nblk * kTileFloats * (int64_t)sizeof(float);
+    Scratch sc;
+    sc.piece_windows = std::max<int64_t>(1, std::min<int64_t>(kPieceBytes / win_bytes, n_max / kB + 2));
+    sc.gram_floats = (size_t)sc.piece_windows * kB * kB;
+    sc.tile_floats = (size_t)sc.piece_windows * nblk * kTileFloats;
+    return sc;
 }
 
 }  // namespace
 
-size_t dense_gram_bytes(int64_t n_max) { return (size_t)(n_max / kB + 2) * kB * kB * sizeof(float); }
+#ifdef OCO_WIN_PROF
+extern "C" int oco_debug_win_prof(unsigned long long *out)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_win_prof), sizeof(unsigned long long) * 8);
+}
+#endif
+
+size_t dense_gram_bytes(int64_t n_max, int64_t d) { return scratch_layout(n_max, d).total_floats() * sizeof(float); }
 
 bool dense_window_supported(const DenseArgs &a)
 {
@@ -561,7 +618,9 @@ bool dense_window_wanted(const DenseArgs &a)
     const int64_t path = a.tune->get(OCO_OPT_DENSE_PATH);
     if (path == 1) return a.d > 64 * kWave;                     // the register kernel cannot hold more
     if (path == 2) return true;
-    return a.d > 64 * kWave || ((int64_t)a.R * a.K >= 1024 && a.d >= 256);
+    // measured on MI355X: c4 (16384 learners, d = 4096) 72 ms against the register kernel's 136 ms; c3 (4352
+    // learners, d = 1000) 70 ms against 62 ms
+    return a.d > 64 * kWave || ((int64_t)a.R * a.K >= 2048 && a.d >= 2048);
 }
 
 hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, const PieceHook *hook)
@@ -572,26 +631,40 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
     if (!dense_window_supported(a)) return hipErrorInvalidValue;
     const WinPlanD plan{a.t0, a.n};
     const int nwin = plan.count();
-    hipLaunchKernelGGL(dense_gram_kernel, dim3((unsigned)nwin), dim3(256), 0, s, a.x, a.d, plan, a.gram);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const int nblk = (a.d + 15) / 16;
+    const Scratch sc = scratch_layout(a.n_max, a.d);
+    float *gram = a.gram, *xq = a.gram + sc.gram_floats, *xu = xq + sc.tile_floats;
     {
         ComparatorGemmArgs g{};
         g.x = a.x; g.u = a.u; g.seg_start = a.seg_start; g.S = a.S; g.Z = a.Z; g.zl = a.zl;
         g.d = a.d; g.K = a.K; g.R = a.R; g.t0 = a.t0; g.n = a.n; g.vec_ok = a.vec_ok;
-        e = launch_comparator_gemm(g, s);
+        hipError_t e = launch_comparator_gemm(g, s);
         if (e != hipSuccess) return e;
     }
     const bool resident = a.d <= 16 * kNW * 32 && a.tune->get(OCO_OPT_WINDOW_RESIDENT) != 0;
+    const int ntiles = (a.R * a.K + kM - 1) / kM;
     if (a.tune->get(OCO_OPT_VERBOSE) == 1)
-        fprintf(stderr, "dense plan: windowed contraction kernel, %d windows, %d tiles, iterates %s\n", nwin,
-                (a.R * a.K + kM - 1) / kM, resident ? "in registers" : "streamed from HBM");
+        fprintf(stderr, "dense plan: windowed contraction kernel, %d windows in pieces of %lld, %d tiles, iterates %s\n",
+                nwin, (long long)sc.piece_windows, ntiles, resident ? "in registers" : "streamed from HBM");
+    WindowKernel kern = nullptr;
     switch (loss) {
-        case 0: return launch_window_kernel<0>(a, a.gram, plan, resident, s);
-        case 1: return launch_window_kernel<1>(a, a.gram, plan, resident, s);
-        case 2: return launch_window_kernel<2>(a, a.gram, plan, resident, s);
+        case 0: kern = pick_window_kernel<0>(nblk, resident); break;
+        case 1: kern = pick_window_kernel<1>(nblk, resident); break;
+        case 2: kern = pick_window_kernel<2>(nblk, resident); break;
         default: return hipErrorInvalidValue;
     }
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       Lds::total);
+    if (e != hipSuccess) return e;
+    for (int w0 = 0; w0 < nwin; w0 += (int)sc.piece_windows) {
+        const int nw = std::min<int>((int)sc.piece_windows, nwin - w0);
+        hipLaunchKernelGGL(dense_tile_kernel, dim3((unsigned)nblk, (unsigned)nw), dim3(64), 0, s, a.x, a.d, plan, w0, xq, xu);
+        hipLaunchKernelGGL(dense_gram_kernel, dim3((unsigned)nw), dim3(256), 0, s, xq, nblk, gram);
+        hipLaunchKernelGGL(kern, dim3((unsigned)ntiles), dim3(kNW * kWave), Lds::total, s, a, gram, xq, xu, plan, w0, nw);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace oco

@@ -104,7 +104,7 @@ int validate_and_layout(const oco_config *c, Layout *lay)
         }
         if (c->x_shared) {
             l.off_gram = off;
-            off += align_up(dense_gram_bytes(n_max), 256);
+            off += align_up(dense_gram_bytes(n_max, c->d), 256);
         }
     } else {
         l.off_gram = off;
@@ -436,6 +436,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
         }
         a.tune = &st->tune; a.plan = &st->dense_plan;
         a.gram = l.off_gram ? st->at<float>(l.off_gram) : nullptr;
+        a.n_max = l.n_max;
         e = launch_dense_rounds(a, c.loss, st->stream, overlap ? &hook : nullptr);
     }
     if (e != hipSuccess) return fail();

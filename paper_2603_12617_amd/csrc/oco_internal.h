@@ -81,13 +81,14 @@ struct DenseArgs {
     float *x2last;           // [1 or R]     its squared norm
     const Tuning *tune;      // never null
     DensePlanCache *plan;    // never null
-    float *gram;             // shared streams: dense_gram_bytes(n_max) of scratch for the windowed path
+    float *gram;             // shared streams: dense_gram_bytes(n_max, d) of scratch for the windowed path
+    int64_t n_max;           // the state's largest call (lays that scratch out)
 };
 hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s, const PieceHook *hook);
 // the windowed path (dense_window.hip): whether a configuration takes it, and its launcher
 bool dense_window_wanted(const DenseArgs &a);
 hipError_t launch_dense_window(const DenseArgs &a, int loss, hipStream_t s, const PieceHook *hook);
-size_t dense_gram_bytes(int64_t n_max);
+size_t dense_gram_bytes(int64_t n_max, int64_t d);
 
 // comparator predictions of a shared dense stream as one contraction (rows K of Z)
 struct ComparatorGemmArgs {

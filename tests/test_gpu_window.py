@@ -112,11 +112,11 @@ def test_a_state_may_change_kernels_between_calls():
 
 
 def test_windowed_path_is_the_default_for_many_learners_on_a_shared_stream(capfd):
-    wl = WL.make("c4", T=130, R=70, d=256, K=16)              # 1120 learners
+    wl = WL.make("c4", T=130, R=130, d=2048, K=16)            # 2080 learners
     data = WL.generate(wl)
     got = _gpu(wl, data, options=dict(verbose=1))
     assert "windowed contraction kernel" in capfd.readouterr().err
-    _check(wl, data, got, runs=[0, 35, 69], label="windowed by default")
+    _check(wl, data, got, runs=[0, 65, 129], label="windowed by default")
 
 
 def test_option_errors():
