@@ -39,10 +39,12 @@
  *  - Results are a pure function of (config, options, inputs, call boundaries).
  *    Dense configurations on the register kernel: splitting [0, T) into
  *    oco_run_rounds calls in any way gives bit-identical state and regret; on the
- *    windowed kernel (OCO_OPT_DENSE_PATH) the rounds are worked in windows that
- *    end at the multiples of 64 of the horizon: splits there are bit-identical,
- *    other splits regroup float32 sums and agree to rounding.  Sparse
- *    configurations work in segments of 4096 rounds of the horizon in the same way.
+ *    windowed kernel (OCO_OPT_DENSE_PATH) the rounds are worked in windows of 64
+ *    whose inner products are grouped differently at the start of a call than
+ *    inside it: the same calls give the same bits, different splits agree to
+ *    float32 rounding.  Sparse configurations work in segments of 4096 rounds of
+ *    the horizon: splits at multiples of 4096 are bit-identical, other splits
+ *    regroup float32 sums and agree to rounding.
  *  - Arithmetic: iterates, inner products and the projection in float32;
  *    losses, cumulative losses, Hedge weights and regret in float64.
  */

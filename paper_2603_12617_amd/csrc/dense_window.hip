@@ -17,9 +17,16 @@
 //       (float64 scalars; one wavefront, a quad of lanes per learner, each lane of the quad
 //       carrying every fourth pending round);
 //   (3) W <- F W - Bm X_w,  F = A_end,  Bm[r] = a_r rho_{r,end}   (M x d contraction over B).
-// (3) of window w and (1) of window w + 1 are taken block by block in one sweep over the
-// coordinates, so the iterates are touched once per window.  ||w||^2 is re-measured from the
-// new iterates in that sweep (no drift across windows).
+// The dependent rounds (2) occupy one wavefront; so that the matrix cores do not wait for them,
+// (2) of window k runs beside the sweep that applies (3) of window k - 1.  Its inner products
+// cannot then be taken with w_k itself (not formed yet); the sweep before took Q' = W_{k-1} X_k^T,
+// and with W_k = F W_{k-1} - Bm X_{k-1},
+//     Q0_k = F Q' - Bm (X_{k-1} X_k^T),
+// a 16 x 64 x 64 contraction with the cross Gram matrix of the two windows (pre-pass), four
+// matrix instructions deep.  One sweep over the coordinates per window, block by block:
+// (3) of window k - 1, then that block's share of W_k X_{k+1}^T, so the iterates are touched once
+// per window.  ||w||^2 is carried through the windows by the scalar identity above (float64) and
+// re-anchored one window late on the exact sum of squares that the sweep takes of the new iterates.
 //
 // Where the tile's iterates fit in the registers of a workgroup (d <= 4096: eight wavefronts,
 // each with every eighth block of 16 coordinates, in the layout the matrix instruction writes:
@@ -59,7 +66,8 @@ namespace {
 
 constexpr int kB = 64;            // rounds per window
 constexpr int kM = 16;            // learners per tile
-constexpr int kNW = 8;            // wavefronts per workgroup
+constexpr int kNW8 = 8;           // wavefronts per workgroup: iterates in registers (two per SIMD, 256 registers each)
+constexpr int kNW16 = 16;         // ... iterates streamed from HBM (four per SIMD: a wavefront's loads hide behind the others' work)
 constexpr int kGStride = 18;      // doubles per (round, quad lane) row of the masked Gram table (16 + padding)
 constexpr int64_t kPieceBytes = 64ll << 20;   // stream per launch (each tiled copy is as large)
 constexpr int kTileFloats = kB * 16;          // one window x one block of 16 coordinates
@@ -126,55 +134,77 @@ __global__ void __launch_bounds__(64) dense_tile_kernel(const float *x, int d, W
     }
 }
 
-// ---- pre-pass 2: G = X_w X_w^T of the same windows, from the tiled rows ------------------------------
-// One workgroup of four wavefronts per window; wavefront v computes rows 16 v .. 16 v + 15 of G
-// (four 16 x 16 blocks), depth block by block.  Fixed summation order.
-__global__ void __launch_bounds__(256) dense_gram_kernel(const float *xq, int nblk, float *gram)
+// ---- pre-pass 2: G = X_w X_w^T of the same windows, from the tiled rows, and the cross Gram
+// matrix Gx[r][t] = <x_r of window w - 1, x_t of window w> for every window but the launch's first.
+// One workgroup of eight wavefronts per window; wavefronts 0..3 compute rows 16 v .. 16 v + 15 of G
+// (four 16 x 16 blocks), wavefronts 4..7 the same rows of Gx, depth block by block.  Fixed
+// summation order.  Gx is written in the order the round kernel's matrix instructions want it:
+// gxt[((t / 16) 4 + r / 16) 256 + (t % 16 + 16 (r % 4)) 4 + (r / 4) % 4].
+__global__ void __launch_bounds__(512) dense_gram_kernel(const float *xq, int nblk, float *gram, float *gxt)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave8 = threadIdx.x >> 6;
+    const int wave = wave8 & 3;
+    const bool cross = wave8 >= 4;
+    if (cross && blockIdx.x == 0) return;
     const int lr = lane & 15, lk = lane >> 4;
     f4 acc[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[b] = f4{0.f, 0.f, 0.f, 0.f};
-    const float *xw = xq + (int64_t)blockIdx.x * nblk * kTileFloats + lane * 4;
+    const float *xw = xq + (int64_t)blockIdx.x * nblk * kTileFloats + lane * 4;          // this window
+    const float *xa = cross ? xw - (int64_t)nblk * kTileFloats : xw;                     // rows: the window before, or this one
     for (int blk = 0; blk < nblk; ++blk) {
         f4 bv[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b) bv[b] = *reinterpret_cast<const f4 *>(xw + (int64_t)blk * kTileFloats + b * 256);
-        const f4 av = wave == 0 ? bv[0] : wave == 1 ? bv[1] : wave == 2 ? bv[2] : bv[3];
+        const f4 av = *reinterpret_cast<const f4 *>(xa + (int64_t)blk * kTileFloats + wave * 256);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int b = 0; b < 4; ++b)
                 acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[r], bv[b][r], acc[b], 0, 0, 0);
     }
-    float *g = gram + (int64_t)blockIdx.x * kB * kB;
+    // acc[b][r]: row 16 wave + 4 lk + r, column 16 b + lr
+    if (!cross) {
+        float *g = gram + (int64_t)blockIdx.x * kB * kB;
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) g[(wave * 16 + 4 * lk + r) * kB + b * 16 + lr] = acc[b][r];
+            for (int r = 0; r < 4; ++r) g[(wave * 16 + 4 * lk + r) * kB + b * 16 + lr] = acc[b][r];
+    } else {
+        float *g = gxt + (int64_t)blockIdx.x * kB * kB;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) g[(b * 4 + wave) * 256 + (lr + 16 * r) * 4 + lk] = acc[b][r];
+    }
 }
 
-// LDS of the window kernel (dynamic), in bytes from the base.  The Gram table, its diagonal and
-// the labels have two buffers: the next window's are staged while this window's are in use.
-struct Lds {
-    static constexpr int gd_bytes = kB * 4 * kGStride * 8;         // double [64][4][kGStride]: G[t][t2], zero for t2 <= t
-    static constexpr int x2_bytes = kB * 8;                        // double [64]: G[t][t]
+// LDS of the window kernel (dynamic), in bytes from the base.  What the dependent rounds of window
+// k write for the sweep (predictions, -Bm, F) and what is staged for them (Gram table with its
+// diagonal in the rows' padding, labels) has two buffers, window k in buffer k % 2: the sweep of
+// window k - 1 and the staging for window k + 1 run beside them.
+template <int NW> struct LdsT {
+    // the Gram table as float64 where the LDS has room (eight wavefronts), else float32
+    using G = std::conditional_t<NW == kNW8, double, float>;
+    static constexpr int gd_bytes = kB * 4 * kGStride * (int)sizeof(G);   // G [64][4][kGStride]: G[t][t2], zero for t2 <= t;
+                                                                   //   [t][0][16] holds G[t][t]
     static constexpr int yb_bytes = kB * kM * 4;                   // float [64][16]: labels
+    static constexpr int zb_bytes = kB * kM * 4;                   // float [64][16]: predictions
+    static constexpr int bm_bytes = kB * kM * 4;                   // float [64][16]: -Bm
     static constexpr int gd = 0;
-    static constexpr int x2 = gd + 2 * gd_bytes;
-    static constexpr int yb = x2 + 2 * x2_bytes;
-    static constexpr int q0 = yb + 2 * yb_bytes;                   // double [64][16]: <w_s, x_t>
+    static constexpr int yb = gd + 2 * gd_bytes;
+    static constexpr int zb = yb + 2 * yb_bytes;
+    static constexpr int bm = zb + 2 * zb_bytes;
+    static constexpr int fv = bm + 2 * bm_bytes;                   // float [2][16]: F
+    static constexpr int q0 = fv + 2 * kM * 4;                     // double [64][16]: W_{k-1} X_k^T
     static constexpr int fl = q0 + kB * kM * 8;                    // double [64][16]: f_t
-    static constexpr int part = fl + kB * kM * 8;                  // float [kNW][64][16]: per-wavefront shares of Q0
-    static constexpr int zb = part + kNW * kB * kM * 4;            // float [64][16]: predictions
-    static constexpr int st = zb + kB * kM * 4;                    // float [64][16]: a_t
-    static constexpr int bm = st + kB * kM * 4;                    // float [64][16]: -Bm
-    static constexpr int fv = bm + kB * kM * 4;                    // float [16]: F
-    static constexpr int n2 = fv + kM * 4;                         // float [kNW][4][16]: shares of ||w||^2
-    static constexpr int total = n2 + kNW * 4 * kM * 4;
+    static constexpr int part = fl + kB * kM * 8;                  // float [NW][64][16]: per-wavefront shares of W X^T
+    static constexpr int st = part + NW * kB * kM * 4;             // float [64][16]: a_t
+    static constexpr int corr = st + kB * kM * 4;                  // float [64][16]: -Bm (X_{k-1} X_k^T)
+    static constexpr int n2 = corr + kB * kM * 4;                  // float [NW][4][16]: shares of ||w||^2
+    static constexpr int total = n2 + NW * 4 * kM * 4;
 };
-static_assert(Lds::total <= 160 * 1024, "LDS of a gfx950 compute unit");
+static_assert(LdsT<kNW8>::total <= 160 * 1024 && LdsT<kNW16>::total <= 160 * 1024, "LDS of a gfx950 compute unit");
 
 // every lane of a quad gets the value of the quad's lane SEL
 template <int SEL> __device__ __forceinline__ double quad_bcast(double v)
@@ -197,30 +227,37 @@ template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// The 64 dependent rounds of one window for the tile's 16 learners: wavefront 0, lane = 4 learner
+// The 64 dependent rounds of window k for the tile's 16 learners: wavefront 0, lane = 4 learner
 // + quad lane s; quad lane s carries the pending predictions of the rounds t2 = 4 j + s.
-// In: q0 (times the scale `sig` of the stored iterates), labels, G, n2 = ||w||^2.  Out: predictions,
-// -Bm and F in LDS; n2 is left to the sweep (it re-measures it).
+// In: q0 = W' X_k^T with W' the iterates before the step of window k - 1 (or the stored ones, for the
+// launch's first window), pmul and corr such that pmul q0 + corr = W_k X_k^T; labels, G; n2 = ||w_k||^2.
+// Out (LDS buffer k % 2): predictions, -Bm, F = fscale f_0 ... f_63; returns F; n2 becomes ||w_{k+1}||^2
+// by the scalar identity, *projected whether any round of the window projected this learner.
 // Straight-line code: a window shorter than 64 rounds (first / last window of a call) runs its
 // missing rounds as rounds without a step (a = 0, so f = 1 and no pending prediction moves; their
 // rows of G are zero).
-template <int LOSS>
-__device__ __forceinline__ void chain_window(char *lds, int buf, int lane, int wl, float eta, double D, double sig, double n2)
+template <int LOSS, int NW>
+__device__ __forceinline__ double chain_window(char *lds, int buf, int lane, int wl, float eta, double D, double pmul,
+                                               double fscale, double &n2, bool &projected)
 {
+    using Lds = LdsT<NW>;
+    using GT = typename Lds::G;
     const int lc = lane >> 2, s = lane & 3;
-    const double *gd = reinterpret_cast<const double *>(lds + Lds::gd + buf * Lds::gd_bytes) + s * kGStride;
-    const double *x2d = reinterpret_cast<const double *>(lds + Lds::x2 + buf * Lds::x2_bytes);
+    const GT *gd = reinterpret_cast<const GT *>(lds + Lds::gd + buf * Lds::gd_bytes) + s * kGStride;
+    const GT *x2d = reinterpret_cast<const GT *>(lds + Lds::gd + buf * Lds::gd_bytes) + 16;
     const double *q0d = reinterpret_cast<const double *>(lds + Lds::q0) + s * kM + lc;
+    const float *cr = reinterpret_cast<const float *>(lds + Lds::corr) + s * kM + lc;
     double *fl = reinterpret_cast<double *>(lds + Lds::fl) + lc;
     const float *yb = reinterpret_cast<const float *>(lds + Lds::yb + buf * Lds::yb_bytes) + lc;
-    float *zb = reinterpret_cast<float *>(lds + Lds::zb) + lc;
+    float *zb = reinterpret_cast<float *>(lds + Lds::zb + buf * Lds::zb_bytes) + lc;
     float *stl = reinterpret_cast<float *>(lds + Lds::st) + lc;
     const double D2 = D * D;
     const float eta2 = 2.f * eta;
+    bool anyp = false;
 
     double p[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) p[j] = sig * q0d[4 * j * kM];
+    for (int j = 0; j < 16; ++j) p[j] = fma(pmul, q0d[4 * j * kM], (double)cr[4 * j * kM]);
 
     static_for<kB>([&](auto tc) __attribute__((always_inline)) {
         constexpr int t = decltype(tc)::value;
@@ -228,9 +265,9 @@ __device__ __forceinline__ void chain_window(char *lds, int buf, int lane, int w
         // this round's row of G first: it does not depend on the scalars below
         double gr[16 - j0];
 #pragma unroll
-        for (int j = j0; j < 16; ++j) gr[j - j0] = gd[t * 4 * kGStride + j];
+        for (int j = j0; j < 16; ++j) gr[j - j0] = (double)gd[t * 4 * kGStride + j];
         const float yt = yb[t * kM];
-        const double x2t = x2d[t];
+        const double x2t = (double)x2d[t * 4 * kGStride];
         const double zt = quad_bcast<(t & 3)>(p[j0]);               // <w_t, x_t>
         const float z32 = (float)zt;
         // a_t = eta c_t; for the squared loss eta * 2 (z - y) = (2 eta) (z - y) exactly
@@ -243,6 +280,7 @@ __device__ __forceinline__ void chain_window(char *lds, int buf, int lane, int w
         const bool pj = m2 > D2;
         const double f = pj ? D * __builtin_amdgcn_rsq(m2) : 1.0;
         n2 = pj ? D2 : m2;
+        anyp = anyp || pj;
         zb[t * kM] = z32;                                            // (the quad's four lanes write the same value)
         stl[t * kM] = a32;
         fl[t * kM] = f;
@@ -251,10 +289,10 @@ __device__ __forceinline__ void chain_window(char *lds, int buf, int lane, int w
         __builtin_amdgcn_sched_barrier(0);                           // rounds are not interleaved: registers
     });
 
-    // Bm[r] = a_r f_r f_{r+1} ... f_63 and F = sig f_0 ... f_63: quad lane s takes the rounds
+    // Bm[r] = a_r f_r f_{r+1} ... f_63 and F = fscale f_0 ... f_63: quad lane s takes the rounds
     // 16 s .. 16 s + 15 backwards, then the quad's products are combined
-    float *bm = reinterpret_cast<float *>(lds + Lds::bm) + lc;
-    float *fv = reinterpret_cast<float *>(lds + Lds::fv);
+    float *bm = reinterpret_cast<float *>(lds + Lds::bm + buf * Lds::bm_bytes) + lc;
+    float *fv = reinterpret_cast<float *>(lds + Lds::fv) + buf * kM;
     double loc[16];
     double acc = 1.0;
 #pragma unroll
@@ -269,7 +307,10 @@ __device__ __forceinline__ void chain_window(char *lds, int buf, int lane, int w
         const int r = 16 * s + k;
         bm[r * kM] = -(float)((double)stl[r * kM] * (loc[k] * tail));
     }
-    if (s == 0) fv[lc] = (float)(sig * (P0 * (P1 * (P2 * P3))));
+    const double F = fscale * (P0 * (P1 * (P2 * P3)));
+    if (s == 0) fv[lc] = (float)F;
+    projected = anyp;
+    return F;
 }
 
 // What a thread is in the sweep, derived from its index.  The window loop re-derives it every
@@ -294,20 +335,43 @@ __device__ __forceinline__ Geo make_geo(int tid, const DenseArgs &a)
     return g;
 }
 
-// The windows w0 .. w0 + nw - 1 of the call's plan; xq / xu / gram hold those windows only.
-// RES: the tile's iterates stay in registers for the whole launch (d <= 16 * kNW * NB); otherwise
-// every block is loaded and stored in the sweep.
-template <int LOSS, int NB, bool RES>
-__global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArgs a, const float *gram, const float *xq,
-                                                                   const float *xu, WinPlanD plan, int w0, int nw)
+// The windows w0 .. w0 + nw - 1 of the call's plan; xq / xu / gram / gxt hold those windows only.
+// RES: the tile's iterates stay in registers for the whole launch (d <= 16 * NW * NB); otherwise
+// every block is loaded and stored in the sweep.  NW: wavefronts per workgroup.
+//
+// Iteration k = 0 .. nw of the main loop (two barriers each):
+//   all        the shares of W' X_k^T -> q0 (float64); wavefronts 0..3: corr = -Bm_{k-1} Gx_k (k >= 1)
+//   wavefront 0    the dependent rounds of window k (k < nw), then its part of the sweep
+//   the others     predictions of window k - 1 to Z, staging for window k + 1, the sweep
+//   sweep (k >= 1) W_k = F_{k-1} W_{k-1} - Bm_{k-1} X_{k-1} block by block, its squared norm, and the
+//                  shares of W_k X_{k+1}^T (k + 1 < nw)
+template <int LOSS, int NB, bool RES, int NW>
+__global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs a, const float *gram, const float *gxt,
+                                                                  const float *xq, const float *xu, WinPlanD plan, int w0,
+                                                                  int nw)
 {
-    constexpr bool BMR = !(RES && NB > 8);     // -Bm in registers for the whole sweep, or re-read from LDS per block
+    constexpr int kNW = NW;
+    using Lds = LdsT<NW>;
+    using GT = typename Lds::G;
+    // -Bm in registers for the whole sweep, or (where registers are short) re-read from LDS per block
+    constexpr bool BMR = RES && NB <= 8;
     extern __shared__ __align__(16) char lds[];
     const int d = a.d, K = a.K;
     const int nq = a.R * K;
     const int nblk = (d + 15) / 16;                             // blocks of 16 coordinates
 
-    // the tile's iterates: block (wave + 8 b) of 16 coordinates x 16 learners, transposed
+    // Which blocks of 16 coordinates a wavefront takes.  In registers: wave, wave + NW, ...  Streamed
+    // with sixteen wavefronts: wavefront 0 also runs the dependent rounds, so it takes half a share:
+    // of every 31 consecutive blocks, wavefronts 1 .. 15 take two each and wavefront 0 the last one.
+    // (A fixed assignment: every sum keeps its order from run to run.)
+    auto nth_block = [&](int wave, int i) __attribute__((always_inline)) {
+        if (NW == kNW16 && !RES) {
+            if (wave == 0) return 31 * i + 30;
+            return 31 * (i >> 1) + (wave - 1) + ((i & 1) ? 15 : 0);
+        }
+        return wave + NW * i;
+    };
+    // the tile's iterates: 16 coordinates x 16 learners per block, transposed
     auto ld_block = [&](const Geo &g, int blk) __attribute__((always_inline)) {
         f4 v = f4{0.f, 0.f, 0.f, 0.f};
         if (g.q_ok && blk * 16 + 4 * g.lk < d) v = *reinterpret_cast<const f4 *>(g.vrow + blk * 16);
@@ -333,8 +397,7 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
         const int w = w0 + wi, buf = wi & 1;
         const int ws = plan.start(w), wl = plan.len(w);
         float *yb = reinterpret_cast<float *>(lds + Lds::yb + buf * Lds::yb_bytes);
-        double *gd = reinterpret_cast<double *>(lds + Lds::gd + buf * Lds::gd_bytes);
-        double *x2d = reinterpret_cast<double *>(lds + Lds::x2 + buf * Lds::x2_bytes);
+        GT *gd = reinterpret_cast<GT *>(lds + Lds::gd + buf * Lds::gd_bytes);
         for (int e = tid; e < kB * kM; e += nthr) {
             const int l16 = e >> 6, t = e & 63;                 // a learner's 64 labels are contiguous
             const int q = (int)blockIdx.x * kM + l16;
@@ -346,11 +409,11 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
         for (int e = tid; e < kB * kB; e += nthr) {
             const int t = e >> 6, t2 = e & 63;
             const float gv = gsrc[e];
-            gd[(t * 4 + (t2 & 3)) * kGStride + (t2 >> 2)] = t2 > t ? (double)gv : 0.0;
-            if (t2 == t) x2d[t] = (double)gv;
+            gd[(t * 4 + (t2 & 3)) * kGStride + (t2 >> 2)] = t2 > t ? (GT)gv : (GT)0;
+            if (t2 == t) gd[t * 4 * kGStride + 16] = (GT)gv;
         }
     };
-    // Q0 shares of this wavefront for one window -> LDS
+    // shares of this wavefront of W X^T for one window -> LDS
     auto put_part = [&](const Geo &g, const f4 (&acc)[4]) __attribute__((always_inline)) {
         float *part = reinterpret_cast<float *>(lds + Lds::part);
 #pragma unroll
@@ -359,26 +422,43 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
             for (int r = 0; r < 4; ++r) part[(g.wave * kB + rb * 16 + 4 * g.lk + r) * kM + g.lr] = acc[rb][r];
     };
 
+    // W' X_k^T = sum of the eight shares, fixed order, as float64
+    auto sum_parts = [&](int tid) __attribute__((always_inline)) {
+        const float *part = reinterpret_cast<const float *>(lds + Lds::part);
+        double *q0d = reinterpret_cast<double *>(lds + Lds::q0);
+#pragma unroll
+        for (int u = 0; u < kB * kM / (kNW * kWave); ++u) {
+            const int e = tid + u * kNW * kWave;
+            double sum = 0.0;
+#pragma unroll
+            for (int v = 0; v < kNW; ++v) sum += (double)part[v * kB * kM + e];
+            q0d[e] = sum;
+        }
+    };
+
     // ---- per-learner state of the dependent rounds (wavefront 0: lane = 4 learner + quad lane) ----
     float eta = 0.f;
-    double sig = 1.0, n2 = 0.0;
+    double pmul = 1.0;          // scale of the iterates q0 was taken with: sigma of the state, then F of the window before
+    double n2 = 0.0;            // ||w_k||^2 as the scalar identity carries it
+    double n2_begin = 0.0;      // what the previous window's rounds started from
+    bool proj_prev = true;      // whether they projected this learner (then n2 was reset to D^2 on the way)
     f4 V[RES ? NB : 1];
     {
         const Geo g = make_geo((int)threadIdx.x, a);
         const int q_ch = (int)blockIdx.x * kM + (g.lane >> 2);
         if (g.wave == 0 && q_ch < nq) {
             eta = a.eta[q_ch % K];
-            sig = (double)a.sigma[q_ch];
-            n2 = a.n2[q_ch] * sig * sig;                        // ||w||^2 of the iterate itself
+            pmul = (double)a.sigma[q_ch];
+            n2 = a.n2[q_ch] * pmul * pmul;                      // ||w||^2 of the iterate itself
         }
         if (RES) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) V[b] = ld_block(g, g.wave + kNW * b);
         }
-        // ---- prologue: inner products of the first window ----------------------------------------
-        f4 acc[4];
+        // ---- prologue: the stored iterates times the rows of the first two windows -----------------
+        f4 acc0[4], acc1[4];
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
+        for (int rb = 0; rb < 4; ++rb) { acc0[rb] = f4{0.f, 0.f, 0.f, 0.f}; acc1[rb] = f4{0.f, 0.f, 0.f, 0.f}; }
         auto q_of = [&](const f4 &vb, int blk) __attribute__((always_inline)) {
             f4 xr[4];
             ldq(g, 0, blk, xr);
@@ -386,7 +466,15 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
             for (int r = 0; r < 4; ++r)
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb)
-                    acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[rb][r], vb[r], acc[rb], 0, 0, 0);
+                    acc0[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[rb][r], vb[r], acc0[rb], 0, 0, 0);
+            if (nw > 1) {
+                ldq(g, 1, blk, xr);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb)
+                        acc1[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[rb][r], vb[r], acc1[rb], 0, 0, 0);
+            }
         };
         if constexpr (RES) {
             static_for<NB>([&](auto bc) __attribute__((always_inline)) {
@@ -395,152 +483,176 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
                 if (blk < nblk) q_of(V[b], blk);
             });
         } else {
-            for (int blk = g.wave; blk < nblk; blk += kNW) q_of(ld_block(g, blk), blk);
+            for (int i = 0, blk = nth_block(g.wave, 0); blk < nblk; blk = nth_block(g.wave, ++i)) q_of(ld_block(g, blk), blk);
         }
-        put_part(g, acc);
+        put_part(g, acc0);
         stage_chain_inputs(g.tid, kNW * kWave, 0);
+        float *corr = reinterpret_cast<float *>(lds + Lds::corr);
+        for (int e = g.tid; e < kB * kM; e += kNW * kWave) corr[e] = 0.f;
+        // the shares of window 0 are summed here, so that those of window 1 can take their place
+        __syncthreads();
+        sum_parts(g.tid);
+        __syncthreads();
+        if (nw > 1) put_part(g, acc1);
     }
 
 #ifdef OCO_WIN_PROF
     unsigned long long prof_[8] = {0, 0, 0, 0, 0, 0, 0, 0}, last_ = wall_clock64();
 #endif
-    for (int wi = 0; wi < nw; ++wi) {
-        const int w = w0 + wi;
-        const int ws = plan.start(w), wl = plan.len(w);
-        __syncthreads();                                         // (A) shares of Q0, labels, G in LDS
-        PROF_T(0);
+    for (int k = 0; k <= nw; ++k) {
         int tid_w = (int)threadIdx.x;
         asm volatile("" : "+v"(tid_w));                          // see Geo
-        {
-            // Q0 = sum of the eight shares, fixed order, as float64
-            const float *part = reinterpret_cast<const float *>(lds + Lds::part);
-            double *q0d = reinterpret_cast<double *>(lds + Lds::q0);
+        const bool rounds = k < nw;                              // this iteration has dependent rounds (window k)
+        const bool sweep = k >= 1;                               // ... and a sweep (window k - 1)
+        const bool more = k + 1 < nw;                            // the sweep also takes W_k X_{k+1}^T
+        // the cross Gram matrix of windows k - 1 and k as matrix operand, on its way across the barrier
+        f4 gx[4];
+        const int wave_w = __builtin_amdgcn_readfirstlane(tid_w >> 6);
+        if (rounds && sweep && wave_w < 4) {
+            const float *t = gxt + (int64_t)k * kB * kB + wave_w * 1024 + (tid_w & 63) * 4;
 #pragma unroll
-            for (int u = 0; u < kB * kM / (kNW * kWave); ++u) {
-                const int e = tid_w + u * kNW * kWave;
-                double sum = 0.0;
+            for (int j = 0; j < 4; ++j) gx[j] = *reinterpret_cast<const f4 *>(t + j * 256);
+        }
+        __syncthreads();                                         // (A) shares of W' X_k^T, -Bm_{k-1}, staged inputs in LDS
+        PROF_T(0);
+        if (rounds) {
+            if (k >= 1) sum_parts(tid_w);                        // (window 0: summed in the prologue)
+            if (sweep && wave_w < 4) {
+                // corr[t][learner] = -sum_r Bm_{k-1}[r][learner] Gx[r][t], rows t = 16 wave .. + 15
+                const float *bmp = reinterpret_cast<const float *>(lds + Lds::bm + ((k - 1) & 1) * Lds::bm_bytes);
+                const int lr = tid_w & 15, lk = (tid_w & 63) >> 4;
+                f4 c = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int v = 0; v < kNW; ++v) sum += (double)part[v * kB * kM + e];
-                q0d[e] = sum;
+                for (int rs = 0; rs < 16; ++rs)
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(gx[rs >> 2][rs & 3], bmp[(rs * 4 + lk) * kM + lr], c, 0, 0, 0);
+                float *corr = reinterpret_cast<float *>(lds + Lds::corr);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) corr[(wave_w * 16 + 4 * lk + r) * kM + lr] = c[r];
             }
         }
         __syncthreads();                                         // (B)
         PROF_T(1);
-        const bool more = wi + 1 < nw;
-        if (__builtin_amdgcn_readfirstlane(tid_w >> 6) == 0) {
-            const int lane = tid_w & 63;
-            if (wi > 0) {
-                // ||w||^2 as the last sweep measured it: 32 shares per learner, fixed order
-                const float *n2s = reinterpret_cast<const float *>(lds + Lds::n2);
-                double m = 0.0;
-                const int lc = lane >> 2;
+        if (wave_w == 0) {
+            if (rounds) {
+                const int lane = tid_w & 63;
+                if (k >= 2 && !proj_prev) {
+                    // ||w_{k-1}||^2 as the sweep of window k - 2 measured it (32 shares per learner,
+                    // fixed order) against what the rounds of window k - 1 started from: without a
+                    // projection in between the difference is still in n2
+                    const float *n2s = reinterpret_cast<const float *>(lds + Lds::n2);
+                    double m = 0.0;
+                    const int lc = lane >> 2;
 #pragma unroll
-                for (int v = 0; v < kNW; ++v)
+                    for (int v = 0; v < kNW; ++v)
 #pragma unroll
-                    for (int g4 = 0; g4 < 4; ++g4) m += (double)n2s[(v * 4 + g4) * kM + lc];
-                n2 = m;
-                sig = 1.0;
+                        for (int g4 = 0; g4 < 4; ++g4) m += (double)n2s[(v * 4 + g4) * kM + lc];
+                    n2 += m - n2_begin;
+                    n2 = n2 > 0.0 ? n2 : 0.0;
+                }
+                n2_begin = n2;
+                const double fscale = k == 0 ? pmul : 1.0;
+                pmul = chain_window<LOSS, NW>(lds, k & 1, lane, plan.len(w0 + k), eta, (double)a.D, pmul, fscale, n2, proj_prev);
             }
-            chain_window<LOSS>(lds, wi & 1, lane, wl, eta, (double)a.D, sig, n2);
-        } else if (more) {
+        } else {
             // beside the dependent rounds: the next window's labels and Gram table into the other buffer
-            stage_chain_inputs(tid_w - kWave, (kNW - 1) * kWave, wi + 1);
+            if (more) stage_chain_inputs(tid_w - kWave, (kNW - 1) * kWave, k + 1);
+            // ... and the predictions of window k - 1 to Z (wavefronts 1 .. 7, a learner's rounds contiguous)
+            if (sweep) {
+                const int w = w0 + k - 1;
+                const int ws = plan.start(w), wl = plan.len(w);
+                const float *zb = reinterpret_cast<const float *>(lds + Lds::zb + ((k - 1) & 1) * Lds::zb_bytes);
+                for (int e = tid_w - kWave; e < kB * kM; e += (kNW - 1) * kWave) {
+                    const int l16 = e >> 6, t = e & 63;
+                    const int q = (int)blockIdx.x * kM + l16;
+                    if (q < nq && t < wl)
+                        a.Z[(int64_t)(q / K) * a.zl.zs_r + (int64_t)(q % K) * a.zl.zs_i + (int64_t)(ws + t) * a.zl.zs_t] = zb[t * kM + l16];
+                }
+            }
         }
         PROF_T(2);
-        __syncthreads();                                         // (C) predictions, -Bm, F in LDS
-        PROF_T(3);
         asm volatile("" : "+v"(tid_w));
         const Geo g = make_geo(tid_w, a);
         const int lr = g.lr, lk = g.lk;
 
-        // predictions of the window to Z
-        {
-            const float *zb = reinterpret_cast<const float *>(lds + Lds::zb);
-            const int l16 = g.tid >> 5, t = g.tid & 31;
-            const int q = (int)blockIdx.x * kM + l16;
-            if (q < nq) {
-                float *zrow = a.Z + (int64_t)(q / K) * a.zl.zs_r + (int64_t)(q % K) * a.zl.zs_i + (int64_t)ws * a.zl.zs_t;
-                if (t < wl) zrow[(int64_t)t * a.zl.zs_t] = zb[t * kM + l16];
-                if (t + 32 < wl) zrow[(int64_t)(t + 32) * a.zl.zs_t] = zb[(t + 32) * kM + l16];
-            }
-        }
-
-        // ---- sweep: (3) of window w and (1) of window w + 1, block by block ----------------------
+        // ---- sweep: (3) of window k - 1 and W_k X_{k+1}^T, block by block ------------------------------
         // The round rows (and, where the iterates live in HBM, the block itself) of the next block
         // are on their way while the matrix instructions of the current block run.
-        const float *bml = reinterpret_cast<const float *>(lds + Lds::bm);
-        float bmr[BMR ? 16 : 1];
-        if (BMR) {
+        if (sweep) {
+            const int wi = k - 1;
+            const float *bml = reinterpret_cast<const float *>(lds + Lds::bm + (wi & 1) * Lds::bm_bytes);
+            float bmr[BMR ? 16 : 1];
+            if (BMR) {
 #pragma unroll
-            for (int rs = 0; rs < 16; ++rs) bmr[rs] = bml[(rs * 4 + lk) * kM + lr];
-        }
-        const float F = reinterpret_cast<const float *>(lds + Lds::fv)[lr];
-        f4 acc[4];
+                for (int rs = 0; rs < 16; ++rs) bmr[rs] = bml[(rs * 4 + lk) * kM + lr];
+            }
+            const float F = reinterpret_cast<const float *>(lds + Lds::fv)[(wi & 1) * kM + lr];
+            f4 acc[4];
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
-        float nn = 0.f;
-        struct BlkIn { f4 xu[4]; f4 xq[4]; f4 vb; };
-        auto load_in = [&](BlkIn &in, int blk) __attribute__((always_inline)) {
+            for (int rb = 0; rb < 4; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
+            float nn = 0.f;
+            struct BlkIn { f4 xu[4]; f4 xq[4]; f4 vb; };
+            auto load_in = [&](BlkIn &in, int blk) __attribute__((always_inline)) {
 #ifdef OCO_WIN_NOLOAD
-            if (blk < 0) {
+                if (blk < 0) {
 #else
-            if (blk < nblk) {
+                if (blk < nblk) {
 #endif
-                ldu(g, wi, blk, in.xu);
-                if (more) ldq(g, wi + 1, blk, in.xq);
-                if (!RES) in.vb = ld_block(g, blk);
+                    ldu(g, wi, blk, in.xu);
+                    if (more) ldq(g, k + 1, blk, in.xq);
+                    if (!RES) in.vb = ld_block(g, blk);
+                }
+            };
+            auto compute = [&](BlkIn &in, f4 &vreg, int blk) __attribute__((always_inline)) {
+                f4 vb = RES ? vreg : in.vb;
+                f4 vo = f4{0.f, 0.f, 0.f, 0.f};                  // two chains of eight dependent instructions
+#pragma unroll
+                for (int r = 0; r < 4; ++r) vb[r] *= F;
+#pragma unroll
+                for (int rs = 0; rs < 16; rs += 2) {
+                    vb = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs >> 2][rs & 3], BMR ? bmr[BMR ? rs : 0] : bml[(rs * 4 + lk) * kM + lr], vb, 0, 0, 0);
+                    vo = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs >> 2][(rs & 3) + 1], BMR ? bmr[BMR ? rs + 1 : 0] : bml[((rs + 1) * 4 + lk) * kM + lr], vo, 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) vb[r] += vo[r];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) nn = fmaf(vb[r], vb[r], nn);
+                if (RES) vreg = vb; else st_block(g, blk, vb);
+                if (more) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+#pragma unroll
+                        for (int rb = 0; rb < 4; ++rb)
+                            acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xq[rb][r], vb[r], acc[rb], 0, 0, 0);
+                }
+            };
+            BlkIn in[RES ? 2 : 1];
+            if constexpr (RES) {
+                load_in(in[0], g.wave);
+                static_for<NB>([&](auto bc) __attribute__((always_inline)) {
+                    constexpr int b = decltype(bc)::value;
+                    const int blk = g.wave + kNW * b;
+                    if (b + 1 < NB) load_in(in[(b + 1) & 1], blk + kNW);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (blk < nblk) compute(in[b & 1], V[b], blk);
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            } else {
+                // One set of input registers: a block's loads are issued when the block before it is
+                // done, and the other three wavefronts of the SIMD keep the matrix cores busy meanwhile.
+                // (Loads issued earlier would not help: the block's store shares their counter, which
+                // only orders loads among themselves, so every wait behind a store waits for everything.)
+                f4 none;
+                for (int i = 0, blk = nth_block(g.wave, 0); blk < nblk; blk = nth_block(g.wave, ++i)) {
+                    load_in(in[0], blk);
+                    __builtin_amdgcn_sched_barrier(0);
+                    compute(in[0], none, blk);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-        };
-        auto compute = [&](BlkIn &in, f4 &vreg, int blk) __attribute__((always_inline)) {
-            f4 vb = RES ? vreg : in.vb;
-            f4 vo = f4{0.f, 0.f, 0.f, 0.f};                      // two chains of eight dependent instructions
-#pragma unroll
-            for (int r = 0; r < 4; ++r) vb[r] *= F;
-#pragma unroll
-            for (int rs = 0; rs < 16; rs += 2) {
-                vb = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs >> 2][rs & 3], BMR ? bmr[BMR ? rs : 0] : bml[(rs * 4 + lk) * kM + lr], vb, 0, 0, 0);
-                vo = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs >> 2][(rs & 3) + 1], BMR ? bmr[BMR ? rs + 1 : 0] : bml[((rs + 1) * 4 + lk) * kM + lr], vo, 0, 0, 0);
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) vb[r] += vo[r];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) nn = fmaf(vb[r], vb[r], nn);
-            if (RES) vreg = vb; else st_block(g, blk, vb);
-            if (more) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int rb = 0; rb < 4; ++rb)
-                        acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xq[rb][r], vb[r], acc[rb], 0, 0, 0);
-            }
-        };
-        BlkIn in[2];
-        load_in(in[0], g.wave);
-        if constexpr (RES) {
-            static_for<NB>([&](auto bc) __attribute__((always_inline)) {
-                constexpr int b = decltype(bc)::value;
-                const int blk = g.wave + kNW * b;
-                if (b + 1 < NB) load_in(in[(b + 1) & 1], blk + kNW);
-                __builtin_amdgcn_sched_barrier(0);
-                if (blk < nblk) compute(in[b & 1], V[b], blk);
-                __builtin_amdgcn_sched_barrier(0);
-            });
-        } else {
-            f4 none;
-            for (int blk = g.wave; blk < nblk; blk += 2 * kNW) {
-                load_in(in[1], blk + kNW);
-                __builtin_amdgcn_sched_barrier(0);
-                compute(in[0], none, blk);
-                __builtin_amdgcn_sched_barrier(0);
-                load_in(in[0], blk + 2 * kNW);
-                __builtin_amdgcn_sched_barrier(0);
-                if (blk + kNW < nblk) compute(in[1], none, blk + kNW);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            PROF_T(4);
+            reinterpret_cast<float *>(lds + Lds::n2)[(g.wave * 4 + lk) * kM + lr] = nn;
+            if (more) put_part(g, acc);
         }
-        PROF_T(4);
-        reinterpret_cast<float *>(lds + Lds::n2)[(g.wave * 4 + lk) * kM + lr] = nn;
-        if (more) put_part(g, acc);
         PROF_T(5);
     }
 #ifdef OCO_WIN_PROF
@@ -569,20 +681,22 @@ __global__ void __launch_bounds__(kNW *kWave) dense_window_kernel(const DenseArg
     }
 }
 
-using WindowKernel = void (*)(const DenseArgs, const float *, const float *, const float *, WinPlanD, int, int);
+using WindowKernel = void (*)(const DenseArgs, const float *, const float *, const float *, const float *, WinPlanD, int, int);
 
-template <int LOSS> WindowKernel pick_window_kernel(int nblk, bool resident)
+template <int LOSS> WindowKernel pick_window_kernel(int nblk, bool resident, int *waves, int *lds_bytes)
 {
-    if (resident && nblk <= 8 * kNW) return dense_window_kernel<LOSS, 8, true>;
-    if (resident && nblk <= 32 * kNW) return dense_window_kernel<LOSS, 32, true>;
-    return dense_window_kernel<LOSS, 1, false>;
+    *waves = resident ? kNW8 : kNW16;
+    *lds_bytes = resident ? LdsT<kNW8>::total : LdsT<kNW16>::total;
+    if (resident && nblk <= 8 * kNW8) return dense_window_kernel<LOSS, 8, true, kNW8>;
+    if (resident) return dense_window_kernel<LOSS, 32, true, kNW8>;
+    return dense_window_kernel<LOSS, 1, false, kNW16>;
 }
 
-// scratch: Gram matrices of the windows of a piece, then the two tiled copies of its rows
+// scratch: Gram and cross Gram matrices of the windows of a piece, then the two tiled copies of its rows
 struct Scratch {
     int64_t piece_windows;      // windows per launch
     size_t gram_floats, tile_floats;
-    size_t total_floats() const { return gram_floats + 2 * tile_floats; }
+    size_t total_floats() const { return 2 * gram_floats + 2 * tile_floats; }
 };
 Scratch scratch_layout(int64_t n_max, int64_t d)
 {
@@ -633,7 +747,7 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
     const int nwin = plan.count();
     const int nblk = (a.d + 15) / 16;
     const Scratch sc = scratch_layout(a.n_max, a.d);
-    float *gram = a.gram, *xq = a.gram + sc.gram_floats, *xu = xq + sc.tile_floats;
+    float *gram = a.gram, *gxt = gram + sc.gram_floats, *xq = gxt + sc.gram_floats, *xu = xq + sc.tile_floats;
     {
         ComparatorGemmArgs g{};
         g.x = a.x; g.u = a.u; g.seg_start = a.seg_start; g.S = a.S; g.Z = a.Z; g.zl = a.zl;
@@ -641,26 +755,27 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
         hipError_t e = launch_comparator_gemm(g, s);
         if (e != hipSuccess) return e;
     }
-    const bool resident = a.d <= 16 * kNW * 32 && a.tune->get(OCO_OPT_WINDOW_RESIDENT) != 0;
+    const bool resident = a.d <= 16 * kNW8 * 32 && a.tune->get(OCO_OPT_WINDOW_RESIDENT) != 0;
     const int ntiles = (a.R * a.K + kM - 1) / kM;
     if (a.tune->get(OCO_OPT_VERBOSE) == 1)
         fprintf(stderr, "dense plan: windowed contraction kernel, %d windows in pieces of %lld, %d tiles, iterates %s\n",
                 nwin, (long long)sc.piece_windows, ntiles, resident ? "in registers" : "streamed from HBM");
     WindowKernel kern = nullptr;
+    int waves = 0, lds_bytes = 0;
     switch (loss) {
-        case 0: kern = pick_window_kernel<0>(nblk, resident); break;
-        case 1: kern = pick_window_kernel<1>(nblk, resident); break;
-        case 2: kern = pick_window_kernel<2>(nblk, resident); break;
+        case 0: kern = pick_window_kernel<0>(nblk, resident, &waves, &lds_bytes); break;
+        case 1: kern = pick_window_kernel<1>(nblk, resident, &waves, &lds_bytes); break;
+        case 2: kern = pick_window_kernel<2>(nblk, resident, &waves, &lds_bytes); break;
         default: return hipErrorInvalidValue;
     }
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       Lds::total);
+                                       lds_bytes);
     if (e != hipSuccess) return e;
     for (int w0 = 0; w0 < nwin; w0 += (int)sc.piece_windows) {
         const int nw = std::min<int>((int)sc.piece_windows, nwin - w0);
         hipLaunchKernelGGL(dense_tile_kernel, dim3((unsigned)nblk, (unsigned)nw), dim3(64), 0, s, a.x, a.d, plan, w0, xq, xu);
-        hipLaunchKernelGGL(dense_gram_kernel, dim3((unsigned)nw), dim3(256), 0, s, xq, nblk, gram);
-        hipLaunchKernelGGL(kern, dim3((unsigned)ntiles), dim3(kNW * kWave), Lds::total, s, a, gram, xq, xu, plan, w0, nw);
+        hipLaunchKernelGGL(dense_gram_kernel, dim3((unsigned)nw), dim3(512), 0, s, xq, nblk, gram, gxt);
+        hipLaunchKernelGGL(kern, dim3((unsigned)ntiles), dim3(waves * kWave), lds_bytes, s, a, gram, gxt, xq, xu, plan, w0, nw);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -74,9 +74,9 @@ def test_steps_far_larger_than_the_ball_and_a_tiny_radius():
 ])
 @pytest.mark.parametrize("resident", [1, 0])
 def test_windowed_results_and_how_the_horizon_is_cut(name, over, resident):
-    """Windows end at the multiples of 64 of the horizon: calls that end there give the same bits
-    as one call; other cuts regroup float32 sums and agree to rounding.  Repeated runs are
-    bit-identical (every sum has a fixed order)."""
+    """Repeated runs are bit-identical (every sum has a fixed order).  Different cuts of the horizon
+    agree to float32 rounding: the first window of a call takes its inner products with the stored
+    iterates, later ones through the window before (and a cut inside a window regroups sums)."""
     opt = dict(WIN, window_resident=resident)
     wl = WL.make(name, **over)
     data = WL.generate(wl)
@@ -88,11 +88,8 @@ def test_windowed_results_and_how_the_horizon_is_cut(name, over, resident):
         print("case windowed", name, over, "chunk", c, flush=True)
         part = _gpu(wl, data, chunk=c, n_max=c, options=opt)
         for k in ("regret", "L", "W", "p", "wbar"):
-            if c % 64 == 0:
-                assert np.array_equal(whole[k], part[k]), (k, c)
-            else:
-                scale = max(1.0, float(np.abs(whole[k]).max()))
-                np.testing.assert_allclose(part[k], whole[k], rtol=0, atol=2e-6 * scale, err_msg="%s %d" % (k, c))
+            scale = max(1.0, float(np.abs(whole[k]).max()))
+            np.testing.assert_allclose(part[k], whole[k], rtol=0, atol=2e-6 * scale, err_msg="%s %d" % (k, c))
     _check(wl, data, part, label="windowed %s chunk 1" % name)
 
 
