@@ -28,13 +28,15 @@
 // per window.  ||w||^2 is carried through the windows by the scalar identity above (float64) and
 // re-anchored one window late on the exact sum of squares that the sweep takes of the new iterates.
 //
-// Where the tile's iterates fit in the registers of a workgroup (d <= 4096: eight wavefronts,
-// each with every eighth block of 16 coordinates, in the layout the matrix instruction writes:
-// a lane holds 4 coordinates of one learner) they stay there for a whole launch and the only
-// memory traffic is the round stream (from L2: every tile reads the same rows).  Otherwise the
-// same sweep loads each 16 x 16 block from HBM, updates it, takes its share of the next
-// window's inner products and writes it back: 8 bytes per coordinate, learner and window, all
-// in full 64-byte segments.
+// The iterates live in HBM between windows: the sweep loads each 16 x 16 block, updates it, takes
+// its share of the next window's inner products and writes it back, 8 bytes per coordinate,
+// learner and window, all in full 64-byte segments.  A workgroup works two tiles, so that every
+// round row a wavefront loads (from L2: all tiles read the same rows) serves 32 learners; a
+// compute unit draws only about 21 bytes per clock from L2, which is what bounds the sweep.
+// Variants (OCO_OPT_WINDOW_RESIDENT): the iterates of one tile held in the registers of the
+// workgroup for a whole launch (d <= 4096: eight wavefronts, each with every eighth block, in
+// the layout the matrix instruction writes: a lane holds 4 coordinates of one learner), and one
+// streamed tile worked by sixteen wavefronts.
 //
 // v_mfma_f32_16x16x4_f32 computes D = A B + C with A 16x4, B 4x16: lane l supplies
 // A[l % 16][l / 16] and B[l / 16][l % 16] and holds D[4 (l / 16) + r][l % 16] in register r.
@@ -71,6 +73,10 @@ constexpr int kNW16 = 16;         // ... iterates streamed from HBM (four per SI
 constexpr int kGStride = 18;      // doubles per (round, quad lane) row of the masked Gram table (16 + padding)
 constexpr int64_t kPieceBytes = 64ll << 20;   // stream per launch (each tiled copy is as large)
 constexpr int kTileFloats = kB * 16;          // one window x one block of 16 coordinates
+// A little scratch that lets the streamed sweep load and store without branches (a load or store
+// that may or may not have been issued makes every later wait a wait for everything): lanes
+// without a learner or past d read kMiscZeros zero floats and write to a sink of their own.
+constexpr int kMiscZeros = 16, kMiscFloats = kMiscZeros + 1024 * 4;
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
@@ -101,8 +107,10 @@ template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
 // One wavefront per (window, block of 16 coordinates).  xq[((w - w0) nblk + blk) 1024 + (rb 64 + l) 4 + r]
 // = x[round 16 rb + l % 16][coordinate 16 blk + 4 (l / 16) + r], xu[... + (k 64 + l) 4 + r]
 // = x[round 4 (4 k + r) + l / 16][coordinate 16 blk + l % 16]; zero past the window or past d.
-__global__ void __launch_bounds__(64) dense_tile_kernel(const float *x, int d, WinPlanD plan, int w0, float *xq, float *xu)
+__global__ void __launch_bounds__(64) dense_tile_kernel(const float *x, int d, WinPlanD plan, int w0, float *xq, float *xu,
+                                                        float *misc)
 {
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < kMiscZeros) misc[threadIdx.x] = 0.f;   // see kMiscZeros
     const int blk = blockIdx.x, w = w0 + blockIdx.y;
     const int nblk = gridDim.x;
     const int ws = plan.start(w), wl = plan.len(w);
@@ -182,29 +190,36 @@ __global__ void __launch_bounds__(512) dense_gram_kernel(const float *xq, int nb
 // LDS of the window kernel (dynamic), in bytes from the base.  What the dependent rounds of window
 // k write for the sweep (predictions, -Bm, F) and what is staged for them (Gram table with its
 // diagonal in the rows' padding, labels) has two buffers, window k in buffer k % 2: the sweep of
-// window k - 1 and the staging for window k + 1 run beside them.
-template <int NW> struct LdsT {
-    // the Gram table as float64 where the LDS has room (eight wavefronts), else float32
-    using G = std::conditional_t<NW == kNW8, double, float>;
+// window k - 1 and the staging for window k + 1 run beside them.  MT: tiles of 16 learners per
+// workgroup (per-tile arrays come MT times; the Gram table and the shares' buffer are common).
+template <int NW, int MT> struct LdsT {
+    // float64 where the LDS has room (one tile, eight wavefronts), else float32
+    static constexpr bool wide = NW == kNW8 && MT == 1;
+    using G = std::conditional_t<wide, double, float>;             // Gram table
+    using S = std::conditional_t<wide, double, float>;             // inner products handed to the rounds, f_t
     static constexpr int gd_bytes = kB * 4 * kGStride * (int)sizeof(G);   // G [64][4][kGStride]: G[t][t2], zero for t2 <= t;
                                                                    //   [t][0][16] holds G[t][t]
-    static constexpr int yb_bytes = kB * kM * 4;                   // float [64][16]: labels
-    static constexpr int zb_bytes = kB * kM * 4;                   // float [64][16]: predictions
-    static constexpr int bm_bytes = kB * kM * 4;                   // float [64][16]: -Bm
+    static constexpr int tile_f = kB * kM * 4;                     // float [64][16]
+    static constexpr int tile_s = kB * kM * (int)sizeof(S);        // S [64][16]
+    static constexpr int yb_bytes = MT * tile_f;                   // labels
+    static constexpr int zb_bytes = MT * tile_f;                   // predictions
+    static constexpr int bm_bytes = MT * tile_f;                   // -Bm
+    static constexpr int fv_bytes = MT * kM * 4;                   // float [16]: F
     static constexpr int gd = 0;
     static constexpr int yb = gd + 2 * gd_bytes;
     static constexpr int zb = yb + 2 * yb_bytes;
     static constexpr int bm = zb + 2 * zb_bytes;
-    static constexpr int fv = bm + 2 * bm_bytes;                   // float [2][16]: F
-    static constexpr int q0 = fv + 2 * kM * 4;                     // double [64][16]: W_{k-1} X_k^T
-    static constexpr int fl = q0 + kB * kM * 8;                    // double [64][16]: f_t
-    static constexpr int part = fl + kB * kM * 8;                  // float [NW][64][16]: per-wavefront shares of W X^T
-    static constexpr int st = part + NW * kB * kM * 4;             // float [64][16]: a_t
-    static constexpr int corr = st + kB * kM * 4;                  // float [64][16]: -Bm (X_{k-1} X_k^T)
-    static constexpr int n2 = corr + kB * kM * 4;                  // float [NW][4][16]: shares of ||w||^2
-    static constexpr int total = n2 + NW * 4 * kM * 4;
+    static constexpr int fv = bm + 2 * bm_bytes;
+    static constexpr int q0 = fv + 2 * fv_bytes;                   // S [MT][64][16]: W' X_k^T
+    static constexpr int fl = q0 + MT * tile_s;                    // S [MT][64][16]: f_t
+    static constexpr int part = fl + MT * tile_s;                  // float [NW][64][16]: per-wavefront shares of W X^T (one tile at a time)
+    static constexpr int st = part + NW * tile_f;                  // float [MT][64][16]: a_t
+    static constexpr int corr = st + MT * tile_f;                  // float [MT][64][16]: -Bm (X_{k-1} X_k^T)
+    static constexpr int n2 = corr + MT * tile_f;                  // float [MT][NW][4][16]: shares of ||w||^2
+    static constexpr int total = n2 + MT * NW * 4 * kM * 4;
 };
-static_assert(LdsT<kNW8>::total <= 160 * 1024 && LdsT<kNW16>::total <= 160 * 1024, "LDS of a gfx950 compute unit");
+static_assert(LdsT<kNW8, 1>::total <= 160 * 1024 && LdsT<kNW16, 1>::total <= 160 * 1024 && LdsT<kNW8, 2>::total <= 160 * 1024,
+              "LDS of a gfx950 compute unit");
 
 // every lane of a quad gets the value of the quad's lane SEL
 template <int SEL> __device__ __forceinline__ double quad_bcast(double v)
@@ -236,28 +251,29 @@ template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
 // Straight-line code: a window shorter than 64 rounds (first / last window of a call) runs its
 // missing rounds as rounds without a step (a = 0, so f = 1 and no pending prediction moves; their
 // rows of G are zero).
-template <int LOSS, int NW>
-__device__ __forceinline__ double chain_window(char *lds, int buf, int lane, int wl, float eta, double D, double pmul,
+template <int LOSS, int NW, int MT>
+__device__ __forceinline__ double chain_window(char *lds, int buf, int m, int lane, int wl, float eta, double D, double pmul,
                                                double fscale, double &n2, bool &projected)
 {
-    using Lds = LdsT<NW>;
+    using Lds = LdsT<NW, MT>;
     using GT = typename Lds::G;
+    using ST = typename Lds::S;
     const int lc = lane >> 2, s = lane & 3;
     const GT *gd = reinterpret_cast<const GT *>(lds + Lds::gd + buf * Lds::gd_bytes) + s * kGStride;
     const GT *x2d = reinterpret_cast<const GT *>(lds + Lds::gd + buf * Lds::gd_bytes) + 16;
-    const double *q0d = reinterpret_cast<const double *>(lds + Lds::q0) + s * kM + lc;
-    const float *cr = reinterpret_cast<const float *>(lds + Lds::corr) + s * kM + lc;
-    double *fl = reinterpret_cast<double *>(lds + Lds::fl) + lc;
-    const float *yb = reinterpret_cast<const float *>(lds + Lds::yb + buf * Lds::yb_bytes) + lc;
-    float *zb = reinterpret_cast<float *>(lds + Lds::zb + buf * Lds::zb_bytes) + lc;
-    float *stl = reinterpret_cast<float *>(lds + Lds::st) + lc;
+    const ST *q0d = reinterpret_cast<const ST *>(lds + Lds::q0 + m * Lds::tile_s) + s * kM + lc;
+    const float *cr = reinterpret_cast<const float *>(lds + Lds::corr + m * Lds::tile_f) + s * kM + lc;
+    ST *fl = reinterpret_cast<ST *>(lds + Lds::fl + m * Lds::tile_s) + lc;
+    const float *yb = reinterpret_cast<const float *>(lds + Lds::yb + buf * Lds::yb_bytes + m * Lds::tile_f) + lc;
+    float *zb = reinterpret_cast<float *>(lds + Lds::zb + buf * Lds::zb_bytes + m * Lds::tile_f) + lc;
+    float *stl = reinterpret_cast<float *>(lds + Lds::st + m * Lds::tile_f) + lc;
     const double D2 = D * D;
     const float eta2 = 2.f * eta;
     bool anyp = false;
 
     double p[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) p[j] = fma(pmul, q0d[4 * j * kM], (double)cr[4 * j * kM]);
+    for (int j = 0; j < 16; ++j) p[j] = fma(pmul, (double)q0d[4 * j * kM], (double)cr[4 * j * kM]);
 
     static_for<kB>([&](auto tc) __attribute__((always_inline)) {
         constexpr int t = decltype(tc)::value;
@@ -283,7 +299,7 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int lane, int
         anyp = anyp || pj;
         zb[t * kM] = z32;                                            // (the quad's four lanes write the same value)
         stl[t * kM] = a32;
-        fl[t * kM] = f;
+        fl[t * kM] = (ST)f;
 #pragma unroll
         for (int j = j0; j < 16; ++j) p[j] = f * fma(-at, gr[j - j0], p[j]);
         __builtin_amdgcn_sched_barrier(0);                           // rounds are not interleaved: registers
@@ -291,13 +307,13 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int lane, int
 
     // Bm[r] = a_r f_r f_{r+1} ... f_63 and F = fscale f_0 ... f_63: quad lane s takes the rounds
     // 16 s .. 16 s + 15 backwards, then the quad's products are combined
-    float *bm = reinterpret_cast<float *>(lds + Lds::bm + buf * Lds::bm_bytes) + lc;
-    float *fv = reinterpret_cast<float *>(lds + Lds::fv) + buf * kM;
+    float *bm = reinterpret_cast<float *>(lds + Lds::bm + buf * Lds::bm_bytes + m * Lds::tile_f) + lc;
+    float *fv = reinterpret_cast<float *>(lds + Lds::fv + buf * Lds::fv_bytes) + m * kM;
     double loc[16];
     double acc = 1.0;
 #pragma unroll
     for (int k = 15; k >= 0; --k) {
-        acc *= fl[(16 * s + k) * kM];
+        acc *= (double)fl[(16 * s + k) * kM];
         loc[k] = acc;
     }
     const double P0 = quad_bcast<0>(acc), P1 = quad_bcast<1>(acc), P2 = quad_bcast<2>(acc), P3 = quad_bcast<3>(acc);
@@ -316,49 +332,57 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int lane, int
 // What a thread is in the sweep, derived from its index.  The window loop re-derives it every
 // iteration from an index the compiler cannot see through, so that none of it (nor the many
 // addresses that follow from it) is kept alive across the dependent rounds.
-struct Geo {
+template <int MT> struct Geo {
     int tid, lane, wave, lr, lk;
-    bool q_ok;                 // this lane's learner exists
-    float *vrow;               // its row of the iterates, at this lane's 4 coordinates of a block
+    bool q_ok[MT];             // this lane's learner of tile m exists
+    float *vrow[MT];           // its row of the iterates, at this lane's 4 coordinates of a block
 };
-__device__ __forceinline__ Geo make_geo(int tid, const DenseArgs &a)
+template <int MT> __device__ __forceinline__ Geo<MT> make_geo(int tid, const DenseArgs &a)
 {
-    Geo g;
+    Geo<MT> g;
     g.tid = tid;
     g.lane = tid & 63;
     g.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     g.lr = g.lane & 15;
     g.lk = g.lane >> 4;
-    const int q = (int)blockIdx.x * kM + g.lr;
-    g.q_ok = q < a.R * a.K;
-    g.vrow = a.V + (int64_t)(g.q_ok ? q : 0) * a.d + 4 * g.lk;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int q = ((int)blockIdx.x * MT + m) * kM + g.lr;
+        g.q_ok[m] = q < a.R * a.K;
+        g.vrow[m] = a.V + (int64_t)(g.q_ok[m] ? q : 0) * a.d + 4 * g.lk;
+    }
     return g;
 }
 
 // The windows w0 .. w0 + nw - 1 of the call's plan; xq / xu / gram / gxt hold those windows only.
-// RES: the tile's iterates stay in registers for the whole launch (d <= 16 * NW * NB); otherwise
-// every block is loaded and stored in the sweep.  NW: wavefronts per workgroup.
+// RES: the iterates stay in registers for the whole launch (one tile, d <= 16 * NW * NB); otherwise
+// every block is loaded and stored in the sweep.  NW: wavefronts per workgroup.  MT: tiles of 16
+// learners per workgroup -- with two, a wavefront uses every round row it loads for both (a compute
+// unit draws only about 21 bytes per clock from L2, and the sweep of one tile needs 8 KB of rows per
+// 32 matrix instructions); wavefront m runs the dependent rounds of tile m.
 //
-// Iteration k = 0 .. nw of the main loop (two barriers each):
-//   all        the shares of W' X_k^T -> q0 (float64); wavefronts 0..3: corr = -Bm_{k-1} Gx_k (k >= 1)
-//   wavefront 0    the dependent rounds of window k (k < nw), then its part of the sweep
+// Iteration k = 0 .. nw of the main loop:
+//   all        the shares of W' X_k^T -> q0, tile by tile; four wavefronts per tile: corr = -Bm_{k-1} Gx_k (k >= 1)
+//   wavefronts < MT    the dependent rounds of window k (k < nw), then their part of the sweep
 //   the others     predictions of window k - 1 to Z, staging for window k + 1, the sweep
 //   sweep (k >= 1) W_k = F_{k-1} W_{k-1} - Bm_{k-1} X_{k-1} block by block, its squared norm, and the
 //                  shares of W_k X_{k+1}^T (k + 1 < nw)
-template <int LOSS, int NB, bool RES, int NW>
+template <int LOSS, int NB, bool RES, int NW, int MT>
 __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs a, const float *gram, const float *gxt,
-                                                                  const float *xq, const float *xu, WinPlanD plan, int w0,
-                                                                  int nw)
+                                                                  const float *xq, const float *xu, float *misc,
+                                                                  WinPlanD plan, int w0, int nw)
 {
-    constexpr int kNW = NW;
-    using Lds = LdsT<NW>;
+    static_assert(!(RES && MT != 1), "iterates in registers: one tile per workgroup");
+    using Lds = LdsT<NW, MT>;
     using GT = typename Lds::G;
+    using ST = typename Lds::S;
     // -Bm in registers for the whole sweep, or (where registers are short) re-read from LDS per block
     constexpr bool BMR = RES && NB <= 8;
     extern __shared__ __align__(16) char lds[];
     const int d = a.d, K = a.K;
     const int nq = a.R * K;
     const int nblk = (d + 15) / 16;                             // blocks of 16 coordinates
+    const int q_base = (int)blockIdx.x * MT * kM;               // first learner of the workgroup
 
     // Which blocks of 16 coordinates a wavefront takes.  In registers: wave, wave + NW, ...  Streamed
     // with sixteen wavefronts: wavefront 0 also runs the dependent rounds, so it takes half a share:
@@ -369,24 +393,42 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
             if (wave == 0) return 31 * i + 30;
             return 31 * (i >> 1) + (wave - 1) + ((i & 1) ? 15 : 0);
         }
+        if (MT == 2) {
+            // two tiles, eight wavefronts: wavefronts 0 and 1 run the dependent rounds first and take two
+            // blocks of every 22, the other six three each
+            if (wave < 2) return 22 * (i >> 1) + 6 + wave + 8 * (i & 1);
+            return 22 * (i / 3) + (wave - 2) + 8 * (i % 3);
+        }
         return wave + NW * i;
     };
-    // the tile's iterates: 16 coordinates x 16 learners per block, transposed
-    auto ld_block = [&](const Geo &g, int blk) __attribute__((always_inline)) {
+    // a tile's iterates: 16 coordinates x 16 learners per block, transposed
+    auto ld_block = [&](const Geo<MT> &g, int m, int blk) __attribute__((always_inline)) {
         f4 v = f4{0.f, 0.f, 0.f, 0.f};
-        if (g.q_ok && blk * 16 + 4 * g.lk < d) v = *reinterpret_cast<const f4 *>(g.vrow + blk * 16);
+        if (g.q_ok[m] && blk * 16 + 4 * g.lk < d) v = *reinterpret_cast<const f4 *>(g.vrow[m] + blk * 16);
         return v;
     };
-    auto st_block = [&](const Geo &g, int blk, const f4 &v) __attribute__((always_inline)) {
-        if (g.q_ok && blk * 16 + 4 * g.lk < d) *reinterpret_cast<f4 *>(g.vrow + blk * 16) = v;
+    auto st_block = [&](const Geo<MT> &g, int m, int blk, const f4 &v) __attribute__((always_inline)) {
+        if (g.q_ok[m] && blk * 16 + 4 * g.lk < d) *reinterpret_cast<f4 *>(g.vrow[m] + blk * 16) = v;
+    };
+    // the same without a branch (streamed sweep): every lane loads and stores, the lanes without a
+    // learner or past d from / to the scratch words
+    auto ld_block_nb = [&](const Geo<MT> &g, int m, int blk) __attribute__((always_inline)) {
+        const bool ok = g.q_ok[m] && blk * 16 + 4 * g.lk < d;
+        const float *src = ok ? g.vrow[m] + blk * 16 : misc;
+        return *reinterpret_cast<const f4 *>(src);
+    };
+    auto st_block_nb = [&](const Geo<MT> &g, int m, int blk, const f4 &v) __attribute__((always_inline)) {
+        const bool ok = g.q_ok[m] && blk * 16 + 4 * g.lk < d;
+        float *dst = ok ? g.vrow[m] + blk * 16 : misc + kMiscZeros + g.tid * 4;
+        *reinterpret_cast<f4 *>(dst) = v;
     };
     // the tiled round rows of window wi (relative to w0), block blk: four 16-byte loads per lane each
-    auto ldq = [&](const Geo &g, int wi, int blk, f4 (&o)[4]) __attribute__((always_inline)) {
+    auto ldq = [&](const Geo<MT> &g, int wi, int blk, f4 (&o)[4]) __attribute__((always_inline)) {
         const float *t = xq + ((int64_t)wi * nblk + blk) * kTileFloats + g.lane * 4;
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) o[rb] = *reinterpret_cast<const f4 *>(t + rb * 256);
     };
-    auto ldu = [&](const Geo &g, int wi, int blk, f4 (&o)[4]) __attribute__((always_inline)) {
+    auto ldu = [&](const Geo<MT> &g, int wi, int blk, f4 (&o)[4]) __attribute__((always_inline)) {
         const float *t = xu + ((int64_t)wi * nblk + blk) * kTileFloats + g.lane * 4;
 #pragma unroll
         for (int k = 0; k < 4; ++k) o[k] = *reinterpret_cast<const f4 *>(t + k * 256);
@@ -398,12 +440,12 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
         const int ws = plan.start(w), wl = plan.len(w);
         float *yb = reinterpret_cast<float *>(lds + Lds::yb + buf * Lds::yb_bytes);
         GT *gd = reinterpret_cast<GT *>(lds + Lds::gd + buf * Lds::gd_bytes);
-        for (int e = tid; e < kB * kM; e += nthr) {
-            const int l16 = e >> 6, t = e & 63;                 // a learner's 64 labels are contiguous
-            const int q = (int)blockIdx.x * kM + l16;
+        for (int e = tid; e < MT * kB * kM; e += nthr) {
+            const int l = e >> 6, t = e & 63;                   // a learner's 64 labels are contiguous
+            const int q = q_base + l;
             float yv = 0.f;
             if (a.y && q < nq && t < wl) yv = a.y[(int64_t)(q / K) * a.y_run_stride + ws + t];
-            yb[t * kM + l16] = yv;
+            yb[((l >> 4) * kB + t) * kM + (l & 15)] = yv;
         }
         const float *gsrc = gram + (int64_t)wi * kB * kB;
         for (int e = tid; e < kB * kB; e += nthr) {
@@ -413,87 +455,110 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
             if (t2 == t) gd[t * 4 * kGStride + 16] = (GT)gv;
         }
     };
-    // shares of this wavefront of W X^T for one window -> LDS
-    auto put_part = [&](const Geo &g, const f4 (&acc)[4]) __attribute__((always_inline)) {
+    // shares of this wavefront of one tile's W X^T for one window -> LDS
+    auto put_part = [&](const Geo<MT> &g, const f4 (&acc)[4]) __attribute__((always_inline)) {
         float *part = reinterpret_cast<float *>(lds + Lds::part);
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) part[(g.wave * kB + rb * 16 + 4 * g.lk + r) * kM + g.lr] = acc[rb][r];
     };
-
-    // W' X_k^T = sum of the eight shares, fixed order, as float64
-    auto sum_parts = [&](int tid) __attribute__((always_inline)) {
+    // tile m's W' X_k^T = sum of the wavefronts' shares, fixed order, summed in float64
+    auto sum_parts = [&](int tid, int m) __attribute__((always_inline)) {
         const float *part = reinterpret_cast<const float *>(lds + Lds::part);
-        double *q0d = reinterpret_cast<double *>(lds + Lds::q0);
+        ST *q0d = reinterpret_cast<ST *>(lds + Lds::q0 + m * Lds::tile_s);
 #pragma unroll
-        for (int u = 0; u < kB * kM / (kNW * kWave); ++u) {
-            const int e = tid + u * kNW * kWave;
+        for (int u = 0; u < kB * kM / (NW * kWave); ++u) {
+            const int e = tid + u * NW * kWave;
             double sum = 0.0;
 #pragma unroll
-            for (int v = 0; v < kNW; ++v) sum += (double)part[v * kB * kM + e];
-            q0d[e] = sum;
+            for (int v = 0; v < NW; ++v) sum += (double)part[v * kB * kM + e];
+            q0d[e] = (ST)sum;
         }
     };
+    // ||w||^2 of tile m's learner lc as the last sweep measured it: 4 NW shares, fixed order
+    auto measured_n2 = [&](int m, int lc) __attribute__((always_inline)) {
+        const float *n2s = reinterpret_cast<const float *>(lds + Lds::n2) + m * NW * 4 * kM;
+        double v = 0.0;
+#pragma unroll
+        for (int i = 0; i < NW * 4; ++i) v += (double)n2s[i * kM + lc];
+        return v;
+    };
 
-    // ---- per-learner state of the dependent rounds (wavefront 0: lane = 4 learner + quad lane) ----
+    // ---- per-learner state of the dependent rounds (wavefront m < MT: lane = 4 learner + quad lane) ----
     float eta = 0.f;
     double pmul = 1.0;          // scale of the iterates q0 was taken with: sigma of the state, then F of the window before
     double n2 = 0.0;            // ||w_k||^2 as the scalar identity carries it
     double n2_begin = 0.0;      // what the previous window's rounds started from
     bool proj_prev = true;      // whether they projected this learner (then n2 was reset to D^2 on the way)
     f4 V[RES ? NB : 1];
+    f4 accq[MT][4];             // this wavefront's shares of W_k X_{k+1}^T; tile 0's go to LDS at once, the others wait their turn
     {
-        const Geo g = make_geo((int)threadIdx.x, a);
-        const int q_ch = (int)blockIdx.x * kM + (g.lane >> 2);
-        if (g.wave == 0 && q_ch < nq) {
+        const Geo<MT> g = make_geo<MT>((int)threadIdx.x, a);
+        const int q_ch = q_base + g.wave * kM + (g.lane >> 2);
+        if (g.wave < MT && q_ch < nq) {
             eta = a.eta[q_ch % K];
             pmul = (double)a.sigma[q_ch];
             n2 = a.n2[q_ch] * pmul * pmul;                      // ||w||^2 of the iterate itself
         }
         if (RES) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) V[b] = ld_block(g, g.wave + kNW * b);
+            for (int b = 0; b < NB; ++b) V[b] = ld_block(g, 0, g.wave + NW * b);
         }
         // ---- prologue: the stored iterates times the rows of the first two windows -----------------
-        f4 acc0[4], acc1[4];
+        f4 acc0[MT][4];
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) { acc0[rb] = f4{0.f, 0.f, 0.f, 0.f}; acc1[rb] = f4{0.f, 0.f, 0.f, 0.f}; }
-        auto q_of = [&](const f4 &vb, int blk) __attribute__((always_inline)) {
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) { acc0[m][rb] = f4{0.f, 0.f, 0.f, 0.f}; accq[m][rb] = f4{0.f, 0.f, 0.f, 0.f}; }
+        auto q_of = [&](const f4 (&vb)[MT], int blk) __attribute__((always_inline)) {
             f4 xr[4];
             ldq(g, 0, blk, xr);
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int rb = 0; rb < 4; ++rb)
-                    acc0[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[rb][r], vb[r], acc0[rb], 0, 0, 0);
-            if (nw > 1) {
-                ldq(g, 1, blk, xr);
+            for (int m = 0; m < MT; ++m)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
 #pragma unroll
                     for (int rb = 0; rb < 4; ++rb)
-                        acc1[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[rb][r], vb[r], acc1[rb], 0, 0, 0);
+                        acc0[m][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[rb][r], vb[m][r], acc0[m][rb], 0, 0, 0);
+            if (nw > 1) {
+                ldq(g, 1, blk, xr);
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+#pragma unroll
+                        for (int rb = 0; rb < 4; ++rb)
+                            accq[m][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[rb][r], vb[m][r], accq[m][rb], 0, 0, 0);
             }
         };
         if constexpr (RES) {
             static_for<NB>([&](auto bc) __attribute__((always_inline)) {
                 constexpr int b = decltype(bc)::value;
-                const int blk = g.wave + kNW * b;
-                if (blk < nblk) q_of(V[b], blk);
+                const int blk = g.wave + NW * b;
+                f4 vb[1] = {V[b]};
+                if (blk < nblk) q_of(vb, blk);
             });
         } else {
-            for (int i = 0, blk = nth_block(g.wave, 0); blk < nblk; blk = nth_block(g.wave, ++i)) q_of(ld_block(g, blk), blk);
+            for (int i = 0, blk = nth_block(g.wave, 0); blk < nblk; blk = nth_block(g.wave, ++i)) {
+                f4 vb[MT];
+#pragma unroll
+                for (int m = 0; m < MT; ++m) vb[m] = ld_block(g, m, blk);
+                q_of(vb, blk);
+            }
         }
-        put_part(g, acc0);
-        stage_chain_inputs(g.tid, kNW * kWave, 0);
+        stage_chain_inputs(g.tid, NW * kWave, 0);
         float *corr = reinterpret_cast<float *>(lds + Lds::corr);
-        for (int e = g.tid; e < kB * kM; e += kNW * kWave) corr[e] = 0.f;
-        // the shares of window 0 are summed here, so that those of window 1 can take their place
-        __syncthreads();
-        sum_parts(g.tid);
-        __syncthreads();
-        if (nw > 1) put_part(g, acc1);
+        for (int e = g.tid; e < MT * kB * kM; e += NW * kWave) corr[e] = 0.f;
+        // the shares of window 0 are summed here, tile by tile, so that those of window 1 can take their place
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            put_part(g, acc0[m]);
+            __syncthreads();
+            sum_parts(g.tid, m);
+            __syncthreads();
+        }
+        if (nw > 1) put_part(g, accq[0]);
     }
 
 #ifdef OCO_WIN_PROF
@@ -508,150 +573,217 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
         // the cross Gram matrix of windows k - 1 and k as matrix operand, on its way across the barrier
         f4 gx[4];
         const int wave_w = __builtin_amdgcn_readfirstlane(tid_w >> 6);
-        if (rounds && sweep && wave_w < 4) {
-            const float *t = gxt + (int64_t)k * kB * kB + wave_w * 1024 + (tid_w & 63) * 4;
+        const bool corr_wave = rounds && sweep && wave_w < 4 * MT;   // four wavefronts per tile
+        if (corr_wave) {
+            const float *t = gxt + (int64_t)k * kB * kB + (wave_w & 3) * 1024 + (tid_w & 63) * 4;
 #pragma unroll
             for (int j = 0; j < 4; ++j) gx[j] = *reinterpret_cast<const f4 *>(t + j * 256);
         }
         __syncthreads();                                         // (A) shares of W' X_k^T, -Bm_{k-1}, staged inputs in LDS
         PROF_T(0);
-        if (rounds) {
-            if (k >= 1) sum_parts(tid_w);                        // (window 0: summed in the prologue)
-            if (sweep && wave_w < 4) {
-                // corr[t][learner] = -sum_r Bm_{k-1}[r][learner] Gx[r][t], rows t = 16 wave .. + 15
-                const float *bmp = reinterpret_cast<const float *>(lds + Lds::bm + ((k - 1) & 1) * Lds::bm_bytes);
-                const int lr = tid_w & 15, lk = (tid_w & 63) >> 4;
-                f4 c = f4{0.f, 0.f, 0.f, 0.f};
+        if (rounds && k >= 1) {                                  // (window 0: summed in the prologue)
+            sum_parts(tid_w, 0);
+            if (MT > 1) {
+                const Geo<MT> g1 = make_geo<MT>(tid_w, a);
 #pragma unroll
-                for (int rs = 0; rs < 16; ++rs)
-                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(gx[rs >> 2][rs & 3], bmp[(rs * 4 + lk) * kM + lr], c, 0, 0, 0);
-                float *corr = reinterpret_cast<float *>(lds + Lds::corr);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) corr[(wave_w * 16 + 4 * lk + r) * kM + lr] = c[r];
+                for (int m = 1; m < MT; ++m) {
+                    __syncthreads();
+                    put_part(g1, accq[m]);
+                    __syncthreads();
+                    sum_parts(tid_w, m);
+                }
             }
+        }
+        if (corr_wave) {
+            // corr[t][learner] = -sum_r Bm_{k-1}[r][learner] Gx[r][t], rows t = 16 (wave % 4) .. + 15, tile wave / 4
+            const int m = wave_w >> 2, rbw = wave_w & 3;
+            const float *bmp = reinterpret_cast<const float *>(lds + Lds::bm + ((k - 1) & 1) * Lds::bm_bytes + m * Lds::tile_f);
+            const int lr = tid_w & 15, lk = (tid_w & 63) >> 4;
+            f4 c = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int rs = 0; rs < 16; ++rs)
+                c = __builtin_amdgcn_mfma_f32_16x16x4f32(gx[rs >> 2][rs & 3], bmp[(rs * 4 + lk) * kM + lr], c, 0, 0, 0);
+            float *corr = reinterpret_cast<float *>(lds + Lds::corr + m * Lds::tile_f);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) corr[(rbw * 16 + 4 * lk + r) * kM + lr] = c[r];
         }
         __syncthreads();                                         // (B)
         PROF_T(1);
-        if (wave_w == 0) {
+        if (wave_w < MT) {
             if (rounds) {
                 const int lane = tid_w & 63;
-                if (k >= 2 && !proj_prev) {
-                    // ||w_{k-1}||^2 as the sweep of window k - 2 measured it (32 shares per learner,
-                    // fixed order) against what the rounds of window k - 1 started from: without a
-                    // projection in between the difference is still in n2
-                    const float *n2s = reinterpret_cast<const float *>(lds + Lds::n2);
-                    double m = 0.0;
-                    const int lc = lane >> 2;
-#pragma unroll
-                    for (int v = 0; v < kNW; ++v)
-#pragma unroll
-                        for (int g4 = 0; g4 < 4; ++g4) m += (double)n2s[(v * 4 + g4) * kM + lc];
-                    n2 += m - n2_begin;
+                if (k >= 2) {
+                    // ||w_{k-1}||^2 as the sweep of window k - 2 measured it against what the rounds of window
+                    // k - 1 started from: the difference (float32 rounding of the sweeps) went through those
+                    // rounds added to every squared norm, and every projection among them scaled it by f^2
+                    // (to first order), so F_{k-1}^2 of it is still in the iterate and missing from n2.  The
+                    // next projection then removes it from the iterate as well.
+                    n2 = fma(measured_n2(wave_w, lane >> 2) - n2_begin, pmul * pmul, n2);
                     n2 = n2 > 0.0 ? n2 : 0.0;
                 }
                 n2_begin = n2;
                 const double fscale = k == 0 ? pmul : 1.0;
-                pmul = chain_window<LOSS, NW>(lds, k & 1, lane, plan.len(w0 + k), eta, (double)a.D, pmul, fscale, n2, proj_prev);
+                pmul = chain_window<LOSS, NW, MT>(lds, k & 1, wave_w, lane, plan.len(w0 + k), eta, (double)a.D, pmul, fscale,
+                                                  n2, proj_prev);
             }
         } else {
+            const int tid_o = tid_w - MT * kWave, nthr_o = (NW - MT) * kWave;
             // beside the dependent rounds: the next window's labels and Gram table into the other buffer
-            if (more) stage_chain_inputs(tid_w - kWave, (kNW - 1) * kWave, k + 1);
-            // ... and the predictions of window k - 1 to Z (wavefronts 1 .. 7, a learner's rounds contiguous)
+            if (more) stage_chain_inputs(tid_o, nthr_o, k + 1);
+            // ... and the predictions of window k - 1 to Z (a learner's rounds contiguous)
             if (sweep) {
                 const int w = w0 + k - 1;
                 const int ws = plan.start(w), wl = plan.len(w);
                 const float *zb = reinterpret_cast<const float *>(lds + Lds::zb + ((k - 1) & 1) * Lds::zb_bytes);
-                for (int e = tid_w - kWave; e < kB * kM; e += (kNW - 1) * kWave) {
-                    const int l16 = e >> 6, t = e & 63;
-                    const int q = (int)blockIdx.x * kM + l16;
+                for (int e = tid_o; e < MT * kB * kM; e += nthr_o) {
+                    const int l = e >> 6, t = e & 63;
+                    const int q = q_base + l;
                     if (q < nq && t < wl)
-                        a.Z[(int64_t)(q / K) * a.zl.zs_r + (int64_t)(q % K) * a.zl.zs_i + (int64_t)(ws + t) * a.zl.zs_t] = zb[t * kM + l16];
+                        a.Z[(int64_t)(q / K) * a.zl.zs_r + (int64_t)(q % K) * a.zl.zs_i + (int64_t)(ws + t) * a.zl.zs_t] =
+                            zb[((l >> 4) * kB + t) * kM + (l & 15)];
                 }
             }
         }
         PROF_T(2);
         asm volatile("" : "+v"(tid_w));
-        const Geo g = make_geo(tid_w, a);
+        const Geo<MT> g = make_geo<MT>(tid_w, a);
         const int lr = g.lr, lk = g.lk;
 
         // ---- sweep: (3) of window k - 1 and W_k X_{k+1}^T, block by block ------------------------------
-        // The round rows (and, where the iterates live in HBM, the block itself) of the next block
-        // are on their way while the matrix instructions of the current block run.
         if (sweep) {
             const int wi = k - 1;
             const float *bml = reinterpret_cast<const float *>(lds + Lds::bm + (wi & 1) * Lds::bm_bytes);
-            float bmr[BMR ? 16 : 1];
-            if (BMR) {
+            float bmr[MT][BMR ? 16 : 1];
+            float F[MT];
 #pragma unroll
-                for (int rs = 0; rs < 16; ++rs) bmr[rs] = bml[(rs * 4 + lk) * kM + lr];
+            for (int m = 0; m < MT; ++m) {
+                if (BMR) {
+#pragma unroll
+                    for (int rs = 0; rs < 16; ++rs) bmr[m][rs] = bml[m * kB * kM + (rs * 4 + lk) * kM + lr];
+                }
+                F[m] = reinterpret_cast<const float *>(lds + Lds::fv + (wi & 1) * Lds::fv_bytes)[m * kM + lr];
             }
-            const float F = reinterpret_cast<const float *>(lds + Lds::fv)[(wi & 1) * kM + lr];
-            f4 acc[4];
+            f4 acc[MT][4];
 #pragma unroll
-            for (int rb = 0; rb < 4; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
-            float nn = 0.f;
-            struct BlkIn { f4 xu[4]; f4 xq[4]; f4 vb; };
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) acc[m][rb] = f4{0.f, 0.f, 0.f, 0.f};
+            float nn[MT];
+#pragma unroll
+            for (int m = 0; m < MT; ++m) nn[m] = 0.f;
+            struct BlkIn { f4 xu[4]; f4 xq[4]; f4 vb[MT]; };
+            const int wq = more ? k + 1 : k;                     // (no window after the last: any rows, unused)
             auto load_in = [&](BlkIn &in, int blk) __attribute__((always_inline)) {
-#ifdef OCO_WIN_NOLOAD
-                if (blk < 0) {
-#else
-                if (blk < nblk) {
-#endif
-                    ldu(g, wi, blk, in.xu);
-                    if (more) ldq(g, k + 1, blk, in.xq);
-                    if (!RES) in.vb = ld_block(g, blk);
+                if constexpr (RES) {
+                    if (blk < nblk) {
+                        ldu(g, wi, blk, in.xu);
+                        if (more) ldq(g, k + 1, blk, in.xq);
+                    }
+                } else {
+                    // no branch around a load: a block past the end reads the last one again
+                    const int b = blk < nblk ? blk : nblk - 1;
+                    ldu(g, wi, b, in.xu);
+                    ldq(g, wq, b, in.xq);
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) in.vb[m] = ld_block_nb(g, m, b);
                 }
             };
             auto compute = [&](BlkIn &in, f4 &vreg, int blk) __attribute__((always_inline)) {
-                f4 vb = RES ? vreg : in.vb;
-                f4 vo = f4{0.f, 0.f, 0.f, 0.f};                  // two chains of eight dependent instructions
+                f4 vb[MT], vo[MT];                               // per tile two chains of eight dependent instructions
 #pragma unroll
-                for (int r = 0; r < 4; ++r) vb[r] *= F;
+                for (int m = 0; m < MT; ++m) {
+                    vb[m] = RES ? vreg : in.vb[m];
+                    vo[m] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int rs = 0; rs < 16; rs += 2) {
-                    vb = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs >> 2][rs & 3], BMR ? bmr[BMR ? rs : 0] : bml[(rs * 4 + lk) * kM + lr], vb, 0, 0, 0);
-                    vo = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs >> 2][(rs & 3) + 1], BMR ? bmr[BMR ? rs + 1 : 0] : bml[((rs + 1) * 4 + lk) * kM + lr], vo, 0, 0, 0);
+                    for (int r = 0; r < 4; ++r) vb[m][r] *= F[m];
                 }
 #pragma unroll
-                for (int r = 0; r < 4; ++r) vb[r] += vo[r];
+                for (int rs = 0; rs < 16; rs += 2)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) nn = fmaf(vb[r], vb[r], nn);
-                if (RES) vreg = vb; else st_block(g, blk, vb);
+                    for (int m = 0; m < MT; ++m) {
+                        const float b0 = BMR ? bmr[m][BMR ? rs : 0] : bml[m * kB * kM + (rs * 4 + lk) * kM + lr];
+                        const float b1 = BMR ? bmr[m][BMR ? rs + 1 : 0] : bml[m * kB * kM + ((rs + 1) * 4 + lk) * kM + lr];
+                        vb[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs >> 2][rs & 3], b0, vb[m], 0, 0, 0);
+                        vo[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xu[rs >> 2][(rs & 3) + 1], b1, vo[m], 0, 0, 0);
+                    }
+#pragma unroll
+                for (int m = 0; m < MT; ++m) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) vb[m][r] += vo[m][r];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) nn[m] = fmaf(vb[m][r], vb[m][r], nn[m]);
+                    if (RES) vreg = vb[m]; else st_block_nb(g, m, blk, vb[m]);
+                }
                 if (more) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
 #pragma unroll
                         for (int rb = 0; rb < 4; ++rb)
-                            acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xq[rb][r], vb[r], acc[rb], 0, 0, 0);
+#pragma unroll
+                            for (int m = 0; m < MT; ++m)
+                                acc[m][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xq[rb][r], vb[m][r], acc[m][rb], 0, 0, 0);
                 }
             };
-            BlkIn in[RES ? 2 : 1];
+            f4 none;
             if constexpr (RES) {
+                // The round rows of the next block are on their way while the matrix instructions of the
+                // current block run.
+                BlkIn in[2];
                 load_in(in[0], g.wave);
                 static_for<NB>([&](auto bc) __attribute__((always_inline)) {
                     constexpr int b = decltype(bc)::value;
-                    const int blk = g.wave + kNW * b;
-                    if (b + 1 < NB) load_in(in[(b + 1) & 1], blk + kNW);
+                    const int blk = g.wave + NW * b;
+                    if (b + 1 < NB) load_in(in[(b + 1) & 1], blk + NW);
                     __builtin_amdgcn_sched_barrier(0);
                     if (blk < nblk) compute(in[b & 1], V[b], blk);
                     __builtin_amdgcn_sched_barrier(0);
                 });
-            } else {
+            } else if constexpr (NW == kNW16) {
                 // One set of input registers: a block's loads are issued when the block before it is
                 // done, and the other three wavefronts of the SIMD keep the matrix cores busy meanwhile.
-                // (Loads issued earlier would not help: the block's store shares their counter, which
-                // only orders loads among themselves, so every wait behind a store waits for everything.)
-                f4 none;
+                BlkIn in;
                 for (int i = 0, blk = nth_block(g.wave, 0); blk < nblk; blk = nth_block(g.wave, ++i)) {
-                    load_in(in[0], blk);
+                    load_in(in, blk);
                     __builtin_amdgcn_sched_barrier(0);
-                    compute(in[0], none, blk);
+                    compute(in, none, blk);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+            } else {
+                // Two sets of input registers: the next block's loads are in flight during a block's
+                // matrix instructions.  No load or store of the loop sits under a branch, so that every
+                // wait leaves exactly the younger ones outstanding (the block's two stores and the eleven
+                // loads of the next block).
+                BlkIn in[2];
+                int i = 0;
+                load_in(in[0], nth_block(g.wave, 0));
+                // (the loop is entered the way it is re-entered, with MT stores younger than the loads:
+                // the wait at its head is computed from both and would otherwise drain the stores)
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    *reinterpret_cast<f4 *>(misc + kMiscZeros + m * 2048 + g.tid * 4) = f4{0.f, 0.f, 0.f, 0.f};
+                for (; nth_block(g.wave, i + 1) < nblk; i += 2) {
+                    load_in(in[1], nth_block(g.wave, i + 1));
+                    __builtin_amdgcn_sched_barrier(0);
+                    compute(in[0], none, nth_block(g.wave, i));
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_in(in[0], nth_block(g.wave, i + 2));
+                    __builtin_amdgcn_sched_barrier(0);
+                    compute(in[1], none, nth_block(g.wave, i + 1));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (nth_block(g.wave, i) < nblk) compute(in[0], none, nth_block(g.wave, i));
             }
             PROF_T(4);
-            reinterpret_cast<float *>(lds + Lds::n2)[(g.wave * 4 + lk) * kM + lr] = nn;
-            if (more) put_part(g, acc);
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+                reinterpret_cast<float *>(lds + Lds::n2)[m * NW * 4 * kM + (g.wave * 4 + lk) * kM + lr] = nn[m];
+            if (more) {
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb) accq[m][rb] = acc[m][rb];
+                put_part(g, accq[0]);
+            }
         }
         PROF_T(5);
     }
@@ -662,41 +794,45 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
 
     // ---- state out: the iterates themselves (scale 1) and their squared norms ---------------------
     {
-        const Geo g = make_geo((int)threadIdx.x, a);
+        const Geo<MT> g = make_geo<MT>((int)threadIdx.x, a);
         if (RES) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) st_block(g, g.wave + kNW * b, V[b]);
+            for (int b = 0; b < NB; ++b) st_block(g, 0, g.wave + NW * b, V[b]);
         }
         __syncthreads();
-        const int q_ch = (int)blockIdx.x * kM + (g.lane >> 2);
-        if (g.wave == 0 && (g.lane & 3) == 0 && q_ch < nq) {
-            const float *n2s = reinterpret_cast<const float *>(lds + Lds::n2);
-            double m = 0.0;
-            const int lc = g.lane >> 2;
-            for (int v = 0; v < kNW; ++v)
-                for (int g4 = 0; g4 < 4; ++g4) m += (double)n2s[(v * 4 + g4) * kM + lc];
+        const int q_ch = q_base + g.wave * kM + (g.lane >> 2);
+        if (g.wave < MT && (g.lane & 3) == 0 && q_ch < nq) {
             a.sigma[q_ch] = 1.f;
-            a.n2[q_ch] = m;
+            a.n2[q_ch] = measured_n2(g.wave, g.lane >> 2);
         }
     }
 }
 
-using WindowKernel = void (*)(const DenseArgs, const float *, const float *, const float *, const float *, WinPlanD, int, int);
+using WindowKernel = void (*)(const DenseArgs, const float *, const float *, const float *, const float *, float *, WinPlanD, int,
+                              int);
 
-template <int LOSS> WindowKernel pick_window_kernel(int nblk, bool resident, int *waves, int *lds_bytes)
+// mode 0: iterates in registers (8 wavefronts, one tile); 1: streamed, two tiles per workgroup
+// (8 wavefronts); 2: streamed, one tile, 16 wavefronts
+template <int LOSS> WindowKernel pick_window_kernel(int nblk, int mode, int *waves, int *tiles, int *lds_bytes)
 {
-    *waves = resident ? kNW8 : kNW16;
-    *lds_bytes = resident ? LdsT<kNW8>::total : LdsT<kNW16>::total;
-    if (resident && nblk <= 8 * kNW8) return dense_window_kernel<LOSS, 8, true, kNW8>;
-    if (resident) return dense_window_kernel<LOSS, 32, true, kNW8>;
-    return dense_window_kernel<LOSS, 1, false, kNW16>;
+    if (mode == 0) {
+        *waves = kNW8; *tiles = 1; *lds_bytes = LdsT<kNW8, 1>::total;
+        if (nblk <= 8 * kNW8) return dense_window_kernel<LOSS, 8, true, kNW8, 1>;
+        return dense_window_kernel<LOSS, 32, true, kNW8, 1>;
+    }
+    if (mode == 1) {
+        *waves = kNW8; *tiles = 2; *lds_bytes = LdsT<kNW8, 2>::total;
+        return dense_window_kernel<LOSS, 1, false, kNW8, 2>;
+    }
+    *waves = kNW16; *tiles = 1; *lds_bytes = LdsT<kNW16, 1>::total;
+    return dense_window_kernel<LOSS, 1, false, kNW16, 1>;
 }
 
 // scratch: Gram and cross Gram matrices of the windows of a piece, then the two tiled copies of its rows
 struct Scratch {
     int64_t piece_windows;      // windows per launch
     size_t gram_floats, tile_floats;
-    size_t total_floats() const { return 2 * gram_floats + 2 * tile_floats; }
+    size_t total_floats() const { return 2 * gram_floats + 2 * tile_floats + kMiscFloats; }
 };
 Scratch scratch_layout(int64_t n_max, int64_t d)
 {
@@ -733,8 +869,9 @@ bool dense_window_wanted(const DenseArgs &a)
     if (path == 1) return a.d > 64 * kWave;                     // the register kernel cannot hold more
     if (path == 2) return true;
     // measured on MI355X: c4 (16384 learners, d = 4096) 72 ms against the register kernel's 136 ms; c3 (4352
-    // learners, d = 1000) 70 ms against 62 ms
-    return a.d > 64 * kWave || ((int64_t)a.R * a.K >= 2048 && a.d >= 2048);
+    // learners, d = 1000) 50 ms against 62 ms.  Narrower problems and fewer learners stay with the register
+    // kernel (a round of the dependent rounds here costs about 0.4 us per tile whatever d is).
+    return a.d > 64 * kWave || ((int64_t)a.R * a.K >= 2048 && a.d >= 512);
 }
 
 hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, const PieceHook *hook)
@@ -748,6 +885,7 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
     const int nblk = (a.d + 15) / 16;
     const Scratch sc = scratch_layout(a.n_max, a.d);
     float *gram = a.gram, *gxt = gram + sc.gram_floats, *xq = gxt + sc.gram_floats, *xu = xq + sc.tile_floats;
+    float *misc = xu + sc.tile_floats;
     {
         ComparatorGemmArgs g{};
         g.x = a.x; g.u = a.u; g.seg_start = a.seg_start; g.S = a.S; g.Z = a.Z; g.zl = a.zl;
@@ -755,27 +893,34 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
         hipError_t e = launch_comparator_gemm(g, s);
         if (e != hipSuccess) return e;
     }
-    const bool resident = a.d <= 16 * kNW8 * 32 && a.tune->get(OCO_OPT_WINDOW_RESIDENT) != 0;
-    const int ntiles = (a.R * a.K + kM - 1) / kM;
+    // where the iterates live: OCO_OPT_WINDOW_RESIDENT 1 registers (d <= 4096), 0 streamed (two tiles per
+    // workgroup), 2 streamed (one tile, sixteen wavefronts).  Unset: streamed, two tiles -- on c4 as fast as
+    // the registers (every round row a wavefront loads serves two tiles), on c3 half as many workgroups.
+    const int64_t ropt = a.tune->get(OCO_OPT_WINDOW_RESIDENT);
+    const bool fits = a.d <= 16 * kNW8 * 32;
+    const int mode = (ropt == 1 && fits) ? 0 : ropt == 2 ? 2 : 1;
+    const bool resident = mode == 0;
     if (a.tune->get(OCO_OPT_VERBOSE) == 1)
         fprintf(stderr, "dense plan: windowed contraction kernel, %d windows in pieces of %lld, %d tiles, iterates %s\n",
-                nwin, (long long)sc.piece_windows, ntiles, resident ? "in registers" : "streamed from HBM");
+                nwin, (long long)sc.piece_windows, (a.R * a.K + kM - 1) / kM,
+                resident ? "in registers" : mode == 1 ? "streamed from HBM, two tiles per workgroup" : "streamed from HBM");
     WindowKernel kern = nullptr;
-    int waves = 0, lds_bytes = 0;
+    int waves = 0, tiles = 1, lds_bytes = 0;
     switch (loss) {
-        case 0: kern = pick_window_kernel<0>(nblk, resident, &waves, &lds_bytes); break;
-        case 1: kern = pick_window_kernel<1>(nblk, resident, &waves, &lds_bytes); break;
-        case 2: kern = pick_window_kernel<2>(nblk, resident, &waves, &lds_bytes); break;
+        case 0: kern = pick_window_kernel<0>(nblk, mode, &waves, &tiles, &lds_bytes); break;
+        case 1: kern = pick_window_kernel<1>(nblk, mode, &waves, &tiles, &lds_bytes); break;
+        case 2: kern = pick_window_kernel<2>(nblk, mode, &waves, &tiles, &lds_bytes); break;
         default: return hipErrorInvalidValue;
     }
+    const int ntiles = (a.R * a.K + kM * tiles - 1) / (kM * tiles);   // workgroups
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        lds_bytes);
     if (e != hipSuccess) return e;
     for (int w0 = 0; w0 < nwin; w0 += (int)sc.piece_windows) {
         const int nw = std::min<int>((int)sc.piece_windows, nwin - w0);
-        hipLaunchKernelGGL(dense_tile_kernel, dim3((unsigned)nblk, (unsigned)nw), dim3(64), 0, s, a.x, a.d, plan, w0, xq, xu);
+        hipLaunchKernelGGL(dense_tile_kernel, dim3((unsigned)nblk, (unsigned)nw), dim3(64), 0, s, a.x, a.d, plan, w0, xq, xu, misc);
         hipLaunchKernelGGL(dense_gram_kernel, dim3((unsigned)nw), dim3(512), 0, s, xq, nblk, gram, gxt);
-        hipLaunchKernelGGL(kern, dim3((unsigned)ntiles), dim3(waves * kWave), lds_bytes, s, a, gram, gxt, xq, xu, plan, w0, nw);
+        hipLaunchKernelGGL(kern, dim3((unsigned)ntiles), dim3(waves * kWave), lds_bytes, s, a, gram, gxt, xq, xu, misc, plan, w0, nw);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
