@@ -6,9 +6,12 @@ HBM: reset the state, run all T rounds of all R runs (round kernel + meta kernel
 the final iterates / Hedge weights / combined iterate, and read back the regret.  The
 metric is learner-updates per second, R*K*T*d / time.
 
-Prints ONE JSON line.  `roofline` prices the dominant kernel (the round kernel: all its launches
-of a step, timed with HIP events on the library's stream inside the timed region) against the
-resource that bounds it; `cpu_baseline` times the fp64 reference on the host cores on a bounded sample.
+Prints ONE JSON line.  `roofline` prices the dominant kernel (the kernel that works the rounds;
+each of its launches timed with a pair of HIP events on the library's stream inside the timed
+region) per launch against the resource that bounds it; `hbm` always says what fraction of the
+HBM roofline the step's compulsory bytes amount to; `binding` names the resource that holds the
+configuration back; `cpu_baseline` times the fp64 reference on the host cores on a bounded
+sample.  Every entry of `other_workloads` carries the same three blocks.
 """
 import argparse
 import json
@@ -19,8 +22,10 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_FP32_TFLOPS = 157.3     # MI355X vector fp32 (256 CUs x 2.4 GHz x 128 lanes x 2, packed)
+PEAK_FP32_TFLOPS = 157.3     # MI355X fp32: vector (256 CUs x 2.4 GHz x 128 lanes x 2, packed) and matrix cores alike
+NONPACKED_FP32_TFLOPS = 78.65  # what vector code reaches when every instruction works 64 lanes x 1 (this build: packed fp32 off)
 PEAK_HBM_GBS = 8000.0
+HBM_TARGET_FRAC = 0.60       # the fraction of the HBM roofline asked of the largest configuration
 
 DESCR = {
     "c1": "c1: single projected OGD, linear loss, d=10 T=1000 K=1 R=1",
@@ -29,29 +34,106 @@ DESCR = {
     "c4": "c4: K=16 OGD + Hedge, logistic loss, shared stream, d=4096 T=20000 R=1024",
     "c5": "c5: K=8 OGD + Hedge, sparse squared loss (32 nnz/round), d=2^20 T=100000 R=16",
 }
+STAMPS = {}                  # profiles/*.json, read once
 
 
-def roofline_model(wl):
-    """Algorithmic work of the round kernels of ONE step (all T rounds of all runs; the library
-    enqueues a long call as several launches of the same kernel).
+def profile_json(name):
+    if name not in STAMPS:
+        path = os.path.join(ROOT, "profiles", name)
+        STAMPS[name] = json.load(open(path)) if os.path.exists(path) else {}
+    return STAMPS[name]
 
-    dense: per learner-coordinate-round 7 flops (inner product 2, gradient step 2, norm of the
-    stepped vector 2, projection scale 1) plus the comparator's inner product (2 per
-    run-coordinate-round).  sparse: per touched learner coordinate 4 B read + 4 B written,
-    plus the round stream (8 B per entry), labels (4 B per run-round) and the comparator's
-    gathers (4 B per run-entry)."""
+
+def algorithmic_hbm_bytes(wl, kernel, launches):
+    """Compulsory HBM bytes of the round kernels of one step.  Dense: the round stream once, the
+    labels, the predictions out, the state in and out per launch; the windowed kernel also
+    moves every iterate in and out once per window of 64 rounds and reads the two re-tiled
+    copies of the stream that its pre-pass wrote.  Sparse: per touched learner coordinate 4 B
+    read + 4 B written, the round stream (8 B per entry), labels and the comparator's gathers."""
     if wl.nnz:
-        b = (wl.R * wl.K * wl.T * wl.nnz * 8 + wl.T * wl.nnz * 8 + wl.R * wl.T * 4
-             + wl.R * wl.T * wl.nnz * 4)
-        return "hbm", float(b), PEAK_HBM_GBS, "GB/s", 1e9
-    f = 7.0 * wl.units + 2.0 * wl.R * wl.T * wl.d
-    return "alu", f, PEAK_FP32_TFLOPS, "TFLOP/s", 1e12
+        return float(wl.R * wl.K * wl.T * wl.nnz * 8 + wl.T * wl.nnz * 8 + wl.R * wl.T * 4 + wl.R * wl.T * wl.nnz * 4)
+    x = 4.0 * wl.T * wl.d * (1 if wl.x_shared else wl.R)
+    b = x + 4.0 * wl.R * wl.T + 4.0 * wl.R * (wl.K + 1) * wl.T + 8.0 * wl.R * wl.K * wl.d * max(launches, 1)
+    if kernel == "dense_window_kernel":
+        b += 8.0 * wl.R * wl.K * wl.d * ((wl.T + 63) // 64) + 4.0 * x
+    return b
 
 
-def run_workload(name, steps, warmup, WL, B, torch, keep=None, optimistic=False):
-    wl = WL.make(name, optimistic=optimistic)
+def roofline_block(wl, kt, config_key):
+    """Roofline of the dominant kernel, per launch: algorithmic work of a launch / its average duration.
+
+    Dense work per unit (one coordinate of one learner for one round): 5 + 2/K flops -- inner
+    product 2, gradient step 2, projection scale 1, the comparator's inner product 2 per run.
+    Executed: the projection is one scalar per learner (lazy scale), so the register kernel
+    issues 4 + 2/K and the windowed kernel 4 (two contractions; the comparator's inner products
+    run in a kernel of their own)."""
+    launches = max(kt["launches"], 1)
+    avg_ms = kt["ms_sum"] / max(kt["timed"], 1)
+    kernel = kt["kernel"]
+    hbm_bytes = algorithmic_hbm_bytes(wl, kernel, launches)
+    entry = profile_json("hbm_traffic.json").get(config_key)
+    entry = entry if isinstance(entry, dict) and entry.get("kernel") == kernel else None
+    traffic = entry["bytes_per_launch"] if entry else None
+    rl = {"kernel": kernel, "launches_per_step": launches, "avg_launch_ms": avg_ms}
+    if wl.nnz:
+        ach = hbm_bytes / launches / (avg_ms * 1e-3) / 1e9
+        rl.update(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS)
+    else:
+        per_unit = 5.0 + 2.0 / wl.K
+        executed = 4.0 if kernel == "dense_window_kernel" else 4.0 + 2.0 / wl.K
+        ach = per_unit * wl.units / launches / (avg_ms * 1e-3) / 1e12
+        rl.update(bound="mfma" if kernel == "dense_window_kernel" else "alu", achieved=ach, peak=PEAK_FP32_TFLOPS,
+                  unit="TFLOP/s", frac=ach / PEAK_FP32_TFLOPS, flops_per_unit=per_unit,
+                  executed_flops_per_unit=executed, executed_flops_frac=ach * executed / per_unit / PEAK_FP32_TFLOPS)
+        if kernel != "dense_window_kernel":
+            rl["non_packed_ceiling"] = {"peak": NONPACKED_FP32_TFLOPS, "unit": "TFLOP/s",
+                                        "executed_flops_frac": ach * executed / per_unit / NONPACKED_FP32_TFLOPS,
+                                        "note": "vector fp32 with packed instructions off, as this build is compiled"}
+    rl["traffic"] = traffic
+    if entry and traffic is not None:
+        rl["traffic_stamp"] = {"commit": entry.get("commit"), "plan": entry.get("plan"),
+                               "source": "profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a device copy)"}
+        rl["traffic_over_algorithmic_bytes"] = traffic * launches / hbm_bytes
+    gbs = hbm_bytes / launches / (avg_ms * 1e-3) / 1e9
+    hbm = {"algorithmic_bytes_per_step": hbm_bytes, "GBps": gbs, "frac_of_peak": gbs / PEAK_HBM_GBS,
+           "target_frac": HBM_TARGET_FRAC, "target_met": bool(gbs / PEAK_HBM_GBS >= HBM_TARGET_FRAC)}
+    if traffic is not None:
+        hbm["counter_GBps"] = traffic / (avg_ms * 1e-3) / 1e9
+        hbm["counter_frac_of_peak"] = hbm["counter_GBps"] / PEAK_HBM_GBS
+    return rl, hbm
+
+
+def binding_block(wl, res, config_key, floor=None):
+    """The resource that bounds the configuration, with its own utilisation."""
+    us_round = res["round_kernel_ms"] * 1e3 / wl.T
+    kernel = res["kernel_timing"]["kernel"]
+    b = {"us_per_round": us_round}
+    if floor is not None:
+        b.update(resource="dependent chain of a round (latency): one wavefront reduction and the scalars behind it",
+                 floor_us_per_round=floor["us_per_round"], floor=floor["what"],
+                 over_floor=us_round / floor["us_per_round"])
+    elif wl.nnz:
+        b.update(profile_json("binding_resource.json").get(config_key) or {})
+        b["us_per_round"] = us_round
+    elif kernel == "dense_window_kernel":
+        kt = res["kernel_timing"]
+        step_ms = kt["ms_sum"] / max(kt["timed"], 1) * max(kt["launches"], 1)      # all launches of a step
+        floor_ms = 4.0 * wl.units / (PEAK_FP32_TFLOPS * 1e12) * 1e3
+        b.update(resource="matrix cores, fed from L2 (round rows) and HBM (iterates); the dependent rounds of a window "
+                          "(64 rounds on float64 scalars, one wavefront per tile of 16 learners) run beside the sweep",
+                 tiles=(wl.R * wl.K + 15) // 16, windows=(wl.T + 63) // 64,
+                 matrix_core_floor_ms=floor_ms, utilisation=floor_ms / step_ms,
+                 dependent_rounds_us_per_round=step_ms * 1e3 / wl.T)
+    else:
+        b.update(resource="vector ALU issue (fused multiply-adds of the inner product and the step)")
+        b.update(profile_json("binding_resource.json").get(config_key.split(" ")[0]) or {})
+    return b
+
+
+def run_workload(name, steps, warmup, WL, B, torch, keep=None, optimistic=False, options=None, over=None):
+    wl = WL.make(name, optimistic=optimistic, **(over or {}))
     data = WL.generate(wl)
-    sim = B.Simulation(wl, data)
+    sim = B.Simulation(wl, data, options=options)
     W = torch.empty((wl.R, wl.K, wl.d), dtype=torch.float32, device="cuda")
     p = torch.empty((wl.R, wl.K), dtype=torch.float32, device="cuda")
     wbar = torch.empty((wl.R, wl.d), dtype=torch.float32, device="cuda")
@@ -66,24 +148,47 @@ def run_workload(name, steps, warmup, WL, B, torch, keep=None, optimistic=False)
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    kern_ms = []
+    kern_ms, ktim = [], []
     t0 = time.perf_counter()
     for _ in range(steps):
         reg = step()
         kern_ms.append(B.oco_last_timing(sim.h))
+        ktim.append(B.oco_last_kernel_timing(sim.h))
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms = 1e3 * dt / steps
+    kt = dict(kernel=ktim[0]["kernel"], launches=ktim[0]["launches"], timed=sum(k["timed"] for k in ktim),
+              ms_sum=sum(k["ms_sum"] for k in ktim))
     out = dict(wl=wl, ms_per_step=ms, value=wl.units / (dt / steps),
                round_kernel_ms=float(sum(k[0] for k in kern_ms) / steps),
                meta_kernel_ms=float(sum(k[1] for k in kern_ms) / steps),
-               regret_mean=float(reg.mean()))
+               kernel_timing=kt, regret_mean=float(reg.mean()))
     if keep is not None:
         keep.update(data=data, regret=reg, accel=sim.accel_bounds(4, 0.05))
     sim.close()
     del sim, W, p, wbar
     torch.cuda.empty_cache()
     return out
+
+
+def empty_round_floor(name, WL, B, torch):
+    """us per round of the same kernel on one learner of d = 4: a round is then only its
+    dependent chain (inner product reduction, slope, step scalars) and the hand-over to the next."""
+    r = run_workload(name, 2, 1, WL, B, torch, over=dict(d=4, K=1, R=1))
+    return {"us_per_round": r["round_kernel_ms"] * 1e3 / r["wl"].T,
+            "what": "same kernel, one learner of d=4, same T and loss (measured in this run)"}
+
+
+def summary_entry(res, config_key, floor=None):
+    wl = res["wl"]
+    rl, hbm = roofline_block(wl, res["kernel_timing"], config_key)
+    e = {"value": res["value"], "ms_per_step": res["ms_per_step"], "round_kernel_ms": res["round_kernel_ms"],
+         "meta_kernel_ms": res["meta_kernel_ms"], "roofline": rl, "hbm": hbm,
+         "binding": binding_block(wl, res, config_key, floor)}
+    if wl.nnz:
+        e["algorithmic_value"] = {"value": wl.R * wl.K * wl.T * wl.nnz / (res["ms_per_step"] * 1e-3),
+                                  "unit": "touched learner-coordinates/s (R*K*T*nnz/s)"}
+    return e
 
 
 def run_specdec(name, reps, WL, B, torch, with_cpu=False):
@@ -132,11 +237,12 @@ def run_specdec(name, reps, WL, B, torch, with_cpu=False):
            "acceptance": {"ms": ma,
                           "roofline": {"bound": "hbm", "achieved": bytes_a / (ma * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                                        "unit": "GB/s", "frac": bytes_a / (ma * 1e-3) / 1e9 / PEAK_HBM_GBS}}}
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        tr = json.load(open(tpath))
-        out["verify"]["roofline"]["traffic"] = tr.get(name + "_verify")
-        out["acceptance"]["roofline"]["traffic"] = tr.get(name + "_acceptance")
+    for part in ("verify", "acceptance"):
+        entry = profile_json("hbm_traffic.json").get(name + "_" + part)
+        entry = entry if isinstance(entry, dict) else None
+        out[part]["roofline"]["traffic"] = entry["bytes_per_launch"] if entry else None
+        if entry:
+            out[part]["roofline"]["traffic_stamp"] = {"commit": entry.get("commit"), "plan": entry.get("plan")}
     if with_cpu:
         from oracle import specdec_oracle as SO
         m = min(Bn, 256)
@@ -155,7 +261,8 @@ def cpu_baseline(wl, data, WL):
     """The fp64 reference as it stands, one run per thread, on a bounded sample."""
     from oracle import oracle as O
     cores = min(16, os.cpu_count() or 1)
-    runs = list(range(min(wl.R, cores if wl.name != "c2" else wl.R)))
+    per_thread = {"c4": 4, "c3": 2}.get(wl.name, 1)          # sized for 10-30 s of CPU work
+    runs = list(range(min(wl.R, cores * per_thread if wl.name != "c2" else wl.R)))
     T = wl.T if wl.name != "c5" else 5000
     swl, sdat = WL.run_slice(wl, data, runs)
     if T != wl.T:
@@ -217,12 +324,8 @@ def main():
     keep = {}
     main_res = run_workload(a.config, a.steps, a.warmup, WL, B, torch, keep)
     wl = main_res["wl"]
-    bound, work, peak, unit, scale = roofline_model(wl)
-    achieved = work / (main_res["round_kernel_ms"] * 1e-3) / scale
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(a.config)
+    floor = empty_round_floor(a.config, WL, B, torch) if a.config in ("c1", "c2") else None
+    rl, hbm = roofline_block(wl, main_res["kernel_timing"], a.config)
     line = {
         "metric": "learner-updates/sec (runs x K x rounds x d / s)",
         "value": main_res["value"], "unit": "learner-updates/s",
@@ -232,31 +335,21 @@ def main():
         "config": {"workload": DESCR[a.config], "R": wl.R, "K": wl.K, "d": wl.d, "T": wl.T,
                    "loss": wl.loss, "nnz": wl.nnz, "rounds_per_call": wl.T},
         "kernels_ms": {"round_kernel": main_res["round_kernel_ms"], "meta_kernel": main_res["meta_kernel_ms"]},
-        "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                     "frac": achieved / peak, "traffic": traffic, "kernel": "round kernel (S0-S2,S4)"},
+        "roofline": rl, "hbm": hbm, "binding": binding_block(wl, main_res, a.config, floor),
     }
-    # what rocprofv3 counted behind L2 for the round kernels of one step, as a rate, against the
-    # nominal peak and against a plain device copy timed here
-    if traffic:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # a plain device copy timed here: what the HBM counters' rate can be held against besides the nominal peak
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    dst.copy_(src)
+    ev0.record()
+    for _ in range(3):
         dst.copy_(src)
-        ev0.record()
-        for _ in range(3):
-            dst.copy_(src)
-        ev1.record()
-        torch.cuda.synchronize()
-        copy_gbs = 3 * 2 * src.numel() * 4 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
-        del src, dst
-        torch.cuda.empty_cache()
-        gbs = traffic / (main_res["round_kernel_ms"] * 1e-3) / 1e9
-        line["hbm_counters"] = {"traffic_bytes_per_step": traffic, "rate_GBps": gbs, "frac_of_peak": gbs / PEAK_HBM_GBS,
-                                "copy_ceiling_GBps": copy_gbs, "frac_of_copy_ceiling": gbs / copy_gbs,
-                                "source": "profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE)"}
-    bpath = os.path.join(ROOT, "profiles", "binding_resource.json")
-    if os.path.exists(bpath):
-        line["binding_resource"] = json.load(open(bpath)).get(a.config)
+    ev1.record()
+    torch.cuda.synchronize()
+    line["hbm"]["copy_ceiling_GBps"] = 3 * 2 * src.numel() * 4 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src, dst
+    torch.cuda.empty_cache()
     ab = keep["accel"]
     line["accel_bounds_k4_alpha0.05"] = {"gamma_lower_mean": float(ab[:, 2].mean()), "gamma_upper": float(ab[0, 3]),
                                          "note": "Theorem 1 from the regret of each run, mean over runs"}
@@ -278,14 +371,16 @@ def main():
         for name in sorted(DESCR):
             if name == a.config:
                 continue
-            r = run_workload(name, 2, 1, WL, B, torch)
-            others[name] = {"value": r["value"], "ms_per_step": r["ms_per_step"],
-                            "round_kernel_ms": r["round_kernel_ms"], "meta_kernel_ms": r["meta_kernel_ms"]}
+            fl = empty_round_floor(name, WL, B, torch) if name in ("c1", "c2") else None
+            others[name] = summary_entry(run_workload(name, 2, 1, WL, B, torch), name, fl)
+        # the same workload on the other dense kernels (labelled: never the headline)
+        if a.config == "c4":
+            for label, opts in (("c4_register_kernel (one wavefront per learner, iterate in registers)", dict(dense_path=1)),
+                                ("c4_window_kernel_iterates_in_registers", dict(dense_path=2, window_resident=1))):
+                others[label] = summary_entry(run_workload("c4", 2, 1, WL, B, torch, options=opts), label)
         for name in ("c3", "c4", "c5"):    # the optimistic two-step update (Eq. (3)) on the same streams
-            r = run_workload(name, 2, 1, WL, B, torch, optimistic=True)
-            others[name + "_optimistic"] = {"value": r["value"], "ms_per_step": r["ms_per_step"],
-                                            "round_kernel_ms": r["round_kernel_ms"],
-                                            "meta_kernel_ms": r["meta_kernel_ms"]}
+            key = name + "_optimistic"
+            others[key] = summary_entry(run_workload(name, 2, 1, WL, B, torch, optimistic=True), key)
         for name in ("v2", "v3"):          # verification step of Algorithm 1 on synthetic distributions
             others["specdec_" + name] = run_specdec(name, 5, WL, B, torch, with_cpu=not a.no_cpu)
         line["other_workloads"] = others

@@ -232,6 +232,14 @@ int oco_reset(oco_state *st);
 int oco_set_timing(oco_state *st, int enable);
 int oco_last_timing(oco_state *st, float *ms_host);
 
+/* The dominant kernel of the most recent timed call alone, launch by launch: the kernel that
+ * works the rounds (Sec. 3.1 / 3.3 update of the base learners), without the passes that prepare
+ * its inputs or the meta kernel.  *ms_sum_host = summed duration of the launches that were timed
+ * (event pairs on the state's stream), *timed_host = how many those were (at most 64 per call),
+ * *launches_host = launches of that kernel in the call, *kernel (may be null) = its name, a
+ * static string.  Same preconditions and errors as oco_last_timing. */
+int oco_last_kernel_timing(oco_state *st, float *ms_sum_host, int *timed_host, int *launches_host, const char **kernel);
+
 /* Rounds consumed so far, or a negative oco_status. */
 int64_t oco_rounds_done(const oco_state *st);
 

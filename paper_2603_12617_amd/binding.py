@@ -25,7 +25,8 @@ OCO_STATIC_WS_BYTES = 64 << 20
 EXPORTS = ("oco_step_grid", "oco_paper_num_learners", "oco_workspace_bytes", "oco_create",
            "oco_create_static", "oco_set_option",
            "oco_set_comparator", "oco_run_rounds", "oco_regret", "oco_get_state",
-           "oco_cum_losses", "oco_accel_bounds", "oco_reset", "oco_set_timing", "oco_last_timing", "oco_rounds_done", "oco_destroy", "oco_strerror",
+           "oco_cum_losses", "oco_accel_bounds", "oco_reset", "oco_set_timing", "oco_last_timing", "oco_last_kernel_timing",
+           "oco_rounds_done", "oco_destroy", "oco_strerror",
            "sd_verify", "sd_acceptance", "sd_strerror")
 
 
@@ -93,6 +94,8 @@ def lib() -> C.CDLL:
         L.oco_set_timing.argtypes = [vp, C.c_int]
         L.oco_last_timing.restype = C.c_int
         L.oco_last_timing.argtypes = [vp, vp]
+        L.oco_last_kernel_timing.restype = C.c_int
+        L.oco_last_kernel_timing.argtypes = [vp, vp, vp, vp, vp]
         L.sd_verify.restype = C.c_int
         L.sd_verify.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, vp, vp]
         L.sd_acceptance.restype = C.c_int
@@ -225,6 +228,15 @@ def oco_last_timing(h: int) -> np.ndarray:
     out = np.zeros(2, dtype=np.float32)
     _check(lib().oco_last_timing(h, out.ctypes.data), "oco_last_timing")
     return out
+
+
+def oco_last_kernel_timing(h: int) -> dict:
+    """The dominant kernel of the last timed call alone: its name, the launches of it in the call,
+    how many of them were timed and their summed duration in ms."""
+    ms, timed, launches, name = C.c_float(0), C.c_int(0), C.c_int(0), C.c_char_p()
+    _check(lib().oco_last_kernel_timing(h, C.addressof(ms), C.addressof(timed), C.addressof(launches), C.addressof(name)),
+           "oco_last_kernel_timing")
+    return dict(kernel=(name.value or b"").decode(), ms_sum=float(ms.value), timed=int(timed.value), launches=int(launches.value))
 
 
 def oco_rounds_done(h: int) -> int:

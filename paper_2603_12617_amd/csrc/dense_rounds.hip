@@ -986,8 +986,11 @@ hipError_t launch_piece(const DensePlan &p, const DenseArgs &a, hipStream_t s)
         grid = dim3((unsigned)p.nwg, 1, 1);
     else
         grid = dim3((unsigned)((per_run + p.wpb - 1) / p.wpb), (unsigned)a.R, 1);
+    hipError_t e = clock_begin(a.clock, s, "dense_round_kernel");
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(p.kern, grid, dim3(p.wpb * kWave), p.smem, s, a);
-    return hipGetLastError();
+    e = hipGetLastError();
+    return e != hipSuccess ? e : clock_end(a.clock, s);
 }
 
 }  // namespace

@@ -131,6 +131,7 @@ struct oco_state {
     bool is_static = false;    // created by oco_create_static: no second stream, no events
     bool timing = false, timed = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    LaunchClock clock;         // events exist once timing has been switched on
     Tuning tune;
     DensePlanCache dense_plan;
     // The meta kernel of a piece of a call depends on that piece's predictions only, and no
@@ -143,6 +144,7 @@ struct oco_state {
 
     ~oco_state() {
         for (auto e : ev) if (e) (void)hipEventDestroy(e);
+        for (auto e : clock.ev) if (e) (void)hipEventDestroy(e);
         for (auto e : piece_ev) if (e) (void)hipEventDestroy(e);
         if (join_ev) (void)hipEventDestroy(join_ev);
         if (side) { (void)hipStreamSynchronize(side); (void)hipStreamDestroy(side); }
@@ -346,6 +348,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
     const ZLayout zl = st->zlayout();
     hipError_t e;
     if (st->timing && hipEventRecord(st->ev[0], st->stream) != hipSuccess) return OCO_EHIP;
+    st->clock.launches = st->clock.timed = 0;
     // from here on part of the call's work may be on the device when an error comes back
     auto fail = [st]() { st->failed = true; return (int)OCO_EHIP; };
 
@@ -415,7 +418,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
             a.last_col = st->at<int32_t>(l.off_lastcol); a.last_val = st->at<float>(l.off_lastval);
             a.xlast_dense = st->at<float>(l.off_xlast);
         }
-        a.tune = &st->tune;
+        a.tune = &st->tune; a.clock = st->timing ? &st->clock : nullptr;
         e = launch_sparse_rounds(a, c.loss, st->stream, overlap ? &hook : nullptr);
     } else {
         DenseArgs a{};
@@ -434,7 +437,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
             a.g01 = st->at<float>(l.off_G01);
             a.xlast = st->at<float>(l.off_xlast); a.x2last = st->at<float>(l.off_x2last);
         }
-        a.tune = &st->tune; a.plan = &st->dense_plan;
+        a.tune = &st->tune; a.plan = &st->dense_plan; a.clock = st->timing ? &st->clock : nullptr;
         a.gram = l.off_gram ? st->at<float>(l.off_gram) : nullptr;
         a.n_max = l.n_max;
         e = launch_dense_rounds(a, c.loss, st->stream, overlap ? &hook : nullptr);
@@ -514,8 +517,12 @@ int oco_set_timing(oco_state *st, int enable)
     if (!st) return OCO_EINVAL;
     if (enable && st->is_static) return OCO_EUNSUPPORTED;     // would create events
     if (enable)
+    {
         for (auto &e : st->ev)
             if (!e && hipEventCreate(&e) != hipSuccess) return OCO_EHIP;
+        for (auto &e : st->clock.ev)
+            if (!e && hipEventCreate(&e) != hipSuccess) return OCO_EHIP;
+    }
     st->timing = enable != 0;
     st->timed = false;
     return OCO_OK;
@@ -527,6 +534,23 @@ int oco_last_timing(oco_state *st, float *ms_host)
     if (hipEventSynchronize(st->ev[2]) != hipSuccess) return OCO_EHIP;
     if (hipEventElapsedTime(&ms_host[0], st->ev[0], st->ev[1]) != hipSuccess) return OCO_EHIP;
     if (hipEventElapsedTime(&ms_host[1], st->ev[1], st->ev[2]) != hipSuccess) return OCO_EHIP;
+    return OCO_OK;
+}
+
+int oco_last_kernel_timing(oco_state *st, float *ms_sum_host, int *timed_host, int *launches_host, const char **kernel)
+{
+    if (!st || !ms_sum_host || !timed_host || !launches_host || !st->timing || !st->timed) return OCO_EINVAL;
+    if (hipEventSynchronize(st->ev[2]) != hipSuccess) return OCO_EHIP;
+    float sum = 0.f;
+    for (int i = 0; i < st->clock.timed; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, st->clock.ev[2 * i], st->clock.ev[2 * i + 1]) != hipSuccess) return OCO_EHIP;
+        sum += ms;
+    }
+    *ms_sum_host = sum;
+    *timed_host = st->clock.timed;
+    *launches_host = st->clock.launches;
+    if (kernel) *kernel = st->clock.kernel;
     return OCO_OK;
 }
 

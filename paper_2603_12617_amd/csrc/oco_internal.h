@@ -47,6 +47,31 @@ struct PieceHook {
     hipError_t (*beside)(void *ctx, hipStream_t *out) = nullptr;
 };
 
+// Event pairs around the launches of a call's dominant kernel (benchmarks: the duration of that
+// kernel alone, launch by launch).  The launchers call begin / end around each such launch; with
+// no clock, or past its capacity, they cost nothing and only count.
+struct LaunchClock {
+    static constexpr int kPairs = 64;
+    hipEvent_t ev[2 * kPairs] = {};
+    int launches = 0;          // of the last call
+    int timed = 0;             // of those, how many have an event pair
+    const char *kernel = "";   // which kernel the launcher timed
+    hipError_t begin(hipStream_t s) { return timed < kPairs && ev[2 * timed] ? hipEventRecord(ev[2 * timed], s) : hipSuccess; }
+    hipError_t end(hipStream_t s)
+    {
+        ++launches;
+        if (timed >= kPairs || !ev[2 * timed + 1]) return hipSuccess;
+        return hipEventRecord(ev[2 * timed++ + 1], s);
+    }
+};
+inline hipError_t clock_begin(LaunchClock *c, hipStream_t s, const char *kernel)
+{
+    if (!c) return hipSuccess;
+    c->kernel = kernel;
+    return c->begin(s);
+}
+inline hipError_t clock_end(LaunchClock *c, hipStream_t s) { return c ? c->end(s) : hipSuccess; }
+
 // ---- dense rounds -----------------------------------------------------------
 struct DenseArgs {
     const float *x;          // round stream (or gradient stream for the linear loss)
@@ -80,6 +105,7 @@ struct DenseArgs {
     float *xlast;            // [1 or R][d]  last round row of the previous call (0 before round 0)
     float *x2last;           // [1 or R]     its squared norm
     const Tuning *tune;      // never null
+    LaunchClock *clock;      // null unless the call is timed
     DensePlanCache *plan;    // never null
     float *gram;             // shared streams: dense_gram_bytes(n_max, d) of scratch for the windowed path
     int64_t n_max;           // the state's largest call (lays that scratch out)
@@ -135,6 +161,7 @@ struct SparseArgs {
     float *last_val;         // [OCO_MAX_NNZ]
     float *xlast_dense;      // [d]  the same row scattered into a dense vector (for the export)
     const Tuning *tune;      // never null
+    LaunchClock *clock;      // null unless the call is timed
 };
 hipError_t launch_sparse_rounds(const SparseArgs &a, int loss, hipStream_t s, const PieceHook *hook);
 size_t sparse_scratch_bytes(int64_t n_max);

@@ -968,8 +968,11 @@ hipError_t launch_window_lpw(const SparseArgs &a, const WinPlan &plan, int wbeg,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
+    hipError_t e = clock_begin(a.clock, s, "sparse_window_kernel");
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, block, smem, s, a, plan, wbeg, wend, pipe);
-    return hipGetLastError();
+    e = hipGetLastError();
+    return e != hipSuccess ? e : clock_end(a.clock, s);
 }
 
 template <int LOSS, bool OPT>

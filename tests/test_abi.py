@@ -112,6 +112,7 @@ def test_create_rejects_bad_arguments_on_the_host():
     assert L.oco_reset(None) == B.OCO_EINVAL
     assert L.oco_set_timing(None, 1) == B.OCO_EINVAL
     assert L.oco_last_timing(None, None) == B.OCO_EINVAL
+    assert L.oco_last_kernel_timing(None, None, None, None, None) == B.OCO_EINVAL
     assert L.oco_rounds_done(None) == B.OCO_EINVAL
     assert L.oco_set_option(None, 0, 0) == B.OCO_EINVAL
     L.oco_destroy(None)
