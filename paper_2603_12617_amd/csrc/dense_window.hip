@@ -188,14 +188,16 @@ __global__ void __launch_bounds__(512) dense_gram_kernel(const float *xq, int nb
 }
 
 // LDS of the window kernel (dynamic), in bytes from the base.  What the dependent rounds of window
-// k write for the sweep (predictions, -Bm, F) and what is staged for them (Gram table with its
-// diagonal in the rows' padding, labels) has two buffers, window k in buffer k % 2: the sweep of
-// window k - 1 and the staging for window k + 1 run beside them.  MT: tiles of 16 learners per
-// workgroup (per-tile arrays come MT times; the Gram table and the shares' buffer are common).
+// k write for the sweep (predictions, -Bm, F) and the labels staged for them have two buffers,
+// window k in buffer k % 2: the sweep of window k - 1 and the staging for window k + 1 run beside
+// them.  The Gram table (float64, its diagonal in the rows' padding) has one: it is written
+// between the two barriers that precede the rounds, from registers loaded before the first.
+// MT: tiles of 16 learners per workgroup (per-tile arrays come MT times; the Gram table and the
+// shares' buffer are common).
 template <int NW, int MT> struct LdsT {
     // float64 where the LDS has room (one tile, eight wavefronts), else float32
     static constexpr bool wide = NW == kNW8 && MT == 1;
-    using G = std::conditional_t<wide, double, float>;             // Gram table
+    using G = double;                                              // Gram table
     using S = std::conditional_t<wide, double, float>;             // inner products handed to the rounds, f_t
     static constexpr int gd_bytes = kB * 4 * kGStride * (int)sizeof(G);   // G [64][4][kGStride]: G[t][t2], zero for t2 <= t;
                                                                    //   [t][0][16] holds G[t][t]
@@ -206,7 +208,7 @@ template <int NW, int MT> struct LdsT {
     static constexpr int bm_bytes = MT * tile_f;                   // -Bm
     static constexpr int fv_bytes = MT * kM * 4;                   // float [16]: F
     static constexpr int gd = 0;
-    static constexpr int yb = gd + 2 * gd_bytes;
+    static constexpr int yb = gd + gd_bytes;
     static constexpr int zb = yb + 2 * yb_bytes;
     static constexpr int bm = zb + 2 * zb_bytes;
     static constexpr int fv = bm + 2 * bm_bytes;
@@ -259,8 +261,8 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
     using GT = typename Lds::G;
     using ST = typename Lds::S;
     const int lc = lane >> 2, s = lane & 3;
-    const GT *gd = reinterpret_cast<const GT *>(lds + Lds::gd + buf * Lds::gd_bytes) + s * kGStride;
-    const GT *x2d = reinterpret_cast<const GT *>(lds + Lds::gd + buf * Lds::gd_bytes) + 16;
+    const GT *gd = reinterpret_cast<const GT *>(lds + Lds::gd) + s * kGStride;
+    const GT *x2d = reinterpret_cast<const GT *>(lds + Lds::gd) + 16;
     const ST *q0d = reinterpret_cast<const ST *>(lds + Lds::q0 + m * Lds::tile_s) + s * kM + lc;
     const float *cr = reinterpret_cast<const float *>(lds + Lds::corr + m * Lds::tile_f) + s * kM + lc;
     ST *fl = reinterpret_cast<ST *>(lds + Lds::fl + m * Lds::tile_s) + lc;
@@ -275,15 +277,28 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
 #pragma unroll
     for (int j = 0; j < 16; ++j) p[j] = fma(pmul, (double)q0d[4 * j * kM], (double)cr[4 * j * kM]);
 
+    // A round has a short dependent part (prediction -> slope -> step -> norm -> projection factor)
+    // and a wide independent one (its update of the pending predictions).  Only the prediction of
+    // the next round is updated at once; the rest of round t - 1's update shares a scheduling
+    // region with the dependent part of round t and fills its latencies.
+    double gprev[16];                 // round t - 1's row of G (elements j >= (t - 1) / 4)
+    double aprev = 0.0, fprev = 1.0;
     static_for<kB>([&](auto tc) __attribute__((always_inline)) {
         constexpr int t = decltype(tc)::value;
-        constexpr int j0 = t >> 2;
+        constexpr int j0 = t >> 2;                                   // pending elements of this lane: j >= j0
+        constexpr int jn = (t + 1) >> 2;                             // holds the prediction of round t + 1
         // this round's row of G first: it does not depend on the scalars below
         double gr[16 - j0];
 #pragma unroll
-        for (int j = j0; j < 16; ++j) gr[j - j0] = (double)gd[t * 4 * kGStride + j];
+        for (int j = j0; j < 16; ++j) gr[j - j0] = gd[t * 4 * kGStride + j];
         const float yt = yb[t * kM];
-        const double x2t = (double)x2d[t * 4 * kGStride];
+        const double x2t = x2d[t * 4 * kGStride];
+        if constexpr (t > 0) {
+            constexpr int jp0 = (t - 1) >> 2;
+#pragma unroll
+            for (int j = jp0; j < 16; ++j)
+                if (j != j0) p[j] = fprev * fma(-aprev, gprev[j], p[j]);   // (element j0 was updated ahead)
+        }
         const double zt = quad_bcast<(t & 3)>(p[j0]);               // <w_t, x_t>
         const float z32 = (float)zt;
         // a_t = eta c_t; for the squared loss eta * 2 (z - y) = (2 eta) (z - y) exactly
@@ -300,9 +315,12 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
         zb[t * kM] = z32;                                            // (the quad's four lanes write the same value)
         stl[t * kM] = a32;
         fl[t * kM] = (ST)f;
+        if constexpr (jn < 16) p[jn] = f * fma(-at, gr[jn - j0], p[jn]);
 #pragma unroll
-        for (int j = j0; j < 16; ++j) p[j] = f * fma(-at, gr[j - j0], p[j]);
-        __builtin_amdgcn_sched_barrier(0);                           // rounds are not interleaved: registers
+        for (int j = j0; j < 16; ++j) gprev[j] = gr[j - j0];
+        aprev = at;
+        fprev = f;
+        __builtin_amdgcn_sched_barrier(0);                           // at most two rounds overlap: registers
     });
 
     // Bm[r] = a_r f_r f_{r+1} ... f_63 and F = fscale f_0 ... f_63: quad lane s takes the rounds
@@ -433,26 +451,37 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
 #pragma unroll
         for (int k = 0; k < 4; ++k) o[k] = *reinterpret_cast<const f4 *>(t + k * 256);
     };
-    // LDS inputs of the dependent rounds of window wi: labels, masked Gram table, its diagonal.
-    // `nthr` threads numbered tid share the work.
+    // The Gram matrix of window wi on its way to LDS: every thread carries kGPer consecutive entries
+    // of a row in registers (loaded before a barrier, stored after it), masked to t2 > t, the
+    // diagonal in the rows' padding.
+    constexpr int kGPer = kB * kB / (NW * kWave);               // 8 or 4
+    auto load_gram = [&](int tid, int wi, f4 (&gv)[kGPer / 4]) __attribute__((always_inline)) {
+        const float *gsrc = gram + (int64_t)wi * kB * kB + tid * kGPer;
+#pragma unroll
+        for (int i = 0; i < kGPer / 4; ++i) gv[i] = *reinterpret_cast<const f4 *>(gsrc + 4 * i);
+    };
+    auto store_gram = [&](int tid, const f4 (&gv)[kGPer / 4]) __attribute__((always_inline)) {
+        GT *gd = reinterpret_cast<GT *>(lds + Lds::gd);
+        const int t = (tid * kGPer) >> 6, t2b = (tid * kGPer) & 63;
+#pragma unroll
+        for (int i = 0; i < kGPer; ++i) {
+            const int t2 = t2b + i;
+            const float v = gv[i >> 2][i & 3];
+            gd[(t * 4 + (i & 3)) * kGStride + (t2 >> 2)] = t2 > t ? (GT)v : (GT)0;   // (t2b is a multiple of 4: t2 & 3 == i & 3)
+            if (t2 == t) gd[t * 4 * kGStride + 16] = (GT)v;
+        }
+    };
+    // LDS inputs of the dependent rounds of window wi: the labels.  `nthr` threads numbered tid share the work.
     auto stage_chain_inputs = [&](int tid, int nthr, int wi) __attribute__((always_inline)) {
         const int w = w0 + wi, buf = wi & 1;
         const int ws = plan.start(w), wl = plan.len(w);
         float *yb = reinterpret_cast<float *>(lds + Lds::yb + buf * Lds::yb_bytes);
-        GT *gd = reinterpret_cast<GT *>(lds + Lds::gd + buf * Lds::gd_bytes);
         for (int e = tid; e < MT * kB * kM; e += nthr) {
             const int l = e >> 6, t = e & 63;                   // a learner's 64 labels are contiguous
             const int q = q_base + l;
             float yv = 0.f;
             if (a.y && q < nq && t < wl) yv = a.y[(int64_t)(q / K) * a.y_run_stride + ws + t];
             yb[((l >> 4) * kB + t) * kM + (l & 15)] = yv;
-        }
-        const float *gsrc = gram + (int64_t)wi * kB * kB;
-        for (int e = tid; e < kB * kB; e += nthr) {
-            const int t = e >> 6, t2 = e & 63;
-            const float gv = gsrc[e];
-            gd[(t * 4 + (t2 & 3)) * kGStride + (t2 >> 2)] = t2 > t ? (GT)gv : (GT)0;
-            if (t2 == t) gd[t * 4 * kGStride + 16] = (GT)gv;
         }
     };
     // shares of this wavefront of one tile's W X^T for one window -> LDS
@@ -548,6 +577,11 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
             }
         }
         stage_chain_inputs(g.tid, NW * kWave, 0);
+        {
+            f4 gv[kGPer / 4];
+            load_gram(g.tid, 0, gv);
+            store_gram(g.tid, gv);
+        }
         float *corr = reinterpret_cast<float *>(lds + Lds::corr);
         for (int e = g.tid; e < MT * kB * kM; e += NW * kWave) corr[e] = 0.f;
         // the shares of window 0 are summed here, tile by tile, so that those of window 1 can take their place
@@ -579,8 +613,12 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
 #pragma unroll
             for (int j = 0; j < 4; ++j) gx[j] = *reinterpret_cast<const f4 *>(t + j * 256);
         }
+        f4 gpre[kGPer / 4];
+        const bool gram_now = rounds && k >= 1;                  // (window 0's table: prologue)
+        if (gram_now) load_gram(tid_w, k, gpre);
         __syncthreads();                                         // (A) shares of W' X_k^T, -Bm_{k-1}, staged inputs in LDS
         PROF_T(0);
+        if (gram_now) store_gram(tid_w, gpre);                   // (the rounds of window k - 1 are long done with theirs)
         if (rounds && k >= 1) {                                  // (window 0: summed in the prologue)
             sum_parts(tid_w, 0);
             if (MT > 1) {
