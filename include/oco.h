@@ -171,9 +171,10 @@ typedef enum {
     OCO_OPT_SPARSE_LPW = 6,      /* (~) learners per workgroup of the sparse kernel: 4, 8, 16, 32, 64 */
     OCO_OPT_SPARSE_PIPE = 7,     /* (~) 0: sparse windows one after the other, no pipeline */
     OCO_OPT_VERBOSE = 8,         /* 1: launch plans on stderr */
-    OCO_OPT_WINDOW_RESIDENT = 9, /* windowed dense path, where the iterates live between windows:
-                                    (~) 0: HBM, two tiles of 16 learners per workgroup; 1: registers of the
-                                    workgroup (d <= 4096, else as 0); 2: HBM, one tile, 16 wavefronts */
+    OCO_OPT_WINDOW_RESIDENT = 9, /* (~) windowed dense path, where the iterates live between windows:
+                                    0: HBM, two tiles of 16 learners per workgroup; 1: registers of the
+                                    workgroup (d <= 4096, else as 0); 2: HBM, one tile, 16 wavefronts;
+                                    3: HBM, four tiles, operands brought to LDS by loading wavefronts */
     OCO_OPT_COUNT = 10
 } oco_option;
 int oco_set_option(oco_state *st, int key, int64_t value);

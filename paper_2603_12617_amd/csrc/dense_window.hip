@@ -199,6 +199,7 @@ template <int NW, int MT> struct LdsT {
     static constexpr bool wide = NW == kNW8 && MT == 1;
     using G = double;                                              // Gram table
     using S = std::conditional_t<wide, double, float>;             // inner products handed to the rounds, f_t
+    static constexpr bool has_corr = true;                         // the rounds start from pmul q0 + corr
     static constexpr int gd_bytes = kB * 4 * kGStride * (int)sizeof(G);   // G [64][4][kGStride]: G[t][t2], zero for t2 <= t;
                                                                    //   [t][0][16] holds G[t][t]
     static constexpr int tile_f = kB * kM * 4;                     // float [64][16]
@@ -253,11 +254,10 @@ template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
 // Straight-line code: a window shorter than 64 rounds (first / last window of a call) runs its
 // missing rounds as rounds without a step (a = 0, so f = 1 and no pending prediction moves; their
 // rows of G are zero).
-template <int LOSS, int NW, int MT>
+template <int LOSS, class Lds>
 __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int lane, int wl, float eta, double D, double pmul,
                                                double fscale, double &n2, bool &projected)
 {
-    using Lds = LdsT<NW, MT>;
     using GT = typename Lds::G;
     using ST = typename Lds::S;
     const int lc = lane >> 2, s = lane & 3;
@@ -275,7 +275,8 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
 
     double p[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) p[j] = fma(pmul, (double)q0d[4 * j * kM], (double)cr[4 * j * kM]);
+    for (int j = 0; j < 16; ++j)
+        p[j] = Lds::has_corr ? fma(pmul, (double)q0d[4 * j * kM], (double)cr[4 * j * kM]) : pmul * (double)q0d[4 * j * kM];
 
     // A round has a short dependent part (prediction -> slope -> step -> norm -> projection factor)
     // and a wide independent one (its update of the pending predictions).  Only the prediction of
@@ -661,7 +662,7 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
                 }
                 n2_begin = n2;
                 const double fscale = k == 0 ? pmul : 1.0;
-                pmul = chain_window<LOSS, NW, MT>(lds, k & 1, wave_w, lane, plan.len(w0 + k), eta, (double)a.D, pmul, fscale,
+                pmul = chain_window<LOSS, Lds>(lds, k & 1, wave_w, lane, plan.len(w0 + k), eta, (double)a.D, pmul, fscale,
                                                   n2, proj_prev);
             }
         } else {
@@ -846,6 +847,351 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
     }
 }
 
+// ---- the same windows with rows and iterates brought to LDS by wavefronts of their own -----------
+// Four tiles of 16 learners per workgroup, two working wavefronts per tile (wavefront tau + 4 sigma:
+// tile tau, blocks 2 s + sigma), and four wavefronts that only load.  All step through the blocks
+// together, one barrier per step.  The loaders bring to a ring of three LDS stages the rows of
+// the step's two blocks -- window k's in the lane order of (3), window k + 1's in that of (1) --
+// which serve all four tiles (4 KB of L2 traffic per tile and block where a wavefront that loads
+// its own rows needs 8 KB), and the eight blocks of iterates of the step; their registers are the
+// prefetch buffer (the loads of four steps are on their way).  The working wavefronts read the
+// operands of step s + 1 from LDS while the matrix instructions of step s run, and store the
+// new block; they never wait for a memory instruction.  (On this hardware one counter per
+// wavefront covers loads and stores alike and runs in issue order, so a wavefront that stores
+// cannot wait for a younger load without also waiting for the acknowledgement of every older
+// store, several microseconds here.)
+// Windows are not overlapped here: sweep k (step (3) of window k, then W X^T for window k + 1)
+// follows the dependent rounds of window k, which wavefront tau runs for tile tau; the inner
+// products they start from are exact (no cross-Gram correction) and ||w||^2 is the sum of squares
+// the sweep has just taken.  Wavefronts of the workgroup exchange data through LDS only, except
+// that the loaders read iterates the others stored one sweep earlier (they wait for those stores
+// once per window, after the dependent rounds); the barriers are therefore bare s_barrier
+// instructions behind a wait for the LDS operations of the wavefront (__syncthreads() would also
+// wait for every store's acknowledgement).
+// Measured on c4 (one workgroup per compute unit, 128 steps per window): 1.07 us per step with the
+// loads switched off against 0.85 us of matrix instructions, 1.35 us with them, whether the
+// loads go through registers or straight to LDS and whatever their distance; the dependent rounds
+// (not overlapped) and the hand-over between the phases add 35 us per window.
+constexpr int kQT = 4, kQS = 2;              // tiles per workgroup, working wavefronts per tile
+constexpr int kQW = kQT * kQS;               // working wavefronts; wavefront kQW loads
+constexpr int kQStages = 3;
+constexpr int kQL = 4, kQSets = 4;           // loading wavefronts; steps of loads each keeps in registers
+struct LdsQ {
+    using G = double;
+    using S = float;
+    static constexpr bool has_corr = false;
+    static constexpr int gd_bytes = kB * 4 * kGStride * 8;
+    static constexpr int tile_f = kB * kM * 4, tile_s = tile_f;
+    static constexpr int yb_bytes = kQT * tile_f, zb_bytes = kQT * tile_f, bm_bytes = kQT * tile_f, fv_bytes = kQT * kM * 4;
+    static constexpr int rows_bytes = kQS * 2 * 4096;              // per step and block: rows for (3), rows for (1)
+    static constexpr int stage_bytes = rows_bytes + kQW * 1024;    // ... and a block of iterates per working wavefront
+    static constexpr int gd = 0;
+    static constexpr int yb = gd + gd_bytes;
+    static constexpr int zb = yb + yb_bytes;
+    static constexpr int bm = zb + zb_bytes;
+    static constexpr int fv = bm + bm_bytes;
+    static constexpr int n2 = fv + fv_bytes;                       // float [kQT][kQS * 4][16]: shares of ||w||^2
+    static constexpr int ring = n2 + kQT * kQS * 4 * kM * 4;
+    // between two sweeps the ring's space holds the shares of W X^T, [kQS][kQT][64][16] (share 0
+    // becomes the sum), and the a_t and f_t of the dependent rounds
+    static constexpr int q0 = ring;
+    static constexpr int part_bytes = kQT * tile_f;
+    static constexpr int st = ring + kQS * part_bytes;
+    static constexpr int fl = st + kQT * tile_f;
+    static constexpr int corr = 0;                                 // (unused)
+    static constexpr int total = ring + kQStages * stage_bytes;
+};
+static_assert(LdsQ::fl + kQT * LdsQ::tile_s <= LdsQ::total && LdsQ::total <= 160 * 1024, "LDS of a gfx950 compute unit");
+
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int LOSS>
+__global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kernel(const DenseArgs a, const float *gram, const float *gxt,
+                                                                               const float *xq, const float *xu, float *misc,
+                                                                               WinPlanD plan, int w0, int nw)
+{
+    (void)gxt;
+    using Lds = LdsQ;
+    constexpr int NT = kQW * kWave;                              // working threads
+    extern __shared__ __align__(16) char lds[];
+    const int d = a.d, K = a.K;
+    const int nq = a.R * K;
+    const int nblk = (d + 15) / 16;
+    const int nstep = (nblk + kQS - 1) / kQS;
+    const int npad = (nstep + kQSets * kQStages - 1) / (kQSets * kQStages) * (kQSets * kQStages);   // steps every wavefront walks
+    const int q_base = (int)blockIdx.x * kQT * kM;
+    const int tid = (int)threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = wave >= kQW;
+    const int tau = wave & (kQT - 1), sg = (wave / kQT) & (kQS - 1);
+    const int lr = lane & 15, lk = lane >> 4;
+    const int q_sw = q_base + tau * kM + lr;                     // this lane's learner in the sweep
+    const bool q_ok = q_sw < nq;
+    float *vrow = a.V + (int64_t)(q_ok ? q_sw : 0) * d + 4 * lk;
+    float *sink = misc + kMiscZeros + (tid & (NT - 1)) * 4;
+
+    // dependent rounds: wavefront m < kQT, lane = 4 learner + quad lane
+    float eta = 0.f;
+    double sigma0 = 1.0, n2_state = 0.0;
+    {
+        const int q_ch = q_base + wave * kM + (lane >> 2);
+        if (wave < kQT && q_ch < nq) {
+            eta = a.eta[q_ch % K];
+            sigma0 = (double)a.sigma[q_ch];
+            n2_state = a.n2[q_ch] * sigma0 * sigma0;
+        }
+    }
+    auto measured_n2 = [&](int m, int lc) __attribute__((always_inline)) {
+        const float *n2s = reinterpret_cast<const float *>(lds + Lds::n2) + m * kQS * 4 * kM;
+        double v = 0.0;
+#pragma unroll
+        for (int i = 0; i < kQS * 4; ++i) v += (double)n2s[i * kM + lc];
+        return v;
+    };
+    constexpr int kGPer = kB * kB / NT;                          // Gram entries per working thread
+    constexpr int kYPer = kQT * kM * kB / NT;                    // labels per working thread
+#ifdef OCO_WIN_PROF
+    unsigned long long prof_[8] = {0, 0, 0, 0, 0, 0, 0, 0}, last_ = wall_clock64();
+#endif
+
+    // The loader's side of a sweep: rows for (3) from window wu of the piece, rows for (1) from window wq.
+    auto load_sweep = [&](int wu, int wq) __attribute__((always_inline)) {
+        // the learners whose blocks this lane loads, tile by tile
+        const float *vr[2];
+        bool vok[2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int q = q_base + (2 * ((wave - kQW) >> 1) + m) * kM + lr;
+            vok[m] = q < nq;
+            vr[m] = a.V + (int64_t)(vok[m] ? q : 0) * d + 4 * lk;
+        }
+        // loader j: block kQS s + (j & 1) of step s; j < 2 its rows for (3) and the iterates of tiles 0, 1,
+        // j >= 2 its rows for (1) and the iterates of tiles 2, 3
+        const int L = (wave - kQW) & 1, part = (wave - kQW) >> 1;
+        struct Regs { f4 r[6]; };
+        Regs rg[kQSets];
+        auto fetch = [&](int step, Regs &o) __attribute__((always_inline)) {
+            const int sc = step < nstep ? step : nstep - 1;
+            int blk = sc * kQS + L;
+            blk = blk < nblk ? blk : nblk - 1;                   // (rows past the last block: loaded again, not used)
+            const float *src = (part == 0 ? xu + ((int64_t)wu * nblk + blk) * kTileFloats
+                                          : xq + ((int64_t)wq * nblk + blk) * kTileFloats) + lane * 4;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o.r[c] = *reinterpret_cast<const f4 *>(src + c * 256);
+            const int vblk = step * kQS + L;
+            const bool bok = step < nstep && vblk < nblk && vblk * 16 + 4 * lk < d;
+#pragma unroll
+            for (int m = 0; m < 2; ++m) o.r[4 + m] = *reinterpret_cast<const f4 *>((bok && vok[m]) ? vr[m] + vblk * 16 : misc);
+        };
+        auto put = [&](int stage, const Regs &o) __attribute__((always_inline)) {
+            char *st = lds + Lds::ring + stage * Lds::stage_bytes + lane * 16;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) *reinterpret_cast<f4 *>(st + L * 8192 + part * 4096 + c * 1024) = o.r[c];
+#pragma unroll
+            for (int m = 0; m < 2; ++m) *reinterpret_cast<f4 *>(st + Lds::rows_bytes + (L * kQT + 2 * part + m) * 1024) = o.r[4 + m];
+        };
+        // Phase p (up to barrier p): step p's operands from registers to stage p % 3, then the loads of step
+        // p + kQSets into the registers they came from (the registers are the prefetch buffer: four steps of
+        // loads are on their way).  After barrier p the working wavefronts read stage p while they work step
+        // p - 1; the stage was last read two phases earlier.
+#pragma unroll
+        for (int s0 = 0; s0 < kQSets; ++s0) fetch(s0, rg[s0]);
+        put(0, rg[0]);
+        fetch(kQSets, rg[0]);
+        lds_barrier();
+        for (int sb = 0; sb < npad; sb += kQSets * kQStages) {
+            static_for<kQSets * kQStages>([&](auto uc) __attribute__((always_inline)) {
+                constexpr int u = decltype(uc)::value;
+                put((u + 1) % kQStages, rg[(u + 1) % kQSets]);
+                fetch(sb + u + 1 + kQSets, rg[(u + 1) % kQSets]);
+                lds_barrier();
+            });
+        }
+        lds_barrier();
+        lds_barrier();
+        lds_barrier();
+    };
+
+    // The working wavefronts' side.  F and -Bm of this lane's learner (bmr[rs]: round 4 rs + lk); do_q: take
+    // the shares of W X^T.  stage_next >= 0: first bring the labels and the Gram table of window stage_next
+    // to LDS; flush_prev >= 0: write the predictions of window flush_prev to Z.
+    auto sweep = [&](bool do_q, float F, const float (&bmr)[16], int stage_next, int flush_prev) __attribute__((always_inline)) {
+        // loads before stores: a wait for the loads then leaves the stores' acknowledgements out
+        f4 gv[kGPer / 4];
+        float yv[kYPer];
+        if (stage_next >= 0) {
+            const int w = w0 + stage_next;
+            const int ws = plan.start(w), wl = plan.len(w);
+            const float *gsrc = gram + (int64_t)stage_next * kB * kB + tid * kGPer;
+#pragma unroll
+            for (int i = 0; i < kGPer / 4; ++i) gv[i] = *reinterpret_cast<const f4 *>(gsrc + 4 * i);
+#pragma unroll
+            for (int i = 0; i < kYPer; ++i) {
+                const int e = tid + i * NT, l = e >> 6, t = e & 63;
+                const int q = q_base + l;
+                const bool ok = a.y && q < nq && t < wl;          // (no label: a zero word)
+                yv[i] = *(ok ? a.y + (int64_t)(q / K) * a.y_run_stride + ws + t : misc);
+            }
+        }
+        if (flush_prev >= 0) {
+            const int w = w0 + flush_prev;
+            const int ws = plan.start(w), wl = plan.len(w);
+            const float *zb = reinterpret_cast<const float *>(lds + Lds::zb);
+            for (int e = tid; e < kQT * kM * kB; e += NT) {
+                const int l = e >> 6, t = e & 63;               // a learner's 64 rounds are contiguous in Z
+                const int q = q_base + l;
+                if (q < nq && t < wl)
+                    a.Z[(int64_t)(q / K) * a.zl.zs_r + (int64_t)(q % K) * a.zl.zs_i + (int64_t)(ws + t) * a.zl.zs_t] =
+                        zb[((l >> 4) * kB + t) * kM + (l & 15)];
+            }
+        }
+        if (stage_next >= 0) {
+            double *gd = reinterpret_cast<double *>(lds + Lds::gd);
+            const int t = (tid * kGPer) >> 6, t2b = (tid * kGPer) & 63;
+#pragma unroll
+            for (int i = 0; i < kGPer; ++i) {
+                const int t2 = t2b + i;
+                const float v = gv[i >> 2][i & 3];
+                gd[(t * 4 + (i & 3)) * kGStride + (t2 >> 2)] = t2 > t ? (double)v : 0.0;
+                if (t2 == t) gd[t * 4 * kGStride + 16] = (double)v;
+            }
+            float *yb = reinterpret_cast<float *>(lds + Lds::yb);
+#pragma unroll
+            for (int i = 0; i < kYPer; ++i) {
+                const int e = tid + i * NT, l = e >> 6, t = e & 63;
+                yb[((l >> 4) * kB + t) * kM + (l & 15)] = yv[i];
+            }
+        }
+        f4 acc[4];
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
+        float nn = 0.f;
+        PROF_T(1);
+        // Two sets of operand registers: while the matrix instructions of step r - 1 run, the
+        // operands of step r come from LDS (the eight wavefronts would otherwise all read right
+        // after the barrier, 72 KB through the LDS port with the matrix cores idle).
+        struct In { f4 xu[4], xq[4], vb; };
+        In in[2];
+        auto read_stage = [&](int stage, In &o) __attribute__((always_inline)) {
+            const char *stg = lds + Lds::ring + stage * Lds::stage_bytes;
+            const char *rows = stg + sg * 8192 + lane * 16;
+            o.vb = *reinterpret_cast<const f4 *>(stg + Lds::rows_bytes + (sg * kQT + tau) * 1024 + lane * 16);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o.xu[c] = *reinterpret_cast<const f4 *>(rows + c * 1024);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o.xq[c] = *reinterpret_cast<const f4 *>(rows + 4096 + c * 1024);
+        };
+        lds_barrier();                                           // the loader has stage 0 complete
+        read_stage(0, in[0]);
+        for (int sb = 0; sb < npad; sb += 2 * kQStages) {
+            static_for<2 * kQStages>([&](auto uc) __attribute__((always_inline)) {
+                constexpr int u = decltype(uc)::value;
+                const int step = sb + u;
+                const int blk = step * kQS + sg;
+                lds_barrier();                                   // stage step + 1 complete, own reads of stage step done
+                read_stage((u + 1) % kQStages, in[(u + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                const bool active = step < nstep && blk < nblk;  // wavefront-uniform
+                if (active) {
+                    In &c = in[u & 1];
+                    f4 vb = c.vb;
+                    f4 vo = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) vb[r] *= F;
+#pragma unroll
+                    for (int rs = 0; rs < 16; rs += 2) {
+                        vb = __builtin_amdgcn_mfma_f32_16x16x4f32(c.xu[rs >> 2][rs & 3], bmr[rs], vb, 0, 0, 0);
+                        vo = __builtin_amdgcn_mfma_f32_16x16x4f32(c.xu[rs >> 2][(rs & 3) + 1], bmr[rs + 1], vo, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) vb[r] += vo[r];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) nn = fmaf(vb[r], vb[r], nn);
+                    {
+                        const bool ok = q_ok && blk * 16 + 4 * lk < d;
+                        float *dst = ok ? vrow + blk * 16 : sink;
+                        *reinterpret_cast<f4 *>(dst) = vb;
+                    }
+                    if (do_q) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+#pragma unroll
+                            for (int rb = 0; rb < 4; ++rb)
+                                acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(c.xq[rb][r], vb[r], acc[rb], 0, 0, 0);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        }
+        PROF_T(2);
+        lds_barrier();                                           // every wavefront is done with the ring
+        {
+            float *part = reinterpret_cast<float *>(lds + Lds::q0 + sg * Lds::part_bytes + tau * Lds::tile_f);
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) part[(rb * 16 + 4 * lk + r) * kM + lr] = acc[rb][r];
+            reinterpret_cast<float *>(lds + Lds::n2)[(tau * kQS * 4 + sg * 4 + lk) * kM + lr] = nn;
+        }
+        lds_barrier();
+        // the two shares of every tile's W X^T, summed in place
+        if (do_q) {
+            float *p0 = reinterpret_cast<float *>(lds + Lds::q0);
+            const float *p1 = reinterpret_cast<const float *>(lds + Lds::q0 + Lds::part_bytes);
+#pragma unroll
+            for (int i = 0; i < kQT * kB * kM / NT; ++i) p0[tid + i * NT] += p1[tid + i * NT];
+        }
+        lds_barrier();
+        PROF_T(3);
+    };
+
+    // ---- the stored iterates times the rows of the first window (a sweep whose step changes nothing) ----
+    if (loader) {
+        load_sweep(0, 0);
+    } else {
+        float zero[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+        sweep(true, 1.f, zero, 0, -1);
+    }
+    for (int k = 0; k < nw; ++k) {
+        const bool more = k + 1 < nw;
+        if (wave < kQT) {
+            double n2 = k == 0 ? n2_state : measured_n2(wave, lane >> 2);
+            const double scale = k == 0 ? sigma0 : 1.0;
+            bool projected;
+            (void)chain_window<LOSS, Lds>(lds, 0, wave, lane, plan.len(w0 + k), eta, (double)a.D, scale, scale, n2, projected);
+        }
+        PROF_T(0);
+        // the iterates the last sweep stored are read by the loader in the next one
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        lds_barrier();
+        PROF_T(4);
+        if (loader) {
+            load_sweep(k, more ? k + 1 : k);
+        } else {
+            float bmr[16];
+            const float *bml = reinterpret_cast<const float *>(lds + Lds::bm + tau * Lds::tile_f);
+#pragma unroll
+            for (int rs = 0; rs < 16; ++rs) bmr[rs] = bml[(rs * 4 + lk) * kM + lr];
+            const float F = reinterpret_cast<const float *>(lds + Lds::fv)[tau * kM + lr];
+            sweep(more, F, bmr, more ? k + 1 : -1, k);
+        }
+    }
+#ifdef OCO_WIN_PROF
+    if (threadIdx.x == 0 && blockIdx.x == 0)
+        for (int i = 0; i < 8; ++i) g_win_prof[i] = prof_[i];
+#endif
+    // ---- state out: the iterates themselves (scale 1) and their squared norms ----------------------
+    {
+        const int q_ch = q_base + wave * kM + (lane >> 2);
+        if (wave < kQT && (lane & 3) == 0 && q_ch < nq) {
+            a.sigma[q_ch] = 1.f;
+            a.n2[q_ch] = measured_n2(wave, lane >> 2);
+        }
+    }
+}
+
 using WindowKernel = void (*)(const DenseArgs, const float *, const float *, const float *, const float *, float *, WinPlanD, int,
                               int);
 
@@ -861,6 +1207,10 @@ template <int LOSS> WindowKernel pick_window_kernel(int nblk, int mode, int *wav
     if (mode == 1) {
         *waves = kNW8; *tiles = 2; *lds_bytes = LdsT<kNW8, 2>::total;
         return dense_window_kernel<LOSS, 1, false, kNW8, 2>;
+    }
+    if (mode == 3) {
+        *waves = kQW + kQL; *tiles = kQT; *lds_bytes = LdsQ::total;
+        return dense_window_shared_kernel<LOSS>;
     }
     *waves = kNW16; *tiles = 1; *lds_bytes = LdsT<kNW16, 1>::total;
     return dense_window_kernel<LOSS, 1, false, kNW16, 1>;
@@ -932,16 +1282,21 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
         if (e != hipSuccess) return e;
     }
     // where the iterates live: OCO_OPT_WINDOW_RESIDENT 1 registers (d <= 4096), 0 streamed (two tiles per
-    // workgroup), 2 streamed (one tile, sixteen wavefronts).  Unset: streamed, two tiles -- on c4 as fast as
-    // the registers (every round row a wavefront loads serves two tiles), on c3 half as many workgroups.
+    // workgroup), 2 streamed (one tile, sixteen wavefronts), 3 streamed with loading wavefronts (four tiles).
+    // Unset: streamed, two tiles -- on c4 as fast as the registers (every round row a wavefront loads
+    // serves two tiles), on c3 half as many workgroups -- or, with at least four tiles per compute unit's
+    // workgroup on every one of 256 compute units and wide rows, the loading wavefronts (c4: 67.4 against
+    // 70.4 ms; c3, bound by the dependent rounds, which that kernel does not overlap: 101 against 47.5 ms).
     const int64_t ropt = a.tune->get(OCO_OPT_WINDOW_RESIDENT);
     const bool fits = a.d <= 16 * kNW8 * 32;
-    const int mode = (ropt == 1 && fits) ? 0 : ropt == 2 ? 2 : 1;
+    const bool many = (int64_t)a.R * a.K >= 1024 * kM && nblk >= 128;
+    const int mode = (ropt == 1 && fits) ? 0 : ropt == 2 ? 2 : (ropt == 3 || (ropt < 0 && many)) ? 3 : 1;
     const bool resident = mode == 0;
     if (a.tune->get(OCO_OPT_VERBOSE) == 1)
         fprintf(stderr, "dense plan: windowed contraction kernel, %d windows in pieces of %lld, %d tiles, iterates %s\n",
                 nwin, (long long)sc.piece_windows, (a.R * a.K + kM - 1) / kM,
-                resident ? "in registers" : mode == 1 ? "streamed from HBM, two tiles per workgroup" : "streamed from HBM");
+                resident ? "in registers" : mode == 1 ? "streamed from HBM, two tiles per workgroup"
+                : mode == 3 ? "streamed from HBM, four tiles per workgroup, rows through LDS" : "streamed from HBM");
     WindowKernel kern = nullptr;
     int waves = 0, tiles = 1, lds_bytes = 0;
     switch (loss) {

@@ -34,7 +34,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("name,over", CASES)
-@pytest.mark.parametrize("resident", [1, 0, 2])
+@pytest.mark.parametrize("resident", [1, 0, 2, 3])
 def test_windowed_rounds_match_the_oracle(name, over, resident):
     wl = WL.make(name, **over)
     data = WL.generate(wl)
@@ -72,7 +72,7 @@ def test_steps_far_larger_than_the_ball_and_a_tiny_radius():
     ("c3", dict(T=400, R=2, d=1000, K=17, seg_len=90)),
     ("c4", dict(T=300, R=2, d=4096, K=4)),
 ])
-@pytest.mark.parametrize("resident", [1, 0, 2])
+@pytest.mark.parametrize("resident", [1, 0, 2, 3])
 def test_windowed_results_and_how_the_horizon_is_cut(name, over, resident):
     """Repeated runs are bit-identical (every sum has a fixed order).  Different cuts of the horizon
     agree to float32 rounding: the first window of a call takes its inner products with the stored
