@@ -22,6 +22,9 @@
  *  - optimistic update (Eq. (3)): hint h_t = gradient of the previous round at
  *    the previously played iterate, h_1 = 0, w^_1 = 0; for K > 1 every learner
  *    runs it independently and Hedge weighs the played iterates;
+ *  - optimism at both levels (appendix on combining optimism and ensemble; no
+ *    update rule in the paper): base learners as above, Hedge on L_{t-1} + m_t
+ *    with the last observed loss as hint m_t (m_1 = 0), no correction term;
  *  - Lemma 1 / Theorem 1: a negative regret is taken as 0.
  * Also here: the accepted-length / acceleration-rate bounds of Lemma 1 and
  * Theorem 1 (closed forms) and the optimistic two-step update of Eq. (3).
@@ -340,7 +343,7 @@ void oco_oracle_accel_bounds(double reg, int64_t T, int64_t k, double alpha, dou
  * [K] sums of ||h_t - g_t||^2; tr->z / tr->loss / tr->p / tr->f / tr->fu /
  * tr->zmix as in oco_oracle_run (z of the played iterates).
  */
-int oco_oracle_run_optimistic(int64_t d, int64_t K, int64_t T, double D, const double *eta,
+static int run_optimistic_impl(int meta_hint, int64_t d, int64_t K, int64_t T, double D, const double *eta,
                               double eps, int loss, const float *x, const float *y,
                               const float *u, const int64_t *seg_start, int64_t S,
                               double *W, double *What, double *L, double *p, double *wbar,
@@ -352,7 +355,9 @@ int oco_oracle_run_optimistic(int64_t d, int64_t K, int64_t T, double D, const d
     double *h = calloc(K * d, sizeof(double));     /* h_t */
     double *z = malloc(sizeof(double) * K), *ell = malloc(sizeof(double) * K);
     double *xt = malloc(sizeof(double) * d), *g = malloc(sizeof(double) * d);
-    if (!hat || !h || !z || !ell || !xt || !g) return -1;
+    double *mh = calloc(K, sizeof(double));        /* meta hint m_t: the last observed loss (m_1 = 0) */
+    double *Lh = malloc(sizeof(double) * K);       /* L_{t-1} + m_t */
+    if (!hat || !h || !z || !ell || !xt || !g || !mh || !Lh) return -1;
     for (int64_t i = 0; i < K; ++i) { L[i] = 0.0; if (delta) delta[i] = 0.0; }
     double reg = 0.0;
     int64_t seg = 0;
@@ -369,7 +374,8 @@ int oco_oracle_run_optimistic(int64_t d, int64_t K, int64_t T, double D, const d
         const float *ut = u + seg * d;
         double yt = y ? (double)y[t] : 0.0;
         for (int64_t j = 0; j < d; ++j) xt[j] = (double)x[t * d + j];
-        oco_oracle_hedge(L, K, eps, p);
+        for (int64_t i = 0; i < K; ++i) Lh[i] = L[i] + (meta_hint ? mh[i] : 0.0);
+        oco_oracle_hedge(Lh, K, eps, p);
 
         double zu = 0.0, zw = 0.0, zmix = 0.0;
         for (int64_t j = 0; j < d; ++j) zu += (double)ut[j] * xt[j];
@@ -412,9 +418,11 @@ int oco_oracle_run_optimistic(int64_t d, int64_t K, int64_t T, double D, const d
             }
             oco_oracle_project(hat + i * d, d, D);
             L[i] += ell[i];
+            mh[i] = ell[i];
         }
     }
-    oco_oracle_hedge(L, K, eps, p);
+    for (int64_t i = 0; i < K; ++i) Lh[i] = L[i] + (meta_hint ? mh[i] : 0.0);
+    oco_oracle_hedge(Lh, K, eps, p);
     for (int64_t j = 0; j < d; ++j) {
         double wj = 0.0;
         for (int64_t i = 0; i < K; ++i) wj += p[i] * W[i * d + j];
@@ -422,8 +430,34 @@ int oco_oracle_run_optimistic(int64_t d, int64_t K, int64_t T, double D, const d
     }
     if (What) memcpy(What, hat, sizeof(double) * K * d);
     *regret = reg;
-    free(hat); free(h); free(z); free(ell); free(xt); free(g);
+    free(hat); free(h); free(z); free(ell); free(xt); free(g); free(mh); free(Lh);
     return 0;
+}
+
+int oco_oracle_run_optimistic(int64_t d, int64_t K, int64_t T, double D, const double *eta,
+                              double eps, int loss, const float *x, const float *y,
+                              const float *u, const int64_t *seg_start, int64_t S,
+                              double *W, double *What, double *L, double *p, double *wbar,
+                              double *regret, double *delta, const oco_oracle_trace *tr)
+{
+    return run_optimistic_impl(0, d, K, T, D, eta, eps, loss, x, y, u, seg_start, S, W, What, L, p, wbar, regret, delta, tr);
+}
+
+/* Optimism at both levels of the ensemble (appendix, "Combining Optimistic Online Learning and
+ * Ensemble Learning": base learners and meta learner both optimistic; the paper gives no update
+ * rule).  Reading: the base learners run Eq. (3) as above; the meta learner is Hedge on the
+ * cumulative losses plus a hint for the coming loss, p_t^i ~ exp(-eps (L_{t-1}^i + m_t^i)), with
+ * the last observed loss as hint, m_t^i = f_{t-1}(w_{t-1}^i), m_1 = 0 -- the same reuse of the
+ * last feedback that Sec. 3.2 makes for the gradient.  The weights handed back are those of
+ * round T + 1.  meta_hint == 0 is oco_oracle_run_optimistic. */
+int oco_oracle_run_optimistic_meta(int64_t d, int64_t K, int64_t T, double D, const double *eta,
+                                   double eps, int loss, const float *x, const float *y,
+                                   const float *u, const int64_t *seg_start, int64_t S,
+                                   double *W, double *What, double *L, double *p, double *wbar,
+                                   double *regret, double *delta, const oco_oracle_trace *tr, int meta_hint)
+{
+    return run_optimistic_impl(meta_hint != 0, d, K, T, D, eta, eps, loss, x, y, u, seg_start, S, W, What, L, p, wbar, regret,
+                               delta, tr);
 }
 
 /*
@@ -444,7 +478,7 @@ int oco_oracle_run_optimistic(int64_t d, int64_t K, int64_t T, double D, const d
  *                    iterate is only evaluated at the coordinates round t reads.
  * Outputs as oco_oracle_run_optimistic.
  */
-int oco_oracle_run_optimistic_sparse(int64_t d, int64_t K, int64_t T, double D, const double *eta,
+static int run_optimistic_sparse_impl(int meta_hint, int64_t d, int64_t K, int64_t T, double D, const double *eta,
                                      double eps, int loss, const int32_t *col, const float *val,
                                      int64_t nnz, const float *y, const float *u,
                                      const int64_t *seg_start, int64_t S, int64_t norm_every,
@@ -462,7 +496,9 @@ int oco_oracle_run_optimistic_sparse(int64_t d, int64_t K, int64_t T, double D, 
     double *wc = malloc(sizeof(double) * K * nnz);     /* played iterates at round t's columns */
     double *saved = malloc(sizeof(double) * nnz);
     double *tmp = calloc(d, sizeof(double));           /* dense scratch, all zero between uses */
-    if (!hat || !cprev || !n2 || !z || !ell || !wc || !saved || !tmp) return -1;
+    double *mh = calloc(K, sizeof(double));            /* meta hint m_t: the last observed loss (m_1 = 0) */
+    double *Lh = malloc(sizeof(double) * K);           /* L_{t-1} + m_t */
+    if (!hat || !cprev || !n2 || !z || !ell || !wc || !saved || !tmp || !mh || !Lh) return -1;
     for (int64_t i = 0; i < K; ++i) { L[i] = 0.0; if (delta) delta[i] = 0.0; }
     double reg = 0.0, drift = 0.0;
     int64_t seg = 0;
@@ -473,7 +509,8 @@ int oco_oracle_run_optimistic_sparse(int64_t d, int64_t K, int64_t T, double D, 
         double yt = y ? (double)y[t] : 0.0;
         const int32_t *ct = col + t * nnz, *cp = t > 0 ? col + (t - 1) * nnz : NULL;
         const float *vt = val + t * nnz, *vp = t > 0 ? val + (t - 1) * nnz : NULL;
-        oco_oracle_hedge(L, K, eps, p);
+        for (int64_t i = 0; i < K; ++i) Lh[i] = L[i] + (meta_hint ? mh[i] : 0.0);
+        oco_oracle_hedge(Lh, K, eps, p);
 
         /* the played iterates w_t^i = Proj[w^_t - eta_i h_t] and their predictions */
         for (int64_t i = 0; i < K; ++i) {
@@ -566,6 +603,7 @@ int oco_oracle_run_optimistic_sparse(int64_t d, int64_t K, int64_t T, double D, 
             n2[i] = s2;
             cprev[i] = c;
             L[i] += ell[i];
+            mh[i] = ell[i];
         }
     }
 
@@ -580,7 +618,8 @@ int oco_oracle_run_optimistic_sparse(int64_t d, int64_t K, int64_t T, double D, 
         }
         oco_oracle_project(w, d, D);
     }
-    oco_oracle_hedge(L, K, eps, p);
+    for (int64_t i = 0; i < K; ++i) Lh[i] = L[i] + (meta_hint ? mh[i] : 0.0);
+    oco_oracle_hedge(Lh, K, eps, p);
     for (int64_t j = 0; j < d; ++j) {
         double wj = 0.0;
         for (int64_t i = 0; i < K; ++i) wj += p[i] * W[i * d + j];
@@ -589,13 +628,38 @@ int oco_oracle_run_optimistic_sparse(int64_t d, int64_t K, int64_t T, double D, 
     if (What) memcpy(What, hat, sizeof(double) * K * d);
     *regret = reg;
     if (max_drift) *max_drift = drift;
-    free(hat); free(cprev); free(n2); free(z); free(ell); free(wc); free(saved); free(tmp);
+    free(hat); free(cprev); free(n2); free(z); free(ell); free(wc); free(saved); free(tmp); free(mh); free(Lh);
     return 0;
+}
+
+int oco_oracle_run_optimistic_sparse(int64_t d, int64_t K, int64_t T, double D, const double *eta,
+                                     double eps, int loss, const int32_t *col, const float *val,
+                                     int64_t nnz, const float *y, const float *u,
+                                     const int64_t *seg_start, int64_t S, int64_t norm_every,
+                                     double *W, double *What, double *L, double *p, double *wbar,
+                                     double *regret, double *delta, double *max_drift,
+                                     const oco_oracle_trace *tr)
+{
+    return run_optimistic_sparse_impl(0, d, K, T, D, eta, eps, loss, col, val, nnz, y, u, seg_start, S, norm_every, W, What, L, p,
+                                      wbar, regret, delta, max_drift, tr);
+}
+
+/* The sparse form with the meta learner's hint (see oco_oracle_run_optimistic_meta). */
+int oco_oracle_run_optimistic_sparse_meta(int64_t d, int64_t K, int64_t T, double D, const double *eta,
+                                          double eps, int loss, const int32_t *col, const float *val,
+                                          int64_t nnz, const float *y, const float *u,
+                                          const int64_t *seg_start, int64_t S, int64_t norm_every,
+                                          double *W, double *What, double *L, double *p, double *wbar,
+                                          double *regret, double *delta, double *max_drift,
+                                          const oco_oracle_trace *tr, int meta_hint)
+{
+    return run_optimistic_sparse_impl(meta_hint != 0, d, K, T, D, eta, eps, loss, col, val, nnz, y, u, seg_start, S, norm_every, W,
+                                      What, L, p, wbar, regret, delta, max_drift, tr);
 }
 
 /* R independent optimistic runs, one per thread at a time; layout as oco_oracle_run_many
  * (dense x[T][d] shared or x[R][T][d]; or, with nnz > 0, shared col/val[T][nnz] and x == NULL). */
-int oco_oracle_run_many_optimistic(int64_t R, int64_t d, int64_t K, int64_t T, double D,
+static int run_many_optimistic_impl(int meta_hint, int64_t R, int64_t d, int64_t K, int64_t T, double D,
                                    const double *eta, double eps, int loss, int x_shared,
                                    const float *x, const int32_t *col, const float *val, int64_t nnz,
                                    const float *y, const float *u,
@@ -616,12 +680,12 @@ int oco_oracle_run_many_optimistic(int64_t R, int64_t d, int64_t K, int64_t T, d
         int rc;
         double dr = 0.0;
         if (nnz > 0)
-            rc = oco_oracle_run_optimistic_sparse(d, K, T, D, eta, eps, loss, col, val, nnz,
+            rc = run_optimistic_sparse_impl(meta_hint, d, K, T, D, eta, eps, loss, col, val, nnz,
                                                   y ? y + r * T : NULL, u + r * S * d, seg_start, S,
                                                   norm_every, W + r * K * d, NULL, L + r * K, p + r * K,
                                                   wbar + r * d, regret + r, NULL, &dr, NULL);
         else
-            rc = oco_oracle_run_optimistic(d, K, T, D, eta, eps, loss, x_shared ? x : x + r * T * d,
+            rc = run_optimistic_impl(meta_hint, d, K, T, D, eta, eps, loss, x_shared ? x : x + r * T * d,
                                            y ? y + r * T : NULL, u + r * S * d, seg_start, S,
                                            W + r * K * d, NULL, L + r * K, p + r * K, wbar + r * d,
                                            regret + r, NULL, NULL);
@@ -630,4 +694,29 @@ int oco_oracle_run_many_optimistic(int64_t R, int64_t d, int64_t K, int64_t T, d
     }
     if (threads_used) *threads_used = used;
     return bad;
+}
+
+int oco_oracle_run_many_optimistic(int64_t R, int64_t d, int64_t K, int64_t T, double D,
+                                   const double *eta, double eps, int loss, int x_shared,
+                                   const float *x, const int32_t *col, const float *val, int64_t nnz,
+                                   const float *y, const float *u,
+                                   const int64_t *seg_start, int64_t S, int64_t norm_every, int threads,
+                                   double *W, double *L, double *p, double *wbar, double *regret,
+                                   double *max_drift, int *threads_used)
+{
+    return run_many_optimistic_impl(0, R, d, K, T, D, eta, eps, loss, x_shared, x, col, val, nnz, y, u, seg_start, S, norm_every,
+                                    threads, W, L, p, wbar, regret, max_drift, threads_used);
+}
+
+/* ... with the meta learner's hint (see oco_oracle_run_optimistic_meta). */
+int oco_oracle_run_many_optimistic_meta(int64_t R, int64_t d, int64_t K, int64_t T, double D,
+                                        const double *eta, double eps, int loss, int x_shared,
+                                        const float *x, const int32_t *col, const float *val, int64_t nnz,
+                                        const float *y, const float *u,
+                                        const int64_t *seg_start, int64_t S, int64_t norm_every, int threads,
+                                        double *W, double *L, double *p, double *wbar, double *regret,
+                                        double *max_drift, int *threads_used, int meta_hint)
+{
+    return run_many_optimistic_impl(meta_hint != 0, R, d, K, T, D, eta, eps, loss, x_shared, x, col, val, nnz, y, u, seg_start, S,
+                                    norm_every, threads, W, L, p, wbar, regret, max_drift, threads_used);
 }

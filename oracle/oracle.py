@@ -68,6 +68,11 @@ def lib() -> C.CDLL:
             + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
             + [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int]
             + [C.c_void_p] * 5 + [C.c_void_p, C.c_void_p])
+        # the same three with the meta learner's hint as a last argument
+        for name in ("oco_oracle_run_optimistic", "oco_oracle_run_optimistic_sparse", "oco_oracle_run_many_optimistic"):
+            f = getattr(_lib, name + "_meta")
+            f.restype = C.c_int
+            f.argtypes = list(getattr(_lib, name).argtypes) + [C.c_int]
     return _lib
 
 
@@ -152,9 +157,10 @@ def accel_bounds(reg: float, T: int, k: int, alpha: float) -> np.ndarray:
 
 def run_optimistic(d: int, K: int, T: int, D: float, eta, eps: float, loss: str, *,
                    x=None, col=None, val=None, y=None, u=None, seg_start=None, norm_every: int = 0,
-                   trace: bool = False) -> Dict[str, np.ndarray]:
+                   trace: bool = False, meta_hint: bool = False) -> Dict[str, np.ndarray]:
     """One run of K optimistic learners (Eq. (3), last-gradient hint) on a dense stream x [T][d]
-    or on sparse rounds col/val [T][nnz]."""
+    or on sparse rounds col/val [T][nnz].  meta_hint: the meta learner is optimistic as well
+    (Hedge on L_{t-1} + the last observed loss; appendix on combining optimism and ensemble)."""
     eta = np.ascontiguousarray(eta, dtype=np.float64)
     assert eta.size == K
     x, val, y, u = _f32(x), _f32(val), _f32(y), _f32(u)
@@ -181,16 +187,17 @@ def run_optimistic(d: int, K: int, T: int, D: float, eta, eps: float, loss: str,
             res["tr_" + name] = arr
             setattr(tr, name, arr.ctypes.data)
     if col is not None:
-        rc = lib().oco_oracle_run_optimistic_sparse(
+        rc = lib().oco_oracle_run_optimistic_sparse_meta(
             d, K, T, float(D), _ptr(eta), float(eps), LOSS_ID[loss], _ptr(col), _ptr(val), col.shape[1],
             _ptr(y), _ptr(u), _ptr(seg_start), S, int(norm_every),
             _ptr(W), _ptr(What), _ptr(L), _ptr(p), _ptr(wbar), _ptr(reg), _ptr(delta), _ptr(drift),
-            C.byref(tr) if tr is not None else None)
+            C.byref(tr) if tr is not None else None, int(bool(meta_hint)))
     else:
-        rc = lib().oco_oracle_run_optimistic(d, K, T, float(D), _ptr(eta), float(eps), LOSS_ID[loss],
-                                             _ptr(x), _ptr(y), _ptr(u), _ptr(seg_start), S,
-                                             _ptr(W), _ptr(What), _ptr(L), _ptr(p), _ptr(wbar), _ptr(reg),
-                                             _ptr(delta), C.byref(tr) if tr is not None else None)
+        rc = lib().oco_oracle_run_optimistic_meta(d, K, T, float(D), _ptr(eta), float(eps), LOSS_ID[loss],
+                                                  _ptr(x), _ptr(y), _ptr(u), _ptr(seg_start), S,
+                                                  _ptr(W), _ptr(What), _ptr(L), _ptr(p), _ptr(wbar), _ptr(reg),
+                                                  _ptr(delta), C.byref(tr) if tr is not None else None,
+                                                  int(bool(meta_hint)))
     if rc != 0:
         raise ValueError("oco_oracle_run_optimistic rejected its arguments")
     res.update(W=W, What=What, L=L, p=p, wbar=wbar, regret=float(reg[0]), delta=delta,
@@ -216,13 +223,14 @@ def run_workload(wl, data, *, threads: int = 0, norm_every: Optional[int] = None
     W = np.empty((R, K, d)); L = np.empty((R, K)); p = np.empty((R, K)); wbar = np.empty((R, d))
     reg = np.zeros(R); drift = np.zeros(R); used = C.c_int(0)
     if getattr(wl, "optimistic", False):
-        bad = lib().oco_oracle_run_many_optimistic(R, d, K, T, float(wl.D), _ptr(eta), float(wl.eps),
-                                                   LOSS_ID[wl.loss], int(bool(wl.x_shared)),
-                                                   _ptr(x), _ptr(col), _ptr(val), nnz,
-                                                   _ptr(y), _ptr(u), _ptr(seg_start), S,
-                                                   int(norm_every), int(threads),
-                                                   _ptr(W), _ptr(L), _ptr(p), _ptr(wbar),
-                                                   _ptr(reg), _ptr(drift), C.byref(used))
+        bad = lib().oco_oracle_run_many_optimistic_meta(R, d, K, T, float(wl.D), _ptr(eta), float(wl.eps),
+                                                        LOSS_ID[wl.loss], int(bool(wl.x_shared)),
+                                                        _ptr(x), _ptr(col), _ptr(val), nnz,
+                                                        _ptr(y), _ptr(u), _ptr(seg_start), S,
+                                                        int(norm_every), int(threads),
+                                                        _ptr(W), _ptr(L), _ptr(p), _ptr(wbar),
+                                                        _ptr(reg), _ptr(drift), C.byref(used),
+                                                        int(int(wl.optimistic) == 2))
         if bad:
             raise ValueError("oco_oracle_run_many_optimistic: %d runs failed" % bad)
         return dict(W=W, L=L, p=p, wbar=wbar, regret=reg, max_drift=drift, threads=used.value)

@@ -52,7 +52,7 @@ class Workload:
     seed: int = 0
     eta: tuple = field(default=())   # filled by make()
     eps: float = 0.0
-    optimistic: bool = False  # Eq. (3) two-step update with the last gradient as hint (dense only)
+    optimistic: int = 0       # 1: Eq. (3) two-step update with the last gradient as hint; 2: the meta learner optimistic too
 
     @property
     def units(self) -> int:

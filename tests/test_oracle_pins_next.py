@@ -74,6 +74,85 @@ def test_optimistic_hand_computed_trajectories(golden, name):
     assert abs(r["delta"][0] - g["delta"]) < tol
 
 
+# ------------------------------------- optimism at both levels of the ensemble ----
+def test_both_levels_optimistic_hand_computed_trajectory(golden):
+    g = golden("optimistic_both_levels_squared_d1.txt")
+    d, K, T = int(g["d"]), int(g["K"]), int(g["T"])
+    x = np.atleast_2d(g["x"]).reshape(T, d)
+    r = O.run_optimistic(d, K, T, g["D"], np.atleast_1d(g["eta"]), g["eps"], g["loss"], x=x, y=np.atleast_1d(g["y"]),
+                         u=np.atleast_2d(g["u"]).reshape(-1, d),
+                         seg_start=np.atleast_1d(g["seg_start"]).astype(np.int64), trace=True, meta_hint=True)
+    tol = 5e-7
+    np.testing.assert_allclose(r["tr_p"], np.atleast_2d(g["p"]).reshape(T, K), atol=tol)
+    np.testing.assert_allclose(r["tr_f"], np.atleast_1d(g["f"]), atol=tol)
+    np.testing.assert_allclose(r["tr_fu"], np.atleast_1d(g["fu"]), atol=tol)
+    np.testing.assert_allclose(r["W"].ravel(), np.atleast_1d(g["W"]), atol=tol)
+    np.testing.assert_allclose(r["What"].ravel(), np.atleast_1d(g["What"]), atol=tol)
+    np.testing.assert_allclose(r["L"], np.atleast_1d(g["L"]), atol=tol)
+    np.testing.assert_allclose(r["p"], np.atleast_1d(g["p_final"]), atol=tol)
+    assert abs(r["wbar"][0] - g["wbar"]) < tol and abs(r["regret"] - g["regret"]) < tol
+    # and without the meta hint round 3 weighs the cumulative losses alone
+    r1 = O.run_optimistic(d, K, T, g["D"], np.atleast_1d(g["eta"]), g["eps"], g["loss"], x=x, y=np.atleast_1d(g["y"]),
+                          u=np.atleast_2d(g["u"]).reshape(-1, d), trace=True)
+    np.testing.assert_allclose(r1["tr_p"][2], [0.8670358, 0.1329642], atol=tol)
+
+
+@pytest.mark.parametrize("sparse", [False, True])
+def test_meta_hint_leaves_the_base_learners_alone_and_tilts_hedge_by_the_last_loss(sparse):
+    """The base learners never read the meta learner's weights, so their losses are the same with
+    and without the meta hint; the hinted weights of round t are then the plain ones tilted by
+    exp(-eps * last loss), and the first round is uniform.  One learner: nothing changes at all."""
+    rng = np.random.default_rng(11)
+    d, K, T, D, eps = 12, 4, 60, 1.0, 0.3
+    eta = [0.05, 0.2, 0.8, 3.2]
+    y = rng.standard_normal(T).astype(np.float32)
+    u = (0.3 * rng.standard_normal((2, d))).astype(np.float32)
+    seg = np.array([0, 25], np.int64)
+    if sparse:
+        nnz = 3
+        col = np.sort(np.argsort(rng.random((T, d)), axis=1)[:, :nnz], axis=1).astype(np.int32)
+        val = rng.standard_normal((T, nnz)).astype(np.float32)
+        kw = dict(col=col, val=val)
+    else:
+        kw = dict(x=(rng.standard_normal((T, d)) / np.sqrt(d)).astype(np.float32))
+    a = O.run_optimistic(d, K, T, D, eta, eps, "squared", y=y, u=u, seg_start=seg, trace=True, **kw)
+    b = O.run_optimistic(d, K, T, D, eta, eps, "squared", y=y, u=u, seg_start=seg, trace=True, meta_hint=True, **kw)
+    np.testing.assert_array_equal(a["tr_z"], b["tr_z"])
+    np.testing.assert_array_equal(a["tr_loss"], b["tr_loss"])
+    np.testing.assert_array_equal(a["W"], b["W"])
+    np.testing.assert_array_equal(a["L"], b["L"])
+    np.testing.assert_array_equal(b["tr_p"][0], np.full(K, 1.0 / K))
+    for t in range(1, T):
+        w = a["tr_p"][t] * np.exp(-eps * a["tr_loss"][t - 1])
+        np.testing.assert_allclose(b["tr_p"][t], w / w.sum(), rtol=1e-12, atol=1e-15)
+    w = a["p"] * np.exp(-eps * a["tr_loss"][T - 1])
+    np.testing.assert_allclose(b["p"], w / w.sum(), rtol=1e-12, atol=1e-15)
+    # the mixed iterate's loss follows the hinted weights
+    zmix = (b["tr_p"] * b["tr_z"]).sum(axis=1)
+    np.testing.assert_allclose(b["tr_f"], (zmix - y.astype(np.float64)) ** 2, rtol=1e-10, atol=1e-13)
+    one = O.run_optimistic(d, 1, T, D, eta[:1], eps, "squared", y=y, u=u, seg_start=seg, **kw)
+    one_h = O.run_optimistic(d, 1, T, D, eta[:1], eps, "squared", y=y, u=u, seg_start=seg, meta_hint=True, **kw)
+    assert one["regret"] == one_h["regret"]
+    np.testing.assert_array_equal(one["W"], one_h["W"])
+
+
+def test_many_run_wrapper_with_the_meta_hint_equals_single_runs():
+    from paper_2603_12617_amd import workloads as WL
+    for name, over in (("c3", dict(T=150, R=3, d=24, K=3, seg_len=50)), ("c2", dict(T=120, R=3, d=10, K=3))):
+        wl = WL.make(name, optimistic=2, **over)
+        data = WL.generate(wl)
+        ref = O.run_workload(wl, data, threads=2)
+        for r in range(wl.R):
+            x = data["x"] if wl.x_shared else data["x"][r]
+            one = O.run_optimistic(wl.d, wl.K, wl.T, wl.D, wl.eta, wl.eps, wl.loss, x=x, y=data["y"][r], u=data["u"][r],
+                                   seg_start=data["seg_start"], meta_hint=True)
+            plain = O.run_optimistic(wl.d, wl.K, wl.T, wl.D, wl.eta, wl.eps, wl.loss, x=x, y=data["y"][r], u=data["u"][r],
+                                     seg_start=data["seg_start"])
+            assert ref["regret"][r] == one["regret"] and ref["regret"][r] != plain["regret"]
+            np.testing.assert_array_equal(ref["p"][r], one["p"])
+            np.testing.assert_array_equal(ref["W"][r], one["W"])
+
+
 def test_optimistic_on_a_constant_gradient_is_plain_ogd_one_round_ahead():
     """Linear loss with the same gradient every round: the hint is exact from round 2 on, the
     intermediate model follows plain OGD, and the played iterate equals plain OGD's NEXT one."""
