@@ -381,6 +381,9 @@ def main():
         for name in ("c3", "c4", "c5"):    # the optimistic two-step update (Eq. (3)) on the same streams
             key = name + "_optimistic"
             others[key] = summary_entry(run_workload(name, 2, 1, WL, B, torch, optimistic=True), key)
+        # optimism at both levels of the ensemble (the meta learner on cumulative plus last observed losses)
+        others["c3_optimistic_both_levels"] = summary_entry(run_workload("c3", 2, 1, WL, B, torch, optimistic=2),
+                                                            "c3_optimistic_both_levels")
         for name in ("v2", "v3"):          # verification step of Algorithm 1 on synthetic distributions
             others["specdec_" + name] = run_specdec(name, 5, WL, B, torch, with_cpu=not a.no_cpu)
         line["other_workloads"] = others

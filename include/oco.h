@@ -107,7 +107,15 @@ typedef struct {
                              Predictions, losses and regret are those of the played iterates
                              w_t; oco_get_state returns the iterates that would be played
                              next.  K = 1 is the paper's method; for K > 1 Hedge weighs the
-                             played iterates (not analysed in the paper)                  */
+                             played iterates (not analysed in the paper);
+                             2: optimism at both levels of the ensemble (appendix on combining
+                             optimistic and ensemble learning, which names the combination and
+                             gives no update rule).  Reading built here: base learners as 1;
+                             the meta learner is Hedge on the cumulative losses plus a hint for
+                             the coming loss, p_t^i ~ exp(-eps (L_{t-1}^i + m_t^i)), with the
+                             last observed loss as hint, m_t^i = f_{t-1}(w_{t-1}^i), m_1 = 0;
+                             no correction term.  oco_get_state hands back the weights of
+                             round T + 1                                                  */
     int64_t n_max;        /* largest n of any oco_run_rounds call; 0 means T          */
 } oco_config;
 

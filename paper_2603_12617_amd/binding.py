@@ -128,7 +128,7 @@ def make_config(*, d, K, T, R, D, G, eta: Sequence[float], eps, loss, x_shared=T
     cfg = OcoConfig(int(d), int(K), int(T), int(R), float(D), float(G),
                     C.cast(eta_arr, C.POINTER(C.c_double)), float(eps),
                     LOSS_ID[loss] if isinstance(loss, str) else int(loss), int(bool(x_shared)),
-                    int(nnz), int(bool(optimistic)), int(n_max))
+                    int(nnz), int(optimistic), int(n_max))
     return cfg, eta_arr
 
 
@@ -267,7 +267,7 @@ class Simulation:
         self.seg_start = np.ascontiguousarray(data["seg_start"], dtype=np.int64)
         self.cfg, self._keep = make_config(d=wl.d, K=wl.K, T=wl.T, R=wl.R, D=wl.D, G=wl.G, eta=wl.eta,
                                            eps=wl.eps, loss=wl.loss, x_shared=wl.x_shared, nnz=wl.nnz,
-                                           n_max=n_max, optimistic=getattr(wl, "optimistic", False))
+                                           n_max=n_max, optimistic=int(getattr(wl, "optimistic", 0)))
         nbytes = oco_workspace_bytes(self.cfg)
         if nbytes == 0:
             raise OcoError(OCO_EINVAL, "oco_workspace_bytes")

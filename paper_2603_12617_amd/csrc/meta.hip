@@ -9,6 +9,9 @@
 //     p_t^i = exp(-eps L_t^i) / sum_j exp(-eps L_t^j)
 //     <w_t, x_t> = sum_i p_t^i z_t^i                (w_t = sum_i p_t^i w_t^i is linear in w)
 //     regret += phi(<w_t, x_t>; y_t) - phi(z_t^u; y_t)
+// With the meta learner's hint (optimism at both levels of the ensemble: Hedge on the cumulative
+// losses plus a guess of the coming loss, the last observed one) the exponent of round t is
+// L_t^i + l_{t-1}^i instead; the last loss of a call is kept in the state for the next call.
 // One workgroup per run walks the rounds in tiles: losses of a tile in
 // parallel over rounds, the running sums by K threads in round order, the
 // weights and the regret terms in parallel over rounds, and the regret sum by
@@ -45,6 +48,8 @@ __global__ void __launch_bounds__(256) meta_kernel(const MetaArgs a)
     const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
 
     double Lacc = (j < K) ? a.L[(int64_t)r * K + j] : 0.0;   // thread i < K carries L^i
+    const bool hint = a.last != nullptr;
+    double lprev = (hint && j < K) ? a.last[(int64_t)r * K + j] : 0.0;   // ... and the last loss l_{t-1}^i
     double reg = (j == 0) ? a.regret[r] : 0.0;
 
     for (int t0 = 0; t0 < a.n; t0 += TM) {
@@ -70,16 +75,18 @@ __global__ void __launch_bounds__(256) meta_kernel(const MetaArgs a)
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
                     const double l = v[u];
-                    v[u] = Lacc;
+                    v[u] = hint ? Lacc + lprev : Lacc;
                     Lacc += l;
+                    lprev = l;
                 }
 #pragma unroll
                 for (int u = 0; u < 16; ++u) lmat[(jj + u) * K + j] = v[u];
             }
             for (; jj < cnt; ++jj) {
                 const double l = lmat[jj * K + j];
-                lmat[jj * K + j] = Lacc;
+                lmat[jj * K + j] = hint ? Lacc + lprev : Lacc;
                 Lacc += l;
+                lprev = l;
             }
         }
         __syncthreads();
@@ -113,17 +120,19 @@ __global__ void __launch_bounds__(256) meta_kernel(const MetaArgs a)
         // lmat/diff are rewritten only after the next tile's first barrier
     }
     if (j < K) a.L[(int64_t)r * K + j] = Lacc;
+    if (hint && j < K) a.last[(int64_t)r * K + j] = lprev;
     if (j == 0) a.regret[r] = reg;
 }
 
 // p = softmax(-eps L) of one run, into shared memory (first K threads)
-__device__ void hedge_weights(const double *L, int K, double eps, double *p_sh)
+// (last: the meta learner's hint, the last observed losses, or null)
+__device__ void hedge_weights(const double *L, const double *last, int K, double eps, double *p_sh)
 {
     if (threadIdx.x == 0) {
-        double Lmin = L[0];
-        for (int i = 1; i < K; ++i) Lmin = fmin(Lmin, L[i]);
+        double Lmin = L[0] + (last ? last[0] : 0.0);
+        for (int i = 1; i < K; ++i) Lmin = fmin(Lmin, L[i] + (last ? last[i] : 0.0));
         double S = 0.0;
-        for (int i = 0; i < K; ++i) { p_sh[i] = exp(-eps * (L[i] - Lmin)); S += p_sh[i]; }
+        for (int i = 0; i < K; ++i) { p_sh[i] = exp(-eps * (L[i] + (last ? last[i] : 0.0) - Lmin)); S += p_sh[i]; }
         for (int i = 0; i < K; ++i) p_sh[i] /= S;
     }
     __syncthreads();
@@ -137,7 +146,7 @@ __global__ void __launch_bounds__(256) export_dense_kernel(const ExportArgs a)
     __shared__ float s_sh[64], h_sh[64], f_sh[64];
     const int r = blockIdx.y;
     const int K = a.K;
-    hedge_weights(a.L + (int64_t)r * K, K, a.eps, p_sh);
+    hedge_weights(a.L + (int64_t)r * K, a.last ? a.last + (int64_t)r * K : nullptr, K, a.eps, p_sh);
     if (threadIdx.x < K) {
         const int64_t q = (int64_t)r * K + threadIdx.x;
         const float sg = static_cast<const float *>(a.sigma)[q];
@@ -226,10 +235,11 @@ __global__ void __launch_bounds__(256) export_sparse_p_wbar_kernel(const ExportA
     if (threadIdx.x < kExpRuns && r0 + (int)threadIdx.x < a.R) {
         const int rl = threadIdx.x, r = r0 + rl;
         const double *L = a.L + (int64_t)r * K;
-        double Lmin = L[0];
-        for (int i = 1; i < K; ++i) Lmin = fmin(Lmin, L[i]);
+        const double *last = a.last ? a.last + (int64_t)r * K : nullptr;      // the meta learner's hint
+        double Lmin = L[0] + (last ? last[0] : 0.0);
+        for (int i = 1; i < K; ++i) Lmin = fmin(Lmin, L[i] + (last ? last[i] : 0.0));
         double S = 0.0;
-        for (int i = 0; i < K; ++i) { p_sh[rl][i] = exp(-a.eps * (L[i] - Lmin)); S += p_sh[rl][i]; }
+        for (int i = 0; i < K; ++i) { p_sh[rl][i] = exp(-a.eps * (L[i] + (last ? last[i] : 0.0) - Lmin)); S += p_sh[rl][i]; }
         for (int i = 0; i < K; ++i) {
             p_sh[rl][i] /= S;
             const double sg = static_cast<const double *>(a.sigma)[r * K + i];

@@ -17,7 +17,7 @@ namespace {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
-    size_t off_V = 0, off_sigma = 0, off_n2 = 0, off_L = 0, off_regret = 0, off_eta = 0,
+    size_t off_V = 0, off_sigma = 0, off_n2 = 0, off_L = 0, off_last = 0, off_regret = 0, off_eta = 0,
            off_seg = 0, off_Z = 0, off_X2 = 0, off_gram = 0, total = 0;
     size_t off_ha = 0, off_hp = 0, off_xlast = 0, off_x2last = 0, off_G01 = 0;   // optimistic mode only
     size_t off_lastcol = 0, off_lastval = 0;                                       // optimistic + sparse
@@ -34,7 +34,7 @@ int validate_and_layout(const oco_config *c, Layout *lay)
 {
     if (!c || !c->eta) return OCO_EINVAL;
     if (c->d <= 0 || c->K <= 0 || c->T <= 0 || c->R <= 0) return OCO_EINVAL;
-    if ((c->optimistic != 0 && c->optimistic != 1) || c->n_max < 0) return OCO_EINVAL;
+    if (c->optimistic < 0 || c->optimistic > 2 || c->n_max < 0) return OCO_EINVAL;
     if (!finite_pos(c->D) || !finite_pos(c->G) || !std::isfinite(c->eps) || c->eps < 0.0) return OCO_EINVAL;
     if (c->loss < OCO_LINEAR || c->loss > OCO_LOGISTIC) return OCO_EINVAL;
     if (c->x_shared != 0 && c->x_shared != 1) return OCO_EINVAL;
@@ -77,6 +77,10 @@ int validate_and_layout(const oco_config *c, Layout *lay)
     }
     l.off_L = off;       off += align_up(sizeof(double) * (size_t)RK, 256);
     l.off_regret = off;  off += align_up(sizeof(double) * (size_t)c->R, 256);
+    if (c->optimistic == 2) {                              // the meta learner's hint: last observed losses
+        l.off_last = off;
+        off += align_up(sizeof(double) * (size_t)RK, 256);
+    }
     if (c->optimistic && c->sparse_nnz > 0) {
         l.off_ha = off;      off += align_up(sizeof(float) * (size_t)l.RKp, 256);
         l.off_hp = off;      off += align_up(sizeof(float) * (size_t)l.RKp, 256);
@@ -399,6 +403,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
     MetaArgs &m = pipe.m;
     m.Z = st->at<float>(l.off_Z); m.zl = zl; m.y = rd->y; m.y_run_stride = yrs;
     m.L = st->at<double>(l.off_L); m.regret = st->at<double>(l.off_regret);
+    m.last = l.off_last ? st->at<double>(l.off_last) : nullptr;
     m.eps = c.eps; m.K = (int)c.K; m.R = (int)c.R; m.n = (int)n;
     const PieceHook hook{&MetaPipe::piece, &pipe, &MetaPipe::beside};
     const bool overlap = st->side != nullptr && st->tune.get(OCO_OPT_META_BESIDE) != 0;
@@ -498,6 +503,7 @@ int oco_get_state(oco_state *st, float *W_dev, float *p_dev, float *wbar_dev)
     a.V = st->at<float>(st->lay.off_V);
     a.sigma = st->at<void>(st->lay.off_sigma);
     a.L = st->at<double>(st->lay.off_L);
+    a.last = st->lay.off_last ? st->at<double>(st->lay.off_last) : nullptr;
     a.eps = st->cfg.eps;
     a.W = W_dev; a.p = p_dev; a.wbar = wbar_dev;
     a.d = (int)st->cfg.d; a.K = (int)st->cfg.K; a.R = (int)st->cfg.R; a.RKp = st->lay.RKp;

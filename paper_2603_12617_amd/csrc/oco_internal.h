@@ -173,6 +173,7 @@ struct MetaArgs {
     const float *y;
     int64_t y_run_stride;
     double *L;               // [R][K] cumulative losses, updated in place
+    double *last;            // [R][K] last observed losses (the meta learner's hint), updated in place; or null
     double *regret;          // [R]
     double eps;
     int K, R, n;
@@ -184,6 +185,7 @@ struct ExportArgs {
     const float *V;
     const void *sigma;       // float [R][K] (dense) or double [RKp] (sparse)
     const double *L;
+    const double *last;      // the meta learner's hint, or null
     double eps;
     float *W, *p, *wbar;     // any may be null
     int d, K, R, RKp;

@@ -66,8 +66,14 @@ def test_workspace_bytes_is_zero_for_bad_configs():
         cfg, keep = _cfg(**bad)
         assert B.oco_workspace_bytes(cfg) == 0, bad
     cfg, keep = _cfg()
+    for bad_opt in (3, -1):
+        cfg.optimistic = bad_opt
+        assert B.oco_workspace_bytes(cfg) == 0
+    # optimism at both levels keeps the last observed losses beside the cumulative ones
+    cfg.optimistic = 1
+    one_level = B.oco_workspace_bytes(cfg)
     cfg.optimistic = 2
-    assert B.oco_workspace_bytes(cfg) == 0
+    assert B.oco_workspace_bytes(cfg) > one_level > 0
     # a shared stream may be wider than one wavefront's registers (iterates streamed from HBM)
     for good in (dict(d=4096, x_shared=False), dict(d=8192), dict(d=65536)):
         cfg, keep = _cfg(**good)

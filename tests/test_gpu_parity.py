@@ -234,6 +234,48 @@ def test_optimistic_results_do_not_depend_on_how_the_horizon_is_cut(name, over, 
             assert np.array_equal(whole[k], part[k]), (k, c)
 
 
+# optimism at both levels of the ensemble (appendix on combining optimistic and ensemble learning):
+# base learners as above, Hedge on the cumulative losses plus the last observed loss
+BOTH_LEVELS = [
+    ("c2", dict(T=400, R=3, d=100, K=15)),
+    ("c2", dict(T=130, R=2, d=131, K=5)),
+    ("c3", dict(T=600, R=3, d=1000, K=17, seg_len=100)),
+    ("c4", dict(T=301, R=3, d=4096, K=16)),
+    ("c5", dict(T=700, R=3, d=5000, K=8, nnz=32, wstar_nnz=200)),
+    ("c5", dict(T=300, R=2, d=400, K=3, nnz=16, wstar_nnz=30, eta=(1.0, 50.0, 3000.0))),
+]
+
+
+@pytest.mark.parametrize("name,over", BOTH_LEVELS)
+def test_rounds_with_optimism_at_both_levels_match_the_oracle(name, over):
+    wl = WL.make(name, optimistic=2, **over)
+    data = WL.generate(wl)
+    print("case both levels optimistic", name, over, flush=True)
+    got = _gpu(wl, data)
+    _check(wl, data, got, norm_every=0 if wl.nnz else None, label="both levels %s %s" % (name, over))
+    # the hint moves the weights: not the result of the base-level optimism alone
+    plain = _gpu(WL.make(name, optimistic=1, **over), data)
+    assert np.array_equal(plain["W"], got["W"]) and np.array_equal(plain["L"], got["L"])
+    assert not np.array_equal(plain["p"], got["p"]) and not np.array_equal(plain["regret"], got["regret"])
+
+
+@pytest.mark.parametrize("name,over,chunks", [
+    ("c2", dict(T=300, R=3, d=100, K=15), (1, 7, 64)),
+    ("c3", dict(T=300, R=2, d=1000, K=5, seg_len=90), (13, 128)),
+])
+def test_both_levels_results_do_not_depend_on_how_the_horizon_is_cut(name, over, chunks):
+    """The meta learner's hint of a call's first round is the last loss of the call before: it is
+    kept in the state."""
+    wl = WL.make(name, optimistic=2, **over)
+    data = WL.generate(wl)
+    whole = _gpu(wl, data)
+    for c in chunks:
+        print("case both levels optimistic", name, over, "chunk", c, flush=True)
+        part = _gpu(wl, data, chunk=c, n_max=c)
+        for k in ("regret", "L", "W", "p", "wbar"):
+            assert np.array_equal(whole[k], part[k]), (k, c)
+
+
 def _check_sparse_optimistic(wl, data, got, label):
     """Against the reference's sparse form of Eq. (3), norms recomputed over all d every round."""
     _check(wl, data, got, norm_every=0, label=label)
@@ -536,6 +578,9 @@ FULL = [
     ("c3", [0, 64, 255], None, True, None),
     ("c4", [0, 511, 1023], None, True, None),
     ("c5", [3, 12], 1000, True, None),
+    ("c2", None, None, 2, None),                 # optimism at both levels of the ensemble
+    ("c3", [9, 200], None, 2, None),
+    ("c5", [8], 1000, 2, None),
     # c3 and c4 on each of the dense kernels by name (the default picks one of them), and c4 with
     # its iterates streamed from HBM every window
     ("c3", [5, 250], None, False, dict(dense_path=1)),
