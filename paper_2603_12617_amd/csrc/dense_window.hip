@@ -269,7 +269,7 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
     const float *yb = reinterpret_cast<const float *>(lds + Lds::yb + buf * Lds::yb_bytes + m * Lds::tile_f) + lc;
     float *zb = reinterpret_cast<float *>(lds + Lds::zb + buf * Lds::zb_bytes + m * Lds::tile_f) + lc;
     float *stl = reinterpret_cast<float *>(lds + Lds::st + m * Lds::tile_f) + lc;
-    const double D2 = D * D;
+    const float Df = (float)D, D2f = Df * Df;
     const float eta2 = 2.f * eta;
     bool anyp = false;
 
@@ -278,12 +278,22 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
     for (int j = 0; j < 16; ++j)
         p[j] = Lds::has_corr ? fma(pmul, (double)q0d[4 * j * kM], (double)cr[4 * j * kM]) : pmul * (double)q0d[4 * j * kM];
 
-    // A round has a short dependent part (prediction -> slope -> step -> norm -> projection factor)
-    // and a wide independent one (its update of the pending predictions).  Only the prediction of
-    // the next round is updated at once; the rest of round t - 1's update shares a scheduling
-    // region with the dependent part of round t and fills its latencies.
+    // A round has a short dependent part (prediction -> slope -> step -> norm -> projection factor
+    // -> next prediction) and a wide independent one (its update of the pending predictions).  The
+    // dependent part runs in float32: the next prediction is taken from the float64 pending value
+    // by one float32 step, f (p - a G), as exact as a float32 inner product of that size; the
+    // squared norm is carried in float32 within the window like the register kernel carries it
+    // between its exact measurements (the caller re-anchors it every window).  The pending
+    // predictions themselves stay float64 (their recurrence is 64 rounds long); round t - 1's
+    // update of them shares a scheduling region with the dependent part of round t and fills its
+    // latencies.
     double gprev[16];                 // round t - 1's row of G (elements j >= (t - 1) / 4)
     double aprev = 0.0, fprev = 1.0;
+    float n2f = (float)n2;
+    float znext = (float)p[0];        // this lane's candidate for the next prediction (round 0: lane 0's is the one)
+    // label and ||x||^2 of a round are read from LDS one round ahead: they are the first things the
+    // dependent part needs, and nothing else would cover the latency of the read
+    float ynext = yb[0], x2next = (float)x2d[0];
     static_for<kB>([&](auto tc) __attribute__((always_inline)) {
         constexpr int t = decltype(tc)::value;
         constexpr int j0 = t >> 2;                                   // pending elements of this lane: j >= j0
@@ -292,37 +302,38 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
         double gr[16 - j0];
 #pragma unroll
         for (int j = j0; j < 16; ++j) gr[j - j0] = gd[t * 4 * kGStride + j];
-        const float yt = yb[t * kM];
-        const double x2t = x2d[t * 4 * kGStride];
+        const float yt = ynext, x2t = x2next;
+        if constexpr (t + 1 < kB) {
+            ynext = yb[(t + 1) * kM];
+            x2next = (float)x2d[(t + 1) * 4 * kGStride];
+        }
         if constexpr (t > 0) {
             constexpr int jp0 = (t - 1) >> 2;
 #pragma unroll
-            for (int j = jp0; j < 16; ++j)
-                if (j != j0) p[j] = fprev * fma(-aprev, gprev[j], p[j]);   // (element j0 was updated ahead)
+            for (int j = jp0; j < 16; ++j) p[j] = fprev * fma(-aprev, gprev[j], p[j]);
         }
-        const double zt = quad_bcast<(t & 3)>(p[j0]);               // <w_t, x_t>
-        const float z32 = (float)zt;
+        const float z32 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(znext), (t & 3) * 0x55, 0xF, 0xF, false));   // <w_t, x_t>
         // a_t = eta c_t; for the squared loss eta * 2 (z - y) = (2 eta) (z - y) exactly
         float a32 = LOSS == 1 ? eta2 * (z32 - yt) : eta * slope<LOSS>(z32, yt);
         a32 = t < wl ? a32 : 0.f;
-        const double at = (double)a32;
         // ||w_t - a_t x_t||^2 and the projection factor
-        double m2 = fma(at, fma(at, x2t, -2.0 * zt), n2);
-        m2 = m2 > 0.0 ? m2 : 0.0;
-        const bool pj = m2 > D2;
-        const double f = pj ? D * __builtin_amdgcn_rsq(m2) : 1.0;
-        n2 = pj ? D2 : m2;
+        const float m2 = fmaxf(fmaf(a32, fmaf(a32, x2t, -2.f * z32), n2f), 0.f);
+        const bool pj = m2 > D2f;
+        const float f32v = pj ? Df * __builtin_amdgcn_rsqf(m2) : 1.f;
+        n2f = pj ? D2f : m2;
         anyp = anyp || pj;
         zb[t * kM] = z32;                                            // (the quad's four lanes write the same value)
         stl[t * kM] = a32;
-        fl[t * kM] = (ST)f;
-        if constexpr (jn < 16) p[jn] = f * fma(-at, gr[jn - j0], p[jn]);
+        fl[t * kM] = (ST)f32v;
+        // (p[jn] has the updates of the rounds before this one: the loop above ran)
+        if constexpr (jn < 16) znext = f32v * fmaf(-a32, (float)gr[jn - j0], (float)p[jn]);
 #pragma unroll
         for (int j = j0; j < 16; ++j) gprev[j] = gr[j - j0];
-        aprev = at;
-        fprev = f;
+        aprev = (double)a32;
+        fprev = (double)f32v;
         __builtin_amdgcn_sched_barrier(0);                           // at most two rounds overlap: registers
     });
+    n2 = (double)n2f;
 
     // Bm[r] = a_r f_r f_{r+1} ... f_63 and F = fscale f_0 ... f_63: quad lane s takes the rounds
     // 16 s .. 16 s + 15 backwards, then the quad's products are combined
@@ -948,14 +959,18 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
         for (int i = 0; i < kQS * 4; ++i) v += (double)n2s[i * kM + lc];
         return v;
     };
-    constexpr int kGPer = kB * kB / NT;                          // Gram entries per working thread
-    constexpr int kYPer = kQT * kM * kB / NT;                    // labels per working thread
 #ifdef OCO_WIN_PROF
     unsigned long long prof_[8] = {0, 0, 0, 0, 0, 0, 0, 0}, last_ = wall_clock64();
 #endif
 
     // The loader's side of a sweep: rows for (3) from window wu of the piece, rows for (1) from window wq.
-    auto load_sweep = [&](int wu, int wq) __attribute__((always_inline)) {
+    struct Regs { f4 r[6]; };
+    Regs rg[kQSets];                                             // loaders: four steps of loads (the prefetch buffer)
+    // The loaders' side of a sweep: rows for (3) from window wu of the piece, rows for (1) from window wq.
+    // `first`: the loads of the first four steps are issued here; otherwise they were issued at the end of
+    // the sweep before (nwu >= 0: issue those of the next sweep, rows from windows nwu / nwq), so that
+    // they travel while the dependent rounds run.
+    auto load_sweep = [&](int wu, int wq, bool first, int nwu, int nwq) __attribute__((always_inline)) {
         // the learners whose blocks this lane loads, tile by tile
         const float *vr[2];
         bool vok[2];
@@ -968,14 +983,12 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
         // loader j: block kQS s + (j & 1) of step s; j < 2 its rows for (3) and the iterates of tiles 0, 1,
         // j >= 2 its rows for (1) and the iterates of tiles 2, 3
         const int L = (wave - kQW) & 1, part = (wave - kQW) >> 1;
-        struct Regs { f4 r[6]; };
-        Regs rg[kQSets];
-        auto fetch = [&](int step, Regs &o) __attribute__((always_inline)) {
+        auto fetch_of = [&](int fu, int fq, int step, Regs &o) __attribute__((always_inline)) {
             const int sc = step < nstep ? step : nstep - 1;
             int blk = sc * kQS + L;
             blk = blk < nblk ? blk : nblk - 1;                   // (rows past the last block: loaded again, not used)
-            const float *src = (part == 0 ? xu + ((int64_t)wu * nblk + blk) * kTileFloats
-                                          : xq + ((int64_t)wq * nblk + blk) * kTileFloats) + lane * 4;
+            const float *src = (part == 0 ? xu + ((int64_t)fu * nblk + blk) * kTileFloats
+                                          : xq + ((int64_t)fq * nblk + blk) * kTileFloats) + lane * 4;
 #pragma unroll
             for (int c = 0; c < 4; ++c) o.r[c] = *reinterpret_cast<const f4 *>(src + c * 256);
             const int vblk = step * kQS + L;
@@ -983,6 +996,7 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
 #pragma unroll
             for (int m = 0; m < 2; ++m) o.r[4 + m] = *reinterpret_cast<const f4 *>((bok && vok[m]) ? vr[m] + vblk * 16 : misc);
         };
+        auto fetch = [&](int step, Regs &o) __attribute__((always_inline)) { fetch_of(wu, wq, step, o); };
         auto put = [&](int stage, const Regs &o) __attribute__((always_inline)) {
             char *st = lds + Lds::ring + stage * Lds::stage_bytes + lane * 16;
 #pragma unroll
@@ -994,8 +1008,10 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
         // p + kQSets into the registers they came from (the registers are the prefetch buffer: four steps of
         // loads are on their way).  After barrier p the working wavefronts read stage p while they work step
         // p - 1; the stage was last read two phases earlier.
+        if (first) {
 #pragma unroll
-        for (int s0 = 0; s0 < kQSets; ++s0) fetch(s0, rg[s0]);
+            for (int s0 = 0; s0 < kQSets; ++s0) fetch(s0, rg[s0]);
+        }
         put(0, rg[0]);
         fetch(kQSets, rg[0]);
         lds_barrier();
@@ -1007,32 +1023,63 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
                 lds_barrier();
             });
         }
+        // (the blocks of iterates of the next sweep's first steps were stored at the start of this one: the
+        // working wavefronts have waited for those stores before the last barrier above)
+        if (nwu >= 0) {
+#pragma unroll
+            for (int s0 = 0; s0 < kQSets; ++s0) fetch_of(nwu, nwq, s0, rg[s0]);
+        }
         lds_barrier();
         lds_barrier();
         lds_barrier();
     };
 
-    // The working wavefronts' side.  F and -Bm of this lane's learner (bmr[rs]: round 4 rs + lk); do_q: take
-    // the shares of W X^T.  stage_next >= 0: first bring the labels and the Gram table of window stage_next
-    // to LDS; flush_prev >= 0: write the predictions of window flush_prev to Z.
-    auto sweep = [&](bool do_q, float F, const float (&bmr)[16], int stage_next, int flush_prev) __attribute__((always_inline)) {
-        // loads before stores: a wait for the loads then leaves the stores' acknowledgements out
-        f4 gv[kGPer / 4];
-        float yv[kYPer];
-        if (stage_next >= 0) {
-            const int w = w0 + stage_next;
-            const int ws = plan.start(w), wl = plan.len(w);
-            const float *gsrc = gram + (int64_t)stage_next * kB * kB + tid * kGPer;
+    // Labels and Gram table of the next window: the working wavefronts that do not run dependent rounds
+    // (kQT .. kQW - 1) load them into registers beside those rounds (whose LDS copies are still in use) and
+    // write them to LDS once the rounds are done.
+    constexpr int kNPre = (kQW - kQT) * kWave;                  // threads that stage
+    constexpr int kGPer = kB * kB / kNPre, kYPer = kQT * kM * kB / kNPre;
+    f4 gpre[kGPer / 4];
+    float ypre[kYPer];
+    auto load_next = [&](int wi) __attribute__((always_inline)) {
+        const int tp = tid - kQT * kWave;
+        const int w = w0 + wi;
+        const int ws = plan.start(w), wl = plan.len(w);
+        const float *gsrc = gram + (int64_t)wi * kB * kB + tp * kGPer;
 #pragma unroll
-            for (int i = 0; i < kGPer / 4; ++i) gv[i] = *reinterpret_cast<const f4 *>(gsrc + 4 * i);
+        for (int i = 0; i < kGPer / 4; ++i) gpre[i] = *reinterpret_cast<const f4 *>(gsrc + 4 * i);
 #pragma unroll
-            for (int i = 0; i < kYPer; ++i) {
-                const int e = tid + i * NT, l = e >> 6, t = e & 63;
-                const int q = q_base + l;
-                const bool ok = a.y && q < nq && t < wl;          // (no label: a zero word)
-                yv[i] = *(ok ? a.y + (int64_t)(q / K) * a.y_run_stride + ws + t : misc);
-            }
+        for (int i = 0; i < kYPer; ++i) {
+            const int e = tp + i * kNPre, l = e >> 6, t = e & 63;
+            const int q = q_base + l;
+            const bool ok = a.y && q < nq && t < wl;              // (no label: a zero word)
+            ypre[i] = *(ok ? a.y + (int64_t)(q / K) * a.y_run_stride + ws + t : misc);
         }
+    };
+    auto store_next = [&]() __attribute__((always_inline)) {
+        const int tp = tid - kQT * kWave;
+        double *gd = reinterpret_cast<double *>(lds + Lds::gd);
+        const int t = (tp * kGPer) >> 6, t2b = (tp * kGPer) & 63;
+#pragma unroll
+        for (int i = 0; i < kGPer; ++i) {
+            const int t2 = t2b + i;
+            const float v = gpre[i >> 2][i & 3];
+            gd[(t * 4 + (i & 3)) * kGStride + (t2 >> 2)] = t2 > t ? (double)v : 0.0;
+            if (t2 == t) gd[t * 4 * kGStride + 16] = (double)v;
+        }
+        float *yb = reinterpret_cast<float *>(lds + Lds::yb);
+#pragma unroll
+        for (int i = 0; i < kYPer; ++i) {
+            const int e = tp + i * kNPre, l = e >> 6, t = e & 63;
+            yb[((l >> 4) * kB + t) * kM + (l & 15)] = ypre[i];
+        }
+    };
+
+    // The working wavefronts' side.  F and -Bm of this lane's learner (bmr[rs]: round 4 rs + lk); do_q: take
+    // the shares of W X^T.  stage_next: first write the staged labels and Gram table to LDS; flush_prev >= 0:
+    // write the predictions of window flush_prev to Z.
+    auto sweep = [&](auto stager, bool do_q, float F, const float (&bmr)[16], bool stage_next, int flush_prev)
+        __attribute__((always_inline)) {
         if (flush_prev >= 0) {
             const int w = w0 + flush_prev;
             const int ws = plan.start(w), wl = plan.len(w);
@@ -1045,22 +1092,8 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
                         zb[((l >> 4) * kB + t) * kM + (l & 15)];
             }
         }
-        if (stage_next >= 0) {
-            double *gd = reinterpret_cast<double *>(lds + Lds::gd);
-            const int t = (tid * kGPer) >> 6, t2b = (tid * kGPer) & 63;
-#pragma unroll
-            for (int i = 0; i < kGPer; ++i) {
-                const int t2 = t2b + i;
-                const float v = gv[i >> 2][i & 3];
-                gd[(t * 4 + (i & 3)) * kGStride + (t2 >> 2)] = t2 > t ? (double)v : 0.0;
-                if (t2 == t) gd[t * 4 * kGStride + 16] = (double)v;
-            }
-            float *yb = reinterpret_cast<float *>(lds + Lds::yb);
-#pragma unroll
-            for (int i = 0; i < kYPer; ++i) {
-                const int e = tid + i * NT, l = e >> 6, t = e & 63;
-                yb[((l >> 4) * kB + t) * kM + (l & 15)] = yv[i];
-            }
+        if constexpr (decltype(stager)::value) {
+            if (stage_next) store_next();
         }
         f4 acc[4];
 #pragma unroll
@@ -1088,6 +1121,9 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
                 constexpr int u = decltype(uc)::value;
                 const int step = sb + u;
                 const int blk = step * kQS + sg;
+                // all but the seven youngest stores have been acknowledged: among them those of the first four
+                // steps (npad >= 12), which the loaders read again right after this barrier
+                if (step == npad - 1) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
                 lds_barrier();                                   // stage step + 1 complete, own reads of stage step done
                 read_stage((u + 1) % kQStages, in[(u + 1) & 1]);
                 __builtin_amdgcn_sched_barrier(0);
@@ -1145,38 +1181,56 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
         PROF_T(3);
     };
 
-    // ---- the stored iterates times the rows of the first window (a sweep whose step changes nothing) ----
-    if (loader) {
-        load_sweep(0, 0);
-    } else {
-        float zero[16];
+    // Three programs with the same sequence of barriers, one per kind of wavefront, so that what one kind
+    // keeps in registers across the window loop (the loaders' prefetch buffer, the staged inputs, the state of
+    // the dependent rounds) is not live in the code of the others.
+    // CHAIN: wavefronts 0 .. kQT - 1 run the dependent rounds of their tile; the other working wavefronts
+    // stage the next window's labels and Gram table meanwhile.
+    auto worker = [&](auto chain_tag) __attribute__((always_inline)) {
+        constexpr bool CHAIN = decltype(chain_tag)::value;
+        using Stager = std::integral_constant<bool, !CHAIN>;
+        {
+            // the stored iterates times the rows of the first window: a sweep whose step changes nothing
+            float zero[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) zero[i] = 0.f;
-        sweep(true, 1.f, zero, 0, -1);
-    }
-    for (int k = 0; k < nw; ++k) {
-        const bool more = k + 1 < nw;
-        if (wave < kQT) {
-            double n2 = k == 0 ? n2_state : measured_n2(wave, lane >> 2);
-            const double scale = k == 0 ? sigma0 : 1.0;
-            bool projected;
-            (void)chain_window<LOSS, Lds>(lds, 0, wave, lane, plan.len(w0 + k), eta, (double)a.D, scale, scale, n2, projected);
+            for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+            if constexpr (!CHAIN) load_next(0);
+            sweep(Stager{}, true, 1.f, zero, true, -1);
         }
-        PROF_T(0);
-        // the iterates the last sweep stored are read by the loader in the next one
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        lds_barrier();
-        PROF_T(4);
-        if (loader) {
-            load_sweep(k, more ? k + 1 : k);
-        } else {
+        for (int k = 0; k < nw; ++k) {
+            const bool more = k + 1 < nw;
+            if constexpr (CHAIN) {
+                double n2 = k == 0 ? n2_state : measured_n2(wave, lane >> 2);
+                const double scale = k == 0 ? sigma0 : 1.0;
+                bool projected;
+                (void)chain_window<LOSS, Lds>(lds, 0, wave, lane, plan.len(w0 + k), eta, (double)a.D, scale, scale, n2, projected);
+            } else {
+                if (more) load_next(k + 1);
+            }
+            PROF_T(0);
+            // the iterates the last sweep stored are read by the loaders in the next one
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            lds_barrier();
+            PROF_T(4);
             float bmr[16];
             const float *bml = reinterpret_cast<const float *>(lds + Lds::bm + tau * Lds::tile_f);
 #pragma unroll
             for (int rs = 0; rs < 16; ++rs) bmr[rs] = bml[(rs * 4 + lk) * kM + lr];
             const float F = reinterpret_cast<const float *>(lds + Lds::fv)[tau * kM + lr];
-            sweep(more, F, bmr, more ? k + 1 : -1, k);
+            sweep(Stager{}, more, F, bmr, more, k);
         }
+    };
+    if (loader) {
+        load_sweep(0, 0, true, 0, nw > 1 ? 1 : 0);
+        for (int k = 0; k < nw; ++k) {
+            const bool more = k + 1 < nw;
+            lds_barrier();
+            load_sweep(k, more ? k + 1 : k, false, more ? k + 1 : -1, k + 2 < nw ? k + 2 : k + 1);
+        }
+    } else if (wave < kQT) {
+        worker(std::true_type{});
+    } else {
+        worker(std::false_type{});
     }
 #ifdef OCO_WIN_PROF
     if (threadIdx.x == 0 && blockIdx.x == 0)
