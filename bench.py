@@ -54,7 +54,7 @@ def algorithmic_hbm_bytes(wl, kernel, launches):
         return float(wl.R * wl.K * wl.T * wl.nnz * 8 + wl.T * wl.nnz * 8 + wl.R * wl.T * 4 + wl.R * wl.T * wl.nnz * 4)
     x = 4.0 * wl.T * wl.d * (1 if wl.x_shared else wl.R)
     b = x + 4.0 * wl.R * wl.T + 4.0 * wl.R * (wl.K + 1) * wl.T + 8.0 * wl.R * wl.K * wl.d * max(launches, 1)
-    if kernel == "dense_window_kernel":
+    if kernel.startswith("dense_window"):
         b += 8.0 * wl.R * wl.K * wl.d * ((wl.T + 63) // 64) + 4.0 * x
     return b
 
@@ -80,12 +80,12 @@ def roofline_block(wl, kt, config_key):
         rl.update(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS)
     else:
         per_unit = 5.0 + 2.0 / wl.K
-        executed = 4.0 if kernel == "dense_window_kernel" else 4.0 + 2.0 / wl.K
+        executed = 4.0 if kernel.startswith("dense_window") else 4.0 + 2.0 / wl.K
         ach = per_unit * wl.units / launches / (avg_ms * 1e-3) / 1e12
-        rl.update(bound="mfma" if kernel == "dense_window_kernel" else "alu", achieved=ach, peak=PEAK_FP32_TFLOPS,
+        rl.update(bound="mfma" if kernel.startswith("dense_window") else "alu", achieved=ach, peak=PEAK_FP32_TFLOPS,
                   unit="TFLOP/s", frac=ach / PEAK_FP32_TFLOPS, flops_per_unit=per_unit,
                   executed_flops_per_unit=executed, executed_flops_frac=ach * executed / per_unit / PEAK_FP32_TFLOPS)
-        if kernel != "dense_window_kernel":
+        if not kernel.startswith("dense_window"):
             rl["non_packed_ceiling"] = {"peak": NONPACKED_FP32_TFLOPS, "unit": "TFLOP/s",
                                         "executed_flops_frac": ach * executed / per_unit / NONPACKED_FP32_TFLOPS,
                                         "note": "vector fp32 with packed instructions off, as this build is compiled"}
@@ -115,7 +115,7 @@ def binding_block(wl, res, config_key, floor=None):
     elif wl.nnz:
         b.update(profile_json("binding_resource.json").get(config_key) or {})
         b["us_per_round"] = us_round
-    elif kernel == "dense_window_kernel":
+    elif kernel.startswith("dense_window"):
         kt = res["kernel_timing"]
         step_ms = kt["ms_sum"] / max(kt["timed"], 1) * max(kt["launches"], 1)      # all launches of a step
         floor_ms = 4.0 * wl.units / (PEAK_FP32_TFLOPS * 1e12) * 1e3

@@ -1367,7 +1367,7 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
         const int nw = std::min<int>((int)sc.piece_windows, nwin - w0);
         hipLaunchKernelGGL(dense_tile_kernel, dim3((unsigned)nblk, (unsigned)nw), dim3(64), 0, s, a.x, a.d, plan, w0, xq, xu, misc);
         hipLaunchKernelGGL(dense_gram_kernel, dim3((unsigned)nw), dim3(512), 0, s, xq, nblk, gram, gxt);
-        e = clock_begin(a.clock, s, "dense_window_kernel");
+        e = clock_begin(a.clock, s, mode == 3 ? "dense_window_shared_kernel" : "dense_window_kernel");
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3((unsigned)ntiles), dim3(waves * kWave), lds_bytes, s, a, gram, gxt, xq, xu, misc, plan, w0, nw);
         e = hipGetLastError();
