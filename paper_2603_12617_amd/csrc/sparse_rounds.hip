@@ -522,7 +522,6 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
     const unsigned zoff4 = 4u * (unsigned)(r * a.zl.zs_r + i * a.zl.zs_i);    // byte offset inside a round's slice of Z
     const int64_t zstep = 4 * a.zl.zs_t;
-    const double D2 = a.D * a.D;
     const WinRec *recs = static_cast<const WinRec *>(a.scratch);
     // the lanes that run the dependent rounds (padding learners of the last workgroup take no part:
     // their step sizes stay zero and their scale stays one)
@@ -539,7 +538,6 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     float eta_r = eta;
     asm volatile("" : "+v"(eta_r), "+v"(sigma), "+v"(n2));
     const float eta2_r = 2.f * eta_r;
-    double sd2 = sigma * sigma;
     float sf = (float)sigma, isf = __builtin_amdgcn_rcpf(sf);
     // optimistic update (Eq. (3)): hint ha * x_{t-1}, hp = <w^_t, x_{t-1}>, x2p = ||x_{t-1}||^2
     float ha = 0.f, hp = 0.f, x2p = 0.f;
@@ -684,7 +682,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             float z = sf * qv;
             if (OPT) {
                 // played iterate w_t = s (w^_t - ha x_{t-1}), s from ||w^_t - ha x_{t-1}||^2: scalars only
-                const float mf = fmaf(ha * ha, x2p, fmaf(-2.f * ha, hp, (float)(sd2 * n2)));
+                const float mf = fmaf(ha * ha, x2p, fmaf(-2.f * ha, hp, (float)((sigma * sigma) * n2)));
                 const float sp = mf > D2f ? Df * __builtin_amdgcn_rsqf(mf) : 1.f;
                 z = sp * fmaf(-ha, g01[t], z);
             }
@@ -710,11 +708,10 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             const double bd = (double)b;
             n2 = fma(bd, fma(bd, rc.x2, (double)(-2.f * qv)), n2);
             n2 = n2 > 0.0 ? n2 : 0.0;
-            // projection: sigma = D / ||v||.  One select, then the values that follow from sigma
-            // (the chain is bound by the number of instructions a single wavefront can issue)
-            const double snew = a.D * rsqrt_pos(n2);
-            sigma = n2 * sd2 > D2 ? snew : sigma;
-            sd2 = sigma * sigma;
+            // projection: ||w|| = sigma ||v|| > D exactly when D / ||v|| < sigma, so sigma = min(sigma, D / ||v||):
+            // one instruction, no product or comparison of squares (the chain is bound by the number
+            // of instructions a single wavefront can issue)
+            sigma = fmin(sigma, a.D * rsqrt_pos(n2));
             sf = (float)sigma;
             isf = __builtin_amdgcn_rcpf(sf);
             if (OPT) {                                      // next round's hint and <w^_{t+1}, x_t>
@@ -849,7 +846,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             double m2 = 0.0;
             for (int wv = 0; wv < kSpWaves; ++wv) m2 += fold_part[wv][l];
             n2 = m2;
-            sigma = 1.0; sd2 = 1.0; sf = 1.f; isf = 1.f;
+            sigma = 1.0; sf = 1.f; isf = 1.f;
         }
         if (threadIdx.x == 0) fold_t = -1;
         gather_q0(std::integral_constant<int, 1>(), std::integral_constant<int, 2>(), v, wave, kSpWaves, q0, yv);   // rare: few registers
