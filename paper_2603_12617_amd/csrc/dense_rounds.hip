@@ -997,6 +997,28 @@ hipError_t launch_piece(const DensePlan &p, const DenseArgs &a, hipStream_t s)
 
 bool dense_supported(int64_t d, int x_shared) { return d >= 1 && d <= (x_shared ? OCO_MAX_DENSE_D : 64 * kWave); }
 
+// The scalars of the round rows that the hint terms of the optimistic update need, for the rounds of a.n
+// (all runs): ||x_t||^2 into a.x2 and <x_{t-1}, x_t> into a.g01 (x_{-1}: the row kept from the call before).
+hipError_t launch_hint_scalars(const DenseArgs &a, hipStream_t s)
+{
+    const int nruns = a.x_shared ? 1 : a.R;
+    const int64_t xstride = a.x_shared ? 0 : a.x_run_stride;
+    const int64_t rows = (int64_t)nruns * a.n;
+    hipLaunchKernelGGL(xnorm2_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a.x, xstride, nruns,
+                       a.n, a.d, a.x2, a.x2_run_stride, a.g01, a.xlast);
+    return hipGetLastError();
+}
+
+// ... and the last row of the call with its squared norm, kept for the next call (a.x2 filled as above)
+hipError_t launch_keep_last_row(const DenseArgs &a, hipStream_t s)
+{
+    const int nruns = a.x_shared ? 1 : a.R;
+    const int64_t xstride = a.x_shared ? 0 : a.x_run_stride;
+    hipLaunchKernelGGL(keep_last_row_kernel, dim3((unsigned)((a.d + 255) / 256), (unsigned)nruns), dim3(256), 0, s,
+                       a.x, xstride, a.n, a.d, a.x2, a.x2_run_stride, a.xlast, a.x2last);
+    return hipGetLastError();
+}
+
 // One piece of a call: the squared norms of its rows, its round kernel, and the row kept for the
 // next piece's hint terms.
 static hipError_t launch_dense_piece(const DensePlan &plan, const DenseArgs &a, hipStream_t s)

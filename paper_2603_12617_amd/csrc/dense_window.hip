@@ -219,7 +219,9 @@ template <int NW, int MT> struct LdsT {
     static constexpr int st = part + NW * tile_f;                  // float [MT][64][16]: a_t
     static constexpr int corr = st + MT * tile_f;                  // float [MT][64][16]: -Bm (X_{k-1} X_k^T)
     static constexpr int n2 = corr + MT * tile_f;                  // float [MT][NW][4][16]: shares of ||w||^2
-    static constexpr int total = n2 + MT * NW * 4 * kM * 4;
+    static constexpr int hg = n2 + MT * NW * 4 * kM * 4;           // float [2][64]: <x_{t-1}, x_t> of the window's rounds (optimistic update)
+    static constexpr int hg_bytes = kB * 4;
+    static constexpr int total = hg + 2 * hg_bytes;
 };
 static_assert(LdsT<kNW8, 1>::total <= 160 * 1024 && LdsT<kNW16, 1>::total <= 160 * 1024 && LdsT<kNW8, 2>::total <= 160 * 1024,
               "LDS of a gfx950 compute unit");
@@ -254,9 +256,13 @@ template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
 // Straight-line code: a window shorter than 64 rounds (first / last window of a call) runs its
 // missing rounds as rounds without a step (a = 0, so f = 1 and no pending prediction moves; their
 // rows of G are zero).
-template <int LOSS, class Lds>
+// The scalars the optimistic update (Eq. (3)) carries from round to round: the hint is ha x_{t-1},
+// hp = <w^_t, x_{t-1}>, x2p = ||x_{t-1}||^2 (the vector the sweeps move is then the intermediate model w^).
+struct Hint { float ha, hp, x2p; };
+
+template <int LOSS, class Lds, bool OPT = false>
 __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int lane, int wl, float eta, double D, double pmul,
-                                               double fscale, double &n2, bool &projected)
+                                               double fscale, double &n2, bool &projected, Hint *hint = nullptr)
 {
     using GT = typename Lds::G;
     using ST = typename Lds::S;
@@ -294,6 +300,10 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
     // label and ||x||^2 of a round are read from LDS one round ahead: they are the first things the
     // dependent part needs, and nothing else would cover the latency of the read
     float ynext = yb[0], x2next = (float)x2d[0];
+    const float *hg = reinterpret_cast<const float *>(lds + Lds::hg + buf * Lds::hg_bytes);
+    float gnext = OPT ? hg[0] : 0.f;
+    float ha = 0.f, hp = 0.f, x2p = 0.f;
+    if (OPT) { ha = hint->ha; hp = hint->hp; x2p = hint->x2p; }
     static_for<kB>([&](auto tc) __attribute__((always_inline)) {
         constexpr int t = decltype(tc)::value;
         constexpr int j0 = t >> 2;                                   // pending elements of this lane: j >= j0
@@ -302,10 +312,11 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
         double gr[16 - j0];
 #pragma unroll
         for (int j = j0; j < 16; ++j) gr[j - j0] = gd[t * 4 * kGStride + j];
-        const float yt = ynext, x2t = x2next;
+        const float yt = ynext, x2t = x2next, g01t = gnext;
         if constexpr (t + 1 < kB) {
             ynext = yb[(t + 1) * kM];
             x2next = (float)x2d[(t + 1) * 4 * kGStride];
+            if (OPT) gnext = hg[t + 1];
         }
         if constexpr (t > 0) {
             constexpr int jp0 = (t - 1) >> 2;
@@ -313,8 +324,16 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
             for (int j = jp0; j < 16; ++j) p[j] = fprev * fma(-aprev, gprev[j], p[j]);
         }
         const float z32 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(znext), (t & 3) * 0x55, 0xF, 0xF, false));   // <w_t, x_t>
+        // the prediction that is played and scored: plain, z32; optimistic, that of w_t = s (w^_t - ha x_{t-1})
+        // with s from ||w^_t - ha x_{t-1}||^2, all from scalars (z32 is then <w^_t, x_t>)
+        float zp = z32;
+        if (OPT) {
+            const float mf = fmaf(ha * ha, x2p, fmaf(-2.f * ha, hp, n2f));
+            const float sp = mf > D2f ? Df * __builtin_amdgcn_rsqf(mf) : 1.f;
+            zp = sp * fmaf(-ha, g01t, z32);
+        }
         // a_t = eta c_t; for the squared loss eta * 2 (z - y) = (2 eta) (z - y) exactly
-        float a32 = LOSS == 1 ? eta2 * (z32 - yt) : eta * slope<LOSS>(z32, yt);
+        float a32 = LOSS == 1 ? eta2 * (zp - yt) : eta * slope<LOSS>(zp, yt);
         a32 = t < wl ? a32 : 0.f;
         // ||w_t - a_t x_t||^2 and the projection factor
         const float m2 = fmaxf(fmaf(a32, fmaf(a32, x2t, -2.f * z32), n2f), 0.f);
@@ -322,9 +341,15 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
         const float f32v = pj ? Df * __builtin_amdgcn_rsqf(m2) : 1.f;
         n2f = pj ? D2f : m2;
         anyp = anyp || pj;
-        zb[t * kM] = z32;                                            // (the quad's four lanes write the same value)
+        zb[t * kM] = zp;                                             // (the quad's four lanes write the same value)
         stl[t * kM] = a32;
         fl[t * kM] = (ST)f32v;
+        if (OPT) {                                                   // next round's hint and <w^_{t+1}, x_t>
+            const bool live = t < wl;                                // (selects, not a branch: the rounds stay straight-line code)
+            hp = live ? f32v * fmaf(-a32, x2t, z32) : hp;
+            ha = live ? a32 : ha;
+            x2p = live ? x2t : x2p;
+        }
         // (p[jn] has the updates of the rounds before this one: the loop above ran)
         if constexpr (jn < 16) znext = f32v * fmaf(-a32, (float)gr[jn - j0], (float)p[jn]);
 #pragma unroll
@@ -334,6 +359,7 @@ __device__ __forceinline__ double chain_window(char *lds, int buf, int m, int la
         __builtin_amdgcn_sched_barrier(0);                           // at most two rounds overlap: registers
     });
     n2 = (double)n2f;
+    if (OPT) { hint->ha = ha; hint->hp = hp; hint->x2p = x2p; }
 
     // Bm[r] = a_r f_r f_{r+1} ... f_63 and F = fscale f_0 ... f_63: quad lane s takes the rounds
     // 16 s .. 16 s + 15 backwards, then the quad's products are combined
@@ -397,7 +423,7 @@ template <int MT> __device__ __forceinline__ Geo<MT> make_geo(int tid, const Den
 //   the others     predictions of window k - 1 to Z, staging for window k + 1, the sweep
 //   sweep (k >= 1) W_k = F_{k-1} W_{k-1} - Bm_{k-1} X_{k-1} block by block, its squared norm, and the
 //                  shares of W_k X_{k+1}^T (k + 1 < nw)
-template <int LOSS, int NB, bool RES, int NW, int MT>
+template <int LOSS, int NB, bool RES, int NW, int MT, bool OPT = false>
 __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs a, const float *gram, const float *gxt,
                                                                   const float *xq, const float *xu, float *misc,
                                                                   WinPlanD plan, int w0, int nw)
@@ -495,6 +521,10 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
             if (a.y && q < nq && t < wl) yv = a.y[(int64_t)(q / K) * a.y_run_stride + ws + t];
             yb[((l >> 4) * kB + t) * kM + (l & 15)] = yv;
         }
+        if (OPT) {
+            float *hg = reinterpret_cast<float *>(lds + Lds::hg + buf * Lds::hg_bytes);
+            for (int t = tid; t < kB; t += nthr) hg[t] = t < wl ? a.g01[ws + t] : 0.f;
+        }
     };
     // shares of this wavefront of one tile's W X^T for one window -> LDS
     auto put_part = [&](const Geo<MT> &g, const f4 (&acc)[4]) __attribute__((always_inline)) {
@@ -532,6 +562,7 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
     double n2 = 0.0;            // ||w_k||^2 as the scalar identity carries it
     double n2_begin = 0.0;      // what the previous window's rounds started from
     bool proj_prev = true;      // whether they projected this learner (then n2 was reset to D^2 on the way)
+    Hint hint{0.f, 0.f, 0.f};   // optimistic update: carried from round to round, window to window, call to call
     f4 V[RES ? NB : 1];
     f4 accq[MT][4];             // this wavefront's shares of W_k X_{k+1}^T; tile 0's go to LDS at once, the others wait their turn
     {
@@ -541,6 +572,12 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
             eta = a.eta[q_ch % K];
             pmul = (double)a.sigma[q_ch];
             n2 = a.n2[q_ch] * pmul * pmul;                      // ||w||^2 of the iterate itself
+            if (OPT) {
+                const int ws0 = plan.start(w0);
+                hint.ha = a.ha[q_ch];
+                hint.hp = a.hp[q_ch];
+                hint.x2p = ws0 == 0 ? a.x2last[0] : a.x2[ws0 - 1];
+            }
         }
         if (RES) {
 #pragma unroll
@@ -673,8 +710,8 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
                 }
                 n2_begin = n2;
                 const double fscale = k == 0 ? pmul : 1.0;
-                pmul = chain_window<LOSS, Lds>(lds, k & 1, wave_w, lane, plan.len(w0 + k), eta, (double)a.D, pmul, fscale,
-                                                  n2, proj_prev);
+                pmul = chain_window<LOSS, Lds, OPT>(lds, k & 1, wave_w, lane, plan.len(w0 + k), eta, (double)a.D, pmul, fscale,
+                                                       n2, proj_prev, &hint);
             }
         } else {
             const int tid_o = tid_w - MT * kWave, nthr_o = (NW - MT) * kWave;
@@ -854,6 +891,7 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
         if (g.wave < MT && (g.lane & 3) == 0 && q_ch < nq) {
             a.sigma[q_ch] = 1.f;
             a.n2[q_ch] = measured_n2(g.wave, g.lane >> 2);
+            if (OPT) { a.ha[q_ch] = hint.ha; a.hp[q_ch] = hint.hp; }
         }
     }
 }
@@ -902,7 +940,9 @@ struct LdsQ {
     static constexpr int bm = zb + zb_bytes;
     static constexpr int fv = bm + bm_bytes;
     static constexpr int n2 = fv + fv_bytes;                       // float [kQT][kQS * 4][16]: shares of ||w||^2
-    static constexpr int ring = n2 + kQT * kQS * 4 * kM * 4;
+    static constexpr int hg = n2 + kQT * kQS * 4 * kM * 4;         // float [64]: <x_{t-1}, x_t> of the window's rounds (optimistic update)
+    static constexpr int hg_bytes = kB * 4;
+    static constexpr int ring = hg + hg_bytes;
     // between two sweeps the ring's space holds the shares of W X^T, [kQS][kQT][64][16] (share 0
     // becomes the sum), and the a_t and f_t of the dependent rounds
     static constexpr int q0 = ring;
@@ -916,7 +956,7 @@ static_assert(LdsQ::fl + kQT * LdsQ::tile_s <= LdsQ::total && LdsQ::total <= 160
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int LOSS>
+template <int LOSS, bool OPT = false>
 __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kernel(const DenseArgs a, const float *gram, const float *gxt,
                                                                                const float *xq, const float *xu, float *misc,
                                                                                WinPlanD plan, int w0, int nw)
@@ -944,12 +984,19 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
     // dependent rounds: wavefront m < kQT, lane = 4 learner + quad lane
     float eta = 0.f;
     double sigma0 = 1.0, n2_state = 0.0;
+    Hint hint{0.f, 0.f, 0.f};   // optimistic update: carried from round to round, window to window, call to call
     {
         const int q_ch = q_base + wave * kM + (lane >> 2);
         if (wave < kQT && q_ch < nq) {
             eta = a.eta[q_ch % K];
             sigma0 = (double)a.sigma[q_ch];
             n2_state = a.n2[q_ch] * sigma0 * sigma0;
+            if (OPT) {
+                const int ws0 = plan.start(w0);
+                hint.ha = a.ha[q_ch];
+                hint.hp = a.hp[q_ch];
+                hint.x2p = ws0 == 0 ? a.x2last[0] : a.x2[ws0 - 1];
+            }
         }
     }
     auto measured_n2 = [&](int m, int lc) __attribute__((always_inline)) {
@@ -1041,6 +1088,7 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
     constexpr int kGPer = kB * kB / kNPre, kYPer = kQT * kM * kB / kNPre;
     f4 gpre[kGPer / 4];
     float ypre[kYPer];
+    float hgpre = 0.f;                                           // (optimistic update: <x_{t-1}, x_t> of one round)
     auto load_next = [&](int wi) __attribute__((always_inline)) {
         const int tp = tid - kQT * kWave;
         const int w = w0 + wi;
@@ -1055,6 +1103,7 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
             const bool ok = a.y && q < nq && t < wl;              // (no label: a zero word)
             ypre[i] = *(ok ? a.y + (int64_t)(q / K) * a.y_run_stride + ws + t : misc);
         }
+        if (OPT) hgpre = *((tp < kB && tp < wl) ? a.g01 + ws + tp : misc);
     };
     auto store_next = [&]() __attribute__((always_inline)) {
         const int tp = tid - kQT * kWave;
@@ -1073,6 +1122,7 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
             const int e = tp + i * kNPre, l = e >> 6, t = e & 63;
             yb[((l >> 4) * kB + t) * kM + (l & 15)] = ypre[i];
         }
+        if (OPT && tp < kB) reinterpret_cast<float *>(lds + Lds::hg)[tp] = hgpre;
     };
 
     // The working wavefronts' side.  F and -Bm of this lane's learner (bmr[rs]: round 4 rs + lk); do_q: take
@@ -1203,7 +1253,8 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
                 double n2 = k == 0 ? n2_state : measured_n2(wave, lane >> 2);
                 const double scale = k == 0 ? sigma0 : 1.0;
                 bool projected;
-                (void)chain_window<LOSS, Lds>(lds, 0, wave, lane, plan.len(w0 + k), eta, (double)a.D, scale, scale, n2, projected);
+                (void)chain_window<LOSS, Lds, OPT>(lds, 0, wave, lane, plan.len(w0 + k), eta, (double)a.D, scale, scale, n2, projected,
+                                                   &hint);
             } else {
                 if (more) load_next(k + 1);
             }
@@ -1242,6 +1293,7 @@ __global__ void __launch_bounds__((kQW + kQL) * kWave) dense_window_shared_kerne
         if (wave < kQT && (lane & 3) == 0 && q_ch < nq) {
             a.sigma[q_ch] = 1.f;
             a.n2[q_ch] = measured_n2(wave, lane >> 2);
+            if (OPT) { a.ha[q_ch] = hint.ha; a.hp[q_ch] = hint.hp; }
         }
     }
 }
@@ -1251,8 +1303,17 @@ using WindowKernel = void (*)(const DenseArgs, const float *, const float *, con
 
 // mode 0: iterates in registers (8 wavefronts, one tile); 1: streamed, two tiles per workgroup
 // (8 wavefronts); 2: streamed, one tile, 16 wavefronts
-template <int LOSS> WindowKernel pick_window_kernel(int nblk, int mode, int *waves, int *tiles, int *lds_bytes)
+// (opt: the optimistic update, built into the two kernels the launcher picks by itself)
+template <int LOSS> WindowKernel pick_window_kernel(int nblk, int mode, bool opt, int *waves, int *tiles, int *lds_bytes)
 {
+    if (opt) {
+        if (mode == 3) {
+            *waves = kQW + kQL; *tiles = kQT; *lds_bytes = LdsQ::total;
+            return dense_window_shared_kernel<LOSS, true>;
+        }
+        *waves = kNW8; *tiles = 2; *lds_bytes = LdsT<kNW8, 2>::total;
+        return dense_window_kernel<LOSS, 1, false, kNW8, 2, true>;
+    }
     if (mode == 0) {
         *waves = kNW8; *tiles = 1; *lds_bytes = LdsT<kNW8, 1>::total;
         if (nblk <= 8 * kNW8) return dense_window_kernel<LOSS, 8, true, kNW8, 1>;
@@ -1300,8 +1361,8 @@ size_t dense_gram_bytes(int64_t n_max, int64_t d) { return scratch_layout(n_max,
 
 bool dense_window_supported(const DenseArgs &a)
 {
-    // a shared stream whose rows can be read 16 bytes at a time; the optimistic update is not built here
-    return a.x_shared && !a.optimistic && a.vec_ok && a.gram != nullptr;
+    // a shared stream whose rows can be read 16 bytes at a time
+    return a.x_shared && a.vec_ok && a.gram != nullptr;
 }
 
 bool dense_window_wanted(const DenseArgs &a)
@@ -1335,6 +1396,11 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
         hipError_t e = launch_comparator_gemm(g, s);
         if (e != hipSuccess) return e;
     }
+    if (a.optimistic) {
+        // ||x_t||^2 and <x_{t-1}, x_t> of the call's rounds (the first against the row kept from the call before)
+        hipError_t e = launch_hint_scalars(a, s);
+        if (e != hipSuccess) return e;
+    }
     // where the iterates live: OCO_OPT_WINDOW_RESIDENT 1 registers (d <= 4096), 0 streamed (two tiles per
     // workgroup), 2 streamed (one tile, sixteen wavefronts), 3 streamed with loading wavefronts (four tiles).
     // Unset: streamed, two tiles -- on c4 as fast as the registers (every round row a wavefront loads
@@ -1344,7 +1410,8 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
     const int64_t ropt = a.tune->get(OCO_OPT_WINDOW_RESIDENT);
     const bool fits = a.d <= 16 * kNW8 * 32;
     const bool many = (int64_t)a.R * a.K >= 1024 * kM && nblk >= 128;
-    const int mode = (ropt == 1 && fits) ? 0 : ropt == 2 ? 2 : (ropt == 3 || (ropt < 0 && many)) ? 3 : 1;
+    int mode = (ropt == 1 && fits) ? 0 : ropt == 2 ? 2 : (ropt == 3 || (ropt < 0 && many)) ? 3 : 1;
+    if (a.optimistic && mode != 3) mode = 1;                 // (the optimistic update: two of the kernels only)
     const bool resident = mode == 0;
     if (a.tune->get(OCO_OPT_VERBOSE) == 1)
         fprintf(stderr, "dense plan: windowed contraction kernel, %d windows in pieces of %lld, %d tiles, iterates %s\n",
@@ -1354,9 +1421,9 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
     WindowKernel kern = nullptr;
     int waves = 0, tiles = 1, lds_bytes = 0;
     switch (loss) {
-        case 0: kern = pick_window_kernel<0>(nblk, mode, &waves, &tiles, &lds_bytes); break;
-        case 1: kern = pick_window_kernel<1>(nblk, mode, &waves, &tiles, &lds_bytes); break;
-        case 2: kern = pick_window_kernel<2>(nblk, mode, &waves, &tiles, &lds_bytes); break;
+        case 0: kern = pick_window_kernel<0>(nblk, mode, a.optimistic != 0, &waves, &tiles, &lds_bytes); break;
+        case 1: kern = pick_window_kernel<1>(nblk, mode, a.optimistic != 0, &waves, &tiles, &lds_bytes); break;
+        case 2: kern = pick_window_kernel<2>(nblk, mode, a.optimistic != 0, &waves, &tiles, &lds_bytes); break;
         default: return hipErrorInvalidValue;
     }
     const int ntiles = (a.R * a.K + kM * tiles - 1) / (kM * tiles);   // workgroups
@@ -1374,7 +1441,7 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
         if (e == hipSuccess) e = clock_end(a.clock, s);
         if (e != hipSuccess) return e;
     }
-    return hipSuccess;
+    return a.optimistic ? launch_keep_last_row(a, s) : hipSuccess;
 }
 
 }  // namespace oco

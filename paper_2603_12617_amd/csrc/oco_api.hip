@@ -51,7 +51,7 @@ int validate_and_layout(const oco_config *c, Layout *lay)
         if (!c->x_shared) return OCO_EUNSUPPORTED;
     } else if (!dense_supported(c->d, c->x_shared)) {
         return OCO_EUNSUPPORTED;
-    } else if (c->d > 4096 && (c->d % 4 != 0 || c->optimistic)) {
+    } else if (c->d > 4096 && c->d % 4 != 0) {
         return OCO_EUNSUPPORTED;      // beyond one wavefront's registers only the windowed kernel runs
     }
     Layout l;
@@ -292,7 +292,7 @@ int oco_set_option(oco_state *st, int key, int64_t value)
         case OCO_OPT_WINDOW_RESIDENT: ok = value <= 3; break;
         case OCO_OPT_DENSE_PATH:
             ok = value == -1 || value == 1 || value == 2;
-            if (value == 2 && (st->cfg.sparse_nnz > 0 || !st->cfg.x_shared || st->cfg.optimistic || st->cfg.d % 4 != 0))
+            if (value == 2 && (st->cfg.sparse_nnz > 0 || !st->cfg.x_shared || st->cfg.d % 4 != 0))
                 return OCO_EUNSUPPORTED;
             if (value == 1 && st->cfg.sparse_nnz == 0 && st->cfg.d > 4096) return OCO_EUNSUPPORTED;
             break;

@@ -114,6 +114,8 @@ hipError_t launch_dense_rounds(const DenseArgs &a, int loss, hipStream_t s, cons
 // the windowed path (dense_window.hip): whether a configuration takes it, and its launcher
 bool dense_window_wanted(const DenseArgs &a);
 hipError_t launch_dense_window(const DenseArgs &a, int loss, hipStream_t s, const PieceHook *hook);
+hipError_t launch_hint_scalars(const DenseArgs &a, hipStream_t s);
+hipError_t launch_keep_last_row(const DenseArgs &a, hipStream_t s);
 size_t dense_gram_bytes(int64_t n_max, int64_t d);
 
 // comparator predictions of a shared dense stream as one contraction (rows K of Z)

@@ -60,7 +60,7 @@ def test_workspace_bytes_is_zero_for_bad_configs():
     for bad in (dict(d=0), dict(K=0), dict(T=0), dict(R=0), dict(D=0.0), dict(D=float("nan")),
                 dict(D=float("inf")), dict(G=-1.0), dict(eps=-0.1), dict(eps=float("nan")),
                 dict(loss=7), dict(eta=[0.1, -0.2, 0.3]), dict(eta=[0.1, float("inf"), 0.3]),
-                dict(n_max=-1), dict(d=4097), dict(d=4100, x_shared=False), dict(d=8192, optimistic=True),
+                dict(n_max=-1), dict(d=4097), dict(d=4100, x_shared=False), dict(d=8192, x_shared=False, optimistic=True),
                 dict(d=65540), dict(K=65, eta=[0.1] * 65),
                 dict(nnz=65, d=1 << 20), dict(nnz=8, d=4), dict(nnz=8, d=1 << 20, x_shared=False)):
         cfg, keep = _cfg(**bad)
@@ -75,7 +75,7 @@ def test_workspace_bytes_is_zero_for_bad_configs():
     cfg.optimistic = 2
     assert B.oco_workspace_bytes(cfg) > one_level > 0
     # a shared stream may be wider than one wavefront's registers (iterates streamed from HBM)
-    for good in (dict(d=4096, x_shared=False), dict(d=8192), dict(d=65536)):
+    for good in (dict(d=4096, x_shared=False), dict(d=8192), dict(d=65536), dict(d=8192, optimistic=True)):
         cfg, keep = _cfg(**good)
         assert B.oco_workspace_bytes(cfg) > 0, good
     cfg, keep = _cfg(d=1 << 20, nnz=8)

@@ -583,6 +583,7 @@ FULL = [
     ("c5", [8], 1000, 2, None),
     # c3 and c4 on each of the dense kernels by name (the default picks one of them), and c4 with
     # its iterates streamed from HBM every window
+    ("c3", [77], None, True, dict(dense_path=1)),        # (the optimistic update on the register kernel by name)
     ("c3", [5, 250], None, False, dict(dense_path=1)),
     ("c3", [5, 250], None, False, dict(dense_path=2)),
     ("c4", [7, 1000], None, False, dict(dense_path=1)),

@@ -43,6 +43,48 @@ def test_windowed_rounds_match_the_oracle(name, over, resident):
     _check(wl, data, got, label="windowed %s %s resident=%d" % (name, over, resident))
 
 
+# the optimistic two-step update (Eq. (3)) in the two windowed kernels that have it (two tiles per
+# workgroup; loading wavefronts), base level only and both levels
+@pytest.mark.parametrize("name,over", [
+    ("c1", dict(T=257, d=64, R=3)),
+    ("c3", dict(T=500, R=3, d=100, K=15, seg_len=100)),
+    ("c3", dict(T=1000, R=3, d=132, K=17, seg_len=100)),
+    ("c3", dict(T=300, R=2, d=2048, K=9, seg_len=64)),
+    ("c4", dict(T=301, R=3, d=4096, K=16)),
+    ("c4", dict(T=150, R=2, d=3000, K=2, eta=(0.5, 20.0))),
+    ("c4", dict(T=130, R=3, d=8192, K=6)),
+])
+@pytest.mark.parametrize("resident", [0, 3])
+@pytest.mark.parametrize("optimistic", [1, 2])
+def test_windowed_optimistic_rounds_match_the_oracle(name, over, resident, optimistic):
+    wl = WL.make(name, optimistic=optimistic, **over)
+    data = WL.generate(wl)
+    print("case windowed optimistic", optimistic, name, over, "resident", resident, flush=True)
+    got = _gpu(wl, data, options=dict(WIN, window_resident=resident))
+    _check(wl, data, got, label="windowed optimistic %s %s resident=%d" % (name, over, resident))
+
+
+@pytest.mark.parametrize("resident", [0, 3])
+def test_windowed_optimistic_results_and_how_the_horizon_is_cut(resident):
+    """The hint of a call's first round needs the last row of the call before and the learners'
+    hint scalars: both are kept in the state.  Different cuts regroup float32 sums (as without
+    the optimistic update); the same cuts give the same bits."""
+    wl = WL.make("c3", optimistic=1, T=400, R=2, d=1000, K=17, seg_len=90)
+    data = WL.generate(wl)
+    opt = dict(WIN, window_resident=resident)
+    whole = _gpu(wl, data, options=opt)
+    _check(wl, data, whole, label="windowed optimistic whole")
+    for c in (64, 100, 37):
+        part = _gpu(wl, data, chunk=c, n_max=c, options=opt)
+        again = _gpu(wl, data, chunk=c, n_max=c, options=opt)
+        _check(wl, data, part, label="windowed optimistic chunk %d" % c)
+        for k in ("regret", "L", "W", "p", "wbar"):
+            assert np.array_equal(part[k], again[k]), (k, c)
+        scale = max(1.0, float(np.abs(whole["regret"]).max()))
+        assert np.abs(part["regret"] - whole["regret"]).max() <= 2e-6 * scale * 10
+        assert np.abs(part["W"] - whole["W"]).max() <= 2e-5
+
+
 @pytest.mark.parametrize("name,over", [
     ("c3", dict(T=200, R=2, d=8192, K=5, seg_len=64)),
     ("c4", dict(T=130, R=3, d=16384, K=6)),
