@@ -80,6 +80,8 @@ constexpr int kMiscZeros = 16, kMiscFloats = kMiscZeros + 1024 * 4;
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
+// (A build with -DOCO_WIN_PROF keeps wall-clock sums of the phases of workgroup 0's window loop in g_win_prof,
+// read back through oco_debug_win_prof: how the figures per phase in the comments below were taken.)
 #ifdef OCO_WIN_PROF
 __device__ unsigned long long g_win_prof[8];
 #define PROF_T(i) do { if (threadIdx.x == 0) { const unsigned long long now_ = wall_clock64(); prof_[i] += now_ - last_; last_ = now_; } } while (0)

@@ -468,7 +468,12 @@ def test_results_do_not_depend_on_how_a_call_is_enqueued(name, over):
     sim.run_all(0)
     assert np.array_equal(sim.regret(), base["regret"])
     assert np.array_equal(sim.cum_losses(), base["L"])
-    assert B.oco_last_timing(sim.h).min() > 0.0
+    both = B.oco_last_timing(sim.h)
+    assert both.min() > 0.0
+    # the dominant kernel alone, launch by launch: inside the bracket of all round kernels
+    kt = B.oco_last_kernel_timing(sim.h)
+    assert kt["kernel"] in ("dense_round_kernel", "dense_window_kernel", "dense_window_shared_kernel", "sparse_window_kernel")
+    assert 1 <= kt["timed"] <= kt["launches"] and 0.0 < kt["ms_sum"] <= both[0] * 1.05
     sim.close()
 
 
