@@ -184,7 +184,9 @@ typedef enum {
                                     workgroup (d <= 4096, else as 0); 2: HBM, one tile, 16 wavefronts;
                                     3: HBM, four tiles, operands brought to LDS by loading wavefronts
                                     (with the optimistic update 1 and 2 are taken as 0) */
-    OCO_OPT_COUNT = 10
+    OCO_OPT_SPARSE_FETCH = 10,   /* 0: no workgroups that fetch the rows of coming sparse windows into L2 ahead of
+                                    the working ones (the library adds them where the grid leaves most of the chip idle) */
+    OCO_OPT_COUNT = 11
 } oco_option;
 int oco_set_option(oco_state *st, int key, int64_t value);
 

@@ -20,7 +20,7 @@ OCO_OK, OCO_EINVAL, OCO_ESEQ, OCO_ERANGE, OCO_ENOMEM, OCO_EHIP, OCO_ENOCOMP, OCO
 LOSS_ID = {"linear": 0, "squared": 1, "logistic": 2}
 # oco_option keys (include/oco.h)
 OPT = dict(meta_beside=0, dense_path=1, dense_wpb=2, comparator_gemm=3, dense_half=4, dense_pieces=5,
-           sparse_lpw=6, sparse_pipe=7, verbose=8, window_resident=9)
+           sparse_lpw=6, sparse_pipe=7, verbose=8, window_resident=9, sparse_fetch=10)
 OCO_STATIC_WS_BYTES = 64 << 20
 EXPORTS = ("oco_step_grid", "oco_paper_num_learners", "oco_workspace_bytes", "oco_create",
            "oco_create_static", "oco_set_option",

@@ -76,6 +76,13 @@
 namespace oco {
 namespace {
 
+#ifndef OCO_SP_NI
+#define OCO_SP_NI 5
+#endif
+#ifndef OCO_SP_LD4
+#define OCO_SP_LD4 2
+#endif
+
 template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
 {
     if (LOSS == 0) return 1.0f;
@@ -87,7 +94,36 @@ template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
 // goes to L2 as well (a device-scope relaxed load never hits in the per-CU cache).
 __device__ __forceinline__ float ldv(const float *p)
 {
+#ifdef OCO_SP_PLAINLD
+    return *p;
+#else
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#endif
+}
+__device__ __forceinline__ void drop_cached_v()
+{
+#if defined(OCO_SP_PLAINLD) || OCO_SP_LD4 < 2
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#endif
+}
+typedef float f4 __attribute__((ext_vector_type(4)));
+// 16 bytes of a row of V (four neighbouring learners) by one lane.
+__device__ __forceinline__ f4 ldv4(const float *p)
+{
+#if OCO_SP_LD4 == 0
+    return *reinterpret_cast<const f4 *>(p);
+#elif OCO_SP_LD4 == 1
+    return __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
+#else
+    f4 r;
+    asm volatile("global_load_dwordx4 %0, %1, off sc0" : "=v"(r) : "v"(p) : "memory");
+    return r;
+#endif
+}
+// x + (x of the lane that `ctrl` pairs this lane with), inside rows of 16 lanes
+template <int CTRL> __device__ __forceinline__ float add_dpp(float x)
+{
+    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
 }
 
 // Workgroup barrier that first waits for every global access of this wavefront (loads,
@@ -106,9 +142,6 @@ __device__ __forceinline__ void wg_sync_chain(int wave)
     __syncthreads();
 }
 
-#ifndef OCO_KMID
-#define OCO_KMID 32
-#endif
 #ifndef OCO_FOLD_LO
 #define OCO_FOLD_LO 0x1p-100
 #define OCO_FOLD_SOFT 0x1p-64
@@ -124,7 +157,23 @@ constexpr int kSpWaves = 16;                 // wavefronts per workgroup
 constexpr int kBesideMaxWorkgroups = 128;    // window grids up to this size leave half the chip idle
 constexpr size_t kLdsBytes = 160 * 1024;     // LDS of a gfx950 compute unit
 constexpr int kMaxCross = 64;                // most round pairs across a window boundary that are corrected
-constexpr int kMid = OCO_KMID;                     // round of a window at which the pipelined kernel's two halves meet
+constexpr int kProgBytes = 4096;             // head of the scratch: the window each workgroup has reached (one int each)
+constexpr int kFetchMaxWorkgroups = 64;      // window grids up to this size get workgroups that fetch rows into L2 ahead of them
+#ifndef OCO_FETCH_AHEAD
+#define OCO_FETCH_AHEAD 3
+#endif
+constexpr int kFetchAhead = OCO_FETCH_AHEAD;               // ... the rows of window x once every workgroup has reached window x - 3
+constexpr int kFetchSpins = 4000;            // ... or after this many looks at the progress words (a hint never waits for good)
+
+// (A build with -DOCO_SP_PROF keeps wall-clock sums (10 ns ticks) of the phases of workgroup 0's window loop in
+// g_sp_prof -- eight entries per wavefront, wavefront 0 runs the dependent rounds -- read back
+// through oco_debug_sp_prof: how the figures per phase in the comments below were taken.)
+#ifdef OCO_SP_PROF
+__device__ unsigned long long g_sp_prof[16 * 16 + 4];
+#define SP_T(i) do { if (blockIdx.x == 0 && (threadIdx.x & 63) == 0) { const unsigned long long now_ = wall_clock64(); prof_[i] += now_ - last_; last_ = now_; } } while (0)
+#else
+#define SP_T(i) do { } while (0)
+#endif
 
 // Pre-pass over the round stream, one workgroup per window of the launch:
 // G[s][t] = <x_s, x_t> for s < t, mask[s] = bit t set iff rounds s and t share a column,
@@ -474,8 +523,9 @@ struct WinView {
 
 // Where the LDS has room for it (pipe) the windows are pipelined: while wavefront 0 runs the
 // dependent rounds of window w, the other fifteen first apply the steps of window w - 1 and
-// stage window w + 1 and then, once those atomics are acknowledged (a workgroup barrier that
-// wavefront 0 meets after round kMid), gather <v, x_t> for window w + 1.  That gather sees V
+// stage window w + 1 and then, once those steps are in memory (the fifteen meet through a counter
+// in LDS; wavefront 0 takes no part and goes on with its rounds), gather <v, x_t> for window w + 1.
+// A workgroup barrier ends the window.  That gather sees V
 // without the steps of window w; they enter as Gram terms over the window boundary,
 //     <v_start(w+1), x_t> = <v_start(w), x_t> - sum_{s in w} b_s <x_s, x_t>,
 // which the pre-pass lists (a handful of pairs for columns drawn at random).  The first window
@@ -483,9 +533,18 @@ struct WinView {
 // the kernel are gathered after all earlier steps have been applied, as without the pipeline.
 // Otherwise (64 learners per workgroup, or 64 entries per round with 32 learners) the LDS holds
 // one set of buffers and every window runs gather, rounds, steps one after the other.
+//
+// A small problem leaves most compute units idle while each of its workgroups draws random rows of V
+// through the one path from its compute unit to memory, which delivers a row that misses the L2 every
+// ~1.5 ns against ~0.4 ns for a row that is there (measured; a window has 2048 of them to gather and as
+// many to update).  The stream of columns is known in advance, so `nfetch` extra workgroups, one per
+// XCD and L2, run ahead of the others and touch the rows of the coming windows: they load the bytes of
+// every row that belong to the learners of their XCD and drop them.  They follow the progress words the
+// working workgroups publish, with a bounded number of looks: being a hint, they never wait for good,
+// and nothing waits for them.
 template <int LOSS, int LPW, bool OPT>
 __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const SparseArgs a, WinPlan plan, int wbeg, int wend,
-                                                                         int pipe)
+                                                                         int pipe, int nfetch)
 {
     constexpr int EPI = kWave / LPW;
     constexpr int kCWaves = kSpWaves - 1;           // wavefronts that apply steps (all but the chain's)
@@ -498,18 +557,79 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     auto stage_of = [&](int w) { return stage_at(stage0 + (PIPE ? (w - wbeg) % 3 : (w - wbeg) & 1) * stage_n, a.nnz); };
     // in-kernel fold: round after which the chain stopped (-1: none), the learners' scales, and
     // one partial squared norm per wavefront and learner
-    __shared__ int fold_t, fold_gp;
+    __shared__ int fold_t, fold_gp, met;
     __shared__ float fold_sf[LPW];
     __shared__ double fold_part[kSpWaves][LPW];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l = lane % LPW, e = lane / LPW;       // learner and slot of this lane
+#ifdef OCO_SP_PROF
+    unsigned long long prof_[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, last_ = wall_clock64();
+#endif
     const int nnz = a.nnz;
     const unsigned mdiv = ((1u << 18) + nnz - 1) / nnz;       // e / nnz == (e * mdiv) >> 18 for e < 4096
     // Workgroups go to the eight XCDs in turn, each with an L2 of its own: the workgroups of one
     // XCD take neighbouring learners, whose segments of a row of V share cache lines.
-    const int nblk = (int)gridDim.x;
+    const int nblk = (int)gridDim.x - nfetch;
+    int *prog = static_cast<int *>(a.scratch);
+    if ((int)blockIdx.x >= nblk) {
+        // ---- a fetching workgroup (nfetch == 8, nblk % 8 == 0): XCD x = blockIdx - nblk holds the working
+        // workgroups x, x + 8, ..., which own nblk / 8 * LPW neighbouring learners
+        const int x = (int)blockIdx.x - nblk, ncx = nblk / 8;
+        const int64_t base = (int64_t)x * ncx * LPW;          // first learner of the XCD
+        const int lines = (ncx * LPW * 4 + 63) / 64;          // 64-byte pieces of a row to touch
+#ifdef OCO_SP_PROF
+        unsigned long long pf_[4] = {0, 0, 0, 0}, pl_ = wall_clock64();
+#endif
+        for (int w = wbeg + 1; w < wend; ++w) {
+            if (threadIdx.x == 0 && w > wbeg + 2) {
+                int m = 0;
+                for (int spin = 0; spin < kFetchSpins; ++spin) {
+                    m = 0x7fffffff;
+                    for (int c = 0; c < ncx; ++c) {
+                        const int v = __hip_atomic_load(prog + x + 8 * c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        m = v < m ? v : m;
+                    }
+                    if (m >= w - kFetchAhead) break;
+                    __builtin_amdgcn_s_sleep(32);
+                }
+#ifdef OCO_SP_PROF
+                pf_[2] += (unsigned long long)(w - m + 1000);
+                pf_[3] += 1;
+#endif
+            }
+#ifdef OCO_SP_PROF
+            if (threadIdx.x == 0) { const unsigned long long n_ = wall_clock64(); pf_[0] += n_ - pl_; pl_ = n_; }
+#endif
+            __syncthreads();
+            const int ws = plan.start(w), total = plan.len(w) * a.nnz * lines;
+            for (int e0 = threadIdx.x; e0 < total; e0 += 4 * (int)blockDim.x) {
+                const float *pv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + u * (int)blockDim.x < total ? e0 + u * (int)blockDim.x : e0;
+                    const int c = a.col[(int64_t)ws * a.nnz + e / lines];
+                    pv[u] = a.V + (int64_t)c * a.RKp + base + (e % lines) * 16;
+                }
+                // The loaded words are dropped, but the registers they arrive in stay reserved until they have
+                // arrived (the wait below names them): the compiler knows nothing of a load inside an asm
+                // statement, and a register it gave to something else would be overwritten when the load returns.
+                float got[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) asm volatile("global_load_dword %0, %1, off" : "=v"(got[u]) : "v"(pv[u]) : "memory");
+                asm volatile("s_waitcnt vmcnt(0)" : "+v"(got[0]), "+v"(got[1]), "+v"(got[2]), "+v"(got[3]) : : "memory");
+            }
+#ifdef OCO_SP_PROF
+            if (threadIdx.x == 0) { const unsigned long long n_ = wall_clock64(); pf_[1] += n_ - pl_; pl_ = n_; }
+#endif
+        }
+#ifdef OCO_SP_PROF
+        if (x == 0 && threadIdx.x == 0)
+            for (int i2 = 0; i2 < 4; ++i2) atomicAdd(&g_sp_prof[16 * 16 + i2], pf_[i2]);
+#endif
+        return;
+    }
     const int blk = nblk % 8 == 0 ? ((int)blockIdx.x % 8) * (nblk / 8) + (int)blockIdx.x / 8 : (int)blockIdx.x;
     const int q = blk * LPW + l;                    // learner (column of V) of this lane
     const unsigned uq = (unsigned)q;
@@ -522,7 +642,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     const float *yrow = a.y ? a.y + (int64_t)r * a.y_run_stride : nullptr;
     const unsigned zoff4 = 4u * (unsigned)(r * a.zl.zs_r + i * a.zl.zs_i);    // byte offset inside a round's slice of Z
     const int64_t zstep = 4 * a.zl.zs_t;
-    const WinRec *recs = static_cast<const WinRec *>(a.scratch);
+    const WinRec *recs = reinterpret_cast<const WinRec *>(static_cast<const char *>(a.scratch) + kProgBytes);
     // the lanes that run the dependent rounds (padding learners of the last workgroup take no part:
     // their step sizes stay zero and their scale stays one)
     const bool chain = wave == 0 && lane < LPW && valid;
@@ -568,6 +688,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         constexpr int RA = decltype(ra_tag)::value, BK = decltype(bk_tag)::value;   // RA * BK gathers in flight
         const int NL = (nnz + EPI - 1) / EPI;
         const int wl = v.wl;
+        drop_cached_v();
         for (int tg = wv; tg < wl; tg += RA * nwv) {
             float acc[RA][4], yl[RA];
 #pragma unroll
@@ -578,6 +699,9 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             }
             for (int k0 = 0; k0 < NL; k0 += BK) {
                 float vv[RA][BK];
+                int ci[RA][BK];
+                // all columns of the batch first: one trip to LDS, not one per gather (the loads of V are
+                // atomic loads, across which the compiler moves no other memory access)
 #pragma unroll
                 for (int ra = 0; ra < RA; ++ra) {
                     const int t = tg + ra * nwv < wl ? tg + ra * nwv : tg;
@@ -585,9 +709,14 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                     for (int u = 0; u < BK; ++u) {
                         const int j = (k0 + u) * EPI + e;
                         const bool in = k0 + u < NL && j < nnz;
-                        vv[ra][u] = ldv(a.V + (int64_t)v.cw[t * nnz + (in ? j : 0)] * a.RKp + uq);
+                        ci[ra][u] = v.cw[t * nnz + (in ? j : 0)];
                     }
                 }
+#pragma unroll
+                for (int ra = 0; ra < RA; ++ra)
+#pragma unroll
+                    for (int u = 0; u < BK; ++u) vv[ra][u] = ldv(a.V + (int64_t)ci[ra][u] * a.RKp + uq);
+                SP_T(8);
 #pragma unroll
                 for (int ra = 0; ra < RA; ++ra) {
                     const int t = tg + ra * nwv < wl ? tg + ra * nwv : tg;
@@ -599,6 +728,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                         acc[ra][u & 3] = fmaf(vv[ra][u], xv, acc[ra][u & 3]);
                     }
                 }
+                SP_T(9);
             }
 #pragma unroll
             for (int ra = 0; ra < RA; ++ra) {
@@ -611,6 +741,81 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                     yvd[t][l] = yl[ra];
                 }
             }
+        }
+    };
+    // The same for four learners per workgroup, where a row's share of the workgroup is 16 bytes: one lane
+    // fetches them all, a round is the lanes of one instruction (nslot of them, two rounds per instruction
+    // for 32 entries per round), and the sum over a round's entries is a butterfly over those lanes, the same
+    // for every caller.  A quarter of the memory instructions of the form above.
+    auto gather_q0_rows = [&](const WinView &v, int wv, int nwv, float (*q0d)[LPW], float (*yvd)[LPW], int pslot = 8) {
+        (void)pslot;
+        constexpr int NB = 3;                                // instructions in flight
+        const int nslot = nnz <= 8 ? 8 : (nnz <= 16 ? 16 : (nnz <= 32 ? 32 : 64));
+        const int rpi = kWave / nslot;                        // rounds per instruction
+        const int j = lane & (nslot - 1), rsub = lane / nslot;
+        const int wl = v.wl;
+        const int ngroups = (wl + rpi - 1) / rpi;
+        const float *Vb = a.V + (int64_t)blk * LPW;
+        drop_cached_v();
+        for (int g0 = wv; g0 < ngroups; g0 += NB * nwv) {
+            int ci[NB];
+            float xv[NB], yl[NB];
+            f4 vv[NB];
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int t = (g0 + u * nwv) * rpi + rsub;
+                const bool in = t < wl && j < nnz;
+                ci[u] = v.cw[in ? t * nnz + j : 0];
+                xv[u] = v.vw[in ? t * nnz + j : 0];
+            }
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int t = (g0 + u * nwv) * rpi + rsub;
+                vv[u] = ldv4(Vb + (int64_t)ci[u] * a.RKp);
+                yl[u] = yrow && t < wl ? yrow[v.ws + t] : 0.f;
+            }
+#if OCO_SP_LD4 == 2
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(vv[0]), "+v"(vv[1]), "+v"(vv[2]), "+v"(yl[0]), "+v"(yl[1]), "+v"(yl[2]) : : "memory");
+#endif
+            SP_T(pslot);
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int t = (g0 + u * nwv) * rpi + rsub;
+                const bool in = t < wl && j < nnz;
+                const float xx = in ? xv[u] : 0.f;
+                float pr[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    float x = __fmul_rn(vv[u][c], xx);       // (a product of its own: both lanes of a pair add the same two numbers)
+                    x = add_dpp<0xB1>(x);                    // lanes ^ 1
+                    x = add_dpp<0x4E>(x);                    // lanes ^ 2
+                    x = add_dpp<0x141>(x);                   // the other quad of eight
+                    pr[c] = x;
+                }
+                if (nslot >= 16) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) pr[c] = add_dpp<0x140>(pr[c]);   // the other eight of sixteen
+                }
+                if (nslot >= 32) {
+                    float o[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) o[c] = __shfl_xor(pr[c], 16);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) pr[c] += o[c];
+                }
+                if (nslot >= 64) {
+                    float o[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) o[c] = __shfl_xor(pr[c], 32);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) pr[c] += o[c];
+                }
+                if (t < wl && j < 4) {
+                    q0d[t][j] = j == 0 ? pr[0] : (j == 1 ? pr[1] : (j == 2 ? pr[2] : pr[3]));
+                    yvd[t][j] = yl[u];
+                }
+            }
+            SP_T(pslot + 1);
         }
     };
     // the predictions of a window go from LDS to Z (wavefronts 1 .. 15, a lane stores for its own learner)
@@ -631,21 +836,40 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         if (wave == 0) return;
         const int beg = __builtin_amdgcn_readfirstlane(v.offs[wave - 1]);
         const int end = __builtin_amdgcn_readfirstlane(v.offs[wave]);
-        constexpr int NI = 4;                                // instructions per batch
+        constexpr int NI = OCO_SP_NI;                        // instructions per batch
         for (int k0 = beg; k0 < end; k0 += NI * EPI) {
             int cc[NI];
             float xv[NI];
             bool dup[NI];
+            // two trips to LDS per batch: the batch's places in the sorted list, then column, value and
+            // step size of each (every read is in bounds: lanes past the share read its last entry, and the
+            // empty asm keeps the compiler from putting a read under a branch of its own, one wait each)
+            int pe[NI];
 #pragma unroll
             for (int n = 0; n < NI; ++n) {
                 const int k = k0 + n * EPI + e;
-                const bool act = k < end;
-                const int pe = v.perm[act ? k : end - 1];
-                const int ee = pe & 0xFFF;
+                pe[n] = v.perm[k < end ? k : end - 1];
+            }
+#pragma unroll
+            for (int n = 0; n < NI; ++n) asm volatile("" : "+v"(pe[n]));
+            float bl[NI];
+#pragma unroll
+            for (int n = 0; n < NI; ++n) {
+                const int ee = pe[n] & 0xFFF;
                 const int t = (int)(((unsigned)ee * mdiv) >> 18);
-                cc[n] = act ? v.cw[ee] : -1;
-                dup[n] = act && (pe & 0x8000);
-                xv[n] = act && (!decltype(partial)::value || t <= tmax) ? -bwp[t][l] * v.vw[ee] : 0.f;
+                cc[n] = v.cw[ee];
+                xv[n] = v.vw[ee];
+                bl[n] = bwp[t][l];
+            }
+#pragma unroll
+            for (int n = 0; n < NI; ++n) asm volatile("" : "+v"(cc[n]), "+v"(xv[n]), "+v"(bl[n]));
+#pragma unroll
+            for (int n = 0; n < NI; ++n) {
+                const bool act = k0 + n * EPI + e < end;
+                const int t = (int)(((unsigned)(pe[n] & 0xFFF) * mdiv) >> 18);
+                cc[n] = act ? cc[n] : -1;
+                dup[n] = act && (pe[n] & 0x8000);
+                xv[n] = act && (!decltype(partial)::value || t <= tmax) ? -bl[n] * xv[n] : 0.f;
             }
 #pragma unroll
             for (int n = 0; n < NI; ++n) {
@@ -663,6 +887,76 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                 if (cc[n] >= 0 && last) unsafeAtomicAdd(a.V + (int64_t)cc[n] * a.RKp + uq, xv[n]);
             }
         }
+    };
+    // The same for four learners per workgroup, where a row's share of the workgroup is 16 bytes: one lane
+    // reads them, takes the step and writes them back.  A column that occurs once in the window is touched
+    // by that lane alone between two barriers, so plain loads and stores do; the entries of a column that
+    // occurs more than once stay with atomics, one lane at a time in the order of the sorted list (round
+    // order).  Measured for the 2048 rows of a window: 2.4 us against 4.6 us with atomics, and rows that
+    // were fetched ahead stay in L2, which they do not beside atomics.
+    auto apply_rows = [&](const WinView &v, const float (*bwp)[LPW], int tmax, auto partial) {
+        if (wave == 0) return;
+        const int beg = __builtin_amdgcn_readfirstlane(v.offs[wave - 1]);
+        const int end = __builtin_amdgcn_readfirstlane(v.offs[wave]);
+        constexpr int NI = 3;                                // instructions per batch
+        float *Vb = a.V + (int64_t)blk * LPW;
+        for (int k0 = beg; k0 < end; k0 += NI * kWave) {
+            int pe[NI];
+#pragma unroll
+            for (int n = 0; n < NI; ++n) {
+                const int k = k0 + n * kWave + lane;
+                pe[n] = v.perm[k < end ? k : end - 1];
+            }
+#pragma unroll
+            for (int n = 0; n < NI; ++n) asm volatile("" : "+v"(pe[n]));
+            int cc[NI];
+            float xv[NI];
+            f4 bl[NI];
+#pragma unroll
+            for (int n = 0; n < NI; ++n) {
+                const int ee = pe[n] & 0xFFF;
+                const int t = (int)(((unsigned)ee * mdiv) >> 18);
+                cc[n] = v.cw[ee];
+                xv[n] = v.vw[ee];
+                bl[n] = *reinterpret_cast<const f4 *>(&bwp[t][0]);
+            }
+#pragma unroll
+            for (int n = 0; n < NI; ++n) asm volatile("" : "+v"(cc[n]), "+v"(xv[n]), "+v"(bl[n]));
+            float *row[NI];
+            f4 cur[NI];
+#pragma unroll
+            for (int n = 0; n < NI; ++n) {
+                row[n] = Vb + (int64_t)cc[n] * a.RKp;
+                cur[n] = ldv4(row[n]);
+            }
+#if OCO_SP_LD4 == 2
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(cur[0]), "+v"(cur[1]), "+v"(cur[2]) : : "memory");
+#endif
+#pragma unroll
+            for (int n = 0; n < NI; ++n) {
+                const int t = (int)(((unsigned)(pe[n] & 0xFFF) * mdiv) >> 18);
+                const bool act = k0 + n * kWave + lane < end && (!decltype(partial)::value || t <= tmax);
+                const bool dup = (pe[n] & 0x8000) != 0;
+                if (act && !dup) {
+                    f4 nv;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) nv[c] = fmaf(-bl[n][c], xv[n], cur[n][c]);
+                    *reinterpret_cast<f4 *>(row[n]) = nv;
+                }
+                unsigned long long dm = __builtin_amdgcn_ballot_w64(act && dup);
+                while (dm) {
+                    const int dl = __builtin_ctzll(dm);
+                    dm &= dm - 1;
+                    if (lane == dl) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) unsafeAtomicAdd(row[n] + c, -bl[n][c] * xv[n]);
+                    }
+                }
+            }
+        }
+    };
+    auto apply = [&](const WinView &v, const float (*bwp)[LPW], int tmax, auto partial) {
+        if constexpr (LPW == 4) apply_rows(v, bwp, tmax, partial); else apply_steps(v, bwp, tmax, partial);
     };
     // ---- B: the dependent rounds tstart .. tstop - 1 of a window, scalars and LDS only (LPW
     // lanes of wavefront 0).  If a learner's sigma falls below the fold threshold the chain stops
@@ -727,6 +1021,16 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         }
         return gp;
     };
+    // A meeting of the wavefronts 1 .. 15 (not a workgroup barrier: wavefront 0 goes on with its rounds): each waits
+    // for its own memory work, counts itself in LDS and waits until all fifteen of this meeting have.  Every one
+    // of them comes to every meeting, so the wait ends.
+    int meetings = 0;
+    auto helpers_meet = [&]() {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        ++meetings;
+        if (lane == 0) __hip_atomic_fetch_add(&met, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        while (__hip_atomic_load(&met, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < meetings * kCWaves) __builtin_amdgcn_s_sleep(2);
+    };
     // What the wavefronts 1 .. 15 do beside the dependent rounds: the loads of window wn (on their
     // way into LDS) are issued first, then the steps and predictions of window wc, and only then
     // are the loads waited for; the next barrier waits for the atomics.
@@ -734,7 +1038,9 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         const int tid = (int)threadIdx.x - kWave;
         StageRegs sr;
         if (wn < wend) sr.load(a, recs[wn], plan.start(wn), plan.len(wn) * nnz, tid, kCWaves * kWave);
-        if (steps) { apply_steps(vc, bwc, 0, std::false_type()); flush_z(vc, zbc); }
+        SP_T(6);
+        if (steps) { apply(vc, bwc, 0, std::false_type()); SP_T(7); flush_z(vc, zbc); }
+        SP_T(10);
         if (wn < wend) sr.store(stage_of(wn), plan.len(wn) * nnz, tid, kCWaves * kWave);
     };
 
@@ -742,11 +1048,12 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     // share its SIMD
     if (wave == 0) __builtin_amdgcn_s_setprio(3);
     stage_window(stage_of(wbeg), a, recs[wbeg], plan.start(wbeg), plan.len(wbeg) * nnz, threadIdx.x, blockDim.x);
-    if (threadIdx.x == 0) fold_t = -1;
+    if (threadIdx.x == 0) { fold_t = -1; met = 0; }
     wg_sync();
     bool have_q0 = false;          // PIPE: this window's <v, x_t> were gathered beside the previous window's rounds
     bool pending = false;          // PIPE: the previous window's steps are not in V yet
     for (int w = wbeg; w < wend; ++w) {
+        if (nfetch && threadIdx.x == kWave) __hip_atomic_store(prog + blockIdx.x, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const WinView v = view(w);
         const int cb = PIPE ? (w - wbeg) & 1 : 0;
         Chain<LPW> &ch = chs[cb];                            // this window's buffers
@@ -758,20 +1065,25 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         const int wl = v.wl;
         if (!have_q0) {
             if (PIPE && pending) {
-                apply_steps(view(w - 1), cho.bw, 0, std::false_type());
+                apply(view(w - 1), cho.bw, 0, std::false_type());
                 flush_z(view(w - 1), cho.zb);
                 wg_sync();
                 pending = false;
             }
-            gather_q0(std::integral_constant<int, LPW == 64 ? 2 : 4>(),
-                      std::integral_constant<int, LPW == 64 ? 16 : (LPW >= 16 ? 8 : (LPW == 8 ? 4 : 2))>(), v, wave,
-                      kSpWaves, q0, yv);
+            if (LPW == 4)
+                gather_q0_rows(v, wave, kSpWaves, q0, yv);
+            else
+                gather_q0(std::integral_constant<int, LPW == 64 ? 2 : 4>(),
+                          std::integral_constant<int, LPW == 64 ? 16 : (LPW >= 16 ? 8 : (LPW == 8 ? 4 : 2))>(), v, wave,
+                          kSpWaves, q0, yv);
             wg_sync();
         }
         int gp = 0;
+        SP_T(0);
         if (PIPE) {
-            // ---- first part: rounds 0 .. kMid - 1 | steps of window w - 1, staging of window w + 1
-            const int tmid = wl < kMid ? wl : kMid;
+            // ---- the rounds of window w | steps of window w - 1 and staging of window w + 1, then, once
+            // those steps are in memory (a meeting of the fifteen wavefronts only: the rounds go on),
+            // <v, x_t> of window w + 1 (V holds the steps up to window w - 1) ----------------------
             if (wave == 0) {
                 if (chain) {
                     if (have_q0) {
@@ -783,24 +1095,30 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                         const float (*bwprev)[LPW] = cho.bw;
                         for (int p = 0; p < nx; ++p) q0[xt[p]][l] = fmaf(-bwprev[xs[p]][l], xg[p], q0[xt[p]][l]);
                     }
-                    gp = run_chain(v, q0, yv, bw, zb, 0, tmid, 0);
+                    gp = run_chain(v, q0, yv, bw, zb, 0, wl, 0);
                 }
+                SP_T(1);
             } else {
                 work_beside(w + 1, pending, pending ? view(w - 1) : v, cho.bw, cho.zb);
+                SP_T(1);
+                helpers_meet();
+                SP_T(3);
             }
-            wg_sync_chain(wave);
-            // ---- second part: the other rounds | <v, x_t> of window w + 1 (V holds the steps up to
-            // window w - 1) ----------------------------------------------------------------------
-            const bool early = w + 1 < wend && stage_of(w + 1).head[4 * kWin + 32 + kWin] >= 0;
-            if (wave == 0) {
-                if (chain && fold_t < 0 && tmid < wl) gp = run_chain(v, q0, yv, bw, zb, tmid, wl, gp);
-            } else if (early) {
-                gather_q0(std::integral_constant<int, 5>(), std::integral_constant<int, LPW >= 16 ? 4 : (LPW == 8 ? 4 : 2)>(),
-                          view(w + 1), wave - 1, kCWaves, cho.q0, cho.yv);
+            if (wave != 0 && w + 1 < wend && stage_of(w + 1).head[4 * kWin + 32 + kWin] >= 0) {
+                if (LPW == 4) {
+                    gather_q0_rows(view(w + 1), wave - 1, kCWaves, cho.q0, cho.yv);
+#ifdef OCO_SP_PROF2
+                    gather_q0_rows(view(w + 1), wave - 1, kCWaves, cho.q0, cho.yv, 12);   // the same again, rows now in L2
+#endif
+                } else
+                    gather_q0(std::integral_constant<int, 5>(), std::integral_constant<int, LPW >= 16 ? 4 : (LPW == 8 ? 4 : 2)>(),
+                              view(w + 1), wave - 1, kCWaves, cho.q0, cho.yv);
             }
+            SP_T(4);
             wg_sync_chain(wave);
+            SP_T(5);
             pending = false;
-            have_q0 = early;
+            have_q0 = w + 1 < wend && stage_of(w + 1).head[4 * kWin + 32 + kWin] >= 0;
         } else {
             if (chain) {
                 run_chain(v, q0, yv, bw, zb, 0, wl, 0);
@@ -815,12 +1133,13 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         // ---- fold inside the window (sigma below 2^-100 before the segment ended): apply the
         // steps taken so far, scale the workgroup's columns of V by sigma with all wavefronts,
         // measure ||v||^2 exactly, and take the remaining rounds' <v, x_t> afresh ----------------
-        apply_steps(v, bw, ft, std::true_type());
+        apply(v, bw, ft, std::true_type());
         wg_sync();
         {
             for (int rd = (int)threadIdx.x / LPW; rd <= ft; rd += kSpWaves * EPI) bw[rd][l] = 0.f;   // applied
             const float fs = fold_sf[l];
             const int64_t nslots = kSpWaves * EPI;
+            drop_cached_v();
             double m2 = 0.0;
             for (int64_t j0 = wave * EPI + e; j0 < a.d; j0 += 4 * nslots) {
                 float vv[4];
@@ -849,7 +1168,10 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             sigma = 1.0; sf = 1.f; isf = 1.f;
         }
         if (threadIdx.x == 0) fold_t = -1;
-        gather_q0(std::integral_constant<int, 1>(), std::integral_constant<int, 2>(), v, wave, kSpWaves, q0, yv);   // rare: few registers
+        if (LPW == 4)
+            gather_q0_rows(v, wave, kSpWaves, q0, yv);
+        else
+            gather_q0(std::integral_constant<int, 1>(), std::integral_constant<int, 2>(), v, wave, kSpWaves, q0, yv);   // rare: few registers
         wg_sync();
         if (chain) run_chain(v, q0, yv, bw, zb, ft + 1, wl, gp0);
         wg_sync();
@@ -857,18 +1179,22 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         if (PIPE) {
             pending = true;                                  // applied beside the next window's rounds
         } else {
-            apply_steps(v, bw, 0, std::false_type());
+            apply(v, bw, 0, std::false_type());
             flush_z(v, zb);
             wg_sync();
         }
     }
     if (PIPE && pending) {
-        apply_steps(view(wend - 1), chs[(wend - 1 - wbeg) & 1].bw, 0, std::false_type());
+        apply(view(wend - 1), chs[(wend - 1 - wbeg) & 1].bw, 0, std::false_type());
         flush_z(view(wend - 1), chs[(wend - 1 - wbeg) & 1].zb);
         wg_sync();
     }
     if (chain) { a.sigma[q] = sigma; a.n2[q] = n2; }
     if (OPT && chain) { a.ha[q] = ha; a.hp[q] = hp; a.hx[q] = x2p; }
+#ifdef OCO_SP_PROF
+    if (blockIdx.x == 0 && (threadIdx.x & 63) == 0)
+        for (int i2 = 0; i2 < 16; ++i2) atomicAdd(&g_sp_prof[(threadIdx.x >> 6) * 16 + i2], prof_[i2]);
+#endif
 }
 
 // Keeps the last round row of a call for the next call's first hint and for the export:
@@ -952,7 +1278,12 @@ template <int LOSS, int LPW, bool OPT>
 hipError_t launch_window_lpw(const SparseArgs &a, const WinPlan &plan, int wbeg, int wend, hipStream_t s)
 {
     const int nq = a.R * a.K;
-    const dim3 grid((unsigned)((nq + LPW - 1) / LPW)), block(kSpWaves * kWave);
+    const int nblk = (nq + LPW - 1) / LPW;
+    // fetching workgroups: one per XCD, where the grid is small, laid out by XCD (a multiple of 8) and a row's
+    // share of an XCD is a few 64-byte pieces
+    int nfetch = nblk % 8 == 0 && nblk <= kFetchMaxWorkgroups && wend - wbeg > 2 ? 8 : 0;
+    if (a.tune->get(OCO_OPT_SPARSE_FETCH) == 0) nfetch = 0;
+    const dim3 grid((unsigned)(nblk + nfetch)), block(kSpWaves * kWave);
     const size_t stage_b = (size_t)stage_ints(a.nnz) * 4, chain_b = sizeof(Chain<LPW>);
     // the pipelined kernel keeps two chain buffers and three staged windows
     int pipe = 2 * chain_b + 3 * stage_b + sparse_static_lds(LPW) <= kLdsBytes;
@@ -967,7 +1298,7 @@ hipError_t launch_window_lpw(const SparseArgs &a, const WinPlan &plan, int wbeg,
     }
     hipError_t e = clock_begin(a.clock, s, "sparse_window_kernel");
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, grid, block, smem, s, a, plan, wbeg, wend, pipe);
+    hipLaunchKernelGGL(kern, grid, block, smem, s, a, plan, wbeg, wend, pipe, nfetch);
     e = hipGetLastError();
     return e != hipSuccess ? e : clock_end(a.clock, s);
 }
@@ -1000,9 +1331,21 @@ hipError_t launch_window(const SparseArgs &a, int loss, int lpw, const WinPlan &
 
 }  // namespace
 
+#ifdef OCO_SP_PROF
+extern "C" int oco_debug_sp_prof(unsigned long long *out, int clear)
+{
+    hipError_t e = hipMemcpyFromSymbol(out, HIP_SYMBOL(g_sp_prof), sizeof(unsigned long long) * 260);
+    if (e == hipSuccess && clear) {
+        unsigned long long z[260] = {0};
+        e = hipMemcpyToSymbol(HIP_SYMBOL(g_sp_prof), z, sizeof z);
+    }
+    return (int)e;
+}
+#endif
+
 size_t sparse_scratch_bytes(int64_t n_max)
 {
-    return (size_t)(n_max / kWin + 2) * sizeof(WinRec);
+    return kProgBytes + (size_t)(n_max / kWin + 2) * sizeof(WinRec);
 }
 
 hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s, const PieceHook *hook)
@@ -1015,7 +1358,8 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s, c
     const WinPlan plan{a.t0, a.n};
     const int nwin = plan.count();
     hipLaunchKernelGGL(sparse_gram_kernel, dim3(nwin), dim3(1024), 0, s, a.col, a.val, a.nnz, plan,
-                       static_cast<WinRec *>(a.scratch), a.optimistic, a.last_col, a.last_val, kSpWaves - 1);
+                       reinterpret_cast<WinRec *>(static_cast<char *>(a.scratch) + kProgBytes), a.optimistic, a.last_col, a.last_val,
+                       kSpWaves - 1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
