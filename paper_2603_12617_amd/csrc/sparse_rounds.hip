@@ -146,7 +146,7 @@ __device__ __forceinline__ void wg_sync_chain(int wave)
 #define OCO_FOLD_LO 0x1p-100
 #define OCO_FOLD_SOFT 0x1p-64
 #endif
-constexpr double kSparseFoldLo = OCO_FOLD_LO;    // in-kernel emergency fold
+constexpr float kSparseFoldLoF = (float)(OCO_FOLD_LO);   // in-kernel emergency fold
 constexpr double kSparseFoldSoft = OCO_FOLD_SOFT;  // fold between segments
 #ifndef OCO_SEGMENT
 #define OCO_SEGMENT 4096
@@ -196,8 +196,10 @@ struct WinRec {
     RoundRec rr[kWin];
     int off[kSpWaves + 1];              // phase C: wavefront c owns perm[off[c] .. off[c+1])
     int ng;                             // number of set mask bits
-    int pad[32 - kSpWaves - 2];
+    unsigned any[2];                    // bit s: mask of round s is not empty
+    int pad[32 - kSpWaves - 4];
     float g01[kWin];                    // <x_{t-1}, x_t> (optimistic update only; x_{-1}: previous call's last row)
+    float x2h[kWin];                    // ||x_s||^2 / 2, as the dependent rounds read it
     int nx;                             // pairs (round s of the previous window, round t of this one) that share
     int padx[31];                       //   a column; -1: too many, or no previous window in this call
     unsigned short xs[kMaxCross], xt[kMaxCross];
@@ -207,6 +209,11 @@ struct WinRec {
 };
 static_assert(sizeof(WinRec) % 128 == 0, "window records stay 256-byte aligned");
 constexpr int kRecHeadInts = (int)(offsetof(WinRec, perm) / 4);
+// places in the head of a record (and of its copy in LDS), in ints
+constexpr int kHeadOffs = (int)(offsetof(WinRec, off) / 4), kHeadAny = (int)(offsetof(WinRec, any) / 4);
+constexpr int kHeadG01 = (int)(offsetof(WinRec, g01) / 4), kHeadX2 = (int)(offsetof(WinRec, x2h) / 4);
+constexpr int kHeadCross = (int)(offsetof(WinRec, nx) / 4);
+static_assert(kHeadOffs == 4 * kWin && kHeadG01 == 4 * kWin + 32 && kHeadCross == 4 * kWin + 32 + 2 * kWin, "record head layout");
 
 __global__ void __launch_bounds__(1024) sparse_gram_kernel(const int32_t *col, const float *val, int nnz,
                                                           WinPlan plan, WinRec *recs, int optimistic,
@@ -259,6 +266,7 @@ __global__ void __launch_bounds__(1024) sparse_gram_kernel(const int32_t *col, c
         if (threadIdx.x < wl)
             for (int a = 0; a < nnz; ++a) acc = fmaf(vs[threadIdx.x * nnz + a], vs[threadIdx.x * nnz + a], acc);
         rec.rr[threadIdx.x].x2 = (double)acc;
+        rec.x2h[threadIdx.x] = 0.5f * acc;
     }
     __syncthreads();
     // rounds that share a column sit next to each other in the sorted order
@@ -317,12 +325,16 @@ __global__ void __launch_bounds__(1024) sparse_gram_kernel(const int32_t *col, c
     __syncthreads();
     if (threadIdx.x == 0) {
         int acc = 0;
+        unsigned long long any = 0;
         for (int s2 = 0; s2 < kWin; ++s2) {
             rowoff[s2] = acc;
             acc += __popc(mk[s2][0]) + __popc(mk[s2][1]);
+            if (mk[s2][0] | mk[s2][1]) any |= 1ull << s2;
         }
         rowoff[kWin] = acc;
         rec.ng = acc;
+        rec.any[0] = (unsigned)any;
+        rec.any[1] = (unsigned)(any >> 32);
         int xacc = 0;
         for (int s2 = 0; s2 < kWin; ++s2) {
             xrowoff[s2] = xacc;
@@ -489,10 +501,6 @@ __device__ __forceinline__ void stage_window(const WinStage &st, const SparseArg
     sr.store(st, total, tid, nthr);
 }
 
-// 1/sqrt(x) for a finite x > 0: the hardware estimate (relative error < 6e-8, measured over
-// [2^-200, 2^200]).  sigma is recomputed from ||v||^2 at every projection, so the error does not
-// accumulate, and the iterate itself is float32.
-__device__ __forceinline__ double rsqrt_pos(double x) { return __builtin_amdgcn_rsq(x); }
 
 // A workgroup owns LPW learners (LPW = 64, 32, 16, 8 or 4; fewer learners per workgroup spread a
 // small problem over more compute units).  A wavefront is EPI = 64 / LPW slots of LPW lanes:
@@ -514,7 +522,8 @@ struct WinView {
     const float *vw;
     const RoundRec *rr;
     const int *offs;
-    const float *g01;
+    const int *any;
+    const float *g01, *x2h;
     const int *xh;                 // nx | pad | xs | xt | xg
     const unsigned short *perm;
     const float *gl;
@@ -651,14 +660,16 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             for (int rd = 0; rd < kWin; ++rd) chs[nb].bw[rd][l] = 0.f;
     }
     if (wave == 0 && lane < LPW) fold_sf[l] = 1.f;
-    double sigma = 1.0, n2 = 0.0;
-    if (chain) { sigma = a.sigma[q]; n2 = a.n2[q]; }
+    double sigma0 = 1.0, n2 = 0.0;                  // n2: ||v||^2 as the state keeps it
+    if (chain) { sigma0 = a.sigma[q]; n2 = a.n2[q]; }
     // Wait for these loads here.  Left to the compiler, the wait lands at their first use inside
     // the round loop, where it also waits for the previous round's store, every round.
     float eta_r = eta;
-    asm volatile("" : "+v"(eta_r), "+v"(sigma), "+v"(n2));
+    asm volatile("" : "+v"(eta_r), "+v"(sigma0), "+v"(n2));
     const float eta2_r = 2.f * eta_r;
+    double sigma = sigma0, hd = 0.5 * n2;           // the scale of w = sigma v, ||v||^2 / 2
     float sf = (float)sigma, isf = __builtin_amdgcn_rcpf(sf);
+    const double Dhd = a.D * 0.70710678118654752440;   // D / sqrt(2)
     // optimistic update (Eq. (3)): hint ha * x_{t-1}, hp = <w^_t, x_{t-1}>, x2p = ||x_{t-1}||^2
     float ha = 0.f, hp = 0.f, x2p = 0.f;
     if (OPT && chain) { ha = a.ha[q]; hp = a.hp[q]; x2p = a.hx[q]; }
@@ -671,9 +682,11 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         v.cw = st.cw;
         v.vw = st.vw;
         v.rr = reinterpret_cast<const RoundRec *>(st.head);
-        v.offs = st.head + 4 * kWin;
-        v.g01 = reinterpret_cast<const float *>(st.head + 4 * kWin + 32);
-        v.xh = st.head + 4 * kWin + 32 + kWin;
+        v.offs = st.head + kHeadOffs;
+        v.any = st.head + kHeadAny;
+        v.g01 = reinterpret_cast<const float *>(st.head + kHeadG01);
+        v.x2h = reinterpret_cast<const float *>(st.head + kHeadX2);
+        v.xh = st.head + kHeadCross;
         v.perm = reinterpret_cast<const unsigned short *>(st.perm2);
         v.gl = st.gl;
         v.ws = plan.start(w);
@@ -962,34 +975,48 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
     // lanes of wavefront 0).  If a learner's sigma falls below the fold threshold the chain stops
     // after that round (fold_t), the whole workgroup folds and the chain goes on from the next
     // round.  gp: next Gram value of the window; returns the one after the rounds taken -----------
+    // A round costs the wavefront that runs it about 7 clocks per instruction of the loop, whatever the
+    // instruction (measured: 47 instructions 350 clocks, 40 instructions 278), so the loop is written for few
+    // instructions.  With h = ||v||^2 / 2 in float64,
+    //     ||v - b x||^2 / 2 = h + b (b ||x||^2 / 2 - <v, x>),
+    // and the projection is sigma = min(sigma, D / ||v||) (||w|| = sigma ||v|| > D exactly when D / ||v|| < sigma):
+    // sigma is taken afresh from ||v|| whenever the projection acts, so its rounding does not add up over the
+    // rounds (a factor multiplied onto sigma round after round would let ||w|| drift off the sphere like a random
+    // walk: 1.4e-5 after 1e5 rounds, measured).  The pre-pass leaves ||x||^2 / 2 for this.  The float64 minimum is
+    // an instruction of its own: the compiler puts one more in front of it to quieten NaNs that cannot occur here
+    // (|h| under the root: a sum that rounding took below zero projects nothing).
     auto run_chain = [&](const WinView &v, float (*q0)[LPW], const float (*yv)[LPW], float (*bw)[LPW], float (*zb)[LPW],
                          int tstart, int tstop, int gp) {
-        float qn = q0[tstart][l], yn = yv[tstart][l];
         const RoundRec *rr = v.rr;
-        const float *gl = v.gl, *g01 = v.g01;
-        RoundRec rn = rr[tstart];
-        int tend = tstop;                                    // a fold request ends the loop early
-        for (int t = tstart; t < tend; ++t) {
-            const float qv = qn, yy = yn;                    // <v_t, x_t>, y_t
-            const RoundRec rc = rn;                          // collisions with later rounds, ||x_t||^2
-            qn = q0[t + 1][l]; yn = yv[t + 1][l]; rn = rr[t + 1];        // next round, early
-            float z = sf * qv;
+        const float *gl = v.gl, *g01 = v.g01, *x2h = v.x2h;
+        // rounds that share a column with a later round of the window (few): tc is the next of them
+        unsigned long long any = (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane(v.any[0]) |
+                                 ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane(v.any[1]) << 32);
+        any &= ~0ull << tstart;
+        int tc = any ? __builtin_ctzll(any) : kWin;
+        // one round; (qv, yy, xh): <v_t, x_t>, y_t, ||x_t||^2 / 2; (qn, yn, xn) receive those of the next round,
+        // early.  True: a scale has fallen below the fold threshold and the rounds stop here.
+        auto round = [&](int t, float qv, float yy, float xh, float &qn, float &yn, float &xn) -> bool {
+            qn = q0[t + 1][l]; yn = yv[t + 1][l]; xn = x2h[t + 1];
+            const float zr = sf * qv;                        // <w_t, x_t>
+            float z = zr;
             if (OPT) {
                 // played iterate w_t = s (w^_t - ha x_{t-1}), s from ||w^_t - ha x_{t-1}||^2: scalars only
-                const float mf = fmaf(ha * ha, x2p, fmaf(-2.f * ha, hp, (float)((sigma * sigma) * n2)));
+                const float mf = fmaf(ha * ha, x2p, fmaf(-2.f * ha, hp, 2.f * (float)((sigma * sigma) * hd)));
                 const float sp = mf > D2f ? Df * __builtin_amdgcn_rsqf(mf) : 1.f;
-                z = sp * fmaf(-ha, g01[t], z);
+                z = sp * fmaf(-ha, g01[t], zr);
             }
-            zb[t][l] = z;         // not to Z from here: a global store would queue behind the other wavefronts' memory work
             // for the squared loss eta * 2 (z - y) = (2 eta) (z - y) exactly
             const float step = LOSS == 1 ? eta2_r * (z - yy) : eta_r * slope<LOSS>(z, yy);
             const float b = step * isf;
+            zb[t][l] = z;         // not to Z from here: a global store would queue behind the other wavefronts' memory work
             bw[t][l] = b;
-            // (readfirstlane returns int: go through unsigned, or the low word sign-extends)
-            unsigned long long m =
-                (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)rc.mask) |
-                ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(rc.mask >> 32)) << 32);
-            if (m) {
+            if (__builtin_expect(t == tc, 0)) {
+                // (readfirstlane returns int: go through unsigned, or the low word sign-extends)
+                const unsigned long long mk = rr[t].mask;
+                unsigned long long m =
+                    (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)mk) |
+                    ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(mk >> 32)) << 32);
                 const bool next_hit = (m >> (t + 1)) & 1;
                 while (m) {
                     const int t2 = __builtin_ctzll(m);
@@ -997,28 +1024,33 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                     q0[t2][l] = fmaf(-b, gl[gp++], q0[t2][l]);
                 }
                 if (next_hit) qn = q0[t + 1][l];
+                any &= any - 1;
+                tc = any ? __builtin_ctzll(any) : kWin;
             }
-            // ||v - b x||^2 = ||v||^2 + b (b ||x||^2 - 2 <v, x>)
-            const double bd = (double)b;
-            n2 = fma(bd, fma(bd, rc.x2, (double)(-2.f * qv)), n2);
-            n2 = n2 > 0.0 ? n2 : 0.0;
-            // projection: ||w|| = sigma ||v|| > D exactly when D / ||v|| < sigma, so sigma = min(sigma, D / ||v||):
-            // one instruction, no product or comparison of squares (the chain is bound by the number
-            // of instructions a single wavefront can issue)
-            sigma = fmin(sigma, a.D * rsqrt_pos(n2));
+            hd = fma((double)b, (double)fmaf(b, xh, -qv), hd);
+            asm("v_min_f64 %0, %1, %2" : "=v"(sigma) : "v"(sigma), "v"(Dhd * __builtin_amdgcn_rsq(__builtin_fabs(hd))));
             sf = (float)sigma;
             isf = __builtin_amdgcn_rcpf(sf);
             if (OPT) {                                      // next round's hint and <w^_{t+1}, x_t>
-                hp = sf * fmaf(-b, (float)rc.x2, qv);
+                hp = sf * fmaf(-b, 2.f * xh, qv);
                 ha = step;
-                x2p = (float)rc.x2;
+                x2p = 2.f * xh;
             }
-            if (__any(sigma < kSparseFoldLo)) {
+            if (__builtin_expect(__any(sf < kSparseFoldLoF), 0)) {
                 if (lane == 0) { fold_t = t; fold_gp = gp; }
                 fold_sf[l] = sf;
-                tend = t + 1;
+                return true;
             }
+            return false;
+        };
+        // two rounds per turn of the loop: the values read ahead alternate between two sets of registers
+        float qa = q0[tstart][l], ya = yv[tstart][l], xa = x2h[tstart], qb, yb, xb;
+        int t = tstart;
+        for (; t + 2 <= tstop; t += 2) {
+            if (round(t, qa, ya, xa, qb, yb, xb)) return gp;
+            if (round(t + 1, qb, yb, xb, qa, ya, xa)) return gp;
         }
+        if (t < tstop) round(t, qa, ya, xa, qb, yb, xb);
         return gp;
     };
     // A meeting of the wavefronts 1 .. 15 (not a workgroup barrier: wavefront 0 goes on with its rounds): each waits
@@ -1104,7 +1136,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                 helpers_meet();
                 SP_T(3);
             }
-            if (wave != 0 && w + 1 < wend && stage_of(w + 1).head[4 * kWin + 32 + kWin] >= 0) {
+            if (wave != 0 && w + 1 < wend && stage_of(w + 1).head[kHeadCross] >= 0) {
                 if (LPW == 4) {
                     gather_q0_rows(view(w + 1), wave - 1, kCWaves, cho.q0, cho.yv);
 #ifdef OCO_SP_PROF2
@@ -1118,7 +1150,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             wg_sync_chain(wave);
             SP_T(5);
             pending = false;
-            have_q0 = w + 1 < wend && stage_of(w + 1).head[4 * kWin + 32 + kWin] >= 0;
+            have_q0 = w + 1 < wend && stage_of(w + 1).head[kHeadCross] >= 0;
         } else {
             if (chain) {
                 run_chain(v, q0, yv, bw, zb, 0, wl, 0);
@@ -1164,7 +1196,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         if (chain) {
             double m2 = 0.0;
             for (int wv = 0; wv < kSpWaves; ++wv) m2 += fold_part[wv][l];
-            n2 = m2;
+            hd = 0.5 * m2;
             sigma = 1.0; sf = 1.f; isf = 1.f;
         }
         if (threadIdx.x == 0) fold_t = -1;
@@ -1189,7 +1221,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         flush_z(view(wend - 1), chs[(wend - 1 - wbeg) & 1].zb);
         wg_sync();
     }
-    if (chain) { a.sigma[q] = sigma; a.n2[q] = n2; }
+    if (chain) { a.sigma[q] = sigma; a.n2[q] = hd > 0.0 ? 2.0 * hd : 0.0; }
     if (OPT && chain) { a.ha[q] = ha; a.hp[q] = hp; a.hx[q] = x2p; }
 #ifdef OCO_SP_PROF
     if (blockIdx.x == 0 && (threadIdx.x & 63) == 0)
