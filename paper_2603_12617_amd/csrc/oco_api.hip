@@ -393,6 +393,32 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
             m.n = len;
             return launch_meta(m, p.loss, st->side);
         }
+        // an event of the pool, recorded on the second stream / waited for by the call's stream
+        hipEvent_t marked = nullptr;
+        static hipError_t mark(void *ctx) {
+            MetaPipe &p = *static_cast<MetaPipe *>(ctx);
+            oco_state *st = p.st;
+            if (p.used == st->piece_ev.size()) {
+                hipEvent_t ev;
+                hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+                if (e != hipSuccess) return e;
+                try {
+                    st->piece_ev.push_back(ev);
+                } catch (...) {
+                    (void)hipEventDestroy(ev);
+                    return hipErrorOutOfMemory;
+                }
+            }
+            p.marked = st->piece_ev[p.used++];
+            return hipEventRecord(p.marked, st->side);
+        }
+        static hipError_t wait_mark(void *ctx) {
+            MetaPipe &p = *static_cast<MetaPipe *>(ctx);
+            if (!p.marked) return hipSuccess;
+            hipError_t e = hipStreamWaitEvent(p.st->stream, p.marked, 0);
+            p.marked = nullptr;
+            return e;
+        }
         hipError_t join() {
             if (!used) return hipSuccess;
             hipError_t e = hipEventRecord(st->join_ev, st->side);
@@ -405,7 +431,7 @@ int oco_run_rounds(oco_state *st, const oco_rounds *rd, int64_t t0, int64_t n)
     m.L = st->at<double>(l.off_L); m.regret = st->at<double>(l.off_regret);
     m.last = l.off_last ? st->at<double>(l.off_last) : nullptr;
     m.eps = c.eps; m.K = (int)c.K; m.R = (int)c.R; m.n = (int)n;
-    const PieceHook hook{&MetaPipe::piece, &pipe, &MetaPipe::beside};
+    const PieceHook hook{&MetaPipe::piece, &pipe, &MetaPipe::beside, &MetaPipe::mark, &MetaPipe::wait_mark};
     const bool overlap = st->side != nullptr && st->tune.get(OCO_OPT_META_BESIDE) != 0;
 
     if (sparse) {

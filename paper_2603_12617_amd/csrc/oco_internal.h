@@ -45,6 +45,10 @@ struct PieceHook {
     // Optional: a stream for work of the call that the round kernels neither wait for nor feed
     // (it starts after the work already on the call's stream, and what fn enqueues follows it).
     hipError_t (*beside)(void *ctx, hipStream_t *out) = nullptr;
+    // Optional, with `beside`: mark remembers what is on that stream now; after wait_mark the call's stream
+    // goes on only when that work is done (for work beside the round kernels that a later one of them needs).
+    hipError_t (*mark)(void *ctx) = nullptr;
+    hipError_t (*wait_mark)(void *ctx) = nullptr;
 };
 
 // Event pairs around the launches of a call's dominant kernel (benchmarks: the duration of that

@@ -217,7 +217,7 @@ static_assert(kHeadOffs == 4 * kWin && kHeadG01 == 4 * kWin + 32 && kHeadCross =
 
 __global__ void __launch_bounds__(1024) sparse_gram_kernel(const int32_t *col, const float *val, int nnz,
                                                           WinPlan plan, WinRec *recs, int optimistic,
-                                                          const int32_t *last_col, const float *last_val, int shares)
+                                                          const int32_t *last_col, const float *last_val, int shares, int wofs)
 {
     __shared__ unsigned int xm[kWin][2];
     __shared__ int xrowoff[kWin + 1];
@@ -227,7 +227,7 @@ __global__ void __launch_bounds__(1024) sparse_gram_kernel(const int32_t *col, c
     __shared__ unsigned int mk[kWin][2];
     __shared__ int rowoff[kWin + 1];
     __shared__ unsigned short pair_s[kWin * (kWin - 1) / 2], pair_t[kWin * (kWin - 1) / 2];
-    const int w = blockIdx.x;
+    const int w = (int)blockIdx.x + wofs;
     const int ws = plan.start(w), wl = plan.len(w);
     const int total = wl * nnz;
     const unsigned mdiv = ((1u << 18) + nnz - 1) / nnz;       // e / nnz == (e * mdiv) >> 18 for e < 4096
@@ -1276,8 +1276,20 @@ __global__ void __launch_bounds__(256) sparse_fold_kernel(float *V, const double
     if (!__any(sg < kSparseFoldSoft)) return;
     const float s = (float)sg;
     const int64_t stride = (int64_t)gridDim.x * 4;
-    for (int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); j < d; j += stride)
-        V[j * RKp + q] *= s;
+    // eight rows in flight per wavefront (one at a time, the pass runs at a fraction of the memory's speed)
+    for (int64_t j0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); j0 < d; j0 += 8 * stride) {
+        float vv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t j = j0 + u * stride;
+            vv[u] = j < d ? V[j * RKp + q] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t j = j0 + u * stride;
+            if (j < d) V[j * RKp + q] = vv[u] * s;
+        }
+    }
 }
 
 __global__ void __launch_bounds__(64) sparse_fold_finish_kernel(double *sigma, double *n2)
@@ -1389,11 +1401,6 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s, c
     // scratch: one record per window of the call
     const WinPlan plan{a.t0, a.n};
     const int nwin = plan.count();
-    hipLaunchKernelGGL(sparse_gram_kernel, dim3(nwin), dim3(1024), 0, s, a.col, a.val, a.nnz, plan,
-                       reinterpret_cast<WinRec *>(static_cast<char *>(a.scratch) + kProgBytes), a.optimistic, a.last_col, a.last_val,
-                       kSpWaves - 1);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
 
     // segments end at the multiples of kSegment of the horizon, which are window boundaries
     const int groups = (a.R * a.K + kWave - 1) / kWave;
@@ -1404,12 +1411,31 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s, c
     // the caller's per-segment work runs beside the following segments only while the window
     // kernel's workgroups leave at least half of the compute units idle
     if ((a.R * a.K + lpw - 1) / lpw > kBesideMaxWorkgroups) hook = nullptr;
+    // The pre-pass of the first segment's windows goes ahead of the round kernels; that of the others runs beside
+    // the first segment's rounds where the caller has a stream for it (the second launch then waits for it).
+    WinRec *recs = reinterpret_cast<WinRec *>(static_cast<char *>(a.scratch) + kProgBytes);
+    int nwin1 = 1;
+    while (nwin1 < nwin && a.t0 + plan.start(nwin1) < (a.t0 / kSegment + 1) * kSegment) ++nwin1;
+    const bool split = hook && hook->beside && hook->mark && hook->wait_mark && nwin1 < nwin;
+    const int nfirst = split ? nwin1 : nwin;
+    hipLaunchKernelGGL(sparse_gram_kernel, dim3(nfirst), dim3(1024), 0, s, a.col, a.val, a.nnz, plan, recs, a.optimistic,
+                       a.last_col, a.last_val, kSpWaves - 1, 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
     // the comparator's predictions feed the meta kernel only: beside the round kernels where
     // those leave room, else ahead of them
     {
         hipStream_t cs = s;
         if (hook && hook->beside) {
             e = hook->beside(hook->ctx, &cs);
+            if (e != hipSuccess) return e;
+        }
+        if (split) {
+            hipLaunchKernelGGL(sparse_gram_kernel, dim3(nwin - nfirst), dim3(1024), 0, cs, a.col, a.val, a.nnz, plan, recs,
+                               a.optimistic, a.last_col, a.last_val, kSpWaves - 1, nfirst);
+            e = hipGetLastError();
+            if (e == hipSuccess) e = hook->mark(hook->ctx);
             if (e != hipSuccess) return e;
         }
         const int64_t nthr = (int64_t)a.n * a.R;
@@ -1421,6 +1447,10 @@ hipError_t launch_sparse_rounds(const SparseArgs &a0, int loss, hipStream_t s, c
         const int64_t seg_end = ((a.t0 + plan.start(wbeg)) / kSegment + 1) * kSegment;   // absolute
         int wend = wbeg + 1;
         while (wend < nwin && a.t0 + plan.start(wend) < seg_end) ++wend;
+        if (split && wbeg == nfirst) {
+            e = hook->wait_mark(hook->ctx);
+            if (e != hipSuccess) return e;
+        }
         e = launch_window(a, loss, lpw, plan, wbeg, wend, s);
         if (e != hipSuccess) return e;
         const int64_t reached = a.t0 + plan.start(wend - 1) + plan.len(wend - 1);
