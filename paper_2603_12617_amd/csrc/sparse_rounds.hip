@@ -33,9 +33,11 @@
 //      (prediction, slope, step size b_t, norm, projection); the Gram terms
 //      <x_r, x_t> come from a pre-pass over the round stream and are almost
 //      all zero (two sparse rows rarely share a column); predictions go to LDS;
-//   C  V[col] += -b_t x_t[col] as no-return float atomics, the entries split
-//      over wavefronts by column so that the adds to one address are issued
-//      by one wavefront in round order (bitwise reproducible), and the
+//   C  V[col] += -b_t x_t[col], the entries split over wavefronts by column so
+//      that the updates of one address are issued by one wavefront in round
+//      order (bitwise reproducible): no-return float atomics, or, with four
+//      learners per workgroup, a plain read-modify-write of the 16 bytes of a
+//      row by one lane where the column occurs once in the window; and the
 //      window's predictions to Z.
 // B is the critical path.  Where the LDS has room for the buffers of three
 // windows, A of the next window and C of the previous one run beside B of the

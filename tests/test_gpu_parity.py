@@ -376,6 +376,24 @@ def test_sparse_rounds_without_the_window_pipeline(lpw):
             np.testing.assert_allclose(piped[k], plain[k], rtol=0, atol=2e-6 * scale, err_msg=k)
 
 
+@pytest.mark.parametrize("over", [
+    dict(T=900, R=16, d=1 << 16, K=8, wstar_nnz=64),                       # 32 workgroups of 4 learners + 8 that fetch
+    dict(T=5000, R=8, d=1 << 15, K=4, nnz=16, wstar_nnz=64),               # 8 + 8, two launch segments
+    dict(T=400, R=4, d=1 << 14, K=16, wstar_nnz=64, optimistic=1),         # 16 + 8, optimistic update
+])
+def test_sparse_workgroups_that_fetch_rows_ahead_change_no_bit(over):
+    """Small sparse problems get one more workgroup per XCD that loads the rows of coming windows
+    into L2 ahead of the working ones.  It only reads: results with and without it are the same bits."""
+    wl = WL.make("c5", **over)
+    data = WL.generate(wl)
+    print("case c5 fetch", over, flush=True)
+    on = _gpu(wl, data, options=dict(sparse_fetch=1))
+    off = _gpu(wl, data, options=dict(sparse_fetch=0))
+    for k in ("regret", "L", "W", "p", "wbar"):
+        assert np.array_equal(on[k], off[k]), k
+    _check(wl, data, on, norm_every=0, label="c5 fetch %s" % over)
+
+
 @pytest.mark.parametrize("lpw", [4, 16, 64])
 def test_sparse_rounds_with_steps_far_larger_than_the_ball(lpw):
     """Steps hundreds of times the radius make the lazy scale shrink by a constant factor every
