@@ -78,13 +78,6 @@
 namespace oco {
 namespace {
 
-#ifndef OCO_SP_NI
-#define OCO_SP_NI 5
-#endif
-#ifndef OCO_SP_LD4
-#define OCO_SP_LD4 2
-#endif
-
 template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
 {
     if (LOSS == 0) return 1.0f;
@@ -92,35 +85,26 @@ template <int LOSS> __device__ __forceinline__ float slope(float z, float y)
     return -y * __builtin_amdgcn_rcpf(1.0f + __expf(y * z));
 }
 
-// V is updated by float atomics, which execute in L2: every read of V in the window kernel
-// goes to L2 as well (a device-scope relaxed load never hits in the per-CU cache).
+// V is updated by float atomics, which execute in L2, or by plain stores, which write through to it: every
+// read of V in the window kernel goes to L2 as well, past the compute unit's own cache.  (Plain cached loads with
+// that cache dropped once per window measured slower: 23.7 against 20.6 ms on the largest sparse workload.)
 __device__ __forceinline__ float ldv(const float *p)
 {
-#ifdef OCO_SP_PLAINLD
-    return *p;
-#else
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-#endif
-}
-__device__ __forceinline__ void drop_cached_v()
-{
-#if defined(OCO_SP_PLAINLD) || OCO_SP_LD4 < 2
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-#endif
 }
 typedef float f4 __attribute__((ext_vector_type(4)));
-// 16 bytes of a row of V (four neighbouring learners) by one lane.
+// 16 bytes of a row of V (four neighbouring learners) by one lane, the same kind of load.  The compiler knows
+// nothing of a load inside an asm statement: the caller keeps the result's registers reserved until the load has
+// returned, by naming them in the s_waitcnt statement it waits with (wait_ldv4).
 __device__ __forceinline__ f4 ldv4(const float *p)
 {
-#if OCO_SP_LD4 == 0
-    return *reinterpret_cast<const f4 *>(p);
-#elif OCO_SP_LD4 == 1
-    return __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
-#else
     f4 r;
     asm volatile("global_load_dwordx4 %0, %1, off sc0" : "=v"(r) : "v"(p) : "memory");
     return r;
-#endif
+}
+__device__ __forceinline__ void wait_ldv4(f4 &a, f4 &b, f4 &c)
+{
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c) : : "memory");
 }
 // x + (x of the lane that `ctrl` pairs this lane with), inside rows of 16 lanes
 template <int CTRL> __device__ __forceinline__ float add_dpp(float x)
@@ -161,10 +145,7 @@ constexpr size_t kLdsBytes = 160 * 1024;     // LDS of a gfx950 compute unit
 constexpr int kMaxCross = 64;                // most round pairs across a window boundary that are corrected
 constexpr int kProgBytes = 4096;             // head of the scratch: the window each workgroup has reached (one int each)
 constexpr int kFetchMaxWorkgroups = 64;      // window grids up to this size get workgroups that fetch rows into L2 ahead of them
-#ifndef OCO_FETCH_AHEAD
-#define OCO_FETCH_AHEAD 3
-#endif
-constexpr int kFetchAhead = OCO_FETCH_AHEAD;               // ... the rows of window x once every workgroup has reached window x - 3
+constexpr int kFetchAhead = 3;               // ... the rows of window x once every workgroup has reached window x - 3
 constexpr int kFetchSpins = 4000;            // ... or after this many looks at the progress words (a hint never waits for good)
 
 // (A build with -DOCO_SP_PROF keeps wall-clock sums (10 ns ticks) of the phases of workgroup 0's window loop in
@@ -703,7 +684,6 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         constexpr int RA = decltype(ra_tag)::value, BK = decltype(bk_tag)::value;   // RA * BK gathers in flight
         const int NL = (nnz + EPI - 1) / EPI;
         const int wl = v.wl;
-        drop_cached_v();
         for (int tg = wv; tg < wl; tg += RA * nwv) {
             float acc[RA][4], yl[RA];
 #pragma unroll
@@ -771,7 +751,6 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         const int wl = v.wl;
         const int ngroups = (wl + rpi - 1) / rpi;
         const float *Vb = a.V + (int64_t)blk * LPW;
-        drop_cached_v();
         for (int g0 = wv; g0 < ngroups; g0 += NB * nwv) {
             int ci[NB];
             float xv[NB], yl[NB];
@@ -789,9 +768,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                 vv[u] = ldv4(Vb + (int64_t)ci[u] * a.RKp);
                 yl[u] = yrow && t < wl ? yrow[v.ws + t] : 0.f;
             }
-#if OCO_SP_LD4 == 2
-            asm volatile("s_waitcnt vmcnt(0)" : "+v"(vv[0]), "+v"(vv[1]), "+v"(vv[2]), "+v"(yl[0]), "+v"(yl[1]), "+v"(yl[2]) : : "memory");
-#endif
+            wait_ldv4(vv[0], vv[1], vv[2]);
             SP_T(pslot);
 #pragma unroll
             for (int u = 0; u < NB; ++u) {
@@ -851,7 +828,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
         if (wave == 0) return;
         const int beg = __builtin_amdgcn_readfirstlane(v.offs[wave - 1]);
         const int end = __builtin_amdgcn_readfirstlane(v.offs[wave]);
-        constexpr int NI = OCO_SP_NI;                        // instructions per batch
+        constexpr int NI = 5;                                // instructions per batch
         for (int k0 = beg; k0 < end; k0 += NI * EPI) {
             int cc[NI];
             float xv[NI];
@@ -944,9 +921,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                 row[n] = Vb + (int64_t)cc[n] * a.RKp;
                 cur[n] = ldv4(row[n]);
             }
-#if OCO_SP_LD4 == 2
-            asm volatile("s_waitcnt vmcnt(0)" : "+v"(cur[0]), "+v"(cur[1]), "+v"(cur[2]) : : "memory");
-#endif
+            wait_ldv4(cur[0], cur[1], cur[2]);
 #pragma unroll
             for (int n = 0; n < NI; ++n) {
                 const int t = (int)(((unsigned)(pe[n] & 0xFFF) * mdiv) >> 18);
@@ -1141,9 +1116,6 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             if (wave != 0 && w + 1 < wend && stage_of(w + 1).head[kHeadCross] >= 0) {
                 if (LPW == 4) {
                     gather_q0_rows(view(w + 1), wave - 1, kCWaves, cho.q0, cho.yv);
-#ifdef OCO_SP_PROF2
-                    gather_q0_rows(view(w + 1), wave - 1, kCWaves, cho.q0, cho.yv, 12);   // the same again, rows now in L2
-#endif
                 } else
                     gather_q0(std::integral_constant<int, 5>(), std::integral_constant<int, LPW >= 16 ? 4 : (LPW == 8 ? 4 : 2)>(),
                               view(w + 1), wave - 1, kCWaves, cho.q0, cho.yv);
@@ -1173,8 +1145,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             for (int rd = (int)threadIdx.x / LPW; rd <= ft; rd += kSpWaves * EPI) bw[rd][l] = 0.f;   // applied
             const float fs = fold_sf[l];
             const int64_t nslots = kSpWaves * EPI;
-            drop_cached_v();
-            double m2 = 0.0;
+                double m2 = 0.0;
             for (int64_t j0 = wave * EPI + e; j0 < a.d; j0 += 4 * nslots) {
                 float vv[4];
 #pragma unroll
