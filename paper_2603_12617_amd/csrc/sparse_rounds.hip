@@ -1020,14 +1020,19 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             }
             return false;
         };
-        // two rounds per turn of the loop: the values read ahead alternate between two sets of registers
+        // four rounds per turn of the loop: the values read ahead alternate between two sets of registers
         float qa = q0[tstart][l], ya = yv[tstart][l], xa = x2h[tstart], qb, yb, xb;
         int t = tstart;
-        for (; t + 2 <= tstop; t += 2) {
+        for (; t + 4 <= tstop; t += 4) {
             if (round(t, qa, ya, xa, qb, yb, xb)) return gp;
             if (round(t + 1, qb, yb, xb, qa, ya, xa)) return gp;
+            if (round(t + 2, qa, ya, xa, qb, yb, xb)) return gp;
+            if (round(t + 3, qb, yb, xb, qa, ya, xa)) return gp;
         }
-        if (t < tstop) round(t, qa, ya, xa, qb, yb, xb);
+        for (; t < tstop; ++t) {
+            if (round(t, qa, ya, xa, qb, yb, xb)) return gp;
+            qa = qb; ya = yb; xa = xb;
+        }
         return gp;
     };
     // A meeting of the wavefronts 1 .. 15 (not a workgroup barrier: wavefront 0 goes on with its rounds): each waits
