@@ -574,7 +574,9 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
 #ifdef OCO_SP_PROF
         unsigned long long pf_[4] = {0, 0, 0, 0}, pl_ = wall_clock64();
 #endif
+        __shared__ int fetch_over;
         for (int w = wbeg + 1; w < wend; ++w) {
+            if (threadIdx.x == 0) fetch_over = 0;
             if (threadIdx.x == 0 && w > wbeg + 2) {
                 int m = 0;
                 for (int spin = 0; spin < kFetchSpins; ++spin) {
@@ -586,6 +588,7 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
                     if (m >= w - kFetchAhead) break;
                     __builtin_amdgcn_s_sleep(32);
                 }
+                fetch_over = m >= wend - 1;                  // every working workgroup is in its last window: nothing left to fetch for
 #ifdef OCO_SP_PROF
                 pf_[2] += (unsigned long long)(w - m + 1000);
                 pf_[3] += 1;
@@ -595,6 +598,9 @@ __global__ void __launch_bounds__(kSpWaves *kWave) sparse_window_kernel(const Sp
             if (threadIdx.x == 0) { const unsigned long long n_ = wall_clock64(); pf_[0] += n_ - pl_; pl_ = n_; }
 #endif
             __syncthreads();
+            const bool over = fetch_over != 0;
+            __syncthreads();                                 // (thread 0 writes the flag again in the next turn)
+            if (over) break;
             const int ws = plan.start(w), total = plan.len(w) * a.nnz * lines;
             for (int e0 = threadIdx.x; e0 < total; e0 += 4 * (int)blockDim.x) {
                 const float *pv[4];
