@@ -378,6 +378,9 @@ def main():
             for label, opts in (("c4_register_kernel (one wavefront per learner, iterate in registers)", dict(dense_path=1)),
                                 ("c4_window_kernel_iterates_in_registers", dict(dense_path=2, window_resident=1))):
                 others[label] = summary_entry(run_workload("c4", 2, 1, WL, B, torch, options=opts), label)
+        # c5 without the workgroups that fetch the rows of coming windows into L2 ahead of the working ones
+        label = "c5_without_fetching_workgroups"
+        others[label] = summary_entry(run_workload("c5", 2, 1, WL, B, torch, options=dict(sparse_fetch=0)), label)
         for name in ("c3", "c4", "c5"):    # the optimistic two-step update (Eq. (3)) on the same streams
             key = name + "_optimistic"
             others[key] = summary_entry(run_workload(name, 2, 1, WL, B, torch, optimistic=True), key)
