@@ -56,5 +56,29 @@ def build(verbose: bool = False, extra_flags=(), lib: str = LIB, tag: str = "") 
     return lib
 
 
+PROBES = ["row_rate_probe.hip", "fetch_ahead_probe.hip"]
+
+
+def build_probes() -> list:
+    """Compile the stand-alone measurement probes under csrc/probes/ into _build/probes/ (executables
+    that time memory access patterns on one GPU; the library does not use them)."""
+    out_dir = os.path.join(OBJ, "probes")
+    os.makedirs(out_dir, exist_ok=True)
+    cc = _hipcc()
+    outs = []
+    for src in PROBES:
+        exe = os.path.join(out_dir, src.replace(".hip", ""))
+        cmd = [cc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               os.path.join(CSRC, "probes", src), "-o", exe]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            sys.stderr.write(res.stdout + res.stderr)
+            raise RuntimeError("hipcc failed on " + src)
+        outs.append(exe)
+    return outs
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))
+    if "--probes" in sys.argv:
+        print(build_probes())
