@@ -416,13 +416,20 @@ dense_rounds_kernel(const DenseArgs a)
         }
     };
 
-    // one round: consumes xc = x_t, fills xn = x_{t+1}
-    auto round = [&](int t, float (&xc)[NV][VW], float (&xn)[NV][VW]) {
-        if ((t & 63) == 0) {
-            if (yrow) yreg = (t + lane < n) ? yrow[t + lane] : 0.f;
-            x2reg = (t + lane < n) ? x2row[t + lane] : 0.f;
-            if (OPT) g01reg = (t + lane < n) ? g01row[t + lane] : 0.f;
-        }
+    // Labels, ||x||^2 and <x_{t-1}, x_t> of the 64 rounds from t on, a lane each (t is a multiple of 64), and the
+    // predictions of the rounds (t & ~63) .. t to Z: both happen at tile boundaries only (a tile's length divides
+    // 64), so the tile loop does them and a round does not test for them.
+    auto load_round_scalars = [&](int t) {
+        if (yrow) yreg = (t + lane < n) ? yrow[t + lane] : 0.f;
+        x2reg = (t + lane < n) ? x2row[t + lane] : 0.f;
+        if (OPT) g01reg = (t + lane < n) ? g01row[t + lane] : 0.f;
+    };
+    auto flush_predictions = [&](int t) {
+        const int tb = t & ~63;
+        if (tb + lane <= t) zrow[(int64_t)(tb + lane) * a.zl.zs_t] = zreg;
+    };
+    // one round: consumes xc = x_t, fills xn = x_{t+1} from xnext; remeasure: ||v||^2 is summed afresh after the step
+    auto round = [&](int t, const V *xnext, bool remeasure, float (&xc)[NV][VW], float (&xn)[NV][VW]) {
         const float yt = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(yreg), t & 63));
         const float x2t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x2reg), t & 63));
         // the prediction that is played and scored: plain, z = <w_t, x_t>; optimistic,
@@ -445,7 +452,7 @@ dense_rounds_kernel(const DenseArgs a)
 #pragma unroll
                 for (int e = 0; e < VW; ++e) wv[m][e] *= sigma;
             n2 *= sigma * sigma;
-            qv = z;
+            qv = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(z)));   // (uniform, like the sum it replaces)
             sigma = 1.f;
             isig = 1.f;
             thr = D2;
@@ -455,9 +462,10 @@ dense_rounds_kernel(const DenseArgs a)
         const float b = step * isig;
         const float qold = qv;
         float aq[VW];
-        if constexpr (kOneRowSet<NPL>) pass_one(b, xrow(t + 1), xc, aq);
-        else pass(b, xrow(t + 1), xc, xn, aq);
-        if (((phase + t) & 63) == 63) {                  // re-measure ||v||^2 exactly
+        if constexpr (kOneRowSet<NPL>) pass_one(b, xnext, xc, aq);
+        else pass(b, xnext, xc, xn, aq);
+        n2 = fmaxf(fmaf(b, fmaf(b, x2t, -2.f * qv), n2), 0.f);
+        if (remeasure) {                                 // re-measure ||v||^2 exactly (replaces the identity's value)
             float an[VW];
 #pragma unroll
             for (int e = 0; e < VW; ++e) an[e] = 0.f;
@@ -466,8 +474,6 @@ dense_rounds_kernel(const DenseArgs a)
 #pragma unroll
                 for (int e = 0; e < VW; ++e) an[e] = fmaf(wv[m][e], wv[m][e], an[e]);
             n2 = wave_sum(combine<VW>(an));
-        } else {
-            n2 = fmaxf(fmaf(b, fmaf(b, x2t, -2.f * qv), n2), 0.f);
         }
         qv = wave_sum(dot_total(aq));                      // <v, x_{t+1}>
         const float nrm = n2;                            // ||v||^2
@@ -483,26 +489,32 @@ dense_rounds_kernel(const DenseArgs a)
             ha = step;
             x2prev = x2t;
         }
-        if ((t & 63) == 63 || t == n - 1) {              // flush the z of rounds (t & ~63) .. t
-            const int tb = t & ~63;
-            if (tb + lane <= t) zrow[(int64_t)(tb + lane) * a.zl.zs_t] = zreg;
-        }
     };
 
+    static_assert(64 % RT == 0, "tiles do not straddle the 64-round groups of labels and predictions");
     for (int k = 0; k < ntiles; ++k) {
         if (k + 2 < ntiles) issue_tile(k + 2);
-        const int rmax = min(RT, n - k * RT);
+        const int t0 = k * RT;
+        const int rmax = min(RT, n - t0);
+        if ((t0 & 63) == 0) load_round_scalars(t0);
+        // rows of this tile follow one another in the ring; the row after its last is the next tile's first
+        const float *rows = ring + (k % kRing) * TILE, *rows_next = ring + ((k + 1) % kRing) * TILE;
+        const int rm = (63 - phase - t0) & 63;               // the round of this tile (if < RT) after which ||v||^2 is re-measured
         if constexpr (kOneRowSet<NPL>) {
 #pragma unroll 1
-            for (int rr = 0; rr < rmax; ++rr) round(k * RT + rr, xa, xa);
+            for (int rr = 0; rr < rmax; ++rr)
+                round(t0 + rr, reinterpret_cast<const V *>(rr + 1 < RT ? rows + (rr + 1) * DP : rows_next), rr == rm, xa, xa);
         } else {
 #pragma unroll 1
             for (int rr = 0; rr < rmax; rr += 2) {
-                const int t = k * RT + rr;
-                round(t, xa, xb);
-                if (rr + 1 < rmax) round(t + 1, xb, xa);
+                const int t = t0 + rr;
+                round(t, reinterpret_cast<const V *>(rows + (rr + 1) * DP), rr == rm, xa, xb);          // (RT is even)
+                if (rr + 1 < rmax)
+                    round(t + 1, reinterpret_cast<const V *>(rr + 2 < RT ? rows + (rr + 2) * DP : rows_next), rr + 1 == rm, xb, xa);
             }
         }
+        const int tl = t0 + rmax - 1;
+        if ((tl & 63) == 63 || tl == n - 1) flush_predictions(tl);
         tile_sync();   // every wavefront has drained its copies: tile k+1 is complete; tile k may be overwritten
     }
 
