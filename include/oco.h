@@ -182,7 +182,8 @@ typedef enum {
     OCO_OPT_WINDOW_RESIDENT = 9, /* (~) windowed dense path, where the iterates live between windows:
                                     0: HBM, two tiles of 16 learners per workgroup; 1: registers of the
                                     workgroup (d <= 4096, else as 0); 2: HBM, one tile, 16 wavefronts;
-                                    3: HBM, four tiles, operands brought to LDS by loading wavefronts
+                                    3: HBM, four tiles, operands brought to LDS by loading wavefronts;
+                                    4: registers, two tiles per workgroup (d <= 1024, else as 0)
                                     (with the optimistic update 1 and 2 are taken as 0) */
     OCO_OPT_SPARSE_FETCH = 10,   /* 0: no workgroups that fetch the rows of coming sparse windows into L2 ahead of
                                     the working ones (the library adds them where the grid leaves most of the chip idle) */

@@ -35,8 +35,11 @@
 // compute unit draws only about 21 bytes per clock from L2, which is what bounds the sweep.
 // Variants (OCO_OPT_WINDOW_RESIDENT): the iterates of one tile held in the registers of the
 // workgroup for a whole launch (d <= 4096: eight wavefronts, each with every eighth block, in
-// the layout the matrix instruction writes: a lane holds 4 coordinates of one learner), and one
-// streamed tile worked by sixteen wavefronts.
+// the layout the matrix instruction writes: a lane holds 4 coordinates of one learner); those of
+// two tiles (d <= 1024; the default for 512 <= d <= 1024: a window's time is then the dependent
+// rounds plus the sweep of the wavefronts that ran them, and without the iterates' loads and stores
+// the sweep is bound by the matrix instructions of each SIMD); and one streamed tile worked by
+// sixteen wavefronts.
 //
 // v_mfma_f32_16x16x4_f32 computes D = A B + C with A 16x4, B 4x16: lane l supplies
 // A[l % 16][l / 16] and B[l / 16][l % 16] and holds D[4 (l / 16) + r][l % 16] in register r.
@@ -84,7 +87,10 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 // read back through oco_debug_win_prof: how the figures per phase in the comments below were taken.)
 #ifdef OCO_WIN_PROF
 __device__ unsigned long long g_win_prof[8];
-#define PROF_T(i) do { if (threadIdx.x == 0) { const unsigned long long now_ = wall_clock64(); prof_[i] += now_ - last_; last_ = now_; } } while (0)
+#ifndef OCO_WIN_PROF_TID
+#define OCO_WIN_PROF_TID 0
+#endif
+#define PROF_T(i) do { if (threadIdx.x == OCO_WIN_PROF_TID) { const unsigned long long now_ = wall_clock64(); prof_[i] += now_ - last_; last_ = now_; } } while (0)
 #else
 #define PROF_T(i) do { } while (0)
 #endif
@@ -430,12 +436,12 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
                                                                   const float *xq, const float *xu, float *misc,
                                                                   WinPlanD plan, int w0, int nw)
 {
-    static_assert(!(RES && MT != 1), "iterates in registers: one tile per workgroup");
+    static_assert(!RES || MT == 1 || (MT == 2 && NW == 8 && NB == 9), "iterates in registers: one tile, or two on eight wavefronts");
     using Lds = LdsT<NW, MT>;
     using GT = typename Lds::G;
     using ST = typename Lds::S;
     // -Bm in registers for the whole sweep, or (where registers are short) re-read from LDS per block
-    constexpr bool BMR = RES && NB <= 8;
+    constexpr bool BMR = RES && NB <= 8 && MT == 1;
     extern __shared__ __align__(16) char lds[];
     const int d = a.d, K = a.K;
     const int nq = a.R * K;
@@ -458,6 +464,31 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
             return 22 * (i / 3) + (wave - 2) + 8 * (i % 3);
         }
         return wave + NW * i;
+    };
+    // Which wavefront runs the dependent rounds of which tile (-1: of none), and the number of a wavefront
+    // among those that run none.  Two tiles in registers: wavefronts 0 and 4, which share a SIMD (a workgroup's
+    // wavefronts are dealt to the four SIMDs in turn), so that the rounds do not share theirs with a wavefront
+    // of matrix instructions (beside one they take 16 us per window instead of 10) and the other three SIMDs
+    // have two sweeping wavefronts each.
+    constexpr bool PAIR = RES && MT == 2;
+    auto rounds_tile = [&](int wave) __attribute__((always_inline)) {
+        if (PAIR) return (wave & 3) == 0 ? wave >> 2 : -1;
+        return wave < MT ? wave : -1;
+    };
+    auto other_index = [&](int wave) __attribute__((always_inline)) {
+        if (PAIR) return wave < 4 ? wave - 1 : wave - 2;
+        return wave - MT;
+    };
+    // Iterates in registers: the b-th block a wavefront keeps.  One tile: wave, wave + NW, ...  Two tiles
+    // (eight wavefronts, NB = 9, at most 64 blocks): the six wavefronts without dependent rounds keep blocks
+    // 0 .. 53, nine each; the two with them sweep only when their rounds are done and keep blocks 54 .. 63:
+    // wavefront 0, whose rounds the SIMD works first, seven of them, wavefront 4 three.
+    auto kept_block = [&](int wave, int b) __attribute__((always_inline)) {
+        if (PAIR) {
+            if ((wave & 3) != 0) return other_index(wave) + 6 * b;
+            return wave == 0 ? (b < 7 ? 54 + b : (1 << 20)) : (b < 3 ? 61 + b : (1 << 20));
+        }
+        return wave + NW * b;
     };
     // a tile's iterates: 16 coordinates x 16 learners per block, transposed
     auto ld_block = [&](const Geo<MT> &g, int m, int blk) __attribute__((always_inline)) {
@@ -565,12 +596,12 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
     double n2_begin = 0.0;      // what the previous window's rounds started from
     bool proj_prev = true;      // whether they projected this learner (then n2 was reset to D^2 on the way)
     Hint hint{0.f, 0.f, 0.f};   // optimistic update: carried from round to round, window to window, call to call
-    f4 V[RES ? NB : 1];
+    f4 V[RES ? NB : 1][MT];     // iterates in registers: block wave + NW b of every tile
     f4 accq[MT][4];             // this wavefront's shares of W_k X_{k+1}^T; tile 0's go to LDS at once, the others wait their turn
     {
         const Geo<MT> g = make_geo<MT>((int)threadIdx.x, a);
-        const int q_ch = q_base + g.wave * kM + (g.lane >> 2);
-        if (g.wave < MT && q_ch < nq) {
+        const int q_ch = q_base + rounds_tile(g.wave) * kM + (g.lane >> 2);
+        if (rounds_tile(g.wave) >= 0 && q_ch < nq) {
             eta = a.eta[q_ch % K];
             pmul = (double)a.sigma[q_ch];
             n2 = a.n2[q_ch] * pmul * pmul;                      // ||w||^2 of the iterate itself
@@ -583,7 +614,9 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
         }
         if (RES) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) V[b] = ld_block(g, 0, g.wave + NW * b);
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int m = 0; m < MT; ++m) V[b][m] = ld_block(g, m, kept_block(g.wave, b));
         }
         // ---- prologue: the stored iterates times the rows of the first two windows -----------------
         f4 acc0[MT][4];
@@ -615,9 +648,8 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
         if constexpr (RES) {
             static_for<NB>([&](auto bc) __attribute__((always_inline)) {
                 constexpr int b = decltype(bc)::value;
-                const int blk = g.wave + NW * b;
-                f4 vb[1] = {V[b]};
-                if (blk < nblk) q_of(vb, blk);
+                const int blk = kept_block(g.wave, b);
+                if (blk < nblk) q_of(V[b], blk);
             });
         } else {
             for (int i = 0, blk = nth_block(g.wave, 0); blk < nblk; blk = nth_block(g.wave, ++i)) {
@@ -698,7 +730,8 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
         }
         __syncthreads();                                         // (B)
         PROF_T(1);
-        if (wave_w < MT) {
+        const int tile_w = rounds_tile(wave_w);
+        if (tile_w >= 0) {
             if (rounds) {
                 const int lane = tid_w & 63;
                 if (k >= 2) {
@@ -707,16 +740,16 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
                     // rounds added to every squared norm, and every projection among them scaled it by f^2
                     // (to first order), so F_{k-1}^2 of it is still in the iterate and missing from n2.  The
                     // next projection then removes it from the iterate as well.
-                    n2 = fma(measured_n2(wave_w, lane >> 2) - n2_begin, pmul * pmul, n2);
+                    n2 = fma(measured_n2(tile_w, lane >> 2) - n2_begin, pmul * pmul, n2);
                     n2 = n2 > 0.0 ? n2 : 0.0;
                 }
                 n2_begin = n2;
                 const double fscale = k == 0 ? pmul : 1.0;
-                pmul = chain_window<LOSS, Lds, OPT>(lds, k & 1, wave_w, lane, plan.len(w0 + k), eta, (double)a.D, pmul, fscale,
+                pmul = chain_window<LOSS, Lds, OPT>(lds, k & 1, tile_w, lane, plan.len(w0 + k), eta, (double)a.D, pmul, fscale,
                                                        n2, proj_prev, &hint);
             }
         } else {
-            const int tid_o = tid_w - MT * kWave, nthr_o = (NW - MT) * kWave;
+            const int tid_o = other_index(wave_w) * kWave + (tid_w & 63), nthr_o = (NW - MT) * kWave;
             // beside the dependent rounds: the next window's labels and Gram table into the other buffer
             if (more) stage_chain_inputs(tid_o, nthr_o, k + 1);
             // ... and the predictions of window k - 1 to Z (a learner's rounds contiguous)
@@ -777,11 +810,11 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
                     for (int m = 0; m < MT; ++m) in.vb[m] = ld_block_nb(g, m, b);
                 }
             };
-            auto compute = [&](BlkIn &in, f4 &vreg, int blk) __attribute__((always_inline)) {
+            auto compute = [&](BlkIn &in, f4 (&vreg)[MT], int blk) __attribute__((always_inline)) {
                 f4 vb[MT], vo[MT];                               // per tile two chains of eight dependent instructions
 #pragma unroll
                 for (int m = 0; m < MT; ++m) {
-                    vb[m] = RES ? vreg : in.vb[m];
+                    vb[m] = RES ? vreg[m] : in.vb[m];
                     vo[m] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int r = 0; r < 4; ++r) vb[m][r] *= F[m];
@@ -801,7 +834,7 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
                     for (int r = 0; r < 4; ++r) vb[m][r] += vo[m][r];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) nn[m] = fmaf(vb[m][r], vb[m][r], nn[m]);
-                    if (RES) vreg = vb[m]; else st_block_nb(g, m, blk, vb[m]);
+                    if (RES) vreg[m] = vb[m]; else st_block_nb(g, m, blk, vb[m]);
                 }
                 if (more) {
 #pragma unroll
@@ -813,16 +846,16 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
                                 acc[m][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.xq[rb][r], vb[m][r], acc[m][rb], 0, 0, 0);
                 }
             };
-            f4 none;
+            f4 none[MT];
             if constexpr (RES) {
                 // The round rows of the next block are on their way while the matrix instructions of the
                 // current block run.
                 BlkIn in[2];
-                load_in(in[0], g.wave);
+                load_in(in[0], kept_block(g.wave, 0));
                 static_for<NB>([&](auto bc) __attribute__((always_inline)) {
                     constexpr int b = decltype(bc)::value;
-                    const int blk = g.wave + NW * b;
-                    if (b + 1 < NB) load_in(in[(b + 1) & 1], blk + NW);
+                    const int blk = kept_block(g.wave, b);
+                    if (b + 1 < NB) load_in(in[(b + 1) & 1], kept_block(g.wave, b + 1));
                     __builtin_amdgcn_sched_barrier(0);
                     if (blk < nblk) compute(in[b & 1], V[b], blk);
                     __builtin_amdgcn_sched_barrier(0);
@@ -877,7 +910,7 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
         PROF_T(5);
     }
 #ifdef OCO_WIN_PROF
-    if (threadIdx.x == 0 && blockIdx.x == 0)
+    if (threadIdx.x == OCO_WIN_PROF_TID && blockIdx.x == 0)
         for (int i = 0; i < 8; ++i) g_win_prof[i] = prof_[i];
 #endif
 
@@ -886,13 +919,15 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
         const Geo<MT> g = make_geo<MT>((int)threadIdx.x, a);
         if (RES) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) st_block(g, 0, g.wave + NW * b, V[b]);
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int m = 0; m < MT; ++m) st_block(g, m, kept_block(g.wave, b), V[b][m]);
         }
         __syncthreads();
-        const int q_ch = q_base + g.wave * kM + (g.lane >> 2);
-        if (g.wave < MT && (g.lane & 3) == 0 && q_ch < nq) {
+        const int q_ch = q_base + rounds_tile(g.wave) * kM + (g.lane >> 2);
+        if (rounds_tile(g.wave) >= 0 && (g.lane & 3) == 0 && q_ch < nq) {
             a.sigma[q_ch] = 1.f;
-            a.n2[q_ch] = measured_n2(g.wave, g.lane >> 2);
+            a.n2[q_ch] = measured_n2(rounds_tile(g.wave), g.lane >> 2);
             if (OPT) { a.ha[q_ch] = hint.ha; a.hp[q_ch] = hint.hp; }
         }
     }
@@ -1304,10 +1339,16 @@ using WindowKernel = void (*)(const DenseArgs, const float *, const float *, con
                               int);
 
 // mode 0: iterates in registers (8 wavefronts, one tile); 1: streamed, two tiles per workgroup
-// (8 wavefronts); 2: streamed, one tile, 16 wavefronts
+// (8 wavefronts); 2: streamed, one tile, 16 wavefronts; 3: four tiles, loading wavefronts; 4: iterates
+// of two tiles in registers (8 wavefronts, d <= 1024)
 // (opt: the optimistic update, built into the two kernels the launcher picks by itself)
 template <int LOSS> WindowKernel pick_window_kernel(int nblk, int mode, bool opt, int *waves, int *tiles, int *lds_bytes)
 {
+    if (mode == 4) {
+        *waves = kNW8; *tiles = 2; *lds_bytes = LdsT<kNW8, 2>::total;
+        if (opt) return dense_window_kernel<LOSS, 9, true, kNW8, 2, true>;
+        return dense_window_kernel<LOSS, 9, true, kNW8, 2>;
+    }
     if (opt) {
         if (mode == 3) {
             *waves = kQW + kQL; *tiles = kQT; *lds_bytes = LdsQ::total;
@@ -1404,21 +1445,25 @@ hipError_t launch_dense_window(const DenseArgs &a0, int loss, hipStream_t s, con
         if (e != hipSuccess) return e;
     }
     // where the iterates live: OCO_OPT_WINDOW_RESIDENT 1 registers (d <= 4096), 0 streamed (two tiles per
-    // workgroup), 2 streamed (one tile, sixteen wavefronts), 3 streamed with loading wavefronts (four tiles).
+    // workgroup), 2 streamed (one tile, sixteen wavefronts), 3 streamed with loading wavefronts (four tiles),
+    // 4 registers, two tiles per workgroup (d <= 1024).
     // Unset: streamed, two tiles -- on c4 as fast as the registers (every round row a wavefront loads
-    // serves two tiles), on c3 half as many workgroups -- or, with at least four tiles per compute unit's
+    // serves two tiles), on c3 half as many workgroups --, two tiles in registers where they fit and the
+    // wavefronts have several blocks each (c3: 41.8 against 46.4 ms), or, with at least four tiles per compute unit's
     // workgroup on every one of 256 compute units and wide rows, the loading wavefronts (c4: 67.4 against
     // 70.4 ms; c3, bound by the dependent rounds, which that kernel does not overlap: 101 against 47.5 ms).
     const int64_t ropt = a.tune->get(OCO_OPT_WINDOW_RESIDENT);
     const bool fits = a.d <= 16 * kNW8 * 32;
     const bool many = (int64_t)a.R * a.K >= 1024 * kM && nblk >= 128;
-    int mode = (ropt == 1 && fits) ? 0 : ropt == 2 ? 2 : (ropt == 3 || (ropt < 0 && many)) ? 3 : 1;
-    if (a.optimistic && mode != 3) mode = 1;                 // (the optimistic update: two of the kernels only)
-    const bool resident = mode == 0;
+    const bool fits2 = a.d <= 16 * kNW8 * 8;
+    int mode = (ropt == 1 && fits) ? 0 : ropt == 2 ? 2 : (ropt == 3 || (ropt < 0 && many)) ? 3
+               : ((ropt == 4 || (ropt < 0 && nblk >= 32)) && fits2) ? 4 : 1;
+    if (a.optimistic && mode != 3 && mode != 4) mode = 1;    // (the optimistic update: three of the kernels only)
+    const bool resident = mode == 0 || mode == 4;
     if (a.tune->get(OCO_OPT_VERBOSE) == 1)
         fprintf(stderr, "dense plan: windowed contraction kernel, %d windows in pieces of %lld, %d tiles, iterates %s\n",
                 nwin, (long long)sc.piece_windows, (a.R * a.K + kM - 1) / kM,
-                resident ? "in registers" : mode == 1 ? "streamed from HBM, two tiles per workgroup"
+                mode == 4 ? "in registers, two tiles per workgroup" : resident ? "in registers" : mode == 1 ? "streamed from HBM, two tiles per workgroup"
                 : mode == 3 ? "streamed from HBM, four tiles per workgroup, rows through LDS" : "streamed from HBM");
     WindowKernel kern = nullptr;
     int waves = 0, tiles = 1, lds_bytes = 0;

@@ -289,7 +289,7 @@ int oco_set_option(oco_state *st, int key, int64_t value)
         case OCO_OPT_META_BESIDE: case OCO_OPT_COMPARATOR_GEMM: case OCO_OPT_DENSE_HALF:
         case OCO_OPT_SPARSE_PIPE: case OCO_OPT_VERBOSE: case OCO_OPT_SPARSE_FETCH:
             ok = value <= 1; break;
-        case OCO_OPT_WINDOW_RESIDENT: ok = value <= 3; break;
+        case OCO_OPT_WINDOW_RESIDENT: ok = value <= 4; break;
         case OCO_OPT_DENSE_PATH:
             ok = value == -1 || value == 1 || value == 2;
             if (value == 2 && (st->cfg.sparse_nnz > 0 || !st->cfg.x_shared || st->cfg.d % 4 != 0))

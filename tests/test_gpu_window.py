@@ -34,7 +34,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("name,over", CASES)
-@pytest.mark.parametrize("resident", [1, 0, 2, 3])
+@pytest.mark.parametrize("resident", [1, 0, 2, 3, 4])
 def test_windowed_rounds_match_the_oracle(name, over, resident):
     wl = WL.make(name, **over)
     data = WL.generate(wl)
@@ -43,8 +43,8 @@ def test_windowed_rounds_match_the_oracle(name, over, resident):
     _check(wl, data, got, label="windowed %s %s resident=%d" % (name, over, resident))
 
 
-# the optimistic two-step update (Eq. (3)) in the two windowed kernels that have it (two tiles per
-# workgroup; loading wavefronts), base level only and both levels
+# the optimistic two-step update (Eq. (3)) in the windowed kernels that have it (two tiles per
+# workgroup, streamed or in registers; loading wavefronts), base level only and both levels
 @pytest.mark.parametrize("name,over", [
     ("c1", dict(T=257, d=64, R=3)),
     ("c3", dict(T=500, R=3, d=100, K=15, seg_len=100)),
@@ -54,7 +54,7 @@ def test_windowed_rounds_match_the_oracle(name, over, resident):
     ("c4", dict(T=150, R=2, d=3000, K=2, eta=(0.5, 20.0))),
     ("c4", dict(T=130, R=3, d=8192, K=6)),
 ])
-@pytest.mark.parametrize("resident", [0, 3])
+@pytest.mark.parametrize("resident", [0, 3, 4])
 @pytest.mark.parametrize("optimistic", [1, 2])
 def test_windowed_optimistic_rounds_match_the_oracle(name, over, resident, optimistic):
     wl = WL.make(name, optimistic=optimistic, **over)
@@ -64,7 +64,7 @@ def test_windowed_optimistic_rounds_match_the_oracle(name, over, resident, optim
     _check(wl, data, got, label="windowed optimistic %s %s resident=%d" % (name, over, resident))
 
 
-@pytest.mark.parametrize("resident", [0, 3])
+@pytest.mark.parametrize("resident", [0, 3, 4])
 def test_windowed_optimistic_results_and_how_the_horizon_is_cut(resident):
     """The hint of a call's first round needs the last row of the call before and the learners'
     hint scalars: both are kept in the state.  Different cuts regroup float32 sums (as without
@@ -114,7 +114,7 @@ def test_steps_far_larger_than_the_ball_and_a_tiny_radius():
     ("c3", dict(T=400, R=2, d=1000, K=17, seg_len=90)),
     ("c4", dict(T=300, R=2, d=4096, K=4)),
 ])
-@pytest.mark.parametrize("resident", [1, 0, 2, 3])
+@pytest.mark.parametrize("resident", [1, 0, 2, 3, 4])
 def test_windowed_results_and_how_the_horizon_is_cut(name, over, resident):
     """Repeated runs are bit-identical (every sum has a fixed order).  Different cuts of the horizon
     agree to float32 rounding: the first window of a call takes its inner products with the stored
