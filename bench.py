@@ -44,18 +44,36 @@ def profile_json(name):
     return STAMPS[name]
 
 
-def algorithmic_hbm_bytes(wl, kernel, launches):
+def window_iterates_in_registers(wl, options):
+    """Whether the windowed dense kernel keeps the iterates in registers for a whole launch: the
+    launcher's rule (include/oco.h, OCO_OPT_WINDOW_RESIDENT), restated for the byte count."""
+    ro = (options or {}).get("window_resident", -1)
+    if ro == 1:
+        return wl.d <= 4096 and not wl.optimistic
+    if ro == 4:
+        return wl.d <= 1024
+    if ro >= 0:
+        return False
+    if wl.R * wl.K >= 16384 and wl.d >= 2048:        # four tiles per workgroup, loading wavefronts
+        return False
+    return (wl.d + 15) // 16 >= 32 and wl.d <= 1024
+
+
+def algorithmic_hbm_bytes(wl, kernel, launches, in_registers=False):
     """Compulsory HBM bytes of the round kernels of one step.  Dense: the round stream once, the
     labels, the predictions out, the state in and out per launch; the windowed kernel also
-    moves every iterate in and out once per window of 64 rounds and reads the two re-tiled
-    copies of the stream that its pre-pass wrote.  Sparse: per touched learner coordinate 4 B
-    read + 4 B written, the round stream (8 B per entry), labels and the comparator's gathers."""
+    reads the two re-tiled copies of the stream that its pre-pass wrote and, unless it keeps
+    them in registers, moves every iterate in and out once per window of 64 rounds.  Sparse: per
+    touched learner coordinate 4 B read + 4 B written, the round stream (8 B per entry), labels
+    and the comparator's gathers."""
     if wl.nnz:
         return float(wl.R * wl.K * wl.T * wl.nnz * 8 + wl.T * wl.nnz * 8 + wl.R * wl.T * 4 + wl.R * wl.T * wl.nnz * 4)
     x = 4.0 * wl.T * wl.d * (1 if wl.x_shared else wl.R)
     b = x + 4.0 * wl.R * wl.T + 4.0 * wl.R * (wl.K + 1) * wl.T + 8.0 * wl.R * wl.K * wl.d * max(launches, 1)
     if kernel.startswith("dense_window"):
-        b += 8.0 * wl.R * wl.K * wl.d * ((wl.T + 63) // 64) + 4.0 * x
+        b += 4.0 * x
+        if not in_registers:
+            b += 8.0 * wl.R * wl.K * wl.d * ((wl.T + 63) // 64)
     return b
 
 
@@ -70,11 +88,13 @@ def roofline_block(wl, kt, config_key):
     launches = max(kt["launches"], 1)
     avg_ms = kt["ms_sum"] / max(kt["timed"], 1)
     kernel = kt["kernel"]
-    hbm_bytes = algorithmic_hbm_bytes(wl, kernel, launches)
+    hbm_bytes = algorithmic_hbm_bytes(wl, kernel, launches, kt.get("iterates") == "registers")
     entry = profile_json("hbm_traffic.json").get(config_key)
     entry = entry if isinstance(entry, dict) and entry.get("kernel") == kernel else None
     traffic = entry["bytes_per_launch"] if entry else None
     rl = {"kernel": kernel, "launches_per_step": launches, "avg_launch_ms": avg_ms}
+    if kernel.startswith("dense_window"):
+        rl["iterates"] = kt.get("iterates", "hbm")
     if wl.nnz:
         ach = hbm_bytes / launches / (avg_ms * 1e-3) / 1e9
         rl.update(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS)
@@ -119,7 +139,9 @@ def binding_block(wl, res, config_key, floor=None):
         kt = res["kernel_timing"]
         step_ms = kt["ms_sum"] / max(kt["timed"], 1) * max(kt["launches"], 1)      # all launches of a step
         floor_ms = 4.0 * wl.units / (PEAK_FP32_TFLOPS * 1e12) * 1e3
-        b.update(resource="matrix cores, fed from L2 (round rows) and HBM (iterates); the dependent rounds of a window "
+        where = ("matrix cores, fed from L2 (round rows), the iterates in registers"
+                 if kt.get("iterates") == "registers" else "matrix cores, fed from L2 (round rows) and HBM (iterates)")
+        b.update(resource=where + "; the dependent rounds of a window "
                           "(64 rounds on float64 scalars, one wavefront per tile of 16 learners) run beside the sweep",
                  tiles=(wl.R * wl.K + 15) // 16, windows=(wl.T + 63) // 64,
                  matrix_core_floor_ms=floor_ms, utilisation=floor_ms / step_ms,
@@ -159,6 +181,8 @@ def run_workload(name, steps, warmup, WL, B, torch, keep=None, optimistic=False,
     ms = 1e3 * dt / steps
     kt = dict(kernel=ktim[0]["kernel"], launches=ktim[0]["launches"], timed=sum(k["timed"] for k in ktim),
               ms_sum=sum(k["ms_sum"] for k in ktim))
+    if kt["kernel"].startswith("dense_window"):
+        kt["iterates"] = "registers" if window_iterates_in_registers(wl, options) else "hbm"
     out = dict(wl=wl, ms_per_step=ms, value=wl.units / (dt / steps),
                round_kernel_ms=float(sum(k[0] for k in kern_ms) / steps),
                meta_kernel_ms=float(sum(k[1] for k in kern_ms) / steps),

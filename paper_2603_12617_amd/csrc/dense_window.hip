@@ -1341,7 +1341,7 @@ using WindowKernel = void (*)(const DenseArgs, const float *, const float *, con
 // mode 0: iterates in registers (8 wavefronts, one tile); 1: streamed, two tiles per workgroup
 // (8 wavefronts); 2: streamed, one tile, 16 wavefronts; 3: four tiles, loading wavefronts; 4: iterates
 // of two tiles in registers (8 wavefronts, d <= 1024)
-// (opt: the optimistic update, built into the two kernels the launcher picks by itself)
+// (opt: the optimistic update, built into the three kernels the launcher picks by itself)
 template <int LOSS> WindowKernel pick_window_kernel(int nblk, int mode, bool opt, int *waves, int *tiles, int *lds_bytes)
 {
     if (mode == 4) {
