@@ -609,6 +609,7 @@ FULL = [
     ("c3", [77], None, True, dict(dense_path=1)),        # (the optimistic update on the register kernel by name)
     ("c3", [5, 250], None, False, dict(dense_path=1)),
     ("c3", [5, 250], None, False, dict(dense_path=2)),
+    ("c3", [5, 250], None, False, dict(dense_path=2, window_resident=0)),
     ("c4", [7, 1000], None, False, dict(dense_path=1)),
     ("c4", [7, 1000], None, False, dict(dense_path=2)),
     ("c4", [7, 1000], None, False, dict(dense_path=2, window_resident=0)),
