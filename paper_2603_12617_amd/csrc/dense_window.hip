@@ -596,7 +596,7 @@ __global__ void __launch_bounds__(NW *kWave) dense_window_kernel(const DenseArgs
     double n2_begin = 0.0;      // what the previous window's rounds started from
     bool proj_prev = true;      // whether they projected this learner (then n2 was reset to D^2 on the way)
     Hint hint{0.f, 0.f, 0.f};   // optimistic update: carried from round to round, window to window, call to call
-    f4 V[RES ? NB : 1][MT];     // iterates in registers: block wave + NW b of every tile
+    f4 V[RES ? NB : 1][MT];     // iterates in registers: the blocks kept_block() names, of every tile
     f4 accq[MT][4];             // this wavefront's shares of W_k X_{k+1}^T; tile 0's go to LDS at once, the others wait their turn
     {
         const Geo<MT> g = make_geo<MT>((int)threadIdx.x, a);
